@@ -1,0 +1,184 @@
+"""Double-precision CPU oracle for the ATOMO encoder/decoder (arXiv 1806.04090).
+
+TEST INFRASTRUCTURE ONLY: imported by the test-suite, by the smoke check and by
+the benchmark's cpu_baseline leg.  The HIP library never imports or calls it,
+and this package imports nothing from the HIP side.
+
+The arithmetic lives in ``atomo_oracle.c`` (plain C, fp64); this module only
+marshals numpy arrays and chains the stages in the order of Section 3:
+decomposition -> Algorithm 1 probabilities -> Bernoulli(p) -> lambda/p -> sum.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "atomo_oracle.c")
+_LIB = os.path.join(_HERE, "libatomo_oracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (a second or two).  Returns the library path."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-fPIC", "-shared", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def _L():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        c = ctypes
+        dp, fp = c.POINTER(c.c_double), c.POINTER(c.c_float)
+        u8p, i64p, u32p = c.POINTER(c.c_uint8), c.POINTER(c.c_int64), c.POINTER(c.c_uint32)
+        lib.oracle_philox4x32_10.argtypes = [u32p, u32p, u32p]
+        lib.oracle_philox4x32_10.restype = None
+        lib.oracle_uniforms.argtypes = [c.c_uint64, c.c_uint64, c.c_int64, c.c_int64, fp]
+        lib.oracle_uniforms.restype = None
+        lib.oracle_bernoulli_mask.argtypes = [fp, c.c_int64, c.c_uint64, c.c_uint64, u8p]
+        lib.oracle_bernoulli_mask.restype = None
+        lib.oracle_probabilities.argtypes = [dp, c.c_int64, c.c_double, dp]
+        lib.oracle_probabilities.restype = c.c_int64
+        lib.oracle_svd.argtypes = [c.c_int32, c.c_int32, dp, dp, dp, dp]
+        lib.oracle_svd.restype = c.c_int
+        lib.oracle_pack_weights.argtypes = [dp, dp, u8p, c.c_int64, i64p, dp]
+        lib.oracle_pack_weights.restype = c.c_int64
+        lib.oracle_decode_svd_accumulate.argtypes = [c.c_int32, c.c_int32, c.c_int64, dp, dp, dp, c.c_double, dp]
+        lib.oracle_decode_svd_accumulate.restype = None
+        lib.oracle_decode_entrywise_accumulate.argtypes = [c.c_int64, i64p, dp, c.c_double, dp]
+        lib.oracle_decode_entrywise_accumulate.restype = None
+        _lib = lib
+    return _lib
+
+
+def _ptr(a, ctype):
+    return a.ctypes.data_as(ctypes.POINTER(ctype))
+
+
+# ---------------------------------------------------------------- stages ----
+
+def philox4x32_10(ctr, key):
+    """One Philox4x32-10 block: 4 counter words, 2 key words -> 4 output words."""
+    ctr = np.ascontiguousarray(ctr, dtype=np.uint32)
+    key = np.ascontiguousarray(key, dtype=np.uint32)
+    out = np.empty(4, dtype=np.uint32)
+    _L().oracle_philox4x32_10(_ptr(ctr, ctypes.c_uint32), _ptr(key, ctypes.c_uint32), _ptr(out, ctypes.c_uint32))
+    return out
+
+
+def uniforms(seed: int, stream: int, n: int, first: int = 0):
+    """u_i in [0,1) for atoms first..first+n of (seed, stream); float32, exact multiples of 2^-24."""
+    u = np.empty(n, dtype=np.float32)
+    _L().oracle_uniforms(seed, stream, first, n, _ptr(u, ctypes.c_float))
+    return u
+
+
+def bernoulli_mask(p32, seed: int, stream: int):
+    """t_i = [u_i < p_i], compared in float32 on the float32 p handed in."""
+    p32 = np.ascontiguousarray(p32, dtype=np.float32)
+    mask = np.empty(p32.size, dtype=np.uint8)
+    _L().oracle_bernoulli_mask(_ptr(p32, ctypes.c_float), p32.size, seed, stream, _ptr(mask, ctypes.c_uint8))
+    return mask.astype(bool)
+
+
+def probabilities(lam, s: float, return_forced: bool = False):
+    """Algorithm 1 on lambda in any order; p comes back in the same order (float64)."""
+    lam = np.ascontiguousarray(lam, dtype=np.float64)
+    p = np.empty_like(lam)
+    forced = _L().oracle_probabilities(_ptr(lam, ctypes.c_double), lam.size, float(s), _ptr(p, ctypes.c_double))
+    return (p, int(forced)) if return_forced else p
+
+
+def svd(G):
+    """Thin SVD of a 2-D array (upcast to float64): (sigma desc, U m x r, V n x r), columns are atoms."""
+    G = np.ascontiguousarray(G, dtype=np.float64)
+    m, n = G.shape
+    r = min(m, n)
+    sigma = np.empty(r)
+    U = np.empty((r, m))            # C column-major m x r  ==  numpy (r, m) row-major
+    V = np.empty((r, n))
+    sweeps = _L().oracle_svd(m, n, _ptr(G, ctypes.c_double), _ptr(sigma, ctypes.c_double),
+                             _ptr(U, ctypes.c_double), _ptr(V, ctypes.c_double))
+    if sweeps < 0:
+        raise RuntimeError("oracle Jacobi SVD did not converge")
+    return sigma, U.T, V.T
+
+
+def pack_weights(lam, p, mask):
+    """Kept atoms (ascending index) and their weights lambda_i / p_i."""
+    lam = np.ascontiguousarray(lam, dtype=np.float64)
+    p = np.ascontiguousarray(p, dtype=np.float64)
+    m8 = np.ascontiguousarray(mask, dtype=np.uint8)
+    idx = np.empty(lam.size, dtype=np.int64)
+    w = np.empty(lam.size, dtype=np.float64)
+    k = _L().oracle_pack_weights(_ptr(lam, ctypes.c_double), _ptr(p, ctypes.c_double), _ptr(m8, ctypes.c_uint8),
+                                 lam.size, _ptr(idx, ctypes.c_int64), _ptr(w, ctypes.c_double))
+    return idx[:k].copy(), w[:k].copy()
+
+
+def decode_svd(messages, m: int, n: int, scale: float = 1.0):
+    """Dense m x n float64 sum of the messages' kept rank-1 atoms, times scale.
+
+    Each message is a dict with 'w' (k,), 'U' (m, k), 'V' (n, k)."""
+    out = np.zeros((m, n))
+    for msg in messages:
+        w = np.ascontiguousarray(msg["w"], dtype=np.float64)
+        k = w.size
+        if k == 0:
+            continue
+        Uc = np.ascontiguousarray(np.asarray(msg["U"], dtype=np.float64).T)   # (k, m) == column-major m x k
+        Vc = np.ascontiguousarray(np.asarray(msg["V"], dtype=np.float64).T)
+        assert Uc.shape == (k, m) and Vc.shape == (k, n)
+        _L().oracle_decode_svd_accumulate(m, n, k, _ptr(w, ctypes.c_double), _ptr(Uc, ctypes.c_double),
+                                          _ptr(Vc, ctypes.c_double), float(scale), _ptr(out, ctypes.c_double))
+    return out
+
+
+def decode_entrywise(messages, n: int, scale: float = 1.0):
+    """Dense length-n float64 sum of the messages' (idx, val) pairs, times scale."""
+    out = np.zeros(n)
+    for msg in messages:
+        idx = np.ascontiguousarray(msg["idx"], dtype=np.int64)
+        val = np.ascontiguousarray(msg["val"], dtype=np.float64)
+        if idx.size:
+            assert idx.min() >= 0 and idx.max() < n
+            _L().oracle_decode_entrywise_accumulate(idx.size, _ptr(idx, ctypes.c_int64), _ptr(val, ctypes.c_double),
+                                                    float(scale), _ptr(out, ctypes.c_double))
+    return out
+
+
+# ----------------------------------------------------------------- chains ----
+
+def encode_svd(G, s: float, seed: int, stream: int, sigma_UV=None, p32=None):
+    """Spectral-ATOMO encode of one matrix.  Optional sigma_UV / p32 splice in another
+    implementation's decomposition / float32 probabilities."""
+    sigma, U, V = svd(G) if sigma_UV is None else sigma_UV
+    sigma = np.asarray(sigma, dtype=np.float64)
+    p = probabilities(sigma, s)
+    p_used32 = p.astype(np.float32) if p32 is None else np.asarray(p32, dtype=np.float32)
+    mask = bernoulli_mask(p_used32, seed, stream)
+    p_for_w = p if p32 is None else p_used32.astype(np.float64)
+    idx, w = pack_weights(sigma, p_for_w, mask)
+    return {"sigma": sigma, "p": p, "mask": mask, "idx": idx, "w": w,
+            "U": np.asarray(U)[:, idx], "V": np.asarray(V)[:, idx]}
+
+
+def encode_entrywise(g, s: float, seed: int, stream: int, p32=None):
+    """Entry-wise ATOMO encode of a flat gradient: atoms e_i, lambda_i = g_i."""
+    g = np.asarray(g, dtype=np.float64).ravel()
+    p = probabilities(g, s)
+    p_used32 = p.astype(np.float32) if p32 is None else np.asarray(p32, dtype=np.float32)
+    mask = bernoulli_mask(p_used32, seed, stream)
+    p_for_w = p if p32 is None else p_used32.astype(np.float64)
+    idx, val = pack_weights(g, p_for_w, mask)
+    return {"p": p, "mask": mask, "idx": idx, "val": val}
