@@ -1,0 +1,183 @@
+/*
+ * atomo.h - C ABI of the MI355X (gfx950) ATOMO gradient encoder / decoder.
+ *
+ * ATOMO ("ATOMO: Communication-efficient Learning via Atomic Sparsification",
+ * arXiv 1806.04090) writes a stochastic gradient in an atomic decomposition
+ * g = sum_i lambda_i a_i with unit-norm atoms (Section 3), draws independent
+ * t_i ~ Bernoulli(p_i) and sends only the kept atoms, rescaled:
+ *
+ *     g_hat = sum_i (lambda_i t_i / p_i) a_i                       (eq. (vhat))
+ *
+ * with the p that minimises the variance under a sparsity budget sum p_i = s
+ * (eq. (opt_prob1), solved by Algorithm 1).  Two decompositions are built:
+ * entry-wise (a_i = e_i, lambda_i = g_i) and, for a gradient viewed as a
+ * matrix, the singular value decomposition (atoms u_i v_i^T, lambda_i =
+ * sigma_i; Section 5, "Spectral-ATOMO").
+ *
+ * Conventions for every entry point
+ *  - All data pointers are DEVICE pointers (HIP global memory on the device the
+ *    context was created for) unless a parameter says "host".  Descriptor
+ *    structs (atomo_mat, atomo_svd_msg, atomo_ew_msg) and arrays of them are
+ *    HOST memory; they are read during the call and may be freed afterwards.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Work is enqueued on it; calls do not wait for the GPU.  Results are
+ *    valid once the stream has reached the end of the enqueued work.
+ *  - The caller owns every input, output and message buffer.  Inputs are never
+ *    modified.  The context owns a device workspace that grows on demand
+ *    (growing it allocates, which synchronises the device; atomo_reserve
+ *    pre-sizes it).  One context must not be used from two streams at once.
+ *  - Return value: ATOMO_OK or a negative atomo_status.  Nothing throws, exits
+ *    or prints.  Conditions that are only known on the GPU (a message that did
+ *    not fit its capacity, a Jacobi run that hit the sweep limit) do not fail
+ *    the call; they are latched on the device and read back by atomo_status.
+ *  - Random numbers: Philox4x32-10 (Salmon et al., SC'11).  Atom i of a call
+ *    with (seed, stream_id) uses output word i mod 4 of the block with counter
+ *    (i div 4 [64 bit], stream_id [64 bit]) and key seed [64 bit];
+ *    u = (word >> 8) * 2^-24 and the atom is kept iff u < p_i, compared in
+ *    single precision.  The paper fixes only t_i ~ Bernoulli(p_i) (Section 3).
+ */
+#ifndef ATOMO_H
+#define ATOMO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum atomo_status_code {
+    ATOMO_OK = 0,
+    ATOMO_EINVAL = -1,     /* null pointer, non-positive size, s <= 0 or NaN, inconsistent shapes  */
+    ATOMO_ECAPACITY = -2,  /* (atomo_status only) more atoms were kept than a message could hold    */
+    ATOMO_ENOCONV = -3,    /* (atomo_status only) the Jacobi SVD stopped at the sweep limit         */
+    ATOMO_EHIP = -4,       /* a HIP runtime call failed; atomo_last_hip_error gives its code        */
+    ATOMO_ENOMEM = -5      /* the workspace could not be allocated                                  */
+} atomo_status_code;
+
+enum { ATOMO_KIND_SVD = 0, ATOMO_KIND_ENTRYWISE = 1 };
+
+typedef struct atomo_ctx atomo_ctx;   /* opaque: device, workspace, latched device-side flags */
+
+/* A gradient viewed as a matrix (Section 5; Fig. 1: a conv gradient [out,in,k,k] is the row-major
+ * out x (in*k*k) matrix it already is in memory).  rows x cols, row stride ld >= cols, float32. */
+typedef struct atomo_mat {
+    int32_t rows, cols;
+    int64_t ld;
+    const float* data;               /* device */
+} atomo_mat;
+
+/* One Spectral-ATOMO message: the kept singular triplets of one matrix ("weighted singular vectors
+ * sampled from the true gradient", Section 6).  Atom index 0 is the largest singular value.
+ * All pointers are caller-owned device memory. */
+typedef struct atomo_svd_msg {
+    int32_t rows, cols;              /* shape of the encoded matrix                                   */
+    int32_t capacity;                /* room for this many kept atoms, 1 <= capacity                 */
+    int32_t* count;                  /* [1]  number of atoms kept (may exceed capacity: see status)  */
+    int32_t* idx;                    /* [capacity] atom indices, ascending                           */
+    float*   w;                      /* [capacity] weights sigma_i / p_i                             */
+    float*   U;                      /* [capacity][rows]  U[k*rows + i] = (u of k-th kept atom)_i, unit norm */
+    float*   V;                      /* [capacity][cols]  V[k*cols + j] = (v of k-th kept atom)_j, unit norm */
+} atomo_svd_msg;
+
+/* One entry-wise ATOMO message: kept coordinates, ascending, with values g_i / p_i. */
+typedef struct atomo_ew_msg {
+    int64_t n;                       /* length of the encoded gradient, 0 < n < 2^32                 */
+    int64_t capacity;                /* room for this many pairs                                     */
+    int64_t* count;                  /* [1]  number of pairs kept (may exceed capacity: see status)  */
+    uint32_t* idx;                   /* [capacity] kept coordinates, ascending                       */
+    float* val;                      /* [capacity] g_i / p_i                                         */
+} atomo_ew_msg;
+
+/* Tuning knobs of the Jacobi SVD; pass NULL to the encoder for the defaults. */
+typedef struct atomo_svd_options {
+    int32_t max_sweeps;              /* default 12                                                   */
+    float   stop_cosine;             /* default 1e-4: stop after the first sweep whose largest       */
+                                     /* |<a_i,a_j>| / (|a_i||a_j|), measured before rotating, is below */
+} atomo_svd_options;
+
+/* -------- context ------------------------------------------------------------------------------ */
+
+/* Creates a context on HIP device `device`.  *out is set on success. */
+int atomo_create(atomo_ctx** out, int device);
+int atomo_destroy(atomo_ctx* ctx);
+
+/* Makes sure the workspace holds at least `bytes`; atomo_svd_workspace_bytes /
+ * atomo_entrywise_workspace_bytes say how much a call will need (host-side arithmetic only). */
+int atomo_reserve(atomo_ctx* ctx, size_t bytes);
+int atomo_svd_workspace_bytes(const atomo_mat* mats /*host*/, int n_mats, size_t* bytes /*host*/);
+int atomo_entrywise_workspace_bytes(int64_t n, size_t* bytes /*host*/);
+
+/* Waits for `stream`, then reports and clears what the GPU latched since the last call:
+ * ATOMO_OK, ATOMO_ECAPACITY, ATOMO_ENOCONV or ATOMO_EHIP.  If sweeps is not NULL it receives the
+ * largest number of Jacobi sweeps any matrix of the last atomo_encode_svd took. */
+int atomo_status(atomo_ctx* ctx, void* stream, int32_t* sweeps /*host, optional*/);
+int atomo_last_hip_error(const atomo_ctx* ctx);
+const char* atomo_strerror(int status);
+
+/* -------- the method --------------------------------------------------------------------------- */
+
+/*
+ * Algorithm 1 ("ATOMO probabilities", Section 3; closed form in the KKT appendix, eq. (p_i)).
+ * For each of n_seg independent segments lambda[offsets[k] .. offsets[k+1]) computes
+ *     p = argmin sum lambda_i^2 / p_i   s.t.  0 <= p_i <= 1,  sum p_i = s
+ * i.e. p_i = 1 for the n_s largest |lambda_i| and p_i = |lambda_i| (s - n_s) / sum_{rest} |lambda_j|
+ * for the rest, n_s the smallest count that keeps every p_i <= 1.  lambda may be in any order and
+ * of any sign; p comes back in the same order.  lambda_i = 0 gets p_i = 0; if s >= #nonzeros every
+ * nonzero gets 1 (then sum p < s).
+ *   lambda, p : device float32 [offsets[n_seg]]      offsets : HOST int64 [n_seg + 1], ascending
+ *   s > 0 (a real number, the same for every segment)
+ */
+int atomo_probabilities(atomo_ctx* ctx, const float* lambda, const int64_t* offsets /*host*/, int n_seg,
+                        double s, float* p, void* stream);
+
+/*
+ * Spectral-ATOMO encode (Section 5; eq. (vhat) on the singular value decomposition).
+ * For each matrix j: thin SVD  G_j = sum_i sigma_i u_i v_i^T  (sigma descending), p = Algorithm 1
+ * on sigma with budget s, t_i ~ Bernoulli(p_i) from Philox stream (seed, stream_base + j), and the
+ * message = kept atoms (index, sigma_i / p_i, u_i, v_i) in ascending index.
+ *   mats, msgs : HOST arrays of n_mats descriptors; msgs[j].rows/cols must equal mats[j].rows/cols.
+ *   sigma_out, p_out : optional device float32, all matrices concatenated, min(rows, cols) values
+ *                      each, descending sigma order (atom order).  Pass NULL to skip.
+ * Supported shapes: min(rows, cols) <= 2048.
+ */
+int atomo_encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s,
+                     uint64_t seed, uint64_t stream_base, const atomo_svd_options* opt /*host, optional*/,
+                     const atomo_svd_msg* msgs, float* sigma_out, float* p_out, void* stream);
+
+/*
+ * Entry-wise ATOMO encode (Section 3 with the standard basis; Section 4 shows 1-bit QSGD and
+ * TernGrad are this with s = |g|_1/|g|_2 and s = |g|_1/|g|_inf).  lambda_i = g_i, p = Algorithm 1,
+ * coordinate i is kept iff u_i < p_i (Philox stream (seed, stream_id)) and stored as
+ * (i, g_i / p_i), ascending in i.
+ *   g : device float32 [msg->n];  p_out : optional device float32 [msg->n].
+ */
+int atomo_encode_entrywise(atomo_ctx* ctx, const float* g, double s, uint64_t seed, uint64_t stream_id,
+                           const atomo_ew_msg* msg /*host*/, float* p_out, void* stream);
+
+/*
+ * Decode (eq. (vhat)): out = scale * sum over the n_msgs messages of sum_k w_k a_k.  With
+ * scale = 1/P and the P workers' messages this is the parameter server's averaged gradient
+ * (Section 2).  `out` is overwritten.
+ *   kind = ATOMO_KIND_SVD:       msgs is a HOST array of n_msgs atomo_svd_msg with equal rows/cols;
+ *                                out is the dense rows x cols row-major matrix with row stride ld.
+ *   kind = ATOMO_KIND_ENTRYWISE: msgs is a HOST array of n_msgs atomo_ew_msg with equal n;
+ *                                out is the dense vector of n floats (ld is ignored).
+ * A message whose count exceeds its capacity contributes its first `capacity` atoms.
+ */
+int atomo_decode(atomo_ctx* ctx, int kind, const void* msgs, int n_msgs, float scale,
+                 float* out, int64_t ld, void* stream);
+
+/*
+ * Batched form of the SVD decode for a whole layer set: for each of n_out outputs, the messages
+ * msgs[first[o] .. first[o+1]) are summed into outs[o] as atomo_decode does, in one launch.
+ *   msgs : HOST array;  first : HOST int32 [n_out + 1];  outs : HOST array of n_out device pointers;
+ *   lds  : HOST int64 [n_out].
+ */
+int atomo_decode_svd_batch(atomo_ctx* ctx, const atomo_svd_msg* msgs, const int32_t* first, int n_out,
+                           float scale, float* const* outs, const int64_t* lds, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ATOMO_H */

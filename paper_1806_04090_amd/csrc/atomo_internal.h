@@ -1,0 +1,123 @@
+// Internal declarations shared by the translation units of libatomo (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/atomo.h"
+
+namespace atomo {
+
+// ---------------------------------------------------------------------------------------------
+// Context
+// ---------------------------------------------------------------------------------------------
+
+// Device-side latched flags (int32 each).
+enum { FLAG_CAPACITY = 0, FLAG_NOCONV = 1, FLAG_MAX_SWEEPS = 2, FLAG_COUNT = 8 };
+
+struct StageSlot {
+    void* host = nullptr;        // pinned
+    size_t bytes = 0;
+    hipEvent_t ev = nullptr;     // recorded after the last copy out of `host`
+    bool pending = false;
+};
+
+}  // namespace atomo
+
+struct atomo_ctx {
+    int device = 0;
+    void* ws = nullptr;          // device workspace
+    size_t ws_bytes = 0;
+    int32_t* d_flags = nullptr;  // [FLAG_COUNT] device
+    int32_t* h_flags = nullptr;  // pinned readback buffer
+    int last_hip = 0;
+    atomo::StageSlot ring[8];
+    int ring_next = 0;
+};
+
+namespace atomo {
+
+#define ATOMO_HIP(ctx, call)                                   \
+    do {                                                       \
+        hipError_t e__ = (call);                               \
+        if (e__ != hipSuccess) {                               \
+            (ctx)->last_hip = (int)e__;                        \
+            return ATOMO_EHIP;                                 \
+        }                                                      \
+    } while (0)
+
+// Grows the workspace to at least `bytes` (contents are not preserved).
+int ensure_workspace(atomo_ctx* ctx, size_t bytes);
+
+// Copies `bytes` of host data to device address `dst` on `stream` through a pinned staging slot,
+// so the caller's host buffer may be reused as soon as this returns.
+int upload(atomo_ctx* ctx, void* dst, const void* src, size_t bytes, hipStream_t stream);
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// A bump allocator over the workspace; first pass with base == nullptr only measures.
+struct Carver {
+    char* base;
+    size_t off = 0;
+    explicit Carver(void* b) : base((char*)b) {}
+    template <typename T>
+    T* take(size_t count) {
+        off = align_up(off, 256);
+        T* p = base ? (T*)(base + off) : nullptr;
+        off += count * sizeof(T);
+        return p;
+    }
+};
+
+// ---------------------------------------------------------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11): device + host inline so every kernel draws the same stream
+// ---------------------------------------------------------------------------------------------
+
+struct u32x4 { uint32_t x, y, z, w; };
+
+__host__ __device__ inline u32x4 philox4x32_10(uint64_t block, uint64_t stream_id, uint64_t seed)
+{
+    uint32_t c0 = (uint32_t)block, c1 = (uint32_t)(block >> 32);
+    uint32_t c2 = (uint32_t)stream_id, c3 = (uint32_t)(stream_id >> 32);
+    uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)p1;
+        c3 = (uint32_t)p0;
+        c0 = n0;
+        c2 = n2;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return u32x4{c0, c1, c2, c3};
+}
+
+// 24 random bits -> [0,1), exact in float32.
+__host__ __device__ inline float u01(uint32_t word) { return (float)(word >> 8) * 5.9604644775390625e-08f; }
+
+// ---------------------------------------------------------------------------------------------
+// Entry points implemented per translation unit
+// ---------------------------------------------------------------------------------------------
+
+int svd_workspace_bytes(const atomo_mat* mats, int n_mats, size_t* bytes);
+int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint64_t seed, uint64_t stream_base,
+               const atomo_svd_options* opt, const atomo_svd_msg* msgs, float* sigma_out, float* p_out,
+               hipStream_t stream);
+
+size_t entrywise_workspace_bytes(int64_t n);
+int encode_entrywise(atomo_ctx* ctx, const float* g, double s, uint64_t seed, uint64_t stream_id,
+                     const atomo_ew_msg* msg, float* p_out, hipStream_t stream);
+int probabilities(atomo_ctx* ctx, const float* lambda, const int64_t* offsets, int n_seg, double s, float* p,
+                  hipStream_t stream);
+
+int decode_svd_batch(atomo_ctx* ctx, const atomo_svd_msg* msgs, const int32_t* first, int n_out, float scale,
+                     float* const* outs, const int64_t* lds, hipStream_t stream);
+int decode_entrywise(atomo_ctx* ctx, const atomo_ew_msg* msgs, int n_msgs, float scale, float* out,
+                     hipStream_t stream);
+
+}  // namespace atomo

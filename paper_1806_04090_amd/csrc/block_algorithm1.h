@@ -1,0 +1,89 @@
+// Algorithm 1 ("ATOMO probabilities", Section 3 of arXiv 1806.04090) for one workgroup of 256
+// threads on up to 2048 magnitudes held in LDS.  HIP side only.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+namespace atomo {
+
+constexpr int ALG1_MAX = 2048;
+
+struct Alg1Scratch {
+    double part[256];
+    double tail_ns;
+    int first_true;
+};
+
+// Bitonic sort of (key, src) pairs, descending by key, ties by ascending src.  P = power of two
+// >= count; entries beyond the data must hold keys below every real key.  All 256 threads call.
+__device__ inline void block_sort_desc(float* key, int* src, int P)
+{
+    const int tid = threadIdx.x;
+    for (int k = 2; k <= P; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int i = tid; i < P; i += 256) {
+                const int o = i ^ j;
+                if (o > i) {
+                    const float ki = key[i], ko = key[o];
+                    const int si = src[i], so = src[o];
+                    const bool i_first = (ki > ko) || (ki == ko && si < so);
+                    const bool desc = (i & k) == 0;
+                    if (desc ? !i_first : i_first) {
+                        key[i] = ko; key[o] = ki;
+                        src[i] = so; src[o] = si;
+                    }
+                }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// key[0..n) holds magnitudes sorted descending.  Finds n_s = the first sorted index i with
+// key_i * (s - i) <= sum_{j >= i} key_j (the test of Algorithm 1 with the budget that remains; it
+// is monotone in i, so "first true" can be searched in parallel) and the tail sum at that index.
+// Thread t owns the slice [t*per, min(n,(t+1)*per)).  After the call every thread may evaluate
+//     p_i = 1                                   for i <  n_s
+//     p_i = key_i * (s - n_s) / tail            for i >= n_s and tail > 0      (eq. (p_i), KKT appendix)
+//     p_i = 0                                   otherwise (only zeros remain)
+// All 256 threads call; returns n_s, and the tail sum through sc.tail_ns (valid if n_s < n).
+__device__ inline int block_algorithm1(const float* key, int n, double s, Alg1Scratch& sc)
+{
+    const int tid = threadIdx.x;
+    const int per = (n + 255) / 256;
+    const int lo = min(n, tid * per), hi = min(n, lo + per);
+    double mine = 0.0;
+    for (int i = hi - 1; i >= lo; --i) mine += (double)key[i];
+    sc.part[tid] = mine;
+    if (tid == 0) { sc.first_true = n; sc.tail_ns = 0.0; }
+    __syncthreads();
+    double after = 0.0;
+    for (int t = 255; t > tid; --t) after += sc.part[t];
+    {
+        double tail = after + mine;
+        int found = n;
+        for (int i = lo; i < hi; ++i) {
+            if ((double)key[i] * (s - (double)i) <= tail) { found = i; break; }
+            tail -= (double)key[i];
+        }
+        if (found < n) atomicMin(&sc.first_true, found);
+    }
+    __syncthreads();
+    const int ns = sc.first_true;
+    if (ns < n && ns >= lo && ns < hi) {
+        double tail = after;
+        for (int i = hi - 1; i >= ns; --i) tail += (double)key[i];
+        sc.tail_ns = tail;
+    }
+    __syncthreads();
+    return ns;
+}
+
+__device__ inline float alg1_probability(float key, int i, int ns, double s, double tail_ns)
+{
+    if (i < ns) return 1.0f;
+    if (tail_ns > 0.0) return fminf(1.0f, (float)((double)key * (s - (double)ns) / tail_ns));
+    return 0.0f;
+}
+
+}  // namespace atomo

@@ -1,0 +1,264 @@
+// C ABI of libatomo: context management, argument validation, dispatch.  See include/atomo.h.
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "atomo_internal.h"
+
+namespace atomo {
+
+int ensure_workspace(atomo_ctx* ctx, size_t bytes)
+{
+    if (bytes <= ctx->ws_bytes) return ATOMO_OK;
+    // Growing frees the old block; hipFree waits for the device, so no kernel still uses it.
+    if (ctx->ws) {
+        ATOMO_HIP(ctx, hipFree(ctx->ws));
+        ctx->ws = nullptr;
+        ctx->ws_bytes = 0;
+    }
+    size_t want = align_up(bytes + bytes / 8, (size_t)1 << 20);
+    hipError_t e = hipMalloc(&ctx->ws, want);
+    if (e != hipSuccess) {
+        ctx->last_hip = (int)e;
+        ctx->ws = nullptr;
+        return ATOMO_ENOMEM;
+    }
+    ctx->ws_bytes = want;
+    return ATOMO_OK;
+}
+
+int upload(atomo_ctx* ctx, void* dst, const void* src, size_t bytes, hipStream_t stream)
+{
+    if (bytes == 0) return ATOMO_OK;
+    const int n_slots = (int)(sizeof(ctx->ring) / sizeof(ctx->ring[0]));
+    StageSlot& slot = ctx->ring[ctx->ring_next];
+    ctx->ring_next = (ctx->ring_next + 1) % n_slots;
+    if (slot.pending) {                       // the copy that last used this slot must have run
+        ATOMO_HIP(ctx, hipEventSynchronize(slot.ev));
+        slot.pending = false;
+    }
+    if (slot.bytes < bytes) {
+        if (slot.host) ATOMO_HIP(ctx, hipHostFree(slot.host));
+        slot.host = nullptr;
+        slot.bytes = 0;
+        size_t want = align_up(bytes * 2, 4096);
+        ATOMO_HIP(ctx, hipHostMalloc(&slot.host, want, hipHostMallocDefault));
+        slot.bytes = want;
+    }
+    if (!slot.ev) ATOMO_HIP(ctx, hipEventCreateWithFlags(&slot.ev, hipEventDisableTiming));
+    memcpy(slot.host, src, bytes);
+    ATOMO_HIP(ctx, hipMemcpyAsync(dst, slot.host, bytes, hipMemcpyHostToDevice, stream));
+    ATOMO_HIP(ctx, hipEventRecord(slot.ev, stream));
+    slot.pending = true;
+    return ATOMO_OK;
+}
+
+}  // namespace atomo
+
+using namespace atomo;
+
+namespace {
+
+struct DeviceGuard {
+    int prev = -1;
+    bool ok = false;
+    explicit DeviceGuard(atomo_ctx* ctx)
+    {
+        if (hipGetDevice(&prev) != hipSuccess) prev = -1;
+        hipError_t e = hipSetDevice(ctx->device);
+        ok = (e == hipSuccess);
+        if (!ok) ctx->last_hip = (int)e;
+    }
+    ~DeviceGuard()
+    {
+        if (prev >= 0) (void)hipSetDevice(prev);
+    }
+};
+
+bool bad_budget(double s) { return !(s > 0.0) || std::isnan(s) || std::isinf(s); }
+
+}  // namespace
+
+extern "C" {
+
+int atomo_create(atomo_ctx** out, int device)
+{
+    if (!out) return ATOMO_EINVAL;
+    *out = nullptr;
+    int n_dev = 0;
+    if (hipGetDeviceCount(&n_dev) != hipSuccess || device < 0 || device >= n_dev) return ATOMO_EHIP;
+    atomo_ctx* ctx = new (std::nothrow) atomo_ctx();
+    if (!ctx) return ATOMO_ENOMEM;
+    ctx->device = device;
+    DeviceGuard guard(ctx);
+    if (!guard.ok) { delete ctx; return ATOMO_EHIP; }
+    if (hipMalloc((void**)&ctx->d_flags, FLAG_COUNT * sizeof(int32_t)) != hipSuccess ||
+        hipMemset(ctx->d_flags, 0, FLAG_COUNT * sizeof(int32_t)) != hipSuccess ||
+        hipHostMalloc((void**)&ctx->h_flags, FLAG_COUNT * sizeof(int32_t), hipHostMallocDefault) != hipSuccess) {
+        if (ctx->d_flags) (void)hipFree(ctx->d_flags);
+        delete ctx;
+        return ATOMO_EHIP;
+    }
+    *out = ctx;
+    return ATOMO_OK;
+}
+
+int atomo_destroy(atomo_ctx* ctx)
+{
+    if (!ctx) return ATOMO_EINVAL;
+    DeviceGuard guard(ctx);
+    (void)hipDeviceSynchronize();
+    for (auto& slot : ctx->ring) {
+        if (slot.ev) (void)hipEventDestroy(slot.ev);
+        if (slot.host) (void)hipHostFree(slot.host);
+    }
+    if (ctx->ws) (void)hipFree(ctx->ws);
+    if (ctx->d_flags) (void)hipFree(ctx->d_flags);
+    if (ctx->h_flags) (void)hipHostFree(ctx->h_flags);
+    delete ctx;
+    return ATOMO_OK;
+}
+
+int atomo_reserve(atomo_ctx* ctx, size_t bytes)
+{
+    if (!ctx) return ATOMO_EINVAL;
+    DeviceGuard guard(ctx);
+    if (!guard.ok) return ATOMO_EHIP;
+    return ensure_workspace(ctx, bytes);
+}
+
+int atomo_svd_workspace_bytes(const atomo_mat* mats, int n_mats, size_t* bytes)
+{
+    if (!mats || n_mats <= 0 || !bytes) return ATOMO_EINVAL;
+    return svd_workspace_bytes(mats, n_mats, bytes);
+}
+
+int atomo_entrywise_workspace_bytes(int64_t n, size_t* bytes)
+{
+    if (n <= 0 || n >= ((int64_t)1 << 32) || !bytes) return ATOMO_EINVAL;
+    *bytes = entrywise_workspace_bytes(n);
+    return ATOMO_OK;
+}
+
+int atomo_status(atomo_ctx* ctx, void* stream, int32_t* sweeps)
+{
+    if (!ctx) return ATOMO_EINVAL;
+    DeviceGuard guard(ctx);
+    if (!guard.ok) return ATOMO_EHIP;
+    hipStream_t st = (hipStream_t)stream;
+    ATOMO_HIP(ctx, hipMemcpyAsync(ctx->h_flags, ctx->d_flags, FLAG_COUNT * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    ATOMO_HIP(ctx, hipMemsetAsync(ctx->d_flags, 0, FLAG_COUNT * sizeof(int32_t), st));
+    ATOMO_HIP(ctx, hipStreamSynchronize(st));
+    if (sweeps) *sweeps = ctx->h_flags[FLAG_MAX_SWEEPS];
+    if (ctx->h_flags[FLAG_CAPACITY]) return ATOMO_ECAPACITY;
+    if (ctx->h_flags[FLAG_NOCONV]) return ATOMO_ENOCONV;
+    return ATOMO_OK;
+}
+
+int atomo_last_hip_error(const atomo_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
+
+const char* atomo_strerror(int status)
+{
+    switch (status) {
+        case ATOMO_OK: return "ok";
+        case ATOMO_EINVAL: return "invalid argument";
+        case ATOMO_ECAPACITY: return "a message kept more atoms than its capacity";
+        case ATOMO_ENOCONV: return "Jacobi SVD reached the sweep limit";
+        case ATOMO_EHIP: return "HIP runtime error";
+        case ATOMO_ENOMEM: return "out of device memory";
+        default: return "unknown status";
+    }
+}
+
+int atomo_probabilities(atomo_ctx* ctx, const float* lambda, const int64_t* offsets, int n_seg, double s, float* p,
+                        void* stream)
+{
+    if (!ctx || !offsets || n_seg < 0 || bad_budget(s)) return ATOMO_EINVAL;
+    if (n_seg == 0) return ATOMO_OK;
+    if (offsets[0] < 0) return ATOMO_EINVAL;
+    for (int k = 0; k < n_seg; ++k) {
+        if (offsets[k + 1] < offsets[k]) return ATOMO_EINVAL;
+        if (offsets[k + 1] - offsets[k] >= ((int64_t)1 << 32)) return ATOMO_EINVAL;
+    }
+    if (offsets[n_seg] == offsets[0]) return ATOMO_OK;
+    if (!lambda || !p) return ATOMO_EINVAL;
+    DeviceGuard guard(ctx);
+    if (!guard.ok) return ATOMO_EHIP;
+    return probabilities(ctx, lambda, offsets, n_seg, s, p, (hipStream_t)stream);
+}
+
+int atomo_encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint64_t seed, uint64_t stream_base,
+                     const atomo_svd_options* opt, const atomo_svd_msg* msgs, float* sigma_out, float* p_out,
+                     void* stream)
+{
+    if (!ctx || !mats || !msgs || n_mats <= 0 || bad_budget(s)) return ATOMO_EINVAL;
+    for (int j = 0; j < n_mats; ++j) {
+        const atomo_mat& a = mats[j];
+        const atomo_svd_msg& m = msgs[j];
+        if (!a.data || a.rows <= 0 || a.cols <= 0 || a.ld < a.cols) return ATOMO_EINVAL;
+        if ((a.rows < a.cols ? a.rows : a.cols) > 2048) return ATOMO_EINVAL;
+        if (m.rows != a.rows || m.cols != a.cols || m.capacity < 1) return ATOMO_EINVAL;
+        if (!m.count || !m.idx || !m.w || !m.U || !m.V) return ATOMO_EINVAL;
+    }
+    if (opt && (opt->max_sweeps < 1 || !(opt->stop_cosine > 0.0f))) return ATOMO_EINVAL;
+    DeviceGuard guard(ctx);
+    if (!guard.ok) return ATOMO_EHIP;
+    return encode_svd(ctx, mats, n_mats, s, seed, stream_base, opt, msgs, sigma_out, p_out, (hipStream_t)stream);
+}
+
+int atomo_encode_entrywise(atomo_ctx* ctx, const float* g, double s, uint64_t seed, uint64_t stream_id,
+                           const atomo_ew_msg* msg, float* p_out, void* stream)
+{
+    if (!ctx || !g || !msg || bad_budget(s)) return ATOMO_EINVAL;
+    if (msg->n <= 0 || msg->n >= ((int64_t)1 << 32) || msg->capacity < 1) return ATOMO_EINVAL;
+    if (!msg->count || !msg->idx || !msg->val) return ATOMO_EINVAL;
+    DeviceGuard guard(ctx);
+    if (!guard.ok) return ATOMO_EHIP;
+    return encode_entrywise(ctx, g, s, seed, stream_id, msg, p_out, (hipStream_t)stream);
+}
+
+int atomo_decode_svd_batch(atomo_ctx* ctx, const atomo_svd_msg* msgs, const int32_t* first, int n_out, float scale,
+                           float* const* outs, const int64_t* lds, void* stream)
+{
+    if (!ctx || !first || !outs || !lds || n_out <= 0) return ATOMO_EINVAL;
+    if (first[0] != 0) return ATOMO_EINVAL;
+    for (int o = 0; o < n_out; ++o) {
+        if (first[o + 1] <= first[o] || !outs[o]) return ATOMO_EINVAL;
+        if (!msgs) return ATOMO_EINVAL;
+        const atomo_svd_msg& m0 = msgs[first[o]];
+        if (m0.rows <= 0 || m0.cols <= 0 || lds[o] < m0.cols) return ATOMO_EINVAL;
+        for (int k = first[o]; k < first[o + 1]; ++k) {
+            const atomo_svd_msg& m = msgs[k];
+            if (m.rows != m0.rows || m.cols != m0.cols || m.capacity < 1) return ATOMO_EINVAL;
+            if (!m.count || !m.idx || !m.w || !m.U || !m.V) return ATOMO_EINVAL;
+        }
+    }
+    DeviceGuard guard(ctx);
+    if (!guard.ok) return ATOMO_EHIP;
+    return decode_svd_batch(ctx, msgs, first, n_out, scale, outs, lds, (hipStream_t)stream);
+}
+
+int atomo_decode(atomo_ctx* ctx, int kind, const void* msgs, int n_msgs, float scale, float* out, int64_t ld,
+                 void* stream)
+{
+    if (!ctx || !msgs || n_msgs <= 0 || !out) return ATOMO_EINVAL;
+    if (kind == ATOMO_KIND_SVD) {
+        const int32_t first[2] = {0, n_msgs};
+        float* const outs[1] = {out};
+        const int64_t lds[1] = {ld};
+        return atomo_decode_svd_batch(ctx, (const atomo_svd_msg*)msgs, first, 1, scale, outs, lds, stream);
+    }
+    if (kind == ATOMO_KIND_ENTRYWISE) {
+        const atomo_ew_msg* m = (const atomo_ew_msg*)msgs;
+        for (int k = 0; k < n_msgs; ++k) {
+            if (m[k].n != m[0].n || m[k].n <= 0 || m[k].n >= ((int64_t)1 << 32) || m[k].capacity < 1) return ATOMO_EINVAL;
+            if (!m[k].count || !m[k].idx || !m[k].val) return ATOMO_EINVAL;
+        }
+        DeviceGuard guard(ctx);
+        if (!guard.ok) return ATOMO_EHIP;
+        return decode_entrywise(ctx, m, n_msgs, scale, out, (hipStream_t)stream);
+    }
+    return ATOMO_EINVAL;
+}
+
+}  // extern "C"

@@ -1,0 +1,482 @@
+// Entry-wise ATOMO (Section 3 of arXiv 1806.04090 with the standard basis: lambda_i = g_i, a_i = e_i)
+// and the stand-alone Algorithm 1 entry point.
+//
+// Algorithm 1 without a sort.  The KKT appendix shows the optimum has the water-filling form
+// p_i = min(1, |lambda_i| / tau) with one level tau, tau = (sum of the uncapped |lambda|) / (s - n_s)
+// (eq. (p_i)).  With N(v) = #{|lambda| > v} and T(v) = sum of the |lambda| <= v, the function
+//     h(v) = v * (s - N(v)) - T(v)
+// is continuous, has h <= 0 below tau and h > 0 above it, and an element is capped (p = 1) exactly
+// when h(|lambda_i|) > 0 - the same test Algorithm 1 applies along the sorted order.  h can be
+// evaluated exactly at bucket edges from a histogram that stores, per bucket of the float bit
+// pattern, the element count and the sum of the 24-bit significands (all elements of a bucket share
+// their exponent, so this integer sum is exact and independent of summation order).  Three levels of
+// 11 + 10 + 10 key bits pin tau down to a single float value; each level is one pass over the data
+// that only histograms elements inside the bucket chosen by the previous level.  A level whose
+// chosen bucket holds zero or one element already decides everything and the remaining levels are
+// skipped on the device.
+//
+// Sampling and packing.  Coordinate i is kept iff u_i < p_i (Philox stream, float32 compare) and is
+// stored as (i, g_i / p_i) in ascending i: a counting pass per 4096-element chunk, a scan of the
+// chunk counts, and a writing pass that repeats the draws.
+#include <cmath>
+#include <vector>
+
+#include "atomo_internal.h"
+#include "block_algorithm1.h"
+
+namespace atomo {
+
+namespace {
+
+constexpr int L0_BITS = 11, L1_BITS = 10, L2_BITS = 10;
+constexpr int NBUCKET = 1 << L0_BITS;        // the largest level
+constexpr int HIST_WGS = 1024;
+constexpr int CHUNK = 4096;                  // elements per sampling workgroup (256 threads x 4 float4)
+
+struct EwState {
+    unsigned int cnt[3][NBUCKET];
+    unsigned long long sig[3][NBUCKET];
+    int resolved;                 // n_s and tail are final
+    unsigned int prefix;          // key bits chosen so far
+    unsigned long long n_above;   // elements above the chosen path
+    double sum_below;             // sum of the elements below the chosen path
+    unsigned long long n_s;       // final: number of capped elements
+    double tail;                  // final: sum of the uncapped magnitudes
+    double budget;                // final: s - n_s
+    unsigned long long total_kept;
+};
+
+
+// value of an integer significand sum for elements whose biased exponent is e
+__device__ inline double sig_value(unsigned long long sigsum, unsigned int e)
+{
+    return ldexp((double)sigsum, (int)(e == 0 ? 1 : e) - 150);
+}
+
+__device__ inline unsigned int significand(unsigned int key)
+{
+    const unsigned int e = key >> 23, mant = key & 0x7FFFFFu;
+    return e ? (mant | 0x800000u) : mant;
+}
+
+__global__ __launch_bounds__(256) void ew_clear(EwState* st)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < 3 * NBUCKET) { (&st->cnt[0][0])[i] = 0u; (&st->sig[0][0])[i] = 0ull; }
+    if (i == 0) {
+        st->resolved = 0; st->prefix = 0u; st->n_above = 0ull; st->sum_below = 0.0;
+        st->n_s = 0ull; st->tail = 0.0; st->budget = 0.0; st->total_kept = 0ull;
+    }
+}
+
+// Histogram of one level.  Elements are visited as float4 where the pointer allows.
+template <int LEVEL>
+__global__ __launch_bounds__(256) void ew_hist(const float* __restrict__ g, long long n, EwState* st)
+{
+    __shared__ unsigned int cnt[NBUCKET];
+    __shared__ unsigned long long sig[NBUCKET];
+    if (LEVEL > 0 && st->resolved) return;
+    constexpr int NB = LEVEL == 0 ? (1 << L0_BITS) : (1 << L1_BITS);
+    constexpr int SHIFT = LEVEL == 0 ? 20 : LEVEL == 1 ? 10 : 0;
+    const unsigned int prefix = LEVEL == 0 ? 0u : st->prefix;
+    for (int b = threadIdx.x; b < NB; b += 256) { cnt[b] = 0u; sig[b] = 0ull; }
+    __syncthreads();
+
+    auto visit = [&](float x) {
+        const unsigned int key = __float_as_uint(x) & 0x7FFFFFFFu;
+        if (LEVEL == 0) {
+            const unsigned int b = key >> SHIFT;
+            atomicAdd(&cnt[b], 1u);
+            atomicAdd(&sig[b], (unsigned long long)significand(key));
+        } else {
+            if ((key >> (SHIFT + (LEVEL == 1 ? L1_BITS : L2_BITS))) == prefix) {
+                const unsigned int b = (key >> SHIFT) & (NB - 1);
+                atomicAdd(&cnt[b], 1u);
+                atomicAdd(&sig[b], (unsigned long long)significand(key));
+            }
+        }
+    };
+
+    const bool vec = (((size_t)g) & 15) == 0;
+    const long long n4 = vec ? n / 4 : 0;
+    const long long stride = (long long)gridDim.x * 256;
+    for (long long q = (long long)blockIdx.x * 256 + threadIdx.x; q < n4; q += stride) {
+        const float4 x = ((const float4*)g)[q];
+        visit(x.x); visit(x.y); visit(x.z); visit(x.w);
+    }
+    for (long long i = n4 * 4 + (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) visit(g[i]);
+    __syncthreads();
+    for (int b = threadIdx.x; b < NB; b += 256) {
+        if (cnt[b]) {
+            atomicAdd(&st->cnt[LEVEL][b], cnt[b]);
+            atomicAdd(&st->sig[LEVEL][b], sig[b]);
+        }
+    }
+}
+
+// Picks the bucket of this level that contains the water level tau (single workgroup).
+template <int LEVEL>
+__global__ __launch_bounds__(256) void ew_solve(EwState* st, double s)
+{
+    __shared__ unsigned long long cpart[256];
+    __shared__ double spart[256];
+    __shared__ int best;
+    if (st->resolved) return;
+    constexpr int NB = LEVEL == 0 ? (1 << L0_BITS) : (1 << L1_BITS);
+    constexpr int SHIFT = LEVEL == 0 ? 20 : LEVEL == 1 ? 10 : 0;
+    constexpr int PER = NB / 256;
+    const int tid = threadIdx.x;
+    const unsigned int prefix = st->prefix;
+    const unsigned long long n_above0 = st->n_above;
+    const double sum_below0 = st->sum_below;
+    // exponent shared by every element on the chosen path (level 0: part of the bucket index)
+    auto bucket_exp = [&](int b) -> unsigned int {
+        const unsigned int key = ((LEVEL == 0 ? 0u : prefix << (LEVEL == 1 ? L1_BITS : L2_BITS)) | (unsigned int)b) << SHIFT;
+        return key >> 23;
+    };
+    auto bucket_lo = [&](int b) -> double {
+        const unsigned int key = ((LEVEL == 0 ? 0u : prefix << (LEVEL == 1 ? L1_BITS : L2_BITS)) | (unsigned int)b) << SHIFT;
+        return (double)__uint_as_float(key);
+    };
+
+    unsigned long long c_mine = 0ull;
+    double s_mine = 0.0;
+    for (int b = tid * PER; b < (tid + 1) * PER; ++b) {
+        c_mine += st->cnt[LEVEL][b];
+        s_mine += sig_value(st->sig[LEVEL][b], bucket_exp(b));
+    }
+    cpart[tid] = c_mine;
+    spart[tid] = s_mine;
+    if (tid == 0) best = 0;
+    __syncthreads();
+    unsigned long long c_after = 0ull;          // count in buckets owned by later threads
+    double s_before = 0.0;                      // sum in buckets owned by earlier threads
+    for (int t = tid + 1; t < 256; ++t) c_after += cpart[t];
+    for (int t = 0; t < tid; ++t) s_before += spart[t];
+
+    // h at the lower edge of bucket b:  lo_b * (s - #{elements in buckets >= b}) - sum(buckets < b)
+    {
+        unsigned long long at_or_above = c_after + c_mine;
+        double below = s_before;
+        int mine_best = -1;
+        for (int b = tid * PER; b < (tid + 1) * PER; ++b) {
+            const double h = bucket_lo(b) * (s - (double)(n_above0 + at_or_above)) - (sum_below0 + below);
+            if (h <= 0.0) mine_best = b;
+            at_or_above -= st->cnt[LEVEL][b];
+            below += sig_value(st->sig[LEVEL][b], bucket_exp(b));
+        }
+        if (mine_best >= 0) atomicMax(&best, mine_best);
+    }
+    __syncthreads();
+    if (tid == 0) {
+        const int bs = best;
+        unsigned long long above = 0ull;
+        double below = 0.0;
+        for (int b = bs + 1; b < NB; ++b) above += st->cnt[LEVEL][b];
+        for (int b = 0; b < bs; ++b) below += sig_value(st->sig[LEVEL][b], bucket_exp(b));
+        const unsigned long long n_above = n_above0 + above;
+        const double sum_below = sum_below0 + below;
+        const unsigned int c = st->cnt[LEVEL][bs];
+        const double bucket_sum = sig_value(st->sig[LEVEL][bs], bucket_exp(bs));
+        bool done = false;
+        unsigned long long n_s = n_above;
+        double tail = sum_below;
+        if (c == 0) {
+            done = true;
+        } else if (c == 1) {
+            const double x = bucket_sum;                       // the element itself
+            if (x * (s - (double)n_above) - sum_below - x > 0.0) n_s = n_above + 1;
+            else tail = sum_below + x;
+            done = true;
+        } else if (LEVEL == 2) {
+            tail = sum_below + bucket_sum;                     // equal elements at the level: uncapped
+            done = true;
+        }
+        if (done) {
+            st->n_s = n_s;
+            st->tail = tail;
+            st->budget = s - (double)n_s;
+            st->resolved = 1;
+        } else {
+            st->n_above = n_above;
+            st->sum_below = sum_below;
+            st->prefix = (LEVEL == 0 ? 0u : prefix << (LEVEL == 1 ? L1_BITS : L2_BITS)) | (unsigned int)bs;
+        }
+    }
+}
+
+__device__ inline float ew_probability(float x, double budget, double tail)
+{
+    const float a = fabsf(x);
+    if (a == 0.0f) return 0.0f;
+    if (!(tail > 0.0)) return 1.0f;
+    return fminf(1.0f, (float)((double)a * budget / tail));
+}
+
+// p for a large segment of atomo_probabilities
+__global__ __launch_bounds__(256) void ew_write_p(const float* __restrict__ lam, long long n, const EwState* st,
+                                                  float* __restrict__ p)
+{
+    const double budget = st->budget, tail = st->tail;
+    const long long stride = (long long)gridDim.x * 256;
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += stride)
+        p[i] = ew_probability(lam[i], budget, tail);
+}
+
+// Draws for the four coordinates 4q .. 4q+3 (one Philox block).  Returns the keep bits.
+__device__ inline unsigned int draw4(const float4 x, long long q, unsigned long long stream_id, unsigned long long seed,
+                                     double budget, double tail, float4& p)
+{
+    const u32x4 rnd = philox4x32_10((unsigned long long)q, stream_id, seed);
+    p.x = ew_probability(x.x, budget, tail);
+    p.y = ew_probability(x.y, budget, tail);
+    p.z = ew_probability(x.z, budget, tail);
+    p.w = ew_probability(x.w, budget, tail);
+    return (u01(rnd.x) < p.x ? 1u : 0u) | (u01(rnd.y) < p.y ? 2u : 0u) | (u01(rnd.z) < p.z ? 4u : 0u) |
+           (u01(rnd.w) < p.w ? 8u : 0u);
+}
+
+__device__ inline float4 load4(const float* g, long long q, long long n, bool vec)
+{
+    const long long i = q * 4;
+    if (vec && i + 3 < n) return ((const float4*)g)[q];
+    float4 x;
+    x.x = i < n ? g[i] : 0.0f;
+    x.y = i + 1 < n ? g[i + 1] : 0.0f;
+    x.z = i + 2 < n ? g[i + 2] : 0.0f;
+    x.w = i + 3 < n ? g[i + 3] : 0.0f;
+    return x;
+}
+
+// Kept coordinates per chunk.  Wave w of a chunk owns float4 [w*256, (w+1)*256) of the chunk, in four
+// iterations of 64 lanes: order inside a chunk is (wave, iteration, lane, component) = ascending index.
+__global__ __launch_bounds__(256) void ew_count(const float* __restrict__ g, long long n, const EwState* st,
+                                                unsigned long long stream_id, unsigned long long seed,
+                                                unsigned int* __restrict__ chunk_count)
+{
+    __shared__ unsigned int wsum[4];
+    const double budget = st->budget, tail = st->tail;
+    const bool vec = (((size_t)g) & 15) == 0;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const long long q0 = (long long)blockIdx.x * (CHUNK / 4) + wave * 256;
+    unsigned int kept = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const long long q = q0 + j * 64 + lane;
+        if (q * 4 < n) {
+            float4 p;
+            kept += __popc(draw4(load4(g, q, n, vec), q, stream_id, seed, budget, tail, p));
+        }
+    }
+    for (int o = 32; o > 0; o >>= 1) kept += __shfl_down(kept, o);
+    if (lane == 0) wsum[wave] = kept;
+    __syncthreads();
+    if (threadIdx.x == 0) chunk_count[blockIdx.x] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+}
+
+// Exclusive scan of the chunk counts (single workgroup).
+__global__ __launch_bounds__(256) void ew_scan(const unsigned int* __restrict__ chunk_count, long long n_chunks,
+                                               unsigned long long* __restrict__ chunk_base, EwState* st,
+                                               long long* count_out, long long capacity, int* flags)
+{
+    __shared__ unsigned long long part[256];
+    const int tid = threadIdx.x;
+    const long long per = (n_chunks + 255) / 256;
+    const long long lo = min(n_chunks, tid * per), hi = min(n_chunks, lo + per);
+    unsigned long long mine = 0ull;
+    for (long long c = lo; c < hi; ++c) mine += chunk_count[c];
+    part[tid] = mine;
+    __syncthreads();
+    unsigned long long base = 0ull;
+    for (int t = 0; t < tid; ++t) base += part[t];
+    for (long long c = lo; c < hi; ++c) {
+        chunk_base[c] = base;
+        base += chunk_count[c];
+    }
+    if (tid == 255) {
+        st->total_kept = base;
+        *count_out = (long long)base;
+        if ((long long)base > capacity) atomicMax(&flags[FLAG_CAPACITY], 1);
+    }
+}
+
+__global__ __launch_bounds__(256) void ew_write(const float* __restrict__ g, long long n, const EwState* st,
+                                                unsigned long long stream_id, unsigned long long seed,
+                                                const unsigned long long* __restrict__ chunk_base, long long capacity,
+                                                unsigned int* __restrict__ idx, float* __restrict__ val,
+                                                float* __restrict__ p_out)
+{
+    __shared__ unsigned int wsum[4];
+    const double budget = st->budget, tail = st->tail;
+    const bool vec = (((size_t)g) & 15) == 0;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const long long q0 = (long long)blockIdx.x * (CHUNK / 4) + wave * 256;
+    const unsigned long long lt_mask = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+
+    float4 xs[4], ps[4];
+    unsigned int bits[4], before[4];           // keep bits; kept coordinates of this wave ahead of this lane's float4
+    unsigned int running = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const long long q = q0 + j * 64 + lane;
+        bits[j] = 0;
+        if (q * 4 < n) {
+            xs[j] = load4(g, q, n, vec);
+            bits[j] = draw4(xs[j], q, stream_id, seed, budget, tail, ps[j]);
+            if (p_out) {
+                const long long i = q * 4;
+                if (i < n) p_out[i] = ps[j].x;
+                if (i + 1 < n) p_out[i + 1] = ps[j].y;
+                if (i + 2 < n) p_out[i + 2] = ps[j].z;
+                if (i + 3 < n) p_out[i + 3] = ps[j].w;
+            }
+        }
+        unsigned int ahead = 0, all = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const unsigned long long ballot = __ballot((bits[j] >> c) & 1u);
+            ahead += __popcll(ballot & lt_mask);
+            all += __popcll(ballot);
+        }
+        before[j] = running + ahead;
+        running += all;
+    }
+    if (lane == 0) wsum[wave] = running;
+    __syncthreads();
+    unsigned long long base = chunk_base[blockIdx.x];
+    for (int w = 0; w < wave; ++w) base += wsum[w];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        if (!bits[j]) continue;
+        const long long i0 = (q0 + j * 64 + lane) * 4;
+        unsigned long long pos = base + before[j];
+        const float xv[4] = {xs[j].x, xs[j].y, xs[j].z, xs[j].w};
+        const float pv[4] = {ps[j].x, ps[j].y, ps[j].z, ps[j].w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if ((bits[j] >> c) & 1u) {
+                if ((long long)pos < capacity) {
+                    idx[pos] = (unsigned int)(i0 + c);
+                    val[pos] = xv[c] / pv[c];
+                }
+                ++pos;
+            }
+        }
+    }
+}
+
+// Small segments of atomo_probabilities: sort-based Algorithm 1, one workgroup per segment.
+struct SmallSeg { long long begin; int n; int pad; };
+
+__global__ __launch_bounds__(256) void prob_small(const float* __restrict__ lam, const SmallSeg* segs, double s,
+                                                  float* __restrict__ p)
+{
+    __shared__ float key[ALG1_MAX];
+    __shared__ int src[ALG1_MAX];
+    __shared__ Alg1Scratch sc;
+    const SmallSeg seg = segs[blockIdx.x];
+    const int n = seg.n, tid = threadIdx.x;
+    if (n <= 0) return;
+    int P = 1;
+    while (P < n) P <<= 1;
+    for (int i = tid; i < P; i += 256) {
+        key[i] = i < n ? fabsf(lam[seg.begin + i]) : -1.0f;
+        src[i] = i;
+    }
+    __syncthreads();
+    block_sort_desc(key, src, P);
+    const int ns = block_algorithm1(key, n, s, sc);
+    const double tail_ns = sc.tail_ns;
+    for (int i = tid; i < n; i += 256) p[seg.begin + src[i]] = alg1_probability(key[i], i, ns, s, tail_ns);
+}
+
+struct EwLayout {
+    EwState* st;
+    unsigned int* chunk_count;
+    unsigned long long* chunk_base;
+    size_t bytes;
+};
+
+EwLayout ew_layout(void* base, int64_t n)
+{
+    Carver carve(base);
+    EwLayout l;
+    const size_t n_chunks = (size_t)((n + CHUNK - 1) / CHUNK);
+    l.st = carve.take<EwState>(1);
+    l.chunk_count = carve.take<unsigned int>(n_chunks);
+    l.chunk_base = carve.take<unsigned long long>(n_chunks);
+    l.bytes = carve.off;
+    return l;
+}
+
+// Enqueues the three histogram / solve levels; afterwards st->{n_s, tail, budget} are final.
+void enqueue_water_level(const float* x, int64_t n, double s, EwState* st, hipStream_t stream)
+{
+    const int wgs = (int)std::min<int64_t>(HIST_WGS, (n + 1023) / 1024);
+    ew_clear<<<(3 * NBUCKET + 255) / 256, 256, 0, stream>>>(st);
+    ew_hist<0><<<wgs, 256, 0, stream>>>(x, n, st);
+    ew_solve<0><<<1, 256, 0, stream>>>(st, s);
+    ew_hist<1><<<wgs, 256, 0, stream>>>(x, n, st);
+    ew_solve<1><<<1, 256, 0, stream>>>(st, s);
+    ew_hist<2><<<wgs, 256, 0, stream>>>(x, n, st);
+    ew_solve<2><<<1, 256, 0, stream>>>(st, s);
+}
+
+}  // namespace
+
+size_t entrywise_workspace_bytes(int64_t n) { return ew_layout(nullptr, n).bytes; }
+
+int encode_entrywise(atomo_ctx* ctx, const float* g, double s, uint64_t seed, uint64_t stream_id,
+                     const atomo_ew_msg* msg, float* p_out, hipStream_t stream)
+{
+    const int64_t n = msg->n;
+    int rc = ensure_workspace(ctx, entrywise_workspace_bytes(n));
+    if (rc != ATOMO_OK) return rc;
+    const EwLayout l = ew_layout(ctx->ws, n);
+    const long long n_chunks = (n + CHUNK - 1) / CHUNK;
+
+    enqueue_water_level(g, n, s, l.st, stream);
+    ew_count<<<(unsigned)n_chunks, 256, 0, stream>>>(g, n, l.st, stream_id, seed, l.chunk_count);
+    ew_scan<<<1, 256, 0, stream>>>(l.chunk_count, n_chunks, l.chunk_base, l.st, (long long*)msg->count,
+                                   (long long)msg->capacity, ctx->d_flags);
+    ew_write<<<(unsigned)n_chunks, 256, 0, stream>>>(g, n, l.st, stream_id, seed, l.chunk_base,
+                                                     (long long)msg->capacity, msg->idx, msg->val, p_out);
+    ATOMO_HIP(ctx, hipGetLastError());
+    return ATOMO_OK;
+}
+
+int probabilities(atomo_ctx* ctx, const float* lambda, const int64_t* offsets, int n_seg, double s, float* p,
+                  hipStream_t stream)
+{
+    std::vector<SmallSeg> small;
+    std::vector<int> large;
+    for (int k = 0; k < n_seg; ++k) {
+        const int64_t len = offsets[k + 1] - offsets[k];
+        if (len == 0) continue;
+        if (len <= ALG1_MAX) small.push_back(SmallSeg{(long long)offsets[k], (int)len, 0});
+        else large.push_back(k);
+    }
+    size_t need = align_up(small.size() * sizeof(SmallSeg), 256) + 256;
+    if (!large.empty()) need += align_up(sizeof(EwState), 256);
+    int rc = ensure_workspace(ctx, need);
+    if (rc != ATOMO_OK) return rc;
+    Carver carve(ctx->ws);
+    SmallSeg* d_small = carve.take<SmallSeg>(small.size());
+    EwState* st = large.empty() ? nullptr : carve.take<EwState>(1);
+    if (!small.empty()) {
+        rc = upload(ctx, d_small, small.data(), small.size() * sizeof(SmallSeg), stream);
+        if (rc != ATOMO_OK) return rc;
+        prob_small<<<(unsigned)small.size(), 256, 0, stream>>>(lambda, d_small, s, p);
+    }
+    for (int k : large) {
+        const int64_t len = offsets[k + 1] - offsets[k];
+        const float* x = lambda + offsets[k];
+        enqueue_water_level(x, len, s, st, stream);
+        const int wgs = (int)std::min<int64_t>(4096, (len + 255) / 256);
+        ew_write_p<<<wgs, 256, 0, stream>>>(x, len, st, p + offsets[k]);
+    }
+    ATOMO_HIP(ctx, hipGetLastError());
+    return ATOMO_OK;
+}
+
+}  // namespace atomo

@@ -1,0 +1,63 @@
+"""CPU-side checks of the C ABI: the library loads, exports what include/atomo.h declares, and the
+host-side argument validation answers without touching a GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_1806_04090_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "atomo.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(atomo_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = declared_symbols()
+    assert {"atomo_encode_svd", "atomo_encode_entrywise", "atomo_probabilities", "atomo_decode"} <= set(names)
+    L = binding.lib()
+    for name in names:
+        assert hasattr(L, name), name
+
+
+def test_strerror_and_null_arguments():
+    L = binding.lib()
+    assert L.atomo_strerror(0) == b"ok"
+    for code in (-1, -2, -3, -4, -5):
+        assert L.atomo_strerror(code) not in (b"ok", b"unknown status")
+    assert L.atomo_create(None, 0) == binding.ATOMO_EINVAL
+    assert L.atomo_destroy(None) == binding.ATOMO_EINVAL
+    assert L.atomo_reserve(None, 10) == binding.ATOMO_EINVAL
+    assert L.atomo_status(None, None, None) == binding.ATOMO_EINVAL
+    offs = (C.c_int64 * 2)(0, 4)
+    assert L.atomo_probabilities(None, None, offs, 1, 1.0, None, None) == binding.ATOMO_EINVAL
+    assert L.atomo_encode_svd(None, None, 1, 1.0, 0, 0, None, None, None, None, None) == binding.ATOMO_EINVAL
+    assert L.atomo_encode_entrywise(None, None, 1.0, 0, 0, None, None, None) == binding.ATOMO_EINVAL
+    assert L.atomo_decode(None, 0, None, 1, 1.0, None, 0, None) == binding.ATOMO_EINVAL
+
+
+def test_workspace_queries_are_host_only():
+    L = binding.lib()
+    mats = (binding.atomo_mat * 2)(binding.atomo_mat(512, 4608, 4608, None), binding.atomo_mat(64, 27, 27, None))
+    nbytes = C.c_size_t(0)
+    assert L.atomo_svd_workspace_bytes(mats, 2, C.byref(nbytes)) == 0
+    assert nbytes.value > 512 * (4608 + 512) * 4
+    bad = (binding.atomo_mat * 1)(binding.atomo_mat(4096, 4096, 4096, None))
+    assert L.atomo_svd_workspace_bytes(bad, 1, C.byref(nbytes)) == binding.ATOMO_EINVAL
+    assert L.atomo_entrywise_workspace_bytes(11_173_962, C.byref(nbytes)) == 0
+    assert nbytes.value > 70_000
+    assert L.atomo_entrywise_workspace_bytes(0, C.byref(nbytes)) == binding.ATOMO_EINVAL
+    assert L.atomo_entrywise_workspace_bytes(1 << 32, C.byref(nbytes)) == binding.ATOMO_EINVAL
+
+
+def test_no_fallback_without_a_gpu():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is visible")
+    with pytest.raises(RuntimeError):
+        binding.Context(0)
