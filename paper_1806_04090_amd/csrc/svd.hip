@@ -40,7 +40,12 @@ constexpr int MAX_R = ALG1_MAX;
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-enum { ST_DONE_AT = 0, ST_SWEEPS = 1, ST_OFFMAX = 2, ST_ARRIVE = 3, ST_WORDS = 4 };
+enum { ST_DONE_AT = 0, ST_SWEEPS = 1, ST_OFFMAX = 2, ST_ARRIVE = 3, ST_SCALE = 4, ST_SCALE_NEXT = 5, ST_WORDS = 8 };
+
+// Rows whose squared norm is below ZERO_REL * (largest squared row norm of the matrix) are rounding
+// residue of the fp32 updates (about 32 ulp of the dominant rows): their directions carry no
+// information, so they neither count in the convergence test nor get rotated among themselves.
+constexpr float ZERO_REL = 3.64e-12f;       // (32 * 2^-24)^2
 
 struct SvdMat {
     float* W;                // rows_alloc x ldw
@@ -175,7 +180,7 @@ __global__ __launch_bounds__(256) void svd_eig(const SvdMat* mats, const Work* w
     __shared__ int rp[32], rq[32];
     __shared__ float ev[PR];
     __shared__ int dest[PR];
-    __shared__ float red[4];
+    __shared__ float red[8];
     __shared__ int rotated;
 
     const Work wk = work[blockIdx.x];
@@ -209,22 +214,31 @@ __global__ __launch_bounds__(256) void svd_eig(const SvdMat* mats, const Work* w
     }
     __syncthreads();
 
-    // 2. largest |cos| between two rows of the pair, before rotating
+    // 2. largest |cos| between two rows of the pair, before rotating (rows at the rounding floor
+    //    are measured against the floor instead of their own length), and the largest squared norm
+    const float z2 = ZERO_REL * __int_as_float(m.state[ST_SCALE]);
     {
-        float mx = 0.0f;
+        float mx = 0.0f, dmax = 0.0f;
         for (int e = tid; e < QSZ; e += 256) {
             const int i = e >> 6, j = e & 63;
             if (i < j) {
                 const float dii = A[i * LDA + i], djj = A[j * LDA + j];
-                if (dii > 0.0f && djj > 0.0f) mx = fmaxf(mx, fabsf(A[i * LDA + j]) * rsqrtf(dii) * rsqrtf(djj));
+                if (dii > 0.0f && djj > 0.0f) mx = fmaxf(mx, fabsf(A[i * LDA + j]) / fmaxf(sqrtf(dii * djj), z2));
+            } else if (i == j) {
+                dmax = fmaxf(dmax, A[i * LDA + i]);
             }
         }
-        for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_down(mx, o));
-        if (lane == 0) red[wave] = mx;
+        for (int o = 32; o > 0; o >>= 1) {
+            mx = fmaxf(mx, __shfl_down(mx, o));
+            dmax = fmaxf(dmax, __shfl_down(dmax, o));
+        }
+        if (lane == 0) { red[wave] = mx; red[4 + wave] = dmax; }
         __syncthreads();
         if (tid == 0) {
             mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+            dmax = fmaxf(fmaxf(red[4], red[5]), fmaxf(red[6], red[7]));
             atomicMax((unsigned int*)&m.state[ST_OFFMAX], __float_as_uint(mx));
+            atomicMax((unsigned int*)&m.state[ST_SCALE_NEXT], __float_as_uint(dmax));
         }
     }
 
@@ -239,7 +253,7 @@ __global__ __launch_bounds__(256) void svd_eig(const SvdMat* mats, const Work* w
                 const int p = a < b ? a : b, q = a < b ? b : a;
                 const float app = A[p * LDA + p], aqq = A[q * LDA + q], apq = A[p * LDA + q];
                 float c = 1.0f, s = 0.0f;
-                if (apq != 0.0f && fabsf(apq) > 1e-7f * sqrtf(fabsf(app * aqq))) {
+                if (apq != 0.0f && fabsf(apq) > 1e-7f * fmaxf(sqrtf(fabsf(app * aqq)), z2)) {
                     const float zeta = (aqq - app) / (2.0f * apq);
                     const float tt = copysignf(1.0f, zeta) / (fabsf(zeta) + sqrtf(1.0f + zeta * zeta));
                     c = 1.0f / sqrtf(1.0f + tt * tt);
@@ -353,6 +367,8 @@ __global__ __launch_bounds__(256) void svd_eig(const SvdMat* mats, const Work* w
             else if (sweeps >= max_sweeps) atomicMax(&flags[FLAG_NOCONV], 1);
             m.state[ST_OFFMAX] = 0;
             m.state[ST_ARRIVE] = 0;
+            const unsigned int grown = atomicAdd((unsigned int*)&m.state[ST_SCALE_NEXT], 0u);
+            if (grown > (unsigned int)m.state[ST_SCALE]) m.state[ST_SCALE] = (int)grown;
         }
     }
 }
@@ -409,7 +425,7 @@ __global__ __launch_bounds__(256) void svd_update(const SvdMat* mats, const Work
 // ------------------------------------------------------------------------------------------------
 // finalise: singular values, Algorithm 1, Bernoulli draws, message
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void svd_norms(const SvdMat* mats, const Work* work)
+__global__ __launch_bounds__(256) void svd_norms(const SvdMat* mats, const Work* work, int init)
 {
     const Work wk = work[blockIdx.x];
     const SvdMat m = mats[wk.mat];
@@ -423,7 +439,14 @@ __global__ __launch_bounds__(256) void svd_norms(const SvdMat* mats, const Work*
         sum += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
     }
     for (int o = 32; o > 0; o >>= 1) sum += __shfl_down(sum, o);
-    if (lane == 0) m.sig_raw[row] = row < m.r ? sqrtf(sum) : 0.0f;
+    if (lane == 0) {
+        if (init) {                                                  // before the first sweep: scale of the matrix
+            atomicMax((unsigned int*)&m.state[ST_SCALE], __float_as_uint(sum));
+            atomicMax((unsigned int*)&m.state[ST_SCALE_NEXT], __float_as_uint(sum));
+        } else {
+            m.sig_raw[row] = row < m.r ? sqrtf(sum) : 0.0f;
+        }
+    }
 }
 
 // One workgroup per matrix.  Sorts sigma (descending), runs Algorithm 1 on it, draws the Bernoulli
@@ -626,6 +649,7 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     if (rc != ATOMO_OK) return rc;
 
     svd_prepare<<<(unsigned)plan.prep.size(), 256, 0, stream>>>(d_mats, d_work + o_prep);
+    svd_norms<<<(unsigned)plan.norms.size(), 256, 0, stream>>>(d_mats, d_work + o_norms, 1);
     const int n_steps = max_sweeps * plan.max_R;
     for (int step = 0; step < n_steps; ++step) {
         svd_gram<<<(unsigned)plan.gram.size(), 256, 0, stream>>>(d_mats, d_work + o_gram, step, max_sweeps);
@@ -633,7 +657,7 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
                                                                ctx->d_flags);
         svd_update<<<(unsigned)plan.upd.size(), 256, 0, stream>>>(d_mats, d_work + o_upd, step, max_sweeps);
     }
-    svd_norms<<<(unsigned)plan.norms.size(), 256, 0, stream>>>(d_mats, d_work + o_norms);
+    svd_norms<<<(unsigned)plan.norms.size(), 256, 0, stream>>>(d_mats, d_work + o_norms, 0);
     svd_select<<<(unsigned)n_mats, 256, 0, stream>>>(d_mats, s, (unsigned long long)seed, ctx->d_flags);
     svd_pack<<<(unsigned)plan.pack.size(), 256, 0, stream>>>(d_mats, d_work + o_pack);
     ATOMO_HIP(ctx, hipGetLastError());
