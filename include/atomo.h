@@ -94,6 +94,9 @@ typedef struct atomo_svd_options {
     int32_t max_sweeps;              /* default 12                                                   */
     float   stop_cosine;             /* default 1e-4: stop after the first sweep whose largest       */
                                      /* |<a_i,a_j>| / (|a_i||a_j|), measured before rotating, is below */
+    int32_t max_inner_sweeps;        /* default 1 (0 = default): most Jacobi sweeps per 64x64 block-pair problem */
+    float   inner_reduction;         /* default 0.01 (0 = default): a block-pair problem stops sweeping once */
+                                     /* its largest |cos| is below inner_reduction x the value it started at */
 } atomo_svd_options;
 
 /* -------- context ------------------------------------------------------------------------------ */
@@ -113,6 +116,15 @@ int atomo_entrywise_workspace_bytes(int64_t n, size_t* bytes /*host*/);
  * largest number of Jacobi sweeps any matrix of the last atomo_encode_svd took. */
 int atomo_status(atomo_ctx* ctx, void* stream, int32_t* sweeps /*host, optional*/);
 int atomo_last_hip_error(const atomo_ctx* ctx);
+
+/* Work counters as read by the most recent atomo_status call (host-side only): how many 64x64
+ * block-pair eigenproblems the Jacobi SVD solved since the status call before it, and how many
+ * inner Jacobi sweeps those took in total. */
+int atomo_last_counters(const atomo_ctx* ctx, int32_t* pair_visits /*host*/, int32_t* inner_sweeps /*host*/);
+
+/* Waits for `stream`, then copies the number of Jacobi sweeps each matrix of the last
+ * atomo_encode_svd took into sweeps[0 .. n_mats) (HOST).  n_mats must match that call. */
+int atomo_svd_sweeps(atomo_ctx* ctx, void* stream, int32_t* sweeps /*host*/, int n_mats);
 const char* atomo_strerror(int status);
 
 /* -------- the method --------------------------------------------------------------------------- */
@@ -176,6 +188,25 @@ int atomo_decode(atomo_ctx* ctx, int kind, const void* msgs, int n_msgs, float s
  */
 int atomo_decode_svd_batch(atomo_ctx* ctx, const atomo_svd_msg* msgs, const int32_t* first, int n_out,
                            float scale, float* const* outs, const int64_t* lds, void* stream);
+
+/* -------- measurement -------------------------------------------------------------------------- */
+
+/* Kernel classes whose GPU time can be measured with HIP events (for benchmarks; not part of the
+ * method).  While profiling is on, every launch of these kernels is bracketed by two events on the
+ * caller's stream, which costs a few microseconds per launch. */
+enum {
+    ATOMO_K_SVD_PREPARE = 0, ATOMO_K_SVD_GRAM, ATOMO_K_SVD_EIG, ATOMO_K_SVD_UPDATE, ATOMO_K_SVD_FINALIZE,
+    ATOMO_K_DECODE_SVD, ATOMO_K_EW_HIST, ATOMO_K_EW_SOLVE, ATOMO_K_EW_SAMPLE, ATOMO_K_EW_DECODE,
+    ATOMO_K_COUNT
+};
+
+/* Switches event bracketing on (enable != 0) or off and discards what was collected. */
+int atomo_profile_enable(atomo_ctx* ctx, int enable);
+
+/* Waits for the recorded events, then adds to total_ms[k] / launches[k] (HOST arrays of
+ * ATOMO_K_COUNT entries, caller-initialised) the GPU time and the number of bracketed launches of
+ * each kernel class since the last read. */
+int atomo_profile_read(atomo_ctx* ctx, double* total_ms, int64_t* launches);
 
 #ifdef __cplusplus
 }

@@ -42,7 +42,8 @@ class atomo_ew_msg(C.Structure):
 
 
 class atomo_svd_options(C.Structure):
-    _fields_ = [("max_sweeps", C.c_int32), ("stop_cosine", C.c_float)]
+    _fields_ = [("max_sweeps", C.c_int32), ("stop_cosine", C.c_float), ("max_inner_sweeps", C.c_int32),
+                ("inner_reduction", C.c_float)]
 
 
 _lib = None
@@ -74,7 +75,11 @@ def lib() -> C.CDLL:
         L.atomo_decode.argtypes = [vp, C.c_int, vp, C.c_int, C.c_float, vp, C.c_int64, vp]
         L.atomo_decode_svd_batch.argtypes = [vp, C.POINTER(atomo_svd_msg), C.POINTER(C.c_int32), C.c_int, C.c_float,
                                              C.POINTER(vp), C.POINTER(C.c_int64), vp]
-        for name in ("atomo_create", "atomo_destroy", "atomo_reserve", "atomo_svd_workspace_bytes",
+        L.atomo_svd_sweeps.argtypes = [vp, vp, C.POINTER(C.c_int32), C.c_int]
+        L.atomo_last_counters.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+        L.atomo_profile_enable.argtypes = [vp, C.c_int]
+        L.atomo_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+        for name in ("atomo_last_counters", "atomo_svd_sweeps", "atomo_profile_enable", "atomo_profile_read", "atomo_create", "atomo_destroy", "atomo_reserve", "atomo_svd_workspace_bytes",
                      "atomo_entrywise_workspace_bytes", "atomo_status", "atomo_last_hip_error", "atomo_probabilities",
                      "atomo_encode_svd", "atomo_encode_entrywise", "atomo_decode", "atomo_decode_svd_batch"):
             getattr(L, name).restype = C.c_int
@@ -190,6 +195,32 @@ class Context:
     def reserve(self, nbytes: int):
         _check(lib().atomo_reserve(self._h, nbytes), "atomo_reserve")
 
+    KERNEL_CLASSES = ("svd_prepare", "svd_gram", "svd_eig", "svd_update", "svd_finalize", "decode_svd",
+                      "ew_hist", "ew_solve", "ew_sample", "ew_decode")
+
+    def profile_enable(self, enable: bool):
+        _check(lib().atomo_profile_enable(self._h, 1 if enable else 0), "atomo_profile_enable")
+
+    def profile_read(self) -> dict:
+        """{kernel class: (total GPU ms, bracketed launches)} since the last read (HIP events)."""
+        n = len(self.KERNEL_CLASSES)
+        ms = (C.c_double * n)()
+        cnt = (C.c_int64 * n)()
+        _check(lib().atomo_profile_read(self._h, ms, cnt), "atomo_profile_read")
+        return {name: (ms[i], cnt[i]) for i, name in enumerate(self.KERNEL_CLASSES)}
+
+    def last_counters(self):
+        """(block-pair eigenproblems solved, inner Jacobi sweeps taken) as of the last status() call."""
+        a, b = C.c_int32(0), C.c_int32(0)
+        _check(lib().atomo_last_counters(self._h, C.byref(a), C.byref(b)), "atomo_last_counters")
+        return int(a.value), int(b.value)
+
+    def svd_sweeps(self, n_mats: int, stream: Optional[torch.cuda.Stream] = None) -> List[int]:
+        """Jacobi sweeps each matrix of the last atomo_encode_svd took (waits for the stream)."""
+        out = (C.c_int32 * n_mats)()
+        _check(lib().atomo_svd_sweeps(self._h, _stream_handle(stream), out, n_mats), "atomo_svd_sweeps")
+        return list(out)
+
     def status(self, stream: Optional[torch.cuda.Stream] = None):
         """Waits for the stream; returns (status, largest Jacobi sweep count of the last SVD encode)."""
         sweeps = C.c_int32(0)
@@ -213,7 +244,8 @@ def atomo_probabilities(ctx: Context, lam: torch.Tensor, offsets: Sequence[int],
 def atomo_encode_svd(ctx: Context, mats: Sequence[torch.Tensor], s: float, seed: int, stream_base: int = 0,
                      msgs: Optional[List[SvdMessage]] = None, sigma_out: Optional[torch.Tensor] = None,
                      p_out: Optional[torch.Tensor] = None, max_sweeps: Optional[int] = None,
-                     stop_cosine: Optional[float] = None, stream=None) -> List[SvdMessage]:
+                     stop_cosine: Optional[float] = None, max_inner_sweeps: int = 0, inner_reduction: float = 0.0,
+                     stream=None) -> List[SvdMessage]:
     """Spectral-ATOMO encode of a list of 2-D float32 CUDA tensors (row stride = tensor stride)."""
     n = len(mats)
     c_mats = (atomo_mat * n)()
@@ -226,9 +258,10 @@ def atomo_encode_svd(ctx: Context, mats: Sequence[torch.Tensor], s: float, seed:
         msgs = [alloc_svd_message(g.shape[0], g.shape[1], default_capacity(s, min(g.shape)), g.device) for g in mats]
     c_msgs = (atomo_svd_msg * n)(*[m.c_struct() for m in msgs])
     opt = None
-    if max_sweeps is not None or stop_cosine is not None:
+    if max_sweeps is not None or stop_cosine is not None or max_inner_sweeps or inner_reduction:
         opt = C.byref(atomo_svd_options(12 if max_sweeps is None else max_sweeps,
-                                        1e-4 if stop_cosine is None else stop_cosine))
+                                        1e-4 if stop_cosine is None else stop_cosine,
+                                        max_inner_sweeps, inner_reduction))
     _check(lib().atomo_encode_svd(ctx._h, c_mats, n, float(s), int(seed) & (2 ** 64 - 1),
                                   int(stream_base) & (2 ** 64 - 1), opt, c_msgs,
                                   None if sigma_out is None else sigma_out.data_ptr(),

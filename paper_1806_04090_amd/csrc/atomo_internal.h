@@ -5,6 +5,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "../../include/atomo.h"
 
 namespace atomo {
@@ -14,7 +16,7 @@ namespace atomo {
 // ---------------------------------------------------------------------------------------------
 
 // Device-side latched flags (int32 each).
-enum { FLAG_CAPACITY = 0, FLAG_NOCONV = 1, FLAG_MAX_SWEEPS = 2, FLAG_COUNT = 8 };
+enum { FLAG_CAPACITY = 0, FLAG_NOCONV = 1, FLAG_MAX_SWEEPS = 2, FLAG_EIG_VISITS = 3, FLAG_EIG_INNER = 4, FLAG_COUNT = 8 };
 
 struct StageSlot {
     void* host = nullptr;        // pinned
@@ -34,6 +36,12 @@ struct atomo_ctx {
     int last_hip = 0;
     atomo::StageSlot ring[8];
     int ring_next = 0;
+    std::vector<int*> svd_state;         // per matrix of the last SVD encode: device state words
+    // optional event bracketing of kernel launches (atomo_profile_*)
+    bool profiling = false;
+    std::vector<hipEvent_t> ev_pool;     // pairs: [2k] start, [2k+1] stop
+    std::vector<int> ev_kind;            // kernel class of pair k
+    size_t ev_used = 0;                  // pairs in use
 };
 
 namespace atomo {
@@ -53,6 +61,32 @@ int ensure_workspace(atomo_ctx* ctx, size_t bytes);
 // Copies `bytes` of host data to device address `dst` on `stream` through a pinned staging slot,
 // so the caller's host buffer may be reused as soon as this returns.
 int upload(atomo_ctx* ctx, void* dst, const void* src, size_t bytes, hipStream_t stream);
+
+// Brackets the launches issued during its lifetime with two events when profiling is on.
+struct ProfScope {
+    atomo_ctx* ctx;
+    hipStream_t stream;
+    hipEvent_t stop = nullptr;
+    ProfScope(atomo_ctx* c, int kind, hipStream_t s) : ctx(c), stream(s)
+    {
+        if (!ctx->profiling) return;
+        if (ctx->ev_used * 2 >= ctx->ev_pool.size()) {
+            hipEvent_t a = nullptr, b = nullptr;
+            if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return;
+            ctx->ev_pool.push_back(a);
+            ctx->ev_pool.push_back(b);
+            ctx->ev_kind.push_back(kind);
+        }
+        ctx->ev_kind[ctx->ev_used] = kind;
+        (void)hipEventRecord(ctx->ev_pool[ctx->ev_used * 2], stream);
+        stop = ctx->ev_pool[ctx->ev_used * 2 + 1];
+        ++ctx->ev_used;
+    }
+    ~ProfScope()
+    {
+        if (stop) (void)hipEventRecord(stop, stream);
+    }
+};
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -108,6 +142,8 @@ int svd_workspace_bytes(const atomo_mat* mats, int n_mats, size_t* bytes);
 int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint64_t seed, uint64_t stream_base,
                const atomo_svd_options* opt, const atomo_svd_msg* msgs, float* sigma_out, float* p_out,
                hipStream_t stream);
+
+int svd_sweeps(atomo_ctx* ctx, hipStream_t stream, int32_t* sweeps, int n_mats);
 
 size_t entrywise_workspace_bytes(int64_t n);
 int encode_entrywise(atomo_ctx* ctx, const float* g, double s, uint64_t seed, uint64_t stream_id,

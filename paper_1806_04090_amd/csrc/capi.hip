@@ -112,6 +112,7 @@ int atomo_destroy(atomo_ctx* ctx)
         if (slot.ev) (void)hipEventDestroy(slot.ev);
         if (slot.host) (void)hipHostFree(slot.host);
     }
+    for (hipEvent_t e : ctx->ev_pool) (void)hipEventDestroy(e);
     if (ctx->ws) (void)hipFree(ctx->ws);
     if (ctx->d_flags) (void)hipFree(ctx->d_flags);
     if (ctx->h_flags) (void)hipHostFree(ctx->h_flags);
@@ -155,7 +156,53 @@ int atomo_status(atomo_ctx* ctx, void* stream, int32_t* sweeps)
     return ATOMO_OK;
 }
 
+int atomo_svd_sweeps(atomo_ctx* ctx, void* stream, int32_t* sweeps, int n_mats)
+{
+    if (!ctx || !sweeps || n_mats <= 0) return ATOMO_EINVAL;
+    DeviceGuard guard(ctx);
+    if (!guard.ok) return ATOMO_EHIP;
+    return svd_sweeps(ctx, (hipStream_t)stream, sweeps, n_mats);
+}
+
+int atomo_profile_enable(atomo_ctx* ctx, int enable)
+{
+    if (!ctx) return ATOMO_EINVAL;
+    DeviceGuard guard(ctx);
+    if (!guard.ok) return ATOMO_EHIP;
+    ATOMO_HIP(ctx, hipDeviceSynchronize());
+    ctx->profiling = enable != 0;
+    ctx->ev_used = 0;
+    return ATOMO_OK;
+}
+
+int atomo_profile_read(atomo_ctx* ctx, double* total_ms, int64_t* launches)
+{
+    if (!ctx || !total_ms || !launches) return ATOMO_EINVAL;
+    DeviceGuard guard(ctx);
+    if (!guard.ok) return ATOMO_EHIP;
+    for (size_t k = 0; k < ctx->ev_used; ++k) {
+        ATOMO_HIP(ctx, hipEventSynchronize(ctx->ev_pool[2 * k + 1]));
+        float ms = 0.0f;
+        ATOMO_HIP(ctx, hipEventElapsedTime(&ms, ctx->ev_pool[2 * k], ctx->ev_pool[2 * k + 1]));
+        const int kind = ctx->ev_kind[k];
+        if (kind >= 0 && kind < ATOMO_K_COUNT) {
+            total_ms[kind] += (double)ms;
+            launches[kind] += 1;
+        }
+    }
+    ctx->ev_used = 0;
+    return ATOMO_OK;
+}
+
 int atomo_last_hip_error(const atomo_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
+
+int atomo_last_counters(const atomo_ctx* ctx, int32_t* pair_visits, int32_t* inner_sweeps)
+{
+    if (!ctx || !pair_visits || !inner_sweeps) return ATOMO_EINVAL;
+    *pair_visits = ctx->h_flags[FLAG_EIG_VISITS];
+    *inner_sweeps = ctx->h_flags[FLAG_EIG_INNER];
+    return ATOMO_OK;
+}
 
 const char* atomo_strerror(int status)
 {

@@ -154,7 +154,10 @@ int decode_svd_batch(atomo_ctx* ctx, const atomo_svd_msg* msgs, const int32_t* f
     if ((rc = upload(ctx, d_msgs, hm.data(), hm.size() * sizeof(DecMsg), stream)) != ATOMO_OK) return rc;
     if ((rc = upload(ctx, d_outs, ho.data(), ho.size() * sizeof(DecOut), stream)) != ATOMO_OK) return rc;
     if ((rc = upload(ctx, d_work, hw.data(), hw.size() * sizeof(DecWork), stream)) != ATOMO_OK) return rc;
-    decode_svd_tiles<<<(unsigned)hw.size(), 256, 0, stream>>>(d_outs, d_msgs, d_work, scale);
+    {
+        ProfScope ps(ctx, ATOMO_K_DECODE_SVD, stream);
+        decode_svd_tiles<<<(unsigned)hw.size(), 256, 0, stream>>>(d_outs, d_msgs, d_work, scale);
+    }
     ATOMO_HIP(ctx, hipGetLastError());
     return ATOMO_OK;
 }
@@ -174,9 +177,12 @@ int decode_entrywise(atomo_ctx* ctx, const atomo_ew_msg* msgs, int n_msgs, float
     EwDecMsg* d_msgs = (EwDecMsg*)ctx->ws;
     if ((rc = upload(ctx, d_msgs, hm.data(), hm.size() * sizeof(EwDecMsg), stream)) != ATOMO_OK) return rc;
     const int fill_wgs = (int)std::min<int64_t>(2048, (n / 4 + 255) / 256 + 1);
-    fill_zero<<<fill_wgs, 256, 0, stream>>>(out, n);
     const int sc_wgs = (int)std::min<int64_t>(1024, (max_cap + 255) / 256);
-    scatter_entrywise<<<dim3(sc_wgs, n_msgs), 256, 0, stream>>>(d_msgs, n_msgs, scale, out, n);
+    {
+        ProfScope ps(ctx, ATOMO_K_EW_DECODE, stream);
+        fill_zero<<<fill_wgs, 256, 0, stream>>>(out, n);
+        scatter_entrywise<<<dim3(sc_wgs, n_msgs), 256, 0, stream>>>(d_msgs, n_msgs, scale, out, n);
+    }
     ATOMO_HIP(ctx, hipGetLastError());
     return ATOMO_OK;
 }

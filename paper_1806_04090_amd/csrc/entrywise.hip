@@ -410,16 +410,16 @@ EwLayout ew_layout(void* base, int64_t n)
 }
 
 // Enqueues the three histogram / solve levels; afterwards st->{n_s, tail, budget} are final.
-void enqueue_water_level(const float* x, int64_t n, double s, EwState* st, hipStream_t stream)
+void enqueue_water_level(atomo_ctx* ctx, const float* x, int64_t n, double s, EwState* st, hipStream_t stream)
 {
     const int wgs = (int)std::min<int64_t>(HIST_WGS, (n + 1023) / 1024);
-    ew_clear<<<(3 * NBUCKET + 255) / 256, 256, 0, stream>>>(st);
-    ew_hist<0><<<wgs, 256, 0, stream>>>(x, n, st);
-    ew_solve<0><<<1, 256, 0, stream>>>(st, s);
-    ew_hist<1><<<wgs, 256, 0, stream>>>(x, n, st);
-    ew_solve<1><<<1, 256, 0, stream>>>(st, s);
-    ew_hist<2><<<wgs, 256, 0, stream>>>(x, n, st);
-    ew_solve<2><<<1, 256, 0, stream>>>(st, s);
+    { ProfScope ps(ctx, ATOMO_K_EW_SOLVE, stream); ew_clear<<<(3 * NBUCKET + 255) / 256, 256, 0, stream>>>(st); }
+    { ProfScope ps(ctx, ATOMO_K_EW_HIST, stream); ew_hist<0><<<wgs, 256, 0, stream>>>(x, n, st); }
+    { ProfScope ps(ctx, ATOMO_K_EW_SOLVE, stream); ew_solve<0><<<1, 256, 0, stream>>>(st, s); }
+    { ProfScope ps(ctx, ATOMO_K_EW_HIST, stream); ew_hist<1><<<wgs, 256, 0, stream>>>(x, n, st); }
+    { ProfScope ps(ctx, ATOMO_K_EW_SOLVE, stream); ew_solve<1><<<1, 256, 0, stream>>>(st, s); }
+    { ProfScope ps(ctx, ATOMO_K_EW_HIST, stream); ew_hist<2><<<wgs, 256, 0, stream>>>(x, n, st); }
+    { ProfScope ps(ctx, ATOMO_K_EW_SOLVE, stream); ew_solve<2><<<1, 256, 0, stream>>>(st, s); }
 }
 
 }  // namespace
@@ -435,12 +435,15 @@ int encode_entrywise(atomo_ctx* ctx, const float* g, double s, uint64_t seed, ui
     const EwLayout l = ew_layout(ctx->ws, n);
     const long long n_chunks = (n + CHUNK - 1) / CHUNK;
 
-    enqueue_water_level(g, n, s, l.st, stream);
-    ew_count<<<(unsigned)n_chunks, 256, 0, stream>>>(g, n, l.st, stream_id, seed, l.chunk_count);
-    ew_scan<<<1, 256, 0, stream>>>(l.chunk_count, n_chunks, l.chunk_base, l.st, (long long*)msg->count,
-                                   (long long)msg->capacity, ctx->d_flags);
-    ew_write<<<(unsigned)n_chunks, 256, 0, stream>>>(g, n, l.st, stream_id, seed, l.chunk_base,
-                                                     (long long)msg->capacity, msg->idx, msg->val, p_out);
+    enqueue_water_level(ctx, g, n, s, l.st, stream);
+    {
+        ProfScope ps(ctx, ATOMO_K_EW_SAMPLE, stream);
+        ew_count<<<(unsigned)n_chunks, 256, 0, stream>>>(g, n, l.st, stream_id, seed, l.chunk_count);
+        ew_scan<<<1, 256, 0, stream>>>(l.chunk_count, n_chunks, l.chunk_base, l.st, (long long*)msg->count,
+                                       (long long)msg->capacity, ctx->d_flags);
+        ew_write<<<(unsigned)n_chunks, 256, 0, stream>>>(g, n, l.st, stream_id, seed, l.chunk_base,
+                                                         (long long)msg->capacity, msg->idx, msg->val, p_out);
+    }
     ATOMO_HIP(ctx, hipGetLastError());
     return ATOMO_OK;
 }
@@ -471,7 +474,7 @@ int probabilities(atomo_ctx* ctx, const float* lambda, const int64_t* offsets, i
     for (int k : large) {
         const int64_t len = offsets[k + 1] - offsets[k];
         const float* x = lambda + offsets[k];
-        enqueue_water_level(x, len, s, st, stream);
+        enqueue_water_level(ctx, x, len, s, st, stream);
         const int wgs = (int)std::min<int64_t>(4096, (len + 255) / 256);
         ew_write_p<<<wgs, 256, 0, stream>>>(x, len, st, p + offsets[k]);
     }

@@ -24,72 +24,14 @@
 #include <cmath>
 #include <vector>
 
-#include "atomo_internal.h"
-#include "block_algorithm1.h"
+#include "svd_common.h"
 
 namespace atomo {
 
 namespace {
 
-constexpr int BS = 32;          // rows per block
-constexpr int PR = 64;          // rows per pair
-constexpr int KCG = 512;        // columns per svd_gram work item
-constexpr int KCU = 256;        // columns per svd_update work item (4 waves x 64)
-constexpr int QSZ = PR * PR;
-constexpr int MAX_R = ALG1_MAX;
+using namespace svd;
 
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-
-enum { ST_DONE_AT = 0, ST_SWEEPS = 1, ST_OFFMAX = 2, ST_ARRIVE = 3, ST_SCALE = 4, ST_SCALE_NEXT = 5, ST_WORDS = 8 };
-
-// Rows whose squared norm is below ZERO_REL * (largest squared row norm of the matrix) are rounding
-// residue of the fp32 updates (about 32 ulp of the dominant rows): their directions carry no
-// information, so they neither count in the convergence test nor get rotated among themselves.
-constexpr float ZERO_REL = 3.64e-12f;       // (32 * 2^-24)^2
-
-struct SvdMat {
-    float* W;                // rows_alloc x ldw
-    int ldw, r, M, Mp, rows_alloc;
-    int nb2, R, npairs, nchg, nchu;
-    float* gram;             // [npairs][nchg][64*64]
-    float* Q;                // [npairs][64*64]
-    int* state;              // [ST_WORDS]
-    float* sig_raw;          // [rows_alloc]
-    const float* G;
-    long long ldg;
-    int rows, cols, transposed;
-    int* count;
-    int* idx;
-    float* w;
-    float* U;
-    float* V;
-    int capacity;
-    float* sigma_out;        // may be null
-    float* p_out;            // may be null
-    unsigned long long stream_id;
-    int* src_row;            // [capacity]
-    float* src_inv;          // [capacity]
-};
-
-struct Work { int mat, a, b, c; };
-
-__device__ inline void pair_blocks(int nb2, int round, int k, int& bi, int& bj)
-{
-    const int n1 = nb2 - 1;
-    int a, b;
-    if (k == 0) { a = n1; b = round; }
-    else { a = (round + k) % n1; b = (round - k + n1) % n1; }
-    bi = a < b ? a : b;
-    bj = a < b ? b : a;
-}
-
-// True if work for `step` of this matrix should be skipped (finished earlier, or past the sweep limit).
-__device__ inline bool skip_step(const SvdMat& m, int step, int max_sweeps)
-{
-    const int done_at = m.state[ST_DONE_AT];
-    if (done_at != 0 && step >= done_at) return true;
-    return step / m.R >= max_sweeps;
-}
 
 // ------------------------------------------------------------------------------------------------
 // prepare: W = [A | T], padded
@@ -163,213 +105,6 @@ __global__ __launch_bounds__(256) void svd_gram(const SvdMat* mats, const Work* 
     for (int v = 0; v < 16; ++v) {
         const int i = qi * BS + 8 * (v >> 2) + 4 * h + (v & 3);
         out[i * PR + qj * BS + l32] = acc[v];
-    }
-}
-
-// ------------------------------------------------------------------------------------------------
-// eig: 64x64 symmetric eigen-decomposition by parallel-ordered two-sided Jacobi in LDS
-// ------------------------------------------------------------------------------------------------
-constexpr int LDA = 65;
-
-__global__ __launch_bounds__(256) void svd_eig(const SvdMat* mats, const Work* work, int step, int max_sweeps,
-                                               float stop_cosine, int* flags)
-{
-    __shared__ float A[PR * LDA];
-    __shared__ float Qm[PR * LDA];
-    __shared__ float rc[32], rs[32];
-    __shared__ int rp[32], rq[32];
-    __shared__ float ev[PR];
-    __shared__ int dest[PR];
-    __shared__ float red[8];
-    __shared__ int rotated;
-
-    const Work wk = work[blockIdx.x];
-    const SvdMat m = mats[wk.mat];
-    if (skip_step(m, step, max_sweeps)) return;
-    const int round = step % m.R;
-    int bi, bj;
-    pair_blocks(m.nb2, round, wk.a, bi, bj);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-
-    // 1. sum the partial Gram matrices in a fixed order
-    {
-        const float* g = m.gram + (size_t)wk.a * m.nchg * QSZ;
-        for (int e = tid; e < QSZ; e += 256) {
-            float sum = 0.0f;
-            for (int c = 0; c < m.nchg; ++c) sum += g[(size_t)c * QSZ + e];
-            const int i = e >> 6, j = e & 63;
-            A[i * LDA + j] = sum;
-            Qm[i * LDA + j] = (i == j) ? 1.0f : 0.0f;
-        }
-    }
-    __syncthreads();
-    // symmetrise (the two off-diagonal quadrants were accumulated in different orders)
-    for (int e = tid; e < QSZ; e += 256) {
-        const int i = e >> 6, j = e & 63;
-        if (i < j) {
-            const float v = 0.5f * (A[i * LDA + j] + A[j * LDA + i]);
-            A[i * LDA + j] = v;
-            A[j * LDA + i] = v;
-        }
-    }
-    __syncthreads();
-
-    // 2. largest |cos| between two rows of the pair, before rotating (rows at the rounding floor
-    //    are measured against the floor instead of their own length), and the largest squared norm
-    const float z2 = ZERO_REL * __int_as_float(m.state[ST_SCALE]);
-    {
-        float mx = 0.0f, dmax = 0.0f;
-        for (int e = tid; e < QSZ; e += 256) {
-            const int i = e >> 6, j = e & 63;
-            if (i < j) {
-                const float dii = A[i * LDA + i], djj = A[j * LDA + j];
-                if (dii > 0.0f && djj > 0.0f) mx = fmaxf(mx, fabsf(A[i * LDA + j]) / fmaxf(sqrtf(dii * djj), z2));
-            } else if (i == j) {
-                dmax = fmaxf(dmax, A[i * LDA + i]);
-            }
-        }
-        for (int o = 32; o > 0; o >>= 1) {
-            mx = fmaxf(mx, __shfl_down(mx, o));
-            dmax = fmaxf(dmax, __shfl_down(dmax, o));
-        }
-        if (lane == 0) { red[wave] = mx; red[4 + wave] = dmax; }
-        __syncthreads();
-        if (tid == 0) {
-            mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-            dmax = fmaxf(fmaxf(red[4], red[5]), fmaxf(red[6], red[7]));
-            atomicMax((unsigned int*)&m.state[ST_OFFMAX], __float_as_uint(mx));
-            atomicMax((unsigned int*)&m.state[ST_SCALE_NEXT], __float_as_uint(dmax));
-        }
-    }
-
-    // 3. Jacobi sweeps, round-robin over 64 indices: 63 steps of 32 disjoint rotations
-    for (int isw = 0; isw < 3; ++isw) {
-        if (tid == 0) rotated = 0;
-        for (int t = 0; t < 63; ++t) {
-            if (tid < 32) {
-                int a, b;
-                if (tid == 0) { a = 63; b = t; }
-                else { a = (t + tid) % 63; b = (t - tid + 63) % 63; }
-                const int p = a < b ? a : b, q = a < b ? b : a;
-                const float app = A[p * LDA + p], aqq = A[q * LDA + q], apq = A[p * LDA + q];
-                float c = 1.0f, s = 0.0f;
-                if (apq != 0.0f && fabsf(apq) > 1e-7f * fmaxf(sqrtf(fabsf(app * aqq)), z2)) {
-                    const float zeta = (aqq - app) / (2.0f * apq);
-                    const float tt = copysignf(1.0f, zeta) / (fabsf(zeta) + sqrtf(1.0f + zeta * zeta));
-                    c = 1.0f / sqrtf(1.0f + tt * tt);
-                    s = c * tt;
-                    rotated = 1;
-                }
-                rc[tid] = c; rs[tid] = s; rp[tid] = p; rq[tid] = q;
-            }
-            __syncthreads();
-            // A <- J^T A J on 2x2 blocks (row pair a, column pair b)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int blk = tid + 256 * e;
-                const int a = blk >> 5, b = blk & 31;
-                const float ca = rc[a], sa = rs[a], cb = rc[b], sb = rs[b];
-                const int pa = rp[a], qa = rq[a], pb = rp[b], qb = rq[b];
-                const float x00 = A[pa * LDA + pb], x01 = A[pa * LDA + qb];
-                const float x10 = A[qa * LDA + pb], x11 = A[qa * LDA + qb];
-                const float y00 = ca * x00 - sa * x10, y01 = ca * x01 - sa * x11;
-                const float y10 = sa * x00 + ca * x10, y11 = sa * x01 + ca * x11;
-                A[pa * LDA + pb] = cb * y00 - sb * y01;
-                A[pa * LDA + qb] = sb * y00 + cb * y01;
-                A[qa * LDA + pb] = cb * y10 - sb * y11;
-                A[qa * LDA + qb] = sb * y10 + cb * y11;
-            }
-            // Q <- Q J
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int item = tid + 256 * e;
-                const int i = item >> 5, b = item & 31;
-                const float cb = rc[b], sb = rs[b];
-                const int pb = rp[b], qb = rq[b];
-                const float x = Qm[i * LDA + pb], y = Qm[i * LDA + qb];
-                Qm[i * LDA + pb] = cb * x - sb * y;
-                Qm[i * LDA + qb] = sb * x + cb * y;
-            }
-            __syncthreads();
-        }
-        if (rotated == 0) break;
-        __syncthreads();
-    }
-
-    // 4. eigenvalues, and where each eigenvector goes: decreasing eigenvalue over the live rows of
-    //    the pair, padding rows stay padding rows
-    const int nI = max(0, min(BS, m.r - bi * BS)), nJ = max(0, min(BS, m.r - bj * BS));
-    if (tid < PR) {
-        const bool live = tid < BS ? tid < nI : tid - BS < nJ;
-        ev[tid] = live ? A[tid * LDA + tid] : -FLT_MAX;
-    }
-    __syncthreads();
-    if (tid < PR) {
-        const float mine = ev[tid];
-        int rank = 0;
-        for (int j = 0; j < PR; ++j) {
-            const float o = ev[j];
-            rank += (o > mine) || (o == mine && j < tid);
-        }
-        int slot;
-        if (rank < nI) slot = rank;
-        else if (rank < nI + nJ) slot = BS + rank - nI;
-        else {
-            const int pad = rank - nI - nJ;                      // padding rows, in order
-            slot = pad < BS - nI ? nI + pad : BS + nJ + pad - (BS - nI);
-        }
-        dest[tid] = slot;
-    }
-    __syncthreads();
-
-    // 5. one Newton-Schulz step  Q <- Q (1.5 I - 0.5 Q^T Q): removes the drift of thousands of fp32 rotations
-    const int qi = wave >> 1, qj = wave & 1, h = lane >> 5, l32 = lane & 31;
-    floatx16 acc;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-    for (int k = 0; k < PR; k += 2) {
-        const float a = Qm[(k + h) * LDA + qi * BS + l32];       // (Q^T)[i][k]
-        const float b = Qm[(k + h) * LDA + qj * BS + l32];       // Q[k][j]
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
-    }
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const int i = qi * BS + 8 * (v >> 2) + 4 * h + (v & 3), j = qj * BS + l32;
-        A[i * LDA + j] = (i == j ? 1.5f : 0.0f) - 0.5f * acc[v];  // F = 1.5 I - 0.5 Q^T Q
-    }
-    __syncthreads();
-#pragma unroll
-    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-    for (int k = 0; k < PR; k += 2) {
-        const float a = Qm[(qi * BS + l32) * LDA + k + h];       // Q[i][k]
-        const float b = A[(k + h) * LDA + qj * BS + l32];        // F[k][j]
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
-    }
-    // 6. write Q with its columns permuted to their destination rows
-    float* qout = m.Q + (size_t)wk.a * QSZ;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const int i = qi * BS + 8 * (v >> 2) + 4 * h + (v & 3), j = qj * BS + l32;
-        qout[i * PR + dest[j]] = acc[v];
-    }
-
-    // 7. end of a sweep: the last pair to arrive decides whether the matrix is finished
-    if (round == m.R - 1 && tid == 0) {
-        __threadfence();
-        const int arrived = atomicAdd(&m.state[ST_ARRIVE], 1);
-        if (arrived == m.npairs - 1) {
-            __threadfence();
-            const float worst = __uint_as_float(atomicAdd((unsigned int*)&m.state[ST_OFFMAX], 0u));
-            const int sweeps = m.state[ST_SWEEPS] + 1;
-            m.state[ST_SWEEPS] = sweeps;
-            atomicMax(&flags[FLAG_MAX_SWEEPS], sweeps);
-            if (worst < stop_cosine) m.state[ST_DONE_AT] = step + 1;
-            else if (sweeps >= max_sweeps) atomicMax(&flags[FLAG_NOCONV], 1);
-            m.state[ST_OFFMAX] = 0;
-            m.state[ST_ARRIVE] = 0;
-            const unsigned int grown = atomicAdd((unsigned int*)&m.state[ST_SCALE_NEXT], 0u);
-            if (grown > (unsigned int)m.state[ST_SCALE]) m.state[ST_SCALE] = (int)grown;
-        }
     }
 }
 
@@ -615,6 +350,8 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
 {
     const int max_sweeps = opt ? opt->max_sweeps : 12;
     const float stop_cosine = opt ? opt->stop_cosine : 1e-4f;
+    const int max_inner = opt && opt->max_inner_sweeps > 0 ? opt->max_inner_sweeps : 1;
+    const float inner_reduction = opt && opt->inner_reduction > 0.0f ? opt->inner_reduction : 0.01f;
 
     Plan sizing;
     build_plan(mats, n_mats, msgs, sigma_out, p_out, stream_base, nullptr, sizing);
@@ -626,6 +363,8 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
 
     SvdMat* d_mats = plan.d_mats;
     Work* d_work = plan.d_work;
+    ctx->svd_state.clear();
+    for (const SvdMat& m : plan.mats) ctx->svd_state.push_back(m.state);
     const size_t n_work = plan.prep.size() + plan.gram.size() + plan.eig.size() + plan.upd.size() +
                           plan.norms.size() + plan.pack.size();
     std::vector<Work> all;
@@ -648,19 +387,43 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     rc = upload(ctx, d_work, all.data(), all.size() * sizeof(Work), stream);
     if (rc != ATOMO_OK) return rc;
 
-    svd_prepare<<<(unsigned)plan.prep.size(), 256, 0, stream>>>(d_mats, d_work + o_prep);
-    svd_norms<<<(unsigned)plan.norms.size(), 256, 0, stream>>>(d_mats, d_work + o_norms, 1);
+    {
+        ProfScope ps(ctx, ATOMO_K_SVD_PREPARE, stream);
+        svd_prepare<<<(unsigned)plan.prep.size(), 256, 0, stream>>>(d_mats, d_work + o_prep);
+        svd_norms<<<(unsigned)plan.norms.size(), 256, 0, stream>>>(d_mats, d_work + o_norms, 1);
+    }
     const int n_steps = max_sweeps * plan.max_R;
     for (int step = 0; step < n_steps; ++step) {
-        svd_gram<<<(unsigned)plan.gram.size(), 256, 0, stream>>>(d_mats, d_work + o_gram, step, max_sweeps);
-        svd_eig<<<(unsigned)plan.eig.size(), 256, 0, stream>>>(d_mats, d_work + o_eig, step, max_sweeps, stop_cosine,
-                                                               ctx->d_flags);
-        svd_update<<<(unsigned)plan.upd.size(), 256, 0, stream>>>(d_mats, d_work + o_upd, step, max_sweeps);
+        {
+            ProfScope ps(ctx, ATOMO_K_SVD_GRAM, stream);
+            svd_gram<<<(unsigned)plan.gram.size(), 256, 0, stream>>>(d_mats, d_work + o_gram, step, max_sweeps);
+        }
+        {
+            ProfScope ps(ctx, ATOMO_K_SVD_EIG, stream);
+            launch_svd_eig(d_mats, d_work + o_eig, (int)plan.eig.size(), step, max_sweeps, stop_cosine,
+                           max_inner, inner_reduction, ctx->d_flags, stream);
+        }
+        {
+            ProfScope ps(ctx, ATOMO_K_SVD_UPDATE, stream);
+            svd_update<<<(unsigned)plan.upd.size(), 256, 0, stream>>>(d_mats, d_work + o_upd, step, max_sweeps);
+        }
     }
-    svd_norms<<<(unsigned)plan.norms.size(), 256, 0, stream>>>(d_mats, d_work + o_norms, 0);
-    svd_select<<<(unsigned)n_mats, 256, 0, stream>>>(d_mats, s, (unsigned long long)seed, ctx->d_flags);
-    svd_pack<<<(unsigned)plan.pack.size(), 256, 0, stream>>>(d_mats, d_work + o_pack);
+    {
+        ProfScope ps(ctx, ATOMO_K_SVD_FINALIZE, stream);
+        svd_norms<<<(unsigned)plan.norms.size(), 256, 0, stream>>>(d_mats, d_work + o_norms, 0);
+        svd_select<<<(unsigned)n_mats, 256, 0, stream>>>(d_mats, s, (unsigned long long)seed, ctx->d_flags);
+        svd_pack<<<(unsigned)plan.pack.size(), 256, 0, stream>>>(d_mats, d_work + o_pack);
+    }
     ATOMO_HIP(ctx, hipGetLastError());
+    return ATOMO_OK;
+}
+
+int svd_sweeps(atomo_ctx* ctx, hipStream_t stream, int32_t* sweeps, int n_mats)
+{
+    if ((size_t)n_mats != ctx->svd_state.size()) return ATOMO_EINVAL;
+    ATOMO_HIP(ctx, hipStreamSynchronize(stream));
+    for (int j = 0; j < n_mats; ++j)
+        ATOMO_HIP(ctx, hipMemcpy(&sweeps[j], ctx->svd_state[j] + ST_SWEEPS, sizeof(int32_t), hipMemcpyDeviceToHost));
     return ATOMO_OK;
 }
 

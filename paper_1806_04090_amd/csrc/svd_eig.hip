@@ -1,0 +1,313 @@
+// svd_eig: eigen-decomposition of the 64x64 Gram matrix of one block pair (the inner problem of the
+// blocked one-sided Jacobi SVD), one workgroup per pair.
+//
+// Two-sided Jacobi with the round-robin ("chess tournament") parallel ordering: 63 steps per sweep,
+// each applying 32 disjoint rotations.  The matrix A and the accumulated rotations Q live in LDS in
+// "slot" order: at every step the 32 rotations act on the slot pairs (0,1), (2,3), ..., (62,63), so
+// no index tables are needed, and the tournament is realised by writing every result to the slot its
+// index occupies in the next step (slot 0 stays; even slots move up by two, 62 -> 63; odd slots move
+// down by two, 1 -> 2).  After 63 steps every index is back in its own slot.  Within a row the even
+// slots are stored in columns 0..31 and the odd slots in columns 32..63, so that the 32 lanes that
+// own the 32 slot pairs read and write consecutive LDS words (no bank conflicts).  A and Q are
+// double-buffered, so a step is: read buffer X, rotate, write buffer Y permuted, barrier.  Every
+// lane computes the rotation of its own column pair from the diagonal 2x2 block (redundantly in
+// every wave, so no second barrier) and fetches the rotations of its row pairs with lane reads.
+#include <cfloat>
+
+#include "svd_common.h"
+
+namespace atomo {
+namespace svd {
+
+namespace {
+
+constexpr int NT = 1024;                // threads per workgroup
+constexpr int ELD = 65;                 // LDS row stride
+constexpr int GROUPS = NT / 32;         // thread groups of 32 (one slot pair of columns per thread)
+constexpr int RP_PER = 32 / GROUPS;     // row pairs of A per thread
+constexpr int QR_PER = 64 / GROUPS;     // rows of Q per thread
+
+__device__ inline int next_slot(int s)
+{
+    if (s == 0) return 0;
+    if (s & 1) return s == 1 ? 2 : s - 2;
+    return s == 62 ? 63 : s + 2;
+}
+
+// column of slot s inside a row: even slots first, then odd slots
+__device__ inline int mem_col(int s) { return (s >> 1) + 32 * (s & 1); }
+
+// Largest |A_ij| / max(sqrt(A_ii A_jj), z2) over i < j, and largest diagonal entry.  All threads call.
+__device__ inline float2 max_cosine(const float* A, float z2, float* red)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    float mx = 0.0f, dmax = 0.0f;
+    for (int e = tid; e < QSZ; e += NT) {
+        const int i = e >> 6, j = e & 63;                        // j is the memory column
+        const int js = j < 32 ? 2 * j : 2 * (j - 32) + 1;        // its slot
+        if (i < js) {
+            const float dii = A[i * ELD + mem_col(i)], djj = A[js * ELD + j];
+            if (dii > 0.0f && djj > 0.0f)
+                mx = fmaxf(mx, fabsf(A[i * ELD + j]) * __builtin_amdgcn_rcpf(fmaxf(__builtin_amdgcn_sqrtf(dii * djj), z2)));
+        } else if (i == js) {
+            dmax = fmaxf(dmax, A[i * ELD + j]);
+        }
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+        mx = fmaxf(mx, __shfl_down(mx, o));
+        dmax = fmaxf(dmax, __shfl_down(dmax, o));
+    }
+    __syncthreads();                     // red[] may still be read from a previous call
+    if (lane == 0) { red[wave] = mx; red[16 + wave] = dmax; }
+    __syncthreads();
+    mx = 0.0f; dmax = 0.0f;
+    for (int w = 0; w < NT / 64; ++w) { mx = fmaxf(mx, red[w]); dmax = fmaxf(dmax, red[16 + w]); }
+    return make_float2(mx, dmax);
+}
+
+// value of x in lane `src` of the wave (src must be wave-uniform)
+__device__ inline float lane_value(float x, int src)
+{
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), src));
+}
+
+// Rotation (c, s) that annihilates the off-diagonal entry of the slot pair (2k, 2k+1).  The hardware
+// reciprocal / square-root approximations (1 ulp) are enough: what a rotation misses the next sweep
+// picks up, and the orthogonality of the product is restored by the Newton-Schulz step.
+__device__ inline float2 pair_rotation(const float* A, int k, float z2)
+{
+    const float app = A[(2 * k) * ELD + k];
+    const float apq = A[(2 * k) * ELD + 32 + k];
+    const float aqq = A[(2 * k + 1) * ELD + 32 + k];
+    float c = 1.0f, s = 0.0f;
+    if (apq != 0.0f && fabsf(apq) > 1e-7f * fmaxf(__builtin_amdgcn_sqrtf(fabsf(app * aqq)), z2)) {
+        const float zeta = (aqq - app) * __builtin_amdgcn_rcpf(2.0f * apq);
+        const float az = fabsf(zeta);
+        // az + sqrt(1 + az^2); for huge |zeta| the square overflows to inf and t becomes 0 (no rotation needed)
+        const float t = copysignf(__builtin_amdgcn_rcpf(az + __builtin_amdgcn_sqrtf(1.0f + az * az)), zeta);
+        c = __builtin_amdgcn_rsqf(1.0f + t * t);
+        s = c * t;
+    }
+    return make_float2(c, s);
+}
+
+__global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* work, int step, int max_sweeps,
+                                              float stop_cosine, int max_inner, float inner_reduction, int* flags)
+{
+    __shared__ float As[2][PR * ELD];
+    __shared__ float Qs[2][PR * ELD];
+    __shared__ float ev[PR];
+    __shared__ int dest[PR];
+    __shared__ float red[32];
+
+    const Work wk = work[blockIdx.x];
+    const SvdMat m = mats[wk.mat];
+    if (skip_step(m, step, max_sweeps)) return;
+    const int round = step % m.R;
+    int bi, bj;
+    pair_blocks(m.nb2, round, wk.a, bi, bj);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    // 1. sum the partial Gram matrices in a fixed order; symmetrise (the two off-diagonal quadrants
+    //    were accumulated in different orders); Q = I
+    {
+        const float* g = m.gram + (size_t)wk.a * m.nchg * QSZ;
+        for (int e = tid; e < QSZ; e += NT) {
+            const int i = e >> 6, j = e & 63;
+            float sum = 0.0f;
+            for (int c = 0; c < m.nchg; ++c) sum += g[(size_t)c * QSZ + e];
+            As[0][i * ELD + mem_col(j)] = sum;
+            Qs[0][i * ELD + mem_col(j)] = (i == j) ? 1.0f : 0.0f;
+        }
+        __syncthreads();
+        for (int e = tid; e < QSZ; e += NT) {
+            const int i = e >> 6, j = e & 63;
+            if (i < j) {
+                const float v = 0.5f * (As[0][i * ELD + mem_col(j)] + As[0][j * ELD + mem_col(i)]);
+                As[0][i * ELD + mem_col(j)] = v;
+                As[0][j * ELD + mem_col(i)] = v;
+            }
+        }
+    }
+    __syncthreads();
+
+    // 2. largest |cos| between two rows of the pair before rotating (rows at the rounding floor are
+    //    measured against the floor instead of their own length), and the largest squared norm
+    const float z2 = ZERO_REL * __int_as_float(m.state[ST_SCALE]);
+    const float2 entry = max_cosine(As[0], z2, red);
+    if (tid == 0) {
+        atomicMax((unsigned int*)&m.state[ST_OFFMAX], __float_as_uint(entry.x));
+        atomicMax((unsigned int*)&m.state[ST_SCALE_NEXT], __float_as_uint(entry.y));
+    }
+
+    // 3. Jacobi sweeps.  Thread (b, g): slot pair b of the columns, row pairs g*RP_PER.. of A, rows
+    //    g*QR_PER.. of Q.  Its two outputs per row go to the columns of slots next(2b), next(2b+1).
+    const int b = tid & 31, grp = tid >> 5;
+    const int wc0 = mem_col(next_slot(2 * b)), wc1 = mem_col(next_slot(2 * b + 1));
+    int cur = 0;
+    int inner_done = 0;
+    if (entry.x > 0.0f) {
+        // inner target: a fixed factor below what came in is enough for the outer iteration
+        const float inner_stop = fmaxf(2e-7f, inner_reduction * entry.x);
+        for (int isw = 0; isw < max_inner; ++isw) {
+            for (int t = 0; t < 63; ++t) {
+                const float* X = As[cur];
+                float* Y = As[cur ^ 1];
+                const float* XQ = Qs[cur];
+                float* YQ = Qs[cur ^ 1];
+                // issue every LDS read of the step first; the rotation arithmetic overlaps their latency
+                float xa[RP_PER][4], xq[QR_PER][2];
+#pragma unroll
+                for (int e = 0; e < RP_PER; ++e) {
+                    const int a = grp * RP_PER + e;
+                    xa[e][0] = X[(2 * a) * ELD + b];     xa[e][1] = X[(2 * a) * ELD + 32 + b];
+                    xa[e][2] = X[(2 * a + 1) * ELD + b]; xa[e][3] = X[(2 * a + 1) * ELD + 32 + b];
+                }
+#pragma unroll
+                for (int e = 0; e < QR_PER; ++e) {
+                    const int i = grp * QR_PER + e;
+                    xq[e][0] = XQ[i * ELD + b];
+                    xq[e][1] = XQ[i * ELD + 32 + b];
+                }
+                // every lane computes the rotation of its own column pair b (both halves of the wave
+                // redundantly); the rotations of the row pairs come from the lanes that own them
+                const float2 pb = pair_rotation(X, b, z2);
+#pragma unroll
+                for (int e = 0; e < RP_PER; ++e) {
+                    const int a = grp * RP_PER + e;
+                    const int a_lo = __builtin_amdgcn_readfirstlane(a - (lane >> 5) * RP_PER);   // row pair of lanes 0..31
+                    const float c_lo = lane_value(pb.x, a_lo), s_lo = lane_value(pb.y, a_lo);
+                    const float c_hi = lane_value(pb.x, a_lo + RP_PER), s_hi = lane_value(pb.y, a_lo + RP_PER);
+                    const float2 pa = make_float2(lane < 32 ? c_lo : c_hi, lane < 32 ? s_lo : s_hi);
+                    const float x00 = xa[e][0], x01 = xa[e][1], x10 = xa[e][2], x11 = xa[e][3];
+                    const float y00 = pa.x * x00 - pa.y * x10, y01 = pa.x * x01 - pa.y * x11;
+                    const float y10 = pa.y * x00 + pa.x * x10, y11 = pa.y * x01 + pa.x * x11;
+                    const int r0 = next_slot(2 * a) * ELD, r1 = next_slot(2 * a + 1) * ELD;
+                    Y[r0 + wc0] = pb.x * y00 - pb.y * y01;
+                    Y[r0 + wc1] = pb.y * y00 + pb.x * y01;
+                    Y[r1 + wc0] = pb.x * y10 - pb.y * y11;
+                    Y[r1 + wc1] = pb.y * y10 + pb.x * y11;
+                }
+#pragma unroll
+                for (int e = 0; e < QR_PER; ++e) {
+                    const int i = grp * QR_PER + e;
+                    const float x = xq[e][0], y = xq[e][1];
+                    YQ[i * ELD + wc0] = pb.x * x - pb.y * y;
+                    YQ[i * ELD + wc1] = pb.y * x + pb.x * y;
+                }
+                cur ^= 1;
+                __syncthreads();
+            }
+            ++inner_done;
+            if (isw + 1 < max_inner) {
+                const float2 now = max_cosine(As[cur], z2, red);
+                if (now.x <= inner_stop) break;
+            }
+        }
+    }
+    const float* Acur = As[cur];
+    float* Qm = As[cur ^ 1];                                     // Q in natural column order
+    float* F = Qs[cur ^ 1];                                      // scratch for the Newton-Schulz factor
+    for (int e = tid; e < QSZ; e += NT) {
+        const int i = e >> 6, j = e & 63;
+        Qm[i * ELD + j] = Qs[cur][i * ELD + mem_col(j)];
+    }
+
+    // 4. eigenvalues, and where each eigenvector goes: decreasing eigenvalue over the live rows of
+    //    the pair, padding rows stay padding rows
+    const int nI = max(0, min(BS, m.r - bi * BS)), nJ = max(0, min(BS, m.r - bj * BS));
+    if (tid < PR) {
+        const bool live = tid < BS ? tid < nI : tid - BS < nJ;
+        ev[tid] = live ? Acur[tid * ELD + mem_col(tid)] : -FLT_MAX;
+    }
+    __syncthreads();
+    if (tid < PR) {
+        const float mine = ev[tid];
+        int rank = 0;
+        for (int j = 0; j < PR; ++j) {
+            const float o = ev[j];
+            rank += (o > mine) || (o == mine && j < tid);
+        }
+        int slot;
+        if (rank < nI) slot = rank;
+        else if (rank < nI + nJ) slot = BS + rank - nI;
+        else {
+            const int pad = rank - nI - nJ;                      // padding rows, in order
+            slot = pad < BS - nI ? nI + pad : BS + nJ + pad - (BS - nI);
+        }
+        dest[tid] = slot;
+    }
+    __syncthreads();
+
+    // 5. one Newton-Schulz step  Q <- Q (1.5 I - 0.5 Q^T Q): removes the drift that thousands of
+    //    fp32 rotations leave in the orthogonality of Q (waves 0..3, one 32x32 quadrant each)
+    const int qi = (wave >> 1) & 1, qj = wave & 1, h = lane >> 5, l32 = lane & 31;
+    floatx16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+    if (wave < 4) {
+        for (int k = 0; k < PR; k += 2) {
+            const float a = Qm[(k + h) * ELD + qi * BS + l32];   // (Q^T)[i][k]
+            const float bq = Qm[(k + h) * ELD + qj * BS + l32];  // Q[k][j]
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bq, acc, 0, 0, 0);
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int i = qi * BS + 8 * (v >> 2) + 4 * h + (v & 3), j = qj * BS + l32;
+            F[i * ELD + j] = (i == j ? 1.5f : 0.0f) - 0.5f * acc[v];
+        }
+    }
+    __syncthreads();
+    if (wave < 4) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+        for (int k = 0; k < PR; k += 2) {
+            const float a = Qm[(qi * BS + l32) * ELD + k + h];   // Q[i][k]
+            const float bq = F[(k + h) * ELD + qj * BS + l32];   // F[k][j]
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bq, acc, 0, 0, 0);
+        }
+        // 6. write Q with its columns permuted to their destination rows
+        float* qout = m.Q + (size_t)wk.a * QSZ;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int i = qi * BS + 8 * (v >> 2) + 4 * h + (v & 3), j = qj * BS + l32;
+            qout[i * PR + dest[j]] = acc[v];
+        }
+    }
+
+    if (tid == 0) {
+        atomicAdd(&flags[FLAG_EIG_VISITS], 1);
+        atomicAdd(&flags[FLAG_EIG_INNER], inner_done);
+    }
+
+    // 7. end of a sweep: the last pair to arrive decides whether the matrix is finished
+    if (round == m.R - 1 && tid == 0) {
+        __threadfence();
+        const int arrived = atomicAdd(&m.state[ST_ARRIVE], 1);
+        if (arrived == m.npairs - 1) {
+            __threadfence();
+            const float worst = __uint_as_float(atomicAdd((unsigned int*)&m.state[ST_OFFMAX], 0u));
+            const int sweeps = m.state[ST_SWEEPS] + 1;
+            m.state[ST_SWEEPS] = sweeps;
+            atomicMax(&flags[FLAG_MAX_SWEEPS], sweeps);
+            if (worst < stop_cosine) m.state[ST_DONE_AT] = step + 1;
+            else if (sweeps >= max_sweeps) atomicMax(&flags[FLAG_NOCONV], 1);
+            m.state[ST_OFFMAX] = 0;
+            m.state[ST_ARRIVE] = 0;
+            const unsigned int grown = atomicAdd((unsigned int*)&m.state[ST_SCALE_NEXT], 0u);
+            if (grown > (unsigned int)m.state[ST_SCALE]) m.state[ST_SCALE] = (int)grown;
+        }
+    }
+}
+
+}  // namespace
+
+void launch_svd_eig(const SvdMat* d_mats, const Work* d_work, int n_items, int step, int max_sweeps,
+                    float stop_cosine, int max_inner, float inner_reduction, int* d_flags, hipStream_t stream)
+{
+    svd_eig<<<(unsigned)n_items, NT, 0, stream>>>(d_mats, d_work, step, max_sweeps, stop_cosine, max_inner,
+                                                  inner_reduction, d_flags);
+}
+
+}  // namespace svd
+}  // namespace atomo
