@@ -1,0 +1,148 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration bench.py times.
+
+Where the fp64 oracle can compute the expected output in reasonable time it is compared value by
+value (every layer of the ResNet-18 set; sampled matrices of the 64-matrix batch; sampled workers of
+the 16-worker aggregate; sampled coordinates of the 11-million-element entry-wise gradient together
+with the full mask).  Everything else is checked through properties that hold at any size: singular
+pairs (G v = sigma u, G^T u = sigma v), sum sigma^2 = |G|_F^2, sum p = s, a mask that the oracle
+reproduces bit-exactly from the GPU's float32 p, and a decode equal to the oracle's decode of the
+same message."""
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1806_04090_amd import binding, inputs
+from gpu_common import ctx, dev, sigma_tolerance_ok, check_svd_message_against_matrix
+
+pytestmark = pytest.mark.gpu
+
+
+def encode_set(mats, s, seed, stream_base, streams=None):
+    c = ctx()
+    d_mats = [dev(g) for g in mats]
+    ranks = [min(g.shape) for g in mats]
+    total = sum(ranks)
+    sigma = torch.zeros(total, dtype=torch.float32, device="cuda")
+    p = torch.zeros(total, dtype=torch.float32, device="cuda")
+    msgs = [binding.alloc_svd_message(g.shape[0], g.shape[1], binding.default_capacity(s, r), "cuda")
+            for g, r in zip(mats, ranks)]
+    binding.atomo_encode_svd(c, d_mats, s, seed, stream_base, msgs=msgs, sigma_out=sigma, p_out=p)
+    status, sweeps = c.status()
+    offs = np.concatenate([[0], np.cumsum(ranks)])
+    sig_h, p_h = sigma.cpu().numpy(), p.cpu().numpy()
+    per = [(sig_h[a:b], p_h[a:b]) for a, b in zip(offs[:-1], offs[1:])]
+    return msgs, per, status, sweeps
+
+
+def properties(G, s, seed, stream, msg, sig_gpu, p_gpu):
+    G64 = G.astype(np.float64)
+    assert (np.diff(sig_gpu) <= 0).all() and (sig_gpu >= 0).all()
+    np.testing.assert_allclose((sig_gpu.astype(np.float64) ** 2).sum(), (G64 ** 2).sum(), rtol=2e-5)
+    np.testing.assert_allclose(p_gpu.astype(np.float64).sum(), min(s, (sig_gpu > 0).sum()), rtol=1e-5)
+    assert (p_gpu > 0).all() and (p_gpu <= 1).all() and (np.diff(p_gpu) <= 0).all()
+    h = msg.to_host()
+    mask = oracle.bernoulli_mask(p_gpu, seed, stream)
+    assert h["count"] == int(mask.sum()) and np.array_equal(h["idx"], np.flatnonzero(mask))
+    check_svd_message_against_matrix(G64, h, sig_gpu, p_gpu)
+    return h
+
+
+def oracle_values(G, s, sig_gpu, p_gpu, h, isolated_gap=1e-2):
+    sig_ref, U_ref, V_ref = oracle.svd(G)
+    assert sigma_tolerance_ok(sig_gpu, sig_ref).all(), float(np.abs(sig_gpu - sig_ref).max())
+    np.testing.assert_allclose(p_gpu, oracle.probabilities(sig_ref, s), rtol=1e-4, atol=1e-9)
+    gaps = np.minimum(np.abs(np.diff(sig_ref, prepend=np.inf)), np.abs(np.diff(sig_ref, append=-np.inf)))
+    for k, i in enumerate(h["idx"]):
+        if gaps[i] > isolated_gap * sig_ref[0]:
+            want = sig_ref[i] * np.outer(U_ref[:, i], V_ref[:, i])
+            got = float(sig_gpu[i]) * np.outer(h["U"][:, k], h["V"][:, k])
+            assert np.linalg.norm(got - want) <= 3e-4 * sig_ref[i]
+    return True
+
+
+def test_resnet18_layer_set_every_layer_against_the_oracle():
+    mats = inputs.resnet18_layer_set(0)
+    msgs, per, status, sweeps = encode_set(mats, 3.0, 0, 0)
+    assert status == 0 and sweeps <= 12
+    hosts = [properties(G, 3.0, 0, j, msgs[j], *per[j]) for j, G in enumerate(mats)]
+    with ThreadPoolExecutor(max_workers=16) as pool:
+        assert all(pool.map(lambda j: oracle_values(mats[j], 3.0, per[j][0], per[j][1], hosts[j]), range(len(mats))))
+    # decode of the whole set in one launch equals the oracle's decode of the same messages
+    outs = binding.atomo_decode_svd_batch(ctx(), [[m] for m in msgs])
+    for G, h, out in zip(mats, hosts, outs):
+        want = oracle.decode_svd([h], *G.shape)
+        assert np.linalg.norm(out.cpu().numpy() - want) <= 1e-5 * max(np.linalg.norm(want), 1e-30)
+
+
+def test_vgg_batch_of_64_deep_conv_layers():
+    mats = inputs.vgg_deep_conv_batch(0)
+    assert len(mats) == 64 and mats[0].shape == (512, 4608)
+    msgs, per, status, sweeps = encode_set(mats, 4.0, 0, 0)
+    assert status == 0
+    hosts = [properties(G, 4.0, 0, j, msgs[j], *per[j]) for j, G in enumerate(mats)]
+    sample = [0, 37]
+    with ThreadPoolExecutor(max_workers=2) as pool:
+        assert all(pool.map(lambda j: oracle_values(mats[j], 4.0, per[j][0], per[j][1], hosts[j]), sample))
+    for j in (5, 63):                                           # LAPACK fp64 singular values on two more
+        assert sigma_tolerance_ok(per[j][0], np.linalg.svd(mats[j].astype(np.float64), compute_uv=False)).all()
+    outs = binding.atomo_decode_svd_batch(ctx(), [[m] for m in msgs])
+    for j in (0, 21, 63):
+        want = oracle.decode_svd([hosts[j]], 512, 4608)
+        assert np.linalg.norm(outs[j].cpu().numpy() - want) <= 1e-5 * max(np.linalg.norm(want), 1e-30)
+
+
+def test_sixteen_worker_aggregate():
+    workers = 16
+    shapes = list(inputs.RESNET18_SHAPES)
+    grads = [inputs.resnet18_layer_set(w) for w in range(workers)]
+    flat = [g for w in range(workers) for g in grads[w]]
+    # stream id = (worker << 32) | layer: encode worker by worker (stream_base differs), all on one stream
+    all_msgs, all_per = [], []
+    for w in range(workers):
+        msgs, per, status, _ = encode_set(grads[w], 3.0, 0, inputs.worker_stream(w, 0))
+        assert status == 0
+        all_msgs.append(msgs); all_per.append(per)
+    hosts = {}
+    for w in (0, 9):
+        for j, G in enumerate(grads[w]):
+            hosts[(w, j)] = properties(G, 3.0, 0, inputs.worker_stream(w, j), all_msgs[w][j], *all_per[w][j])
+    small = [j for j, (m, n) in enumerate(shapes) if min(m, n) <= 128]
+    with ThreadPoolExecutor(max_workers=16) as pool:
+        jobs = [(w, j) for w in (0, 9) for j in small]
+        assert all(pool.map(lambda wj: oracle_values(grads[wj[0]][wj[1]], 3.0, all_per[wj[0]][wj[1]][0],
+                                                     all_per[wj[0]][wj[1]][1], hosts[wj]), jobs))
+    # parameter-server average: every layer decoded from its 16 messages, scaled by 1/16, in one launch
+    groups = [[all_msgs[w][j] for w in range(workers)] for j in range(len(shapes))]
+    outs = binding.atomo_decode_svd_batch(ctx(), groups, scale=1.0 / workers)
+    for j in (0, 3, 9, 17, 20):
+        msgs_h = [all_msgs[w][j].to_host() for w in range(workers)]
+        want = oracle.decode_svd(msgs_h, *shapes[j], scale=1.0 / workers)
+        assert np.linalg.norm(outs[j].cpu().numpy() - want) <= 1e-5 * max(np.linalg.norm(want), 1e-30)
+    del flat
+
+
+def test_entrywise_full_gradient():
+    n = inputs.RESNET18_PARAMETERS
+    g = inputs.flat_heavy_tail(seed=0)
+    assert g.size == n
+    s = n / 100
+    d = dev(g)
+    p = torch.zeros(n, dtype=torch.float32, device="cuda")
+    msg = binding.atomo_encode_entrywise(ctx(), d, s, 0, 0, p_out=p)
+    out = binding.atomo_decode(ctx(), [msg])
+    assert ctx().status()[0] == 0
+    p_gpu = p.cpu().numpy()
+    p_ref = oracle.probabilities(g.astype(np.float64), s)
+    np.testing.assert_allclose(p_gpu, p_ref, rtol=1e-6, atol=1e-12)
+    np.testing.assert_allclose(p_gpu.astype(np.float64).sum(), s, rtol=1e-6)
+    h = msg.to_host()
+    ref = oracle.encode_entrywise(g, s, 0, 0, p32=p_gpu)
+    assert h["count"] == ref["idx"].size and np.array_equal(h["idx"], ref["idx"])
+    np.testing.assert_allclose(h["val"], ref["val"], rtol=1e-6)
+    own = oracle.encode_entrywise(g, s, 0, 0)
+    assert len(set(own["idx"].tolist()) ^ set(h["idx"].tolist())) <= 4
+    want = oracle.decode_entrywise([h], n).astype(np.float32)
+    np.testing.assert_array_equal(out.cpu().numpy(), want)
