@@ -195,7 +195,8 @@ int atomo_decode_svd_batch(atomo_ctx* ctx, const atomo_svd_msg* msgs, const int3
  * method).  While profiling is on, every launch of these kernels is bracketed by two events on the
  * caller's stream, which costs a few microseconds per launch. */
 enum {
-    ATOMO_K_SVD_PREPARE = 0, ATOMO_K_SVD_GRAM, ATOMO_K_SVD_EIG, ATOMO_K_SVD_UPDATE, ATOMO_K_SVD_FINALIZE,
+    ATOMO_K_SVD_PREPARE = 0, ATOMO_K_SVD_GRAM, ATOMO_K_SVD_EIG, ATOMO_K_SVD_UPDATE, ATOMO_K_SVD_REFRESH,
+    ATOMO_K_SVD_FINALIZE,
     ATOMO_K_DECODE_SVD, ATOMO_K_EW_HIST, ATOMO_K_EW_SOLVE, ATOMO_K_EW_SAMPLE, ATOMO_K_EW_DECODE,
     ATOMO_K_COUNT
 };

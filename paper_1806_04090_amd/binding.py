@@ -195,7 +195,7 @@ class Context:
     def reserve(self, nbytes: int):
         _check(lib().atomo_reserve(self._h, nbytes), "atomo_reserve")
 
-    KERNEL_CLASSES = ("svd_prepare", "svd_gram", "svd_eig", "svd_update", "svd_finalize", "decode_svd",
+    KERNEL_CLASSES = ("svd_prepare", "svd_gram", "svd_eig", "svd_update", "svd_refresh", "svd_finalize", "decode_svd",
                       "ew_hist", "ew_solve", "ew_sample", "ew_decode")
 
     def profile_enable(self, enable: bool):

@@ -4,22 +4,32 @@
 //
 // Layout.  For a matrix G (rows x cols) let r = min(rows, cols) and M = max(rows, cols).  The r
 // vectors of length M that get orthogonalised (the rows of G, or of G^T when rows > cols) are the
-// rows of a workspace matrix W = [A | T]: A (r x M) starts as those vectors, T (r x r) starts as the
-// identity.  Every rotation is applied to whole rows of W, so at all times  A = T * A0  with T
-// orthogonal, and on convergence row i of A is sigma_i times one singular vector and row i of T is
-// the matching singular vector of the other side.  Rows are padded to blocks of 32 (plus one extra
-// zero block if the number of blocks is odd); columns of A and T are padded to multiples of 64 with
-// zeros, so the kernels need no edge handling.
+// rows of a workspace matrix W = [A | T]: A (r x M) starts as those vectors (times a power of two
+// that brings the largest entry into [1, 2)), T (r x r) starts as the identity.  Every rotation is
+// applied to whole rows of W, so at all times  A = T * A0  with T orthogonal, and on convergence row
+// i of A is sigma_i times one singular vector and row i of T is the matching singular vector of the
+// other side.  Rows are padded to blocks of 32 (plus one extra zero block if the number of blocks is
+// odd); columns of A and T are padded to multiples of 64 with zeros: no edge handling in the kernels.
 //
-// One Jacobi "step" visits, for every matrix at once, one round of a round-robin tournament over
-// its row blocks: for each pair of blocks (64 rows)
-//     svd_gram   : partial 64x64 Gram matrices of the pair over column chunks      (MFMA)
-//     svd_eig    : sums the partials, diagonalises the Gram matrix by two-sided Jacobi in LDS,
-//                  re-orthogonalises the accumulated rotation (one Newton-Schulz step, MFMA) and
-//                  orders its columns by decreasing eigenvalue
-//     svd_update : rows <- Q^T rows over all of W                                   (MFMA)
-// A sweep is R = (#blocks - 1) rounds.  Matrices with fewer blocks simply run through their sweeps
-// faster; a matrix stops when, in one sweep, no pair of rows had |cos| above the threshold.
+// One Jacobi "tick" visits, for every matrix of the call at once, one round of a round-robin
+// tournament over its row blocks.  A sweep is R = (#blocks - 1) rounds.
+//
+// Small matrices (fewer than 8 row blocks) iterate in data space; per tick and block pair (64 rows):
+//     svd_gram<false> : partial 64x64 Gram matrices of the pair over column chunks          (MFMA)
+//     svd_eig         : sums the partials and diagonalises the Gram matrix (see svd_eig.hip)
+//     svd_rowop       : rows <- Q^T rows over all of W                                      (MFMA)
+// and stop after the first sweep in which no pair of rows had |cos| above the threshold.
+//
+// Large matrices iterate in Gram space: the rotations of a pair depend on the rows only through
+// their Gram matrix, so the r x r matrix C = A A^T is formed once (svd_gram<true>, MFMA), the sweeps
+// rotate C two-sidedly and accumulate the rotations in Tgs (svd_eig reads its 64x64 block straight
+// from C; svd_twosided computes C <- D^T C D tile by tile, D being the block rotations of the round,
+// and Tgs <- D^T Tgs), and only when a sweep finds C diagonal to the threshold are the accumulated
+// rotations applied to the data as one contraction W <- Tgs * W (svd_apply, MFMA).  fp32 rounding
+// makes C drift from the true Gram matrix of the rotated rows, so after every application C is
+// formed afresh from the data (svd_gram<true> again); the matrix is finished when that fresh C is
+// diagonal to a quarter of the threshold, otherwise the sweeps continue from it.  The O(M r^2) work
+// thus happens in two or three large contractions instead of in every round.
 #include <cfloat>
 #include <cmath>
 #include <vector>
@@ -32,75 +42,153 @@ namespace {
 
 using namespace svd;
 
+__device__ inline bool refreshing(const SvdMat& m)
+{
+    return m.gs && m.state[ST_DONE_AT] == 0 && m.state[ST_MODE] == MODE_NEED_REFRESH;
+}
 
 // ------------------------------------------------------------------------------------------------
-// prepare: W = [A | T], padded
+// reset / absmax / prepare
 // ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void svd_reset(const SvdMat* mats, int n_mats)
+{
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    const int j = t / ST_WORDS, w = t % ST_WORDS;
+    if (j < n_mats) mats[j].state[w] = (w == ST_FIRST) ? 1 : 0;
+}
+
+__global__ __launch_bounds__(256) void svd_absmax(const SvdMat* mats, const Work* work)
+{
+    __shared__ float red[4];
+    const Work wk = work[blockIdx.x];
+    const SvdMat m = mats[wk.mat];
+    const int row0 = wk.a * BS;
+    const int c = wk.b * 256 + threadIdx.x;
+    float mx = 0.0f;
+    if (c < m.M) {
+        for (int i = row0; i < min(m.r, row0 + BS); ++i) {
+            const float v = m.transposed ? m.G[(long long)c * m.ldg + i] : m.G[(long long)i * m.ldg + c];
+            mx = fmaxf(mx, fabsf(v));
+        }
+    }
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_down(mx, o));
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        if (mx > 0.0f && mx <= FLT_MAX) atomicMax((unsigned int*)&m.state[ST_ABSMAX], __float_as_uint(mx));
+    }
+}
+
+// exponent e such that absmax * 2^-e lies in [1, 2); 0 for an all-zero matrix
+__device__ inline int scale_exponent(const SvdMat& m)
+{
+    const unsigned int bits = (unsigned int)m.state[ST_ABSMAX];
+    if (bits == 0u) return 0;
+    const int e = (int)(bits >> 23) - 127;
+    return e < -126 ? -126 : e;
+}
+
 __global__ __launch_bounds__(256) void svd_prepare(const SvdMat* mats, const Work* work)
 {
     const Work wk = work[blockIdx.x];
     const SvdMat m = mats[wk.mat];
     const int row0 = wk.a * BS;
     const int c = wk.b * 256 + threadIdx.x;
-    if (wk.a == 0 && wk.b == 0 && threadIdx.x < ST_WORDS) m.state[threadIdx.x] = 0;
+    const int e = scale_exponent(m);
+    if (wk.a == 0 && wk.b == 0 && threadIdx.x == 0) m.state[ST_EXP] = e;
     if (c >= m.ldw) return;
+    const float factor = ldexpf(1.0f, -e);
     for (int i = row0; i < row0 + BS; ++i) {
         float v = 0.0f;
         if (i < m.r) {
-            if (c < m.M) v = m.transposed ? m.G[(long long)c * m.ldg + i] : m.G[(long long)i * m.ldg + c];
+            if (c < m.M) v = factor * (m.transposed ? m.G[(long long)c * m.ldg + i] : m.G[(long long)i * m.ldg + c]);
             else if (c - m.Mp == i) v = 1.0f;
         }
-        m.W[(size_t)i * m.ldw + c] = v;
+        m.W[0][(size_t)i * m.ldw + c] = v;
     }
 }
 
 // ------------------------------------------------------------------------------------------------
-// gram: partial Gram matrix of one 64-row pair over one column chunk
+// gram: partial Gram matrix of 64 rows against 64 rows over one column chunk.
+//   FULL = false: the two row blocks of a tournament pair against themselves (data-space matrices)
+//   FULL = true : tile (ti, tj), ti <= tj, of the full r x r Gram matrix (Gram-space matrices, refresh)
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void svd_gram(const SvdMat* mats, const Work* work, int step, int max_sweeps)
+template <bool FULL>
+__global__ __launch_bounds__(256) void svd_gram(const SvdMat* mats, const Work* work, int tick, int max_sweeps)
 {
-    __shared__ float tile[PR][68];
+    __shared__ float tile[FULL ? 2 * PR : PR][68];
     const Work wk = work[blockIdx.x];
     const SvdMat m = mats[wk.mat];
-    if (skip_step(m, step, max_sweeps)) return;
-    int bi, bj;
-    pair_blocks(m.nb2, step % m.R, wk.a, bi, bj);
-    const int c_begin = wk.b * KCG;
+    int rowA0, rowA1, rowB0, rowB1, chunk, out_index;
+    const float* W;
+    if (FULL) {
+        if (!refreshing(m)) return;
+        const int cur = m.state[ST_CUR] & 1;
+        W = m.W[m.state[ST_FIRST] ? cur : cur ^ 1];              // what svd_apply has just written
+        const int ti = wk.a, tj = wk.b, nt = m.nb2 / 2;
+        rowA0 = ti * PR; rowA1 = rowA0 + BS; rowB0 = tj * PR; rowB1 = rowB0 + BS;
+        chunk = wk.c;
+        out_index = ti * nt - ti * (ti - 1) / 2 + (tj - ti);
+    } else {
+        if (m.gs || skip_step(m, tick, max_sweeps)) return;
+        W = m.W[0];
+        int bi, bj;
+        pair_blocks(m.nb2, tick % m.R, wk.a, bi, bj);
+        rowA0 = rowB0 = bi * BS; rowA1 = rowB1 = bj * BS;
+        chunk = wk.b;
+        out_index = wk.a;
+    }
+    const bool same = !FULL || rowA0 == rowB0;
+    const int c_begin = chunk * KCG;
     const int c_end = min(m.Mp, c_begin + KCG);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int qi = wave >> 1, qj = wave & 1;
     const int h = lane >> 5, l32 = lane & 31;
-    // loader mapping: 16 threads per row (float4 each), 16 rows per pass, 4 passes
+    // loader mapping: 16 threads per row (float4 each), 16 rows per pass
     const int lrow = tid >> 4, lc4 = (tid & 15) * 4;
+    const int boff = same ? 0 : PR;                              // where the B rows sit in the tile
 
     floatx16 acc;
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 
     for (int c0 = c_begin; c0 < c_end; c0 += 64) {
-        float4 ld[4];
+        float4 ld[FULL ? 8 : 4];
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
-            const int lr = lrow + 16 * p;                       // 0..63
-            const int grow = (lr < BS ? bi * BS + lr : bj * BS + lr - BS);
-            ld[p] = *(const float4*)(m.W + (size_t)grow * m.ldw + c0 + lc4);
+            const int lr = lrow + 16 * p;                        // 0..63
+            const int grow = (lr < BS ? rowA0 + lr : rowA1 + lr - BS);
+            ld[p] = *(const float4*)(W + (size_t)grow * m.ldw + c0 + lc4);
+        }
+        if (FULL && !same) {
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const int lr = lrow + 16 * p;
+                const int grow = (lr < BS ? rowB0 + lr : rowB1 + lr - BS);
+                ld[4 + p] = *(const float4*)(W + (size_t)grow * m.ldw + c0 + lc4);
+            }
         }
         __syncthreads();                                         // previous tile fully consumed
 #pragma unroll
         for (int p = 0; p < 4; ++p) *(float4*)&tile[lrow + 16 * p][lc4] = ld[p];
+        if (FULL && !same) {
+#pragma unroll
+            for (int p = 0; p < 4; ++p) *(float4*)&tile[PR + lrow + 16 * p][lc4] = ld[4 + p];
+        }
         __syncthreads();
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
             const float4 a = *(const float4*)&tile[qi * BS + l32][h * 32 + 4 * s];
-            const float4 b = *(const float4*)&tile[qj * BS + l32][h * 32 + 4 * s];
+            const float4 b = *(const float4*)&tile[boff + qj * BS + l32][h * 32 + 4 * s];
             acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, acc, 0, 0, 0);
             acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.y, acc, 0, 0, 0);
             acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b.z, acc, 0, 0, 0);
             acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b.w, acc, 0, 0, 0);
         }
     }
-    float* out = m.gram + ((size_t)wk.a * m.nchg + wk.b) * QSZ;
+    float* out = m.gram + ((size_t)out_index * m.nchg + chunk) * QSZ;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
         const int i = qi * BS + 8 * (v >> 2) + 4 * h + (v & 3);
@@ -108,16 +196,102 @@ __global__ __launch_bounds__(256) void svd_gram(const SvdMat* mats, const Work* 
     }
 }
 
+// Sums the partial tiles of the full Gram matrix into C (both triangles) and resets Tgs to I.
+__global__ __launch_bounds__(256) void svd_fullgram_reduce(const SvdMat* mats, const Work* work)
+{
+    __shared__ float t[PR][PR + 1];
+    const Work wk = work[blockIdx.x];
+    const SvdMat m = mats[wk.mat];
+    if (!refreshing(m)) return;
+    const int ti = wk.a, tj = wk.b, nt = m.nb2 / 2;
+    const int tile_index = ti * nt - ti * (ti - 1) / 2 + (tj - ti);
+    const float* g = m.gram + (size_t)tile_index * m.nchg * QSZ;
+    const int tid = threadIdx.x;
+    for (int e = tid; e < QSZ; e += 256) {
+        float sum = 0.0f;
+        for (int c = 0; c < m.nchg; ++c) sum += g[(size_t)c * QSZ + e];
+        t[e >> 6][e & 63] = sum;
+    }
+    __syncthreads();
+    const int Rp = m.rows_alloc;
+    for (int e = tid; e < QSZ; e += 256) {
+        const int i = e >> 6, j = e & 63;
+        const float v = ti == tj ? 0.5f * (t[i][j] + t[j][i]) : t[i][j];
+        m.CT[(size_t)(ti * PR + i) * m.ldc + tj * PR + j] = v;
+        m.CT[(size_t)(ti * PR + i) * m.ldc + Rp + tj * PR + j] = (ti == tj && i == j) ? 1.0f : 0.0f;
+        if (ti != tj) {                                          // mirrored tile: row index runs over j
+            m.CT[(size_t)(tj * PR + i) * m.ldc + ti * PR + j] = t[j][i];
+            m.CT[(size_t)(tj * PR + i) * m.ldc + Rp + ti * PR + j] = 0.0f;
+        }
+    }
+}
+
+// Largest |cos| between two rows according to the fresh Gram matrix; the last tile to finish decides
+// whether the matrix is done or sweeps on.
+__global__ __launch_bounds__(256) void svd_fresh_check(const SvdMat* mats, const Work* work, int tick, int max_sweeps,
+                                                       float stop_cosine, float fresh_stop, int* flags)
+{
+    __shared__ float red[8];
+    const Work wk = work[blockIdx.x];
+    const SvdMat m = mats[wk.mat];
+    if (!refreshing(m)) return;
+    const int ti = wk.a, tj = wk.b;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const float z2 = ZERO_REL * __int_as_float(m.state[ST_SCALE]);
+    float mx = 0.0f, dmax = 0.0f;
+    for (int e = tid; e < QSZ; e += 256) {
+        const int gi = ti * PR + (e >> 6), gj = tj * PR + (e & 63);
+        if (gi < gj) {
+            const float dii = m.CT[(size_t)gi * m.ldc + gi], djj = m.CT[(size_t)gj * m.ldc + gj];
+            if (dii > 0.0f && djj > 0.0f)
+                mx = fmaxf(mx, fabsf(m.CT[(size_t)gi * m.ldc + gj]) / fmaxf(sqrtf(dii * djj), z2));
+        } else if (gi == gj) {
+            dmax = fmaxf(dmax, m.CT[(size_t)gi * m.ldc + gi]);
+        }
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+        mx = fmaxf(mx, __shfl_down(mx, o));
+        dmax = fmaxf(dmax, __shfl_down(dmax, o));
+    }
+    if (lane == 0) { red[wave] = mx; red[4 + wave] = dmax; }
+    __syncthreads();
+    if (tid != 0) return;
+    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    dmax = fmaxf(fmaxf(red[4], red[5]), fmaxf(red[6], red[7]));
+    atomicMax((unsigned int*)&m.state[ST_FRESH], __float_as_uint(mx));
+    atomicMax((unsigned int*)&m.state[ST_SCALE_NEXT], __float_as_uint(dmax));
+    __threadfence();
+    const int arrived = atomicAdd(&m.state[ST_ARRIVE2], 1);
+    if (arrived != m.ntiles - 1) return;
+    __threadfence();
+    const float fresh = __uint_as_float(atomicAdd((unsigned int*)&m.state[ST_FRESH], 0u));
+    const int sweeps = m.state[ST_SWEEPS];
+    if (!m.state[ST_FIRST]) m.state[ST_CUR] = (m.state[ST_CUR] & 1) ^ 1;     // svd_apply wrote the other buffer
+    m.state[ST_FIRST] = 0;
+    if (fresh < fresh_stop || sweeps >= max_sweeps) {
+        m.state[ST_MODE] = MODE_DONE;
+        m.state[ST_DONE_AT] = tick + 1;
+        if (!(fresh < stop_cosine)) atomicMax(&flags[FLAG_NOCONV], 1);
+    } else {
+        m.state[ST_MODE] = MODE_SWEEPS;
+    }
+    m.state[ST_FRESH] = 0;
+    m.state[ST_ARRIVE2] = 0;
+    m.state[ST_OFFMAX] = 0;
+    const unsigned int grown = atomicAdd((unsigned int*)&m.state[ST_SCALE_NEXT], 0u);
+    if (grown > (unsigned int)m.state[ST_SCALE]) m.state[ST_SCALE] = (int)grown;
+}
+
 // ------------------------------------------------------------------------------------------------
-// update: rows of the pair <- Q^T rows, over one 256-column chunk of W (in place)
+// rowop: data-space matrices, the 64 rows of a pair <- Q^T rows, over one 256-column chunk of W (in place)
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void svd_update(const SvdMat* mats, const Work* work, int step, int max_sweeps)
+__global__ __launch_bounds__(256) void svd_rowop(const SvdMat* mats, const Work* work, int tick, int max_sweeps)
 {
     const Work wk = work[blockIdx.x];
     const SvdMat m = mats[wk.mat];
-    if (skip_step(m, step, max_sweeps)) return;
+    if (m.gs || skip_step(m, tick, max_sweeps)) return;
     int bi, bj;
-    pair_blocks(m.nb2, step % m.R, wk.a, bi, bj);
+    pair_blocks(m.nb2, tick % m.R, wk.a, bi, bj);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int h = lane >> 5, l32 = lane & 31;
     const int c0 = wk.b * KCU + wave * 64;
@@ -132,13 +306,13 @@ __global__ __launch_bounds__(256) void svd_update(const SvdMat* mats, const Work
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[e][ib][v] = 0.0f;
 
-    float* rowI = m.W + (size_t)bi * BS * m.ldw + c0 + 2 * l32;
-    float* rowJ = m.W + (size_t)bj * BS * m.ldw + c0 + 2 * l32;
+    float* rowI = m.W[0] + (size_t)bi * BS * m.ldw + c0 + 2 * l32;
+    float* rowJ = m.W[0] + (size_t)bj * BS * m.ldw + c0 + 2 * l32;
 #pragma unroll 4
     for (int s = 0; s < 32; ++s) {
         const int k = 2 * s + h;                                 // local row of the pair, 0..63
-        const float* src = (k < BS ? rowI + (size_t)k * m.ldw : rowJ + (size_t)(k - BS) * m.ldw);
-        const float2 x = *(const float2*)src;
+        const float* p = (k < BS ? rowI + (size_t)k * m.ldw : rowJ + (size_t)(k - BS) * m.ldw);
+        const float2 x = *(const float2*)p;
         const float q0 = q[k * PR + l32];                        // (Q^T)[i][k], i in block 0
         const float q1 = q[k * PR + BS + l32];                   //              i in block 1
         acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(q0, x.x, acc[0][0], 0, 0, 0);
@@ -157,6 +331,132 @@ __global__ __launch_bounds__(256) void svd_update(const SvdMat* mats, const Work
     }
 }
 
+// Gram-space matrices: the two-sided update  C <- D^T C D  (D = the block rotations of the round) and
+// Tgs <- D^T Tgs, one 64x64 tile per workgroup, in place.
+//   kind 1: tile (pair a, pair b) of C:  Qa^T * C[rows of a, columns of b] * Qb
+//   kind 2: 64 rows of pair a x 64 columns of Tgs:  Qa^T * Tgs[rows of a, chunk]
+__global__ __launch_bounds__(256) void svd_twosided(const SvdMat* mats, const Work* work, int tick)
+{
+    __shared__ float xs[PR][PR + 1];
+    __shared__ float ys[PR][PR + 1];
+    const Work wk = work[blockIdx.x];
+    const SvdMat m = mats[wk.mat];
+    if (m.state[ST_QTICK] != tick + 1) return;                   // svd_eig did not run for this matrix in this tick
+    const int kind = wk.c;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int qi = wave >> 1, qj = wave & 1, h = lane >> 5, l32 = lane & 31;
+    int ai, aj, bi = 0, bj = 0;
+    pair_blocks(m.nb2, tick % m.R, wk.a, ai, aj);
+    if (kind == 1) pair_blocks(m.nb2, tick % m.R, wk.b, bi, bj);
+    const float* qa = m.Q + (size_t)wk.a * QSZ;
+    const float* qb = m.Q + (size_t)wk.b * QSZ;
+    // column of local index j: inside C the columns of pair b, inside Tgs a plain 64-column chunk
+    auto col_of = [&](int j) { return kind == 1 ? (j < BS ? bi * BS + j : bj * BS + j - BS) : m.rows_alloc + wk.b * PR + j; };
+    auto row_of = [&](int i) { return i < BS ? ai * BS + i : aj * BS + i - BS; };
+
+    // every global load of the workgroup is issued before the first use: the tile, and the MFMA
+    // operands that come from Qa and Qb
+    float tile_regs[QSZ / 256], qa_regs[PR / 2], qb_regs[PR / 2];
+#pragma unroll
+    for (int p = 0; p < QSZ / 256; ++p) {
+        const int e = tid + 256 * p, i = e >> 6, j = e & 63;
+        tile_regs[p] = m.CT[(size_t)row_of(i) * m.ldc + col_of(j)];
+    }
+#pragma unroll
+    for (int s = 0; s < PR / 2; ++s) {
+        qa_regs[s] = qa[(2 * s + h) * PR + qi * BS + l32];       // (Qa^T)[i][k]
+        qb_regs[s] = kind == 1 ? qb[(2 * s + h) * PR + qj * BS + l32] : 0.0f;    // Qb[k][j]
+    }
+#pragma unroll
+    for (int p = 0; p < QSZ / 256; ++p) {
+        const int e = tid + 256 * p;
+        xs[e >> 6][e & 63] = tile_regs[p];
+    }
+    __syncthreads();
+    floatx16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+#pragma unroll
+    for (int s = 0; s < PR / 2; ++s)
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(qa_regs[s], xs[2 * s + h][qj * BS + l32], acc, 0, 0, 0);
+    if (kind == 1) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) ys[qi * BS + 8 * (v >> 2) + 4 * h + (v & 3)][qj * BS + l32] = acc[v];
+        __syncthreads();
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+#pragma unroll
+        for (int s = 0; s < PR / 2; ++s)
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(ys[qi * BS + l32][2 * s + h], qb_regs[s], acc, 0, 0, 0);
+    }
+    const int c = col_of(qj * BS + l32);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int i = qi * BS + 8 * (v >> 2) + 4 * h + (v & 3);
+        m.CT[(size_t)row_of(i) * m.ldc + c] = acc[v];
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// apply: W[other] <- Tgs * W[cur] for a Gram-space matrix (64 output rows x 256 columns per workgroup)
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void svd_apply(const SvdMat* mats, const Work* work)
+{
+    __shared__ float tt[PR][PR + 1];
+    const Work wk = work[blockIdx.x];
+    const SvdMat m = mats[wk.mat];
+    if (!refreshing(m) || m.state[ST_FIRST]) return;
+    const int cur = m.state[ST_CUR] & 1;
+    const float* src = m.W[cur];
+    float* dst = m.W[cur ^ 1];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int h = lane >> 5, l32 = lane & 31;
+    const int row0 = wk.a * PR;
+    const int c0 = wk.b * KCU + wave * 64;
+    const bool active = c0 < m.ldw;                              // all waves take part in the staging
+    const int Rp = m.rows_alloc;
+    const float* T = m.CT + Rp;                                  // Tgs: columns Rp.. of [C | Tgs]
+
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int e = 0; e < 2; ++e)
+#pragma unroll
+        for (int ib = 0; ib < 2; ++ib)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[e][ib][v] = 0.0f;
+
+    for (int k0 = 0; k0 < Rp; k0 += PR) {
+        __syncthreads();
+        for (int e = tid; e < QSZ; e += 256)
+            tt[e >> 6][e & 63] = T[(size_t)(row0 + (e >> 6)) * m.ldc + k0 + (e & 63)];
+        __syncthreads();
+        if (active) {
+            const float* x0 = src + (size_t)k0 * m.ldw + c0 + 2 * l32;
+#pragma unroll 4
+            for (int s = 0; s < 32; ++s) {
+                const int k = 2 * s + h;
+                const float2 x = *(const float2*)(x0 + (size_t)k * m.ldw);
+                const float a0 = tt[l32][k];                     // Tgs[row0 + i][k0 + k], i in block 0
+                const float a1 = tt[BS + l32][k];
+                acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, x.x, acc[0][0], 0, 0, 0);
+                acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, x.y, acc[1][0], 0, 0, 0);
+                acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, x.x, acc[0][1], 0, 0, 0);
+                acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, x.y, acc[1][1], 0, 0, 0);
+            }
+        }
+    }
+    if (!active) return;
+#pragma unroll
+    for (int ib = 0; ib < 2; ++ib) {
+        float* base = dst + (size_t)(row0 + ib * BS) * m.ldw + c0 + 2 * l32;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int i = 8 * (v >> 2) + 4 * h + (v & 3);
+            *(float2*)(base + (size_t)i * m.ldw) = make_float2(acc[0][ib][v], acc[1][ib][v]);
+        }
+    }
+}
+
 // ------------------------------------------------------------------------------------------------
 // finalise: singular values, Algorithm 1, Bernoulli draws, message
 // ------------------------------------------------------------------------------------------------
@@ -167,7 +467,7 @@ __global__ __launch_bounds__(256) void svd_norms(const SvdMat* mats, const Work*
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int row = wk.a * 4 + wave;
     if (row >= m.rows_alloc) return;
-    const float* a = m.W + (size_t)row * m.ldw;
+    const float* a = current_w(m) + (size_t)row * m.ldw;
     float sum = 0.0f;
     for (int c = lane * 4; c < m.Mp; c += 256) {
         const float4 x = *(const float4*)(a + c);
@@ -175,11 +475,11 @@ __global__ __launch_bounds__(256) void svd_norms(const SvdMat* mats, const Work*
     }
     for (int o = 32; o > 0; o >>= 1) sum += __shfl_down(sum, o);
     if (lane == 0) {
-        if (init) {                                                  // before the first sweep: scale of the matrix
+        if (init) {                                              // before the first sweep: scale of the matrix
             atomicMax((unsigned int*)&m.state[ST_SCALE], __float_as_uint(sum));
             atomicMax((unsigned int*)&m.state[ST_SCALE_NEXT], __float_as_uint(sum));
-        } else {
-            m.sig_raw[row] = row < m.r ? sqrtf(sum) : 0.0f;
+        } else {                                                 // singular values, input scaling undone
+            m.sig_raw[row] = row < m.r ? ldexpf(sqrtf(sum), m.state[ST_EXP]) : 0.0f;
         }
     }
 }
@@ -228,6 +528,7 @@ __global__ __launch_bounds__(256) void svd_select(const SvdMat* mats, double s, 
         *m.count = total;
         if (total > m.capacity) atomicMax(&flags[FLAG_CAPACITY], 1);
     }
+    const float unscale = ldexpf(1.0f, -m.state[ST_EXP]);       // sigma in the units of the scaled rows of W
     for (int i = lo; i < hi; ++i) {
         const float p = alg1_probability(key[i], i, ns, s, tail_ns);
         const u32x4 rnd = philox4x32_10((unsigned long long)(i >> 2), m.stream_id, seed);
@@ -237,7 +538,7 @@ __global__ __launch_bounds__(256) void svd_select(const SvdMat* mats, double s, 
                 m.idx[pos] = i;
                 m.w[pos] = key[i] / p;
                 m.src_row[pos] = src[i];
-                m.src_inv[pos] = 1.0f / key[i];
+                m.src_inv[pos] = 1.0f / (key[i] * unscale);
             }
             ++pos;
         }
@@ -254,7 +555,7 @@ __global__ __launch_bounds__(256) void svd_pack(const SvdMat* mats, const Work* 
     if (slot >= kept) return;
     const int row = m.src_row[slot];
     const float inv = m.src_inv[slot];
-    const float* a = m.W + (size_t)row * m.ldw;
+    const float* a = current_w(m) + (size_t)row * m.ldw;
     float* long_out = m.transposed ? m.U + (size_t)slot * m.rows : m.V + (size_t)slot * m.cols;
     float* short_out = m.transposed ? m.V + (size_t)slot * m.cols : m.U + (size_t)slot * m.rows;
     for (int c = threadIdx.x; c < m.M; c += 256) long_out[c] = a[c] * inv;
@@ -263,11 +564,18 @@ __global__ __launch_bounds__(256) void svd_pack(const SvdMat* mats, const Work* 
 
 struct Plan {
     std::vector<SvdMat> mats;
-    std::vector<Work> prep, gram, eig, upd, norms, pack;
+    std::vector<Work> prep, gram, fullgram, tiles, apply, eig, rowop1, twosided, norms, pack;
+    std::vector<int> gs_periods;     // distinct R of the Gram-space matrices
     int max_R = 1;
+    int max_R_ds = 1;                // largest R among the data-space matrices
     size_t bytes = 0;
-    SvdMat* d_mats = nullptr;    // device copies of `mats` and of the concatenated work lists
+    SvdMat* d_mats = nullptr;        // device copies of `mats` and of the concatenated work lists
     Work* d_work = nullptr;
+    size_t n_work() const
+    {
+        return prep.size() + gram.size() + fullgram.size() + tiles.size() + apply.size() + eig.size() +
+               rowop1.size() + twosided.size() + norms.size() + pack.size();
+    }
 };
 
 // Lays the workspace out (base == nullptr: sizes only).
@@ -294,8 +602,15 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
         m.npairs = m.nb2 / 2;
         m.nchg = (m.Mp + KCG - 1) / KCG;
         m.nchu = (m.ldw + KCU - 1) / KCU;
-        m.W = carve.take<float>((size_t)m.rows_alloc * m.ldw);
-        m.gram = carve.take<float>((size_t)m.npairs * m.nchg * QSZ);
+        m.gs = m.nb2 >= GS_MIN_BLOCKS;
+        const int nt = m.nb2 / 2;
+        m.ntiles = nt * (nt + 1) / 2;
+        m.ldc = 2 * m.rows_alloc;
+        m.W[0] = carve.take<float>((size_t)m.rows_alloc * m.ldw);
+        m.W[1] = m.gs ? carve.take<float>((size_t)m.rows_alloc * m.ldw) : nullptr;
+        m.CT = m.gs ? carve.take<float>((size_t)m.rows_alloc * m.ldc) : nullptr;
+        m.C2 = nullptr;
+        m.gram = carve.take<float>((size_t)(m.gs ? m.ntiles : m.npairs) * m.nchg * QSZ);
         m.Q = carve.take<float>((size_t)m.npairs * QSZ);
         m.state = carve.take<int>(ST_WORDS);
         m.sig_raw = carve.take<float>(m.rows_alloc);
@@ -314,19 +629,35 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
         atom_off += m.r;
         m.stream_id = stream_base + (uint64_t)j;
         if (m.R > plan.max_R) plan.max_R = m.R;
+        if (!m.gs && m.R > plan.max_R_ds) plan.max_R_ds = m.R;
         for (int b = 0; b < m.nb2; ++b)
             for (int c = 0; c < (m.ldw + 255) / 256; ++c) plan.prep.push_back(Work{j, b, c, 0});
         for (int k = 0; k < m.npairs; ++k) {
-            for (int c = 0; c < m.nchg; ++c) plan.gram.push_back(Work{j, k, c, 0});
             plan.eig.push_back(Work{j, k, 0, 0});
-            for (int c = 0; c < m.nchu; ++c) plan.upd.push_back(Work{j, k, c, 0});
+            if (m.gs) {
+                for (int k2 = 0; k2 < m.npairs; ++k2) plan.twosided.push_back(Work{j, k, k2, 1});
+                for (int c = 0; c < m.rows_alloc / PR; ++c) plan.twosided.push_back(Work{j, k, c, 2});
+            } else {
+                for (int c = 0; c < m.nchg; ++c) plan.gram.push_back(Work{j, k, c, 0});
+                for (int c = 0; c < m.nchu; ++c) plan.rowop1.push_back(Work{j, k, c, 0});
+            }
+        }
+        if (m.gs) {
+            bool seen = false;
+            for (int p : plan.gs_periods) seen = seen || p == m.R;
+            if (!seen) plan.gs_periods.push_back(m.R);
+            for (int ti = 0; ti < nt; ++ti)
+                for (int tj = ti; tj < nt; ++tj) {
+                    plan.tiles.push_back(Work{j, ti, tj, 0});
+                    for (int c = 0; c < m.nchg; ++c) plan.fullgram.push_back(Work{j, ti, tj, c});
+                }
+            for (int t = 0; t < nt; ++t)
+                for (int c = 0; c < m.nchu; ++c) plan.apply.push_back(Work{j, t, c, 0});
         }
         for (int g = 0; g < m.rows_alloc / 4; ++g) plan.norms.push_back(Work{j, g, 0, 0});
         for (int k = 0; k < m.capacity; ++k) plan.pack.push_back(Work{j, k, 0, 0});
     }
-    const size_t n_work = plan.prep.size() + plan.gram.size() + plan.eig.size() + plan.upd.size() +
-                          plan.norms.size() + plan.pack.size();
-    plan.d_work = carve.take<Work>(n_work);
+    plan.d_work = carve.take<Work>(plan.n_work());
     plan.bytes = carve.off;
 }
 
@@ -352,6 +683,7 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     const float stop_cosine = opt ? opt->stop_cosine : 1e-4f;
     const int max_inner = opt && opt->max_inner_sweeps > 0 ? opt->max_inner_sweeps : 1;
     const float inner_reduction = opt && opt->inner_reduction > 0.0f ? opt->inner_reduction : 0.01f;
+    const float fresh_stop = 0.25f * stop_cosine;
 
     Plan sizing;
     build_plan(mats, n_mats, msgs, sigma_out, p_out, stream_base, nullptr, sizing);
@@ -360,59 +692,75 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
 
     Plan plan;
     build_plan(mats, n_mats, msgs, sigma_out, p_out, stream_base, ctx->ws, plan);
-
     SvdMat* d_mats = plan.d_mats;
-    Work* d_work = plan.d_work;
     ctx->svd_state.clear();
     for (const SvdMat& m : plan.mats) ctx->svd_state.push_back(m.state);
-    const size_t n_work = plan.prep.size() + plan.gram.size() + plan.eig.size() + plan.upd.size() +
-                          plan.norms.size() + plan.pack.size();
+
     std::vector<Work> all;
-    all.reserve(n_work);
-    const size_t o_prep = 0;
-    all.insert(all.end(), plan.prep.begin(), plan.prep.end());
-    const size_t o_gram = all.size();
-    all.insert(all.end(), plan.gram.begin(), plan.gram.end());
-    const size_t o_eig = all.size();
-    all.insert(all.end(), plan.eig.begin(), plan.eig.end());
-    const size_t o_upd = all.size();
-    all.insert(all.end(), plan.upd.begin(), plan.upd.end());
-    const size_t o_norms = all.size();
-    all.insert(all.end(), plan.norms.begin(), plan.norms.end());
-    const size_t o_pack = all.size();
-    all.insert(all.end(), plan.pack.begin(), plan.pack.end());
+    all.reserve(plan.n_work());
+    auto place = [&](const std::vector<Work>& list) {
+        const Work* at = plan.d_work + all.size();
+        all.insert(all.end(), list.begin(), list.end());
+        return at;
+    };
+    const Work* w_prep = place(plan.prep);
+    const Work* w_gram = place(plan.gram);
+    const Work* w_fullgram = place(plan.fullgram);
+    const Work* w_tiles = place(plan.tiles);
+    const Work* w_apply = place(plan.apply);
+    const Work* w_eig = place(plan.eig);
+    const Work* w_rowop1 = place(plan.rowop1);
+    const Work* w_twosided = place(plan.twosided);
+    const Work* w_norms = place(plan.norms);
+    const Work* w_pack = place(plan.pack);
 
     rc = upload(ctx, d_mats, plan.mats.data(), plan.mats.size() * sizeof(SvdMat), stream);
     if (rc != ATOMO_OK) return rc;
-    rc = upload(ctx, d_work, all.data(), all.size() * sizeof(Work), stream);
+    rc = upload(ctx, plan.d_work, all.data(), all.size() * sizeof(Work), stream);
     if (rc != ATOMO_OK) return rc;
 
+    auto grid = [](const std::vector<Work>& list) { return (unsigned)list.size(); };
     {
         ProfScope ps(ctx, ATOMO_K_SVD_PREPARE, stream);
-        svd_prepare<<<(unsigned)plan.prep.size(), 256, 0, stream>>>(d_mats, d_work + o_prep);
-        svd_norms<<<(unsigned)plan.norms.size(), 256, 0, stream>>>(d_mats, d_work + o_norms, 1);
+        svd_reset<<<(unsigned)((n_mats * ST_WORDS + 255) / 256), 256, 0, stream>>>(d_mats, n_mats);
+        svd_absmax<<<grid(plan.prep), 256, 0, stream>>>(d_mats, w_prep);
+        svd_prepare<<<grid(plan.prep), 256, 0, stream>>>(d_mats, w_prep);
+        svd_norms<<<grid(plan.norms), 256, 0, stream>>>(d_mats, w_norms, 1);
     }
-    const int n_steps = max_sweeps * plan.max_R;
-    for (int step = 0; step < n_steps; ++step) {
-        {
+    const int n_ticks = max_sweeps * plan.max_R + 1;
+    for (int tick = 0; tick < n_ticks; ++tick) {
+        bool boundary = false;
+        for (int period : plan.gs_periods) boundary = boundary || tick % period == 0;
+        if (boundary) {
+            ProfScope ps(ctx, ATOMO_K_SVD_REFRESH, stream);
+            svd_apply<<<grid(plan.apply), 256, 0, stream>>>(d_mats, w_apply);
+            svd_gram<true><<<grid(plan.fullgram), 256, 0, stream>>>(d_mats, w_fullgram, tick, max_sweeps);
+            svd_fullgram_reduce<<<grid(plan.tiles), 256, 0, stream>>>(d_mats, w_tiles);
+            svd_fresh_check<<<grid(plan.tiles), 256, 0, stream>>>(d_mats, w_tiles, tick, max_sweeps, stop_cosine,
+                                                                  fresh_stop, ctx->d_flags);
+        }
+        const bool ds_active = !plan.gram.empty() && tick < max_sweeps * plan.max_R_ds;
+        if (ds_active) {
             ProfScope ps(ctx, ATOMO_K_SVD_GRAM, stream);
-            svd_gram<<<(unsigned)plan.gram.size(), 256, 0, stream>>>(d_mats, d_work + o_gram, step, max_sweeps);
+            svd_gram<false><<<grid(plan.gram), 256, 0, stream>>>(d_mats, w_gram, tick, max_sweeps);
         }
         {
             ProfScope ps(ctx, ATOMO_K_SVD_EIG, stream);
-            launch_svd_eig(d_mats, d_work + o_eig, (int)plan.eig.size(), step, max_sweeps, stop_cosine,
-                           max_inner, inner_reduction, ctx->d_flags, stream);
+            launch_svd_eig(d_mats, w_eig, (int)plan.eig.size(), tick, max_sweeps, stop_cosine, max_inner,
+                           inner_reduction, ctx->d_flags, stream);
         }
         {
             ProfScope ps(ctx, ATOMO_K_SVD_UPDATE, stream);
-            svd_update<<<(unsigned)plan.upd.size(), 256, 0, stream>>>(d_mats, d_work + o_upd, step, max_sweeps);
+            if (ds_active) svd_rowop<<<grid(plan.rowop1), 256, 0, stream>>>(d_mats, w_rowop1, tick, max_sweeps);
+            if (!plan.twosided.empty())
+                svd_twosided<<<grid(plan.twosided), 256, 0, stream>>>(d_mats, w_twosided, tick);
         }
     }
     {
         ProfScope ps(ctx, ATOMO_K_SVD_FINALIZE, stream);
-        svd_norms<<<(unsigned)plan.norms.size(), 256, 0, stream>>>(d_mats, d_work + o_norms, 0);
+        svd_norms<<<grid(plan.norms), 256, 0, stream>>>(d_mats, w_norms, 0);
         svd_select<<<(unsigned)n_mats, 256, 0, stream>>>(d_mats, s, (unsigned long long)seed, ctx->d_flags);
-        svd_pack<<<(unsigned)plan.pack.size(), 256, 0, stream>>>(d_mats, d_work + o_pack);
+        svd_pack<<<grid(plan.pack), 256, 0, stream>>>(d_mats, w_pack);
     }
     ATOMO_HIP(ctx, hipGetLastError());
     return ATOMO_OK;

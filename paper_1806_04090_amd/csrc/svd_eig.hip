@@ -102,20 +102,32 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
 
     const Work wk = work[blockIdx.x];
     const SvdMat m = mats[wk.mat];
-    if (skip_step(m, step, max_sweeps)) return;
+    if (m.gs) {
+        if (m.state[ST_DONE_AT] != 0 || m.state[ST_MODE] != MODE_SWEEPS) return;
+    } else if (skip_step(m, step, max_sweeps)) {
+        return;
+    }
     const int round = step % m.R;
     int bi, bj;
     pair_blocks(m.nb2, round, wk.a, bi, bj);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
-    // 1. sum the partial Gram matrices in a fixed order; symmetrise (the two off-diagonal quadrants
-    //    were accumulated in different orders); Q = I
+    // 1. the Gram matrix of the pair: its block of C (Gram-space matrices), or the partial sums in a
+    //    fixed order (data-space matrices); symmetrise (the two triangles were accumulated in
+    //    different orders); Q = I
     {
         const float* g = m.gram + (size_t)wk.a * m.nchg * QSZ;
+        if (m.gs && tid == 0) m.state[ST_QTICK] = step + 1;
         for (int e = tid; e < QSZ; e += NT) {
             const int i = e >> 6, j = e & 63;
             float sum = 0.0f;
-            for (int c = 0; c < m.nchg; ++c) sum += g[(size_t)c * QSZ + e];
+            if (m.gs) {
+                const int gi = i < BS ? bi * BS + i : bj * BS + i - BS;
+                const int gj = j < BS ? bi * BS + j : bj * BS + j - BS;
+                sum = m.CT[(size_t)gi * m.ldc + gj];
+            } else {
+                for (int c = 0; c < m.nchg; ++c) sum += g[(size_t)c * QSZ + e];
+            }
             As[0][i * ELD + mem_col(j)] = sum;
             Qs[0][i * ELD + mem_col(j)] = (i == j) ? 1.0f : 0.0f;
         }
@@ -290,8 +302,15 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
             const int sweeps = m.state[ST_SWEEPS] + 1;
             m.state[ST_SWEEPS] = sweeps;
             atomicMax(&flags[FLAG_MAX_SWEEPS], sweeps);
-            if (worst < stop_cosine) m.state[ST_DONE_AT] = step + 1;
-            else if (sweeps >= max_sweeps) atomicMax(&flags[FLAG_NOCONV], 1);
+            if (m.gs) {
+                // Gram space: diagonal to the threshold (or out of sweeps) -> apply the rotations to the
+                // data and look at a fresh Gram matrix at the next tick
+                if (worst < stop_cosine || sweeps >= max_sweeps) m.state[ST_MODE] = MODE_NEED_REFRESH;
+            } else if (worst < stop_cosine) {
+                m.state[ST_DONE_AT] = step + 1;
+            } else if (sweeps >= max_sweeps) {
+                atomicMax(&flags[FLAG_NOCONV], 1);
+            }
             m.state[ST_OFFMAX] = 0;
             m.state[ST_ARRIVE] = 0;
             const unsigned int grown = atomicAdd((unsigned int*)&m.state[ST_SCALE_NEXT], 0u);
