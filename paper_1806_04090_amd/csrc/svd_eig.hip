@@ -71,22 +71,25 @@ __device__ inline float lane_value(float x, int src)
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), src));
 }
 
-// Rotation (c, s) that annihilates the off-diagonal entry of the slot pair (2k, 2k+1).  The hardware
-// reciprocal / square-root approximations (1 ulp) are enough: what a rotation misses the next sweep
-// picks up, and the orthogonality of the product is restored by the Newton-Schulz step.
+// Rotation (c, s) that annihilates the off-diagonal entry of the slot pair (2k, 2k+1), from the
+// double-angle form: with d = a_qq - a_pp and w = 2 a_pq,  cos 2t = |d| / sqrt(d^2 + w^2),
+// c = sqrt((1 + cos 2t) / 2),  s = sign(d) w / (2 c sqrt(d^2 + w^2)).  Two reciprocal square roots
+// (hardware approximations, 1 ulp) and no division: what a rotation misses the next sweep picks up,
+// and the orthogonality of the product is restored by the Newton-Schulz step.
 __device__ inline float2 pair_rotation(const float* A, int k, float z2)
 {
     const float app = A[(2 * k) * ELD + k];
     const float apq = A[(2 * k) * ELD + 32 + k];
     const float aqq = A[(2 * k + 1) * ELD + 32 + k];
     float c = 1.0f, s = 0.0f;
-    if (apq != 0.0f && fabsf(apq) > 1e-7f * fmaxf(__builtin_amdgcn_sqrtf(fabsf(app * aqq)), z2)) {
-        const float zeta = (aqq - app) * __builtin_amdgcn_rcpf(2.0f * apq);
-        const float az = fabsf(zeta);
-        // az + sqrt(1 + az^2); for huge |zeta| the square overflows to inf and t becomes 0 (no rotation needed)
-        const float t = copysignf(__builtin_amdgcn_rcpf(az + __builtin_amdgcn_sqrtf(1.0f + az * az)), zeta);
-        c = __builtin_amdgcn_rsqf(1.0f + t * t);
-        s = c * t;
+    // rotate only if |a_pq| > 1e-7 * max(sqrt(a_pp a_qq), floor), compared in squares
+    if (apq * apq > 1e-14f * fmaxf(fabsf(app * aqq), z2 * z2)) {
+        const float d = aqq - app, w = 2.0f * apq;
+        const float ir = __builtin_amdgcn_rsqf(fmaf(d, d, w * w));
+        const float hc = fmaf(0.5f * fabsf(d), ir, 0.5f);        // (1 + cos 2t) / 2 = c^2
+        const float ic = __builtin_amdgcn_rsqf(hc);
+        c = hc * ic;
+        s = copysignf(0.5f * w * ir * ic, d * w);
     }
     return make_float2(c, s);
 }
