@@ -65,12 +65,6 @@ __device__ inline float2 max_cosine(const float* A, float z2, float* red)
     return make_float2(mx, dmax);
 }
 
-// value of x in lane `src` of the wave (src must be wave-uniform)
-__device__ inline float lane_value(float x, int src)
-{
-    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), src));
-}
-
 // Rotation (c, s) that annihilates the off-diagonal entry of the slot pair (2k, 2k+1), from the
 // double-angle form: with d = a_qq - a_pp and w = 2 a_pq,  cos 2t = |d| / sqrt(d^2 + w^2),
 // c = sqrt((1 + cos 2t) / 2),  s = sign(d) w / (2 c sqrt(d^2 + w^2)).  Two reciprocal square roots
@@ -164,55 +158,62 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
     if (entry.x > 0.0f) {
         // inner target: a fixed factor below what came in is enough for the outer iteration
         const float inner_stop = fmaxf(2e-7f, inner_reduction * entry.x);
-        for (int isw = 0; isw < max_inner; ++isw) {
-            for (int t = 0; t < 63; ++t) {
-                const float* X = As[cur];
-                float* Y = As[cur ^ 1];
-                const float* XQ = Qs[cur];
-                float* YQ = Qs[cur ^ 1];
-                // issue every LDS read of the step first; the rotation arithmetic overlaps their latency
-                float xa[RP_PER][4], xq[QR_PER][2];
+        // One step: read buffer X, rotate, write buffer Y with the slots advanced.  Written as a lambda
+        // and called with the buffers swapped so that every LDS address is loop-invariant.
+        auto jacobi_step = [&](const float* X, float* Y, const float* XQ, float* YQ) {
+            // issue every LDS read of the step first; the rotation arithmetic overlaps their latency
+            float xa[RP_PER][4], xq[QR_PER][2];
 #pragma unroll
-                for (int e = 0; e < RP_PER; ++e) {
-                    const int a = grp * RP_PER + e;
-                    xa[e][0] = X[(2 * a) * ELD + b];     xa[e][1] = X[(2 * a) * ELD + 32 + b];
-                    xa[e][2] = X[(2 * a + 1) * ELD + b]; xa[e][3] = X[(2 * a + 1) * ELD + 32 + b];
-                }
-#pragma unroll
-                for (int e = 0; e < QR_PER; ++e) {
-                    const int i = grp * QR_PER + e;
-                    xq[e][0] = XQ[i * ELD + b];
-                    xq[e][1] = XQ[i * ELD + 32 + b];
-                }
-                // every lane computes the rotation of its own column pair b (both halves of the wave
-                // redundantly); the rotations of the row pairs come from the lanes that own them
-                const float2 pb = pair_rotation(X, b, z2);
-#pragma unroll
-                for (int e = 0; e < RP_PER; ++e) {
-                    const int a = grp * RP_PER + e;
-                    const int a_lo = __builtin_amdgcn_readfirstlane(a - (lane >> 5) * RP_PER);   // row pair of lanes 0..31
-                    const float c_lo = lane_value(pb.x, a_lo), s_lo = lane_value(pb.y, a_lo);
-                    const float c_hi = lane_value(pb.x, a_lo + RP_PER), s_hi = lane_value(pb.y, a_lo + RP_PER);
-                    const float2 pa = make_float2(lane < 32 ? c_lo : c_hi, lane < 32 ? s_lo : s_hi);
-                    const float x00 = xa[e][0], x01 = xa[e][1], x10 = xa[e][2], x11 = xa[e][3];
-                    const float y00 = pa.x * x00 - pa.y * x10, y01 = pa.x * x01 - pa.y * x11;
-                    const float y10 = pa.y * x00 + pa.x * x10, y11 = pa.y * x01 + pa.x * x11;
-                    const int r0 = next_slot(2 * a) * ELD, r1 = next_slot(2 * a + 1) * ELD;
-                    Y[r0 + wc0] = pb.x * y00 - pb.y * y01;
-                    Y[r0 + wc1] = pb.y * y00 + pb.x * y01;
-                    Y[r1 + wc0] = pb.x * y10 - pb.y * y11;
-                    Y[r1 + wc1] = pb.y * y10 + pb.x * y11;
-                }
-#pragma unroll
-                for (int e = 0; e < QR_PER; ++e) {
-                    const int i = grp * QR_PER + e;
-                    const float x = xq[e][0], y = xq[e][1];
-                    YQ[i * ELD + wc0] = pb.x * x - pb.y * y;
-                    YQ[i * ELD + wc1] = pb.y * x + pb.x * y;
-                }
-                cur ^= 1;
-                __syncthreads();
+            for (int e = 0; e < RP_PER; ++e) {
+                const int a = grp * RP_PER + e;
+                xa[e][0] = X[(2 * a) * ELD + b];     xa[e][1] = X[(2 * a) * ELD + 32 + b];
+                xa[e][2] = X[(2 * a + 1) * ELD + b]; xa[e][3] = X[(2 * a + 1) * ELD + 32 + b];
             }
+#pragma unroll
+            for (int e = 0; e < QR_PER; ++e) {
+                const int i = grp * QR_PER + e;
+                xq[e][0] = XQ[i * ELD + b];
+                xq[e][1] = XQ[i * ELD + 32 + b];
+            }
+            // every lane computes the rotation of its own column pair b (both halves of the wave
+            // redundantly); the rotation of a row pair is fetched from the lane of this half-wave
+            // that owns it
+            const float2 pb = pair_rotation(X, b, z2);
+#pragma unroll
+            for (int e = 0; e < RP_PER; ++e) {
+                const int a = grp * RP_PER + e;
+                const int from = ((lane & 32) | a) << 2;
+                const float2 pa = make_float2(__int_as_float(__builtin_amdgcn_ds_bpermute(from, __float_as_int(pb.x))),
+                                              __int_as_float(__builtin_amdgcn_ds_bpermute(from, __float_as_int(pb.y))));
+                const float x00 = xa[e][0], x01 = xa[e][1], x10 = xa[e][2], x11 = xa[e][3];
+                const float y00 = pa.x * x00 - pa.y * x10, y01 = pa.x * x01 - pa.y * x11;
+                const float y10 = pa.y * x00 + pa.x * x10, y11 = pa.y * x01 + pa.x * x11;
+                const int r0 = next_slot(2 * a) * ELD, r1 = next_slot(2 * a + 1) * ELD;
+                Y[r0 + wc0] = pb.x * y00 - pb.y * y01;
+                Y[r0 + wc1] = pb.y * y00 + pb.x * y01;
+                Y[r1 + wc0] = pb.x * y10 - pb.y * y11;
+                Y[r1 + wc1] = pb.y * y10 + pb.x * y11;
+            }
+#pragma unroll
+            for (int e = 0; e < QR_PER; ++e) {
+                const int i = grp * QR_PER + e;
+                const float x = xq[e][0], y = xq[e][1];
+                YQ[i * ELD + wc0] = pb.x * x - pb.y * y;
+                YQ[i * ELD + wc1] = pb.y * x + pb.x * y;
+            }
+            __syncthreads();
+        };
+        for (int isw = 0; isw < max_inner; ++isw) {
+            float* A0 = As[cur];
+            float* A1 = As[cur ^ 1];
+            float* Q0 = Qs[cur];
+            float* Q1 = Qs[cur ^ 1];
+            for (int t = 0; t < 62; t += 2) {
+                jacobi_step(A0, A1, Q0, Q1);
+                jacobi_step(A1, A0, Q1, Q0);
+            }
+            jacobi_step(A0, A1, Q0, Q1);
+            cur ^= 1;
             ++inner_done;
             if (isw + 1 < max_inner) {
                 const float2 now = max_cosine(As[cur], z2, red);
