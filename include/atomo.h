@@ -123,8 +123,11 @@ int atomo_last_hip_error(const atomo_ctx* ctx);
 int atomo_last_counters(const atomo_ctx* ctx, int32_t* pair_visits /*host*/, int32_t* inner_sweeps /*host*/);
 
 /* Waits for `stream`, then copies the number of Jacobi sweeps each matrix of the last
- * atomo_encode_svd took into sweeps[0 .. n_mats) (HOST).  n_mats must match that call. */
-int atomo_svd_sweeps(atomo_ctx* ctx, void* stream, int32_t* sweeps /*host*/, int n_mats);
+ * atomo_encode_svd took into sweeps[0 .. n_mats) (HOST) and, if refreshes is not NULL, how many
+ * times the full Gram matrix of the matrix was formed from the data (0 for matrices small enough
+ * to iterate directly on the data).  n_mats must match that call. */
+int atomo_svd_sweeps(atomo_ctx* ctx, void* stream, int32_t* sweeps /*host*/, int32_t* refreshes /*host, optional*/,
+                     int n_mats);
 const char* atomo_strerror(int status);
 
 /* -------- the method --------------------------------------------------------------------------- */

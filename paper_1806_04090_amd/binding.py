@@ -75,7 +75,7 @@ def lib() -> C.CDLL:
         L.atomo_decode.argtypes = [vp, C.c_int, vp, C.c_int, C.c_float, vp, C.c_int64, vp]
         L.atomo_decode_svd_batch.argtypes = [vp, C.POINTER(atomo_svd_msg), C.POINTER(C.c_int32), C.c_int, C.c_float,
                                              C.POINTER(vp), C.POINTER(C.c_int64), vp]
-        L.atomo_svd_sweeps.argtypes = [vp, vp, C.POINTER(C.c_int32), C.c_int]
+        L.atomo_svd_sweeps.argtypes = [vp, vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int]
         L.atomo_last_counters.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         L.atomo_profile_enable.argtypes = [vp, C.c_int]
         L.atomo_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
@@ -218,7 +218,14 @@ class Context:
     def svd_sweeps(self, n_mats: int, stream: Optional[torch.cuda.Stream] = None) -> List[int]:
         """Jacobi sweeps each matrix of the last atomo_encode_svd took (waits for the stream)."""
         out = (C.c_int32 * n_mats)()
-        _check(lib().atomo_svd_sweeps(self._h, _stream_handle(stream), out, n_mats), "atomo_svd_sweeps")
+        _check(lib().atomo_svd_sweeps(self._h, _stream_handle(stream), out, None, n_mats), "atomo_svd_sweeps")
+        return list(out)
+
+    def svd_refreshes(self, n_mats: int, stream: Optional[torch.cuda.Stream] = None) -> List[int]:
+        """How often each matrix of the last atomo_encode_svd had its full Gram matrix formed from the data."""
+        sweeps = (C.c_int32 * n_mats)()
+        out = (C.c_int32 * n_mats)()
+        _check(lib().atomo_svd_sweeps(self._h, _stream_handle(stream), sweeps, out, n_mats), "atomo_svd_sweeps")
         return list(out)
 
     def status(self, stream: Optional[torch.cuda.Stream] = None):

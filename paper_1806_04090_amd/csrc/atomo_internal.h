@@ -143,7 +143,7 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
                const atomo_svd_options* opt, const atomo_svd_msg* msgs, float* sigma_out, float* p_out,
                hipStream_t stream);
 
-int svd_sweeps(atomo_ctx* ctx, hipStream_t stream, int32_t* sweeps, int n_mats);
+int svd_sweeps(atomo_ctx* ctx, hipStream_t stream, int32_t* sweeps, int32_t* refreshes, int n_mats);
 
 size_t entrywise_workspace_bytes(int64_t n);
 int encode_entrywise(atomo_ctx* ctx, const float* g, double s, uint64_t seed, uint64_t stream_id,

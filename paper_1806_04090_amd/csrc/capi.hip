@@ -156,12 +156,12 @@ int atomo_status(atomo_ctx* ctx, void* stream, int32_t* sweeps)
     return ATOMO_OK;
 }
 
-int atomo_svd_sweeps(atomo_ctx* ctx, void* stream, int32_t* sweeps, int n_mats)
+int atomo_svd_sweeps(atomo_ctx* ctx, void* stream, int32_t* sweeps, int32_t* refreshes, int n_mats)
 {
     if (!ctx || !sweeps || n_mats <= 0) return ATOMO_EINVAL;
     DeviceGuard guard(ctx);
     if (!guard.ok) return ATOMO_EHIP;
-    return svd_sweeps(ctx, (hipStream_t)stream, sweeps, n_mats);
+    return svd_sweeps(ctx, (hipStream_t)stream, sweeps, refreshes, n_mats);
 }
 
 int atomo_profile_enable(atomo_ctx* ctx, int enable)

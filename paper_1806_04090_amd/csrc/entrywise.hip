@@ -43,6 +43,7 @@ struct EwState {
     unsigned long long n_s;       // final: number of capped elements
     double tail;                  // final: sum of the uncapped magnitudes
     double budget;                // final: s - n_s
+    double ratio;                 // final: budget / tail, +inf if tail == 0
     unsigned long long total_kept;
 };
 
@@ -65,56 +66,64 @@ __global__ __launch_bounds__(256) void ew_clear(EwState* st)
     if (i < 3 * NBUCKET) { (&st->cnt[0][0])[i] = 0u; (&st->sig[0][0])[i] = 0ull; }
     if (i == 0) {
         st->resolved = 0; st->prefix = 0u; st->n_above = 0ull; st->sum_below = 0.0;
-        st->n_s = 0ull; st->tail = 0.0; st->budget = 0.0; st->total_kept = 0ull;
+        st->n_s = 0ull; st->tail = 0.0; st->budget = 0.0; st->ratio = 0.0; st->total_kept = 0ull;
     }
 }
 
 // Histogram of one level.  Elements are visited as float4 where the pointer allows.
 template <int LEVEL>
-__global__ __launch_bounds__(256) void ew_hist(const float* __restrict__ g, long long n, EwState* st)
+__global__ __launch_bounds__(LEVEL == 0 ? 1024 : 256) void ew_hist(const float* __restrict__ g, long long n, EwState* st)
 {
-    __shared__ unsigned int cnt[NBUCKET];
-    __shared__ unsigned long long sig[NBUCKET];
-    if (LEVEL > 0 && st->resolved) return;
+    // Level 0 sees every element and most of them fall into a few dozen buckets: four copies of the
+    // histogram (one per lane mod 4) keep lanes of a wave from queueing on the same LDS word.
+    // One 64-bit word per bucket: element count in bits 40.., sum of 24-bit significands below.  A
+    // workgroup visits fewer than 2^16 elements (checked by the launcher), so neither field overflows.
+    constexpr int COPIES = LEVEL == 0 ? 4 : 1;
+    constexpr int TPB = LEVEL == 0 ? 1024 : 256;
     constexpr int NB = LEVEL == 0 ? (1 << L0_BITS) : (1 << L1_BITS);
+    __shared__ unsigned long long acc[COPIES * NB];
+    if (LEVEL > 0 && st->resolved) return;
     constexpr int SHIFT = LEVEL == 0 ? 20 : LEVEL == 1 ? 10 : 0;
     const unsigned int prefix = LEVEL == 0 ? 0u : st->prefix;
-    for (int b = threadIdx.x; b < NB; b += 256) { cnt[b] = 0u; sig[b] = 0ull; }
+    const unsigned int copy = LEVEL == 0 ? (threadIdx.x & (COPIES - 1)) * NB : 0u;
+    for (int b = threadIdx.x; b < COPIES * NB; b += TPB) acc[b] = 0ull;
     __syncthreads();
 
     auto visit = [&](float x) {
         const unsigned int key = __float_as_uint(x) & 0x7FFFFFFFu;
+        const unsigned long long word = (1ull << 40) | (unsigned long long)significand(key);
         if (LEVEL == 0) {
-            const unsigned int b = key >> SHIFT;
-            atomicAdd(&cnt[b], 1u);
-            atomicAdd(&sig[b], (unsigned long long)significand(key));
+            atomicAdd(&acc[copy + (key >> SHIFT)], word);
         } else {
-            if ((key >> (SHIFT + (LEVEL == 1 ? L1_BITS : L2_BITS))) == prefix) {
-                const unsigned int b = (key >> SHIFT) & (NB - 1);
-                atomicAdd(&cnt[b], 1u);
-                atomicAdd(&sig[b], (unsigned long long)significand(key));
-            }
+            if ((key >> (SHIFT + (LEVEL == 1 ? L1_BITS : L2_BITS))) == prefix)
+                atomicAdd(&acc[(key >> SHIFT) & (NB - 1)], word);
         }
     };
 
     const bool vec = (((size_t)g) & 15) == 0;
     const long long n4 = vec ? n / 4 : 0;
-    const long long stride = (long long)gridDim.x * 256;
-    for (long long q = (long long)blockIdx.x * 256 + threadIdx.x; q < n4; q += stride) {
+    const long long stride = (long long)gridDim.x * TPB;
+    for (long long q = (long long)blockIdx.x * TPB + threadIdx.x; q < n4; q += stride) {
         const float4 x = ((const float4*)g)[q];
         visit(x.x); visit(x.y); visit(x.z); visit(x.w);
     }
-    for (long long i = n4 * 4 + (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) visit(g[i]);
+    for (long long i = n4 * 4 + (long long)blockIdx.x * TPB + threadIdx.x; i < n; i += stride) visit(g[i]);
     __syncthreads();
-    for (int b = threadIdx.x; b < NB; b += 256) {
-        if (cnt[b]) {
-            atomicAdd(&st->cnt[LEVEL][b], cnt[b]);
-            atomicAdd(&st->sig[LEVEL][b], sig[b]);
+    for (int b = threadIdx.x; b < NB; b += TPB) {
+        unsigned int c = 0u;
+        unsigned long long sg = 0ull;
+#pragma unroll
+        for (int k = 0; k < COPIES; ++k) {
+            const unsigned long long w = acc[k * NB + b];
+            c += (unsigned int)(w >> 40);
+            sg += w & ((1ull << 40) - 1);
+        }
+        if (c) {
+            atomicAdd(&st->cnt[LEVEL][b], c);
+            atomicAdd(&st->sig[LEVEL][b], sg);
         }
     }
 }
-
-// Picks the bucket of this level that contains the water level tau (single workgroup).
 template <int LEVEL>
 __global__ __launch_bounds__(256) void ew_solve(EwState* st, double s)
 {
@@ -139,45 +148,66 @@ __global__ __launch_bounds__(256) void ew_solve(EwState* st, double s)
         return (double)__uint_as_float(key);
     };
 
+    // this thread's PER consecutive buckets stay in registers
+    unsigned int cnt_r[PER];
+    double sum_r[PER];
     unsigned long long c_mine = 0ull;
     double s_mine = 0.0;
-    for (int b = tid * PER; b < (tid + 1) * PER; ++b) {
-        c_mine += st->cnt[LEVEL][b];
-        s_mine += sig_value(st->sig[LEVEL][b], bucket_exp(b));
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+        const int b = tid * PER + e;
+        cnt_r[e] = st->cnt[LEVEL][b];
+        sum_r[e] = sig_value(st->sig[LEVEL][b], bucket_exp(b));
+        c_mine += cnt_r[e];
+        s_mine += sum_r[e];
     }
     cpart[tid] = c_mine;
     spart[tid] = s_mine;
     if (tid == 0) best = 0;
     __syncthreads();
-    unsigned long long c_after = 0ull;          // count in buckets owned by later threads
-    double s_before = 0.0;                      // sum in buckets owned by earlier threads
-    for (int t = tid + 1; t < 256; ++t) c_after += cpart[t];
-    for (int t = 0; t < tid; ++t) s_before += spart[t];
+    // suffix scan of the counts and prefix scan of the sums over the 256 threads (log-step, in LDS)
+    for (int off = 1; off < 256; off <<= 1) {
+        const unsigned long long cv = tid + off < 256 ? cpart[tid + off] : 0ull;
+        const double sv = tid >= off ? spart[tid - off] : 0.0;
+        __syncthreads();
+        cpart[tid] += cv;
+        spart[tid] += sv;
+        __syncthreads();
+    }
+    const unsigned long long c_after = tid < 255 ? cpart[tid + 1] : 0ull;   // count in buckets owned by later threads
+    const double s_before = tid > 0 ? spart[tid - 1] : 0.0;                 // sum in buckets owned by earlier threads
 
     // h at the lower edge of bucket b:  lo_b * (s - #{elements in buckets >= b}) - sum(buckets < b)
     {
         unsigned long long at_or_above = c_after + c_mine;
         double below = s_before;
         int mine_best = -1;
-        for (int b = tid * PER; b < (tid + 1) * PER; ++b) {
+#pragma unroll
+        for (int e = 0; e < PER; ++e) {
+            const int b = tid * PER + e;
             const double h = bucket_lo(b) * (s - (double)(n_above0 + at_or_above)) - (sum_below0 + below);
             if (h <= 0.0) mine_best = b;
-            at_or_above -= st->cnt[LEVEL][b];
-            below += sig_value(st->sig[LEVEL][b], bucket_exp(b));
+            at_or_above -= cnt_r[e];
+            below += sum_r[e];
         }
         if (mine_best >= 0) atomicMax(&best, mine_best);
     }
     __syncthreads();
-    if (tid == 0) {
-        const int bs = best;
-        unsigned long long above = 0ull;
-        double below = 0.0;
-        for (int b = bs + 1; b < NB; ++b) above += st->cnt[LEVEL][b];
-        for (int b = 0; b < bs; ++b) below += sig_value(st->sig[LEVEL][b], bucket_exp(b));
+    const int bs = best;
+    if (tid == bs / PER) {                      // the owner of the chosen bucket finishes from its registers
+        unsigned long long above = c_after;
+        double below = s_before;
+        unsigned int c = 0;
+        double bucket_sum = 0.0;
+#pragma unroll
+        for (int e = 0; e < PER; ++e) {
+            const int b = tid * PER + e;
+            if (b > bs) above += cnt_r[e];
+            if (b < bs) below += sum_r[e];
+            if (b == bs) { c = cnt_r[e]; bucket_sum = sum_r[e]; }
+        }
         const unsigned long long n_above = n_above0 + above;
         const double sum_below = sum_below0 + below;
-        const unsigned int c = st->cnt[LEVEL][bs];
-        const double bucket_sum = sig_value(st->sig[LEVEL][bs], bucket_exp(bs));
         bool done = false;
         unsigned long long n_s = n_above;
         double tail = sum_below;
@@ -196,6 +226,7 @@ __global__ __launch_bounds__(256) void ew_solve(EwState* st, double s)
             st->n_s = n_s;
             st->tail = tail;
             st->budget = s - (double)n_s;
+            st->ratio = tail > 0.0 ? (s - (double)n_s) / tail : __longlong_as_double(0x7FF0000000000000LL);
             st->resolved = 1;
         } else {
             st->n_above = n_above;
@@ -205,33 +236,34 @@ __global__ __launch_bounds__(256) void ew_solve(EwState* st, double s)
     }
 }
 
-__device__ inline float ew_probability(float x, double budget, double tail)
+// p = min(1, |x| (s - n_s) / tail) (eq. (p_i), KKT appendix); `ratio` = (s - n_s) / tail in double,
+// or +inf when nothing is left uncapped.  One double multiply and one rounding to float per element.
+__device__ inline float ew_probability(float x, double ratio)
 {
     const float a = fabsf(x);
     if (a == 0.0f) return 0.0f;
-    if (!(tail > 0.0)) return 1.0f;
-    return fminf(1.0f, (float)((double)a * budget / tail));
+    return fminf(1.0f, (float)((double)a * ratio));
 }
 
 // p for a large segment of atomo_probabilities
 __global__ __launch_bounds__(256) void ew_write_p(const float* __restrict__ lam, long long n, const EwState* st,
                                                   float* __restrict__ p)
 {
-    const double budget = st->budget, tail = st->tail;
+    const double ratio = st->ratio;
     const long long stride = (long long)gridDim.x * 256;
     for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += stride)
-        p[i] = ew_probability(lam[i], budget, tail);
+        p[i] = ew_probability(lam[i], ratio);
 }
 
 // Draws for the four coordinates 4q .. 4q+3 (one Philox block).  Returns the keep bits.
 __device__ inline unsigned int draw4(const float4 x, long long q, unsigned long long stream_id, unsigned long long seed,
-                                     double budget, double tail, float4& p)
+                                     double ratio, float4& p)
 {
     const u32x4 rnd = philox4x32_10((unsigned long long)q, stream_id, seed);
-    p.x = ew_probability(x.x, budget, tail);
-    p.y = ew_probability(x.y, budget, tail);
-    p.z = ew_probability(x.z, budget, tail);
-    p.w = ew_probability(x.w, budget, tail);
+    p.x = ew_probability(x.x, ratio);
+    p.y = ew_probability(x.y, ratio);
+    p.z = ew_probability(x.z, ratio);
+    p.w = ew_probability(x.w, ratio);
     return (u01(rnd.x) < p.x ? 1u : 0u) | (u01(rnd.y) < p.y ? 2u : 0u) | (u01(rnd.z) < p.z ? 4u : 0u) |
            (u01(rnd.w) < p.w ? 8u : 0u);
 }
@@ -248,27 +280,39 @@ __device__ inline float4 load4(const float* g, long long q, long long n, bool ve
     return x;
 }
 
-// Kept coordinates per chunk.  Wave w of a chunk owns float4 [w*256, (w+1)*256) of the chunk, in four
-// iterations of 64 lanes: order inside a chunk is (wave, iteration, lane, component) = ascending index.
+// Kept coordinates per chunk, and their keep bits.  Wave w of a chunk owns float4 [w*256, (w+1)*256) of the
+// chunk, in four iterations of 64 lanes: order inside a chunk is (wave, iteration, lane, component) =
+// ascending index.  keep[((chunk*4 + wave)*4 + iteration)*4 + component] holds one bit per lane, so that the
+// writer neither draws the random numbers again nor reads the gradient outside the kept coordinates.
 __global__ __launch_bounds__(256) void ew_count(const float* __restrict__ g, long long n, const EwState* st,
                                                 unsigned long long stream_id, unsigned long long seed,
-                                                unsigned int* __restrict__ chunk_count)
+                                                unsigned int* __restrict__ chunk_count,
+                                                unsigned long long* __restrict__ keep)
 {
     __shared__ unsigned int wsum[4];
-    const double budget = st->budget, tail = st->tail;
+    const double ratio = st->ratio;
     const bool vec = (((size_t)g) & 15) == 0;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const long long q0 = (long long)blockIdx.x * (CHUNK / 4) + wave * 256;
-    unsigned int kept = 0;
+    unsigned long long* kw = keep + ((long long)blockIdx.x * 4 + wave) * 16;
+    unsigned int kept = 0;                                   // wave-uniform
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const long long q = q0 + j * 64 + lane;
+        unsigned int bits = 0;
         if (q * 4 < n) {
             float4 p;
-            kept += __popc(draw4(load4(g, q, n, vec), q, stream_id, seed, budget, tail, p));
+            bits = draw4(load4(g, q, n, vec), q, stream_id, seed, ratio, p);
         }
+        unsigned long long mine = 0ull;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const unsigned long long ballot = __ballot((bits >> c) & 1u);
+            kept += __popcll(ballot);
+            if (lane == c) mine = ballot;
+        }
+        if (lane < 4) kw[j * 4 + lane] = mine;
     }
-    for (int o = 32; o > 0; o >>= 1) kept += __shfl_down(kept, o);
     if (lane == 0) wsum[wave] = kept;
     __syncthreads();
     if (threadIdx.x == 0) chunk_count[blockIdx.x] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
@@ -287,8 +331,13 @@ __global__ __launch_bounds__(256) void ew_scan(const unsigned int* __restrict__ 
     for (long long c = lo; c < hi; ++c) mine += chunk_count[c];
     part[tid] = mine;
     __syncthreads();
-    unsigned long long base = 0ull;
-    for (int t = 0; t < tid; ++t) base += part[t];
+    for (int off = 1; off < 256; off <<= 1) {
+        const unsigned long long v = tid >= off ? part[tid - off] : 0ull;
+        __syncthreads();
+        part[tid] += v;
+        __syncthreads();
+    }
+    unsigned long long base = tid > 0 ? part[tid - 1] : 0ull;
     for (long long c = lo; c < hi; ++c) {
         chunk_base[c] = base;
         base += chunk_count[c];
@@ -300,41 +349,30 @@ __global__ __launch_bounds__(256) void ew_scan(const unsigned int* __restrict__ 
     }
 }
 
-__global__ __launch_bounds__(256) void ew_write(const float* __restrict__ g, long long n, const EwState* st,
-                                                unsigned long long stream_id, unsigned long long seed,
+// Writes the kept coordinates of one chunk in ascending order.  The keep bits give every kept coordinate
+// its rank inside the chunk; the coordinates are first listed in LDS by rank, then thread t takes the t-th
+// one, so the gradient is read and the message written in one batch of loads and coalesced stores.
+__global__ __launch_bounds__(256) void ew_write(const float* __restrict__ g, const EwState* st,
+                                                const unsigned long long* __restrict__ keep,
                                                 const unsigned long long* __restrict__ chunk_base, long long capacity,
-                                                unsigned int* __restrict__ idx, float* __restrict__ val,
-                                                float* __restrict__ p_out)
+                                                unsigned int* __restrict__ idx, float* __restrict__ val)
 {
     __shared__ unsigned int wsum[4];
-    const double budget = st->budget, tail = st->tail;
-    const bool vec = (((size_t)g) & 15) == 0;
+    __shared__ unsigned short local[CHUNK];    // coordinate offsets inside the chunk, by rank
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const long long q0 = (long long)blockIdx.x * (CHUNK / 4) + wave * 256;
+    const unsigned long long* kw = keep + ((long long)blockIdx.x * 4 + wave) * 16;
     const unsigned long long lt_mask = lane == 0 ? 0ull : (~0ull >> (64 - lane));
 
-    float4 xs[4], ps[4];
     unsigned int bits[4], before[4];           // keep bits; kept coordinates of this wave ahead of this lane's float4
     unsigned int running = 0;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const long long q = q0 + j * 64 + lane;
-        bits[j] = 0;
-        if (q * 4 < n) {
-            xs[j] = load4(g, q, n, vec);
-            bits[j] = draw4(xs[j], q, stream_id, seed, budget, tail, ps[j]);
-            if (p_out) {
-                const long long i = q * 4;
-                if (i < n) p_out[i] = ps[j].x;
-                if (i + 1 < n) p_out[i + 1] = ps[j].y;
-                if (i + 2 < n) p_out[i + 2] = ps[j].z;
-                if (i + 3 < n) p_out[i + 3] = ps[j].w;
-            }
-        }
         unsigned int ahead = 0, all = 0;
+        bits[j] = 0;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            const unsigned long long ballot = __ballot((bits[j] >> c) & 1u);
+            const unsigned long long ballot = kw[j * 4 + c];
+            bits[j] |= (unsigned int)((ballot >> lane) & 1ull) << c;
             ahead += __popcll(ballot & lt_mask);
             all += __popcll(ballot);
         }
@@ -343,24 +381,31 @@ __global__ __launch_bounds__(256) void ew_write(const float* __restrict__ g, lon
     }
     if (lane == 0) wsum[wave] = running;
     __syncthreads();
-    unsigned long long base = chunk_base[blockIdx.x];
-    for (int w = 0; w < wave; ++w) base += wsum[w];
+    unsigned int wave_base = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        if (w < wave) wave_base += wsum[w];
+        total += wsum[w];
+    }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        if (!bits[j]) continue;
-        const long long i0 = (q0 + j * 64 + lane) * 4;
-        unsigned long long pos = base + before[j];
-        const float xv[4] = {xs[j].x, xs[j].y, xs[j].z, xs[j].w};
-        const float pv[4] = {ps[j].x, ps[j].y, ps[j].z, ps[j].w};
+        unsigned int pos = wave_base + before[j];
+        const unsigned int off = (unsigned int)(wave * 256 + j * 64 + lane) * 4u;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            if ((bits[j] >> c) & 1u) {
-                if ((long long)pos < capacity) {
-                    idx[pos] = (unsigned int)(i0 + c);
-                    val[pos] = xv[c] / pv[c];
-                }
-                ++pos;
-            }
+        for (int c = 0; c < 4; ++c)
+            if ((bits[j] >> c) & 1u) local[pos++] = (unsigned short)(off + c);
+    }
+    __syncthreads();
+    const double ratio = st->ratio;
+    const unsigned long long base = chunk_base[blockIdx.x];
+    const long long i0 = (long long)blockIdx.x * CHUNK;
+    for (unsigned int t = threadIdx.x; t < total; t += 256) {
+        const unsigned long long pos = base + t;
+        if ((long long)pos < capacity) {
+            const long long i = i0 + local[t];
+            const float x = g[i];
+            idx[pos] = (unsigned int)i;
+            val[pos] = x / ew_probability(x, ratio);
         }
     }
 }
@@ -394,6 +439,7 @@ struct EwLayout {
     EwState* st;
     unsigned int* chunk_count;
     unsigned long long* chunk_base;
+    unsigned long long* keep;     // [n_chunks][64] keep bits, see ew_count
     size_t bytes;
 };
 
@@ -405,6 +451,7 @@ EwLayout ew_layout(void* base, int64_t n)
     l.st = carve.take<EwState>(1);
     l.chunk_count = carve.take<unsigned int>(n_chunks);
     l.chunk_base = carve.take<unsigned long long>(n_chunks);
+    l.keep = carve.take<unsigned long long>(n_chunks * 64);
     l.bytes = carve.off;
     return l;
 }
@@ -412,9 +459,12 @@ EwLayout ew_layout(void* base, int64_t n)
 // Enqueues the three histogram / solve levels; afterwards st->{n_s, tail, budget} are final.
 void enqueue_water_level(atomo_ctx* ctx, const float* x, int64_t n, double s, EwState* st, hipStream_t stream)
 {
-    const int wgs = (int)std::min<int64_t>(HIST_WGS, (n + 1023) / 1024);
+    // No workgroup may visit 2^16 elements or more (field widths of the packed histogram word).
+    const int64_t floor_wgs = (n + 49151) / 49152;
+    const int wgs = (int)std::max<int64_t>(std::min<int64_t>(HIST_WGS, (n + 1023) / 1024), floor_wgs);
+    const int wgs0 = (int)std::max<int64_t>(std::min<int64_t>(256, (n + 4095) / 4096), floor_wgs);
     { ProfScope ps(ctx, ATOMO_K_EW_SOLVE, stream); ew_clear<<<(3 * NBUCKET + 255) / 256, 256, 0, stream>>>(st); }
-    { ProfScope ps(ctx, ATOMO_K_EW_HIST, stream); ew_hist<0><<<wgs, 256, 0, stream>>>(x, n, st); }
+    { ProfScope ps(ctx, ATOMO_K_EW_HIST, stream); ew_hist<0><<<wgs0, 1024, 0, stream>>>(x, n, st); }
     { ProfScope ps(ctx, ATOMO_K_EW_SOLVE, stream); ew_solve<0><<<1, 256, 0, stream>>>(st, s); }
     { ProfScope ps(ctx, ATOMO_K_EW_HIST, stream); ew_hist<1><<<wgs, 256, 0, stream>>>(x, n, st); }
     { ProfScope ps(ctx, ATOMO_K_EW_SOLVE, stream); ew_solve<1><<<1, 256, 0, stream>>>(st, s); }
@@ -438,11 +488,12 @@ int encode_entrywise(atomo_ctx* ctx, const float* g, double s, uint64_t seed, ui
     enqueue_water_level(ctx, g, n, s, l.st, stream);
     {
         ProfScope ps(ctx, ATOMO_K_EW_SAMPLE, stream);
-        ew_count<<<(unsigned)n_chunks, 256, 0, stream>>>(g, n, l.st, stream_id, seed, l.chunk_count);
+        ew_count<<<(unsigned)n_chunks, 256, 0, stream>>>(g, n, l.st, stream_id, seed, l.chunk_count, l.keep);
         ew_scan<<<1, 256, 0, stream>>>(l.chunk_count, n_chunks, l.chunk_base, l.st, (long long*)msg->count,
                                        (long long)msg->capacity, ctx->d_flags);
-        ew_write<<<(unsigned)n_chunks, 256, 0, stream>>>(g, n, l.st, stream_id, seed, l.chunk_base,
-                                                         (long long)msg->capacity, msg->idx, msg->val, p_out);
+        ew_write<<<(unsigned)n_chunks, 256, 0, stream>>>(g, l.st, l.keep, l.chunk_base, (long long)msg->capacity,
+                                                         msg->idx, msg->val);
+        if (p_out) ew_write_p<<<(int)std::min<int64_t>(4096, (n + 255) / 256), 256, 0, stream>>>(g, n, l.st, p_out);
     }
     ATOMO_HIP(ctx, hipGetLastError());
     return ATOMO_OK;

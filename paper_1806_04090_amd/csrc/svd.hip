@@ -268,6 +268,7 @@ __global__ __launch_bounds__(256) void svd_fresh_check(const SvdMat* mats, const
     const int sweeps = m.state[ST_SWEEPS];
     if (!m.state[ST_FIRST]) m.state[ST_CUR] = (m.state[ST_CUR] & 1) ^ 1;     // svd_apply wrote the other buffer
     m.state[ST_FIRST] = 0;
+    m.state[ST_REFRESHES] += 1;
     if (fresh < fresh_stop || sweeps >= max_sweeps) {
         m.state[ST_MODE] = MODE_DONE;
         m.state[ST_DONE_AT] = tick + 1;
@@ -766,12 +767,16 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     return ATOMO_OK;
 }
 
-int svd_sweeps(atomo_ctx* ctx, hipStream_t stream, int32_t* sweeps, int n_mats)
+int svd_sweeps(atomo_ctx* ctx, hipStream_t stream, int32_t* sweeps, int32_t* refreshes, int n_mats)
 {
     if ((size_t)n_mats != ctx->svd_state.size()) return ATOMO_EINVAL;
     ATOMO_HIP(ctx, hipStreamSynchronize(stream));
-    for (int j = 0; j < n_mats; ++j)
+    for (int j = 0; j < n_mats; ++j) {
         ATOMO_HIP(ctx, hipMemcpy(&sweeps[j], ctx->svd_state[j] + ST_SWEEPS, sizeof(int32_t), hipMemcpyDeviceToHost));
+        if (refreshes)
+            ATOMO_HIP(ctx, hipMemcpy(&refreshes[j], ctx->svd_state[j] + ST_REFRESHES, sizeof(int32_t),
+                                     hipMemcpyDeviceToHost));
+    }
     return ATOMO_OK;
 }
 

@@ -32,6 +32,7 @@ enum {
     ST_ARRIVE2 = 10,    // workgroups of svd_fresh_check that finished
     ST_EXP = 11,        // input was multiplied by 2^-ST_EXP before the iteration
     ST_ABSMAX = 12,     // largest |entry| of the input (float bits)
+    ST_REFRESHES = 14,  // Gram-space matrices: fresh Gram matrices formed so far
     ST_QTICK = 13,      // Gram-space matrices: 1 + the tick in which svd_eig last produced rotations
     ST_WORDS = 16
 };
