@@ -27,33 +27,55 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3        # MI355X published dense fp32 matrix peak
-PEAK_FP32_VALU_TFLOPS = 78.6         # 256 CUs x 4 SIMD x 16 lanes x 2 flop x 2.4 GHz (packed fp32 off)
+PEAK_FP32_VALU_TFLOPS = 157.3        # published vector fp32 peak (packed); 78.6 for the unpacked code built here
 PEAK_HBM_GBS = 8000.0
 
 
-def algorithmic_flops(shapes, sweeps):
-    """Contraction flops of blocked one-sided Jacobi on real data, no padding:
-    per sweep and matrix, Gram 4 M r^2, row update 4 M r^2, accumulation of the rotations 4 r^3."""
-    gram = upd = 0.0
-    for (m, n), sw in zip(shapes, sweeps):
-        r, M = min(m, n), max(m, n)
-        gram += sw * 4.0 * M * r * r
-        upd += sw * (4.0 * M * r * r + 4.0 * r ** 3)
-    return gram, upd
+def layer_geometry(m, n):
+    """(r, M, Gram-space?) of one layer as the library schedules it: 32-row blocks, an even number of
+    them, and from eight blocks up the sweeps run on the r x r Gram matrix instead of the data."""
+    r, M = min(m, n), max(m, n)
+    nb = -(-r // 32)
+    nb2 = nb + (nb & 1)
+    return r, M, nb2 >= 8
 
 
-def eig_flops(shapes, sweeps, inner_sweeps=2):
-    """Vector-ALU flops of the 64x64 two-sided Jacobi solves (2016 rotations per inner sweep, each
-    touching 2 rows + 2 columns of the Gram matrix and 2 columns of the accumulator: 3 * 64 * 6 flops)
-    plus the Newton-Schulz step (2 products of 64^3)."""
-    total = 0.0
-    for (m, n), sw in zip(shapes, sweeps):
-        r = min(m, n)
-        nb = -(-r // 32)
-        nb2 = nb + (nb & 1)
-        visits = sw * (nb2 - 1) * (nb2 // 2)
-        total += visits * (inner_sweeps * 2016 * 3 * 64 * 6 + 2 * 2 * 64 ** 3)
-    return total
+def executed_work(shapes, sweeps, refreshes, pair_visits, inner_sweeps, n_elem, kept_atoms):
+    """Arithmetic and bytes the algorithm executes on real data (no padding) per step, by kernel class.
+
+    Data-space layers (r < 225), per sweep: block-pair Gram matrices 4 M r^2, rotation of [A | T] 4 M r^2 + 4 r^3.
+    Gram-space layers, per refresh: upper-triangular tiles of A A^T  M r (r + 64), and (every refresh but
+    the first) A <- T A and T <- T T_old, 2 r^2 (M + r); per sweep: two-sided rotation of C 8 r^3 and
+    accumulation into T 4 r^3.
+    64 x 64 eigen-solves: 2016 rotations per inner sweep, each 3 x 64 x 6 flops on the vector ALU (rows and
+    columns of the block, columns of the accumulator), plus a Newton-Schulz step of two 64^3 products.
+    """
+    gram = upd = refresh = 0.0
+    for (m, n), sw, rf in zip(shapes, sweeps, refreshes):
+        r, M, gs = layer_geometry(m, n)
+        if gs:
+            refresh += rf * M * r * (r + 64.0) + max(rf - 1, 0) * 2.0 * r * r * (M + r)
+            upd += sw * 12.0 * r ** 3
+        else:
+            gram += sw * 4.0 * M * r * r
+            upd += sw * (4.0 * M * r * r + 4.0 * r ** 3)
+    eig = inner_sweeps * 2016 * 3 * 64 * 6 + pair_visits * 2 * 2 * 64 ** 3
+    decode_bytes = 4.0 * n_elem + sum(4.0 * k * (m + n + 1) for (m, n), k in zip(shapes, kept_atoms))
+    return {
+        "svd_gram": ("mfma", gram, PEAK_FP32_MFMA_TFLOPS, "TFLOP/s"),
+        "svd_update": ("mfma", upd, PEAK_FP32_MFMA_TFLOPS, "TFLOP/s"),
+        "svd_refresh": ("mfma", refresh, PEAK_FP32_MFMA_TFLOPS, "TFLOP/s"),
+        "svd_eig": ("alu", eig, PEAK_FP32_VALU_TFLOPS, "TFLOP/s"),
+        "svd_prepare": ("hbm", 12.0 * n_elem, PEAK_HBM_GBS, "GB/s"),
+        "svd_finalize": ("hbm", 4.0 * n_elem, PEAK_HBM_GBS, "GB/s"),
+        "decode_svd": ("hbm", decode_bytes, PEAK_HBM_GBS, "GB/s"),
+    }
+
+
+def paper_form_flops(shapes, sweeps):
+    """The contraction count of textbook blocked one-sided Jacobi, sweeps x (8 M r^2 + 4 r^3) per layer: what
+    the same number of sweeps would cost without the Gram-space reformulation.  For comparison only."""
+    return sum(sw * (8.0 * max(m, n) * min(m, n) ** 2 + 4.0 * min(m, n) ** 3) for (m, n), sw in zip(shapes, sweeps))
 
 
 def main():
@@ -62,6 +84,10 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-entrywise", action="store_true", help="skip the entry-wise leg")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run five plain device copies of 1 GiB, the known-size reference that scales the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (the design note in DESIGN.md says "
@@ -97,6 +123,8 @@ def main():
         print(f"warm-up reported status {status}", file=sys.stderr)
         sys.exit(1)
     sweeps = ctx.svd_sweeps(len(mats))
+    refreshes = ctx.svd_refreshes(len(mats))
+    kept_atoms = [int(m.count.item()) for m in msgs]
 
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -118,35 +146,53 @@ def main():
     torch.cuda.synchronize()
     ms_per_step_profiled = (time.perf_counter() - tp0) * 1e3 / args.steps
     ctx.profile_enable(False)
+    ctx.status()
+    step()                                      # one step between two status reads: counters of exactly one step
+    ctx.status()
+    pair_visits, inner_sweeps = ctx.last_counters()
 
-    gram_fl, upd_fl = algorithmic_flops(shapes, sweeps)
     per_step_ms = {k: v[0] / args.steps for k, v in prof.items() if v[1]}
     launches = {k: v[1] / args.steps for k, v in prof.items() if v[1]}
     dominant = max(per_step_ms, key=per_step_ms.get)
-    work = {
-        "svd_gram": ("mfma", gram_fl, PEAK_FP32_MFMA_TFLOPS, "TFLOP/s"),
-        "svd_update": ("mfma", upd_fl, PEAK_FP32_MFMA_TFLOPS, "TFLOP/s"),
-        "svd_eig": ("alu", eig_flops(shapes, sweeps), PEAK_FP32_VALU_TFLOPS, "TFLOP/s"),
-        "decode_svd": ("hbm", 4.0 * n_elem, PEAK_HBM_GBS, "GB/s"),
-    }
-    bound, amount, peak, unit = work.get(dominant, ("alu", 0.0, PEAK_FP32_VALU_TFLOPS, "TFLOP/s"))
+    work = executed_work(shapes, sweeps, refreshes, pair_visits, inner_sweeps, n_elem, kept_atoms)
+    bound, amount, peak, unit = work[dominant]
     dom_ms = per_step_ms[dominant]
     achieved = amount / (dom_ms * 1e-3) / (1e12 if unit == "TFLOP/s" else 1e9)
+    contraction = sum(work[k][1] for k in ("svd_gram", "svd_update", "svd_refresh"))
+    contraction_ms = sum(per_step_ms.get(k, 0.0) for k in ("svd_gram", "svd_update", "svd_refresh"))
+    encode_ms = sum(v for k, v in per_step_ms.items() if k.startswith("svd_"))
+    by_kernel = {}
+    for k, v in sorted(per_step_ms.items()):
+        kb, ka, kp, ku = work[k]
+        rate = ka / (v * 1e-3) / (1e12 if ku == "TFLOP/s" else 1e9)
+        by_kernel[k] = {"ms": round(v, 4), "scopes": launches[k], "bound": kb, "achieved": round(rate, 3), "unit": ku,
+                        "frac": round(rate / kp, 5)}
     roofline = {
         "kernel": dominant, "bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
         "frac": round(achieved / peak, 5), "traffic": None,
         "avg_launch_us": round(dom_ms * 1e3 / launches[dominant], 2), "launches_per_step": launches[dominant],
-        "per_step_ms_by_kernel": {k: round(v, 4) for k, v in sorted(per_step_ms.items())},
+        "by_kernel": by_kernel,
         "ms_per_step_with_events": round(ms_per_step_profiled, 4),
         "jacobi_sweeps_per_layer": sweeps,
+        "gram_refreshes_per_layer": refreshes,
+        "eigen_solves_per_step": pair_visits, "inner_sweeps_per_step": inner_sweeps,
         "encode_contraction": {
-            "flops_per_step": gram_fl + upd_fl,
-            "tflops_over_mfma_kernels": round((gram_fl + upd_fl) / ((per_step_ms.get("svd_gram", 0) +
-                                              per_step_ms.get("svd_update", 0)) * 1e-3) / 1e12, 3),
-            "tflops_over_whole_encode": round((gram_fl + upd_fl) / (sum(v for k, v in per_step_ms.items()
-                                              if k.startswith("svd_")) * 1e-3) / 1e12, 3),
+            "executed_flops_per_step": contraction,
+            "tflops_over_mfma_kernels": round(contraction / (contraction_ms * 1e-3) / 1e12, 3),
+            "tflops_over_whole_encode": round(contraction / (encode_ms * 1e-3) / 1e12, 3),
+            "paper_form_flops_same_sweeps": paper_form_flops(shapes, sweeps),
+            "paper_form_tflops_over_whole_encode": round(paper_form_flops(shapes, sweeps) / (encode_ms * 1e-3) / 1e12, 3),
+            "frac_of_fp32_mfma_peak_paper_form": round(paper_form_flops(shapes, sweeps) / (encode_ms * 1e-3) / 1e12
+                                                       / PEAK_FP32_MFMA_TFLOPS, 5),
         },
     }
+    entrywise = None if args.no_entrywise else entrywise_leg(ctx, torch, binding, inputs)
+    if args.calibration_copy:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     cpu = None
     if not args.no_cpu_baseline and os.environ.get("ATOMO_BENCH_SKIP_CPU") != "1":
@@ -162,8 +208,55 @@ def main():
                    "elements_per_step": n_elem, "budget_s": S, "philox_seed": SEED},
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "entrywise": entrywise,
     }
     print(json.dumps(line))
+
+
+def entrywise_leg(ctx, torch, binding, inputs, reps=40, sets=8):
+    """The entry-wise path on the full flat gradient (11,173,962 elements, s = N/100), outside the timed
+    steps of the headline metric: encode + decode, HBM-bound.  Eight input/message/output sets are rotated
+    so that one repetition does not find the previous one's data in the last-level cache.  Algorithmic
+    traffic: two reads of g (a global reduction must precede sampling) and one dense write, 12 B per
+    element, plus 8 B out and 12 B in/out per kept pair."""
+    n = inputs.RESNET18_PARAMETERS
+    g = torch.from_numpy(inputs.flat_heavy_tail(0))
+    s = n / 100
+    gs = [g.cuda() for _ in range(sets)]
+    outs = [torch.empty(n, dtype=torch.float32, device="cuda") for _ in range(sets)]
+    msgs = [binding.alloc_entrywise_message(n, binding.default_capacity(s, n), "cuda") for _ in range(sets)]
+
+    def step(i):
+        k = i % sets
+        binding.atomo_encode_entrywise(ctx, gs[k], s, 0, 0, msg=msgs[k])
+        binding.atomo_decode(ctx, [msgs[k]], out=outs[k])
+
+    for i in range(sets):
+        step(i)
+    torch.cuda.synchronize()
+    if ctx.status()[0] != 0:
+        return None
+    t0 = time.perf_counter()
+    for i in range(reps):
+        step(i)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / reps
+    kept = int(msgs[0].count.item())
+    ctx.profile_enable(True)
+    ctx.profile_read()
+    prof = {}
+    for i in range(reps):
+        step(i)
+        for name, (ms, cnt) in ctx.profile_read().items():
+            if cnt:
+                prof[name] = prof.get(name, 0.0) + ms
+    ctx.profile_enable(False)
+    nbytes = 12.0 * n + 20.0 * kept
+    return {"workload": "flat_heavy_tail: N=11,173,962 fp32, N(0,1e-3^2) + 11,173 entries x100, s=N/100, encode + decode",
+            "elements_per_s": n / dt, "us_per_step": round(dt * 1e6, 2), "kept": kept,
+            "roofline": {"bound": "hbm", "achieved": round(nbytes / dt / 1e9, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                         "frac": round(nbytes / dt / 1e9 / PEAK_HBM_GBS, 4), "algorithmic_bytes_per_step": nbytes},
+            "us_per_step_by_kernel_class": {k: round(v / reps * 1e3, 2) for k, v in sorted(prof.items())}}
 
 
 def cpu_baseline(host_mats, s, seed):

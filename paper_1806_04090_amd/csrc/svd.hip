@@ -105,7 +105,7 @@ __global__ __launch_bounds__(256) void svd_prepare(const SvdMat* mats, const Wor
             if (c < m.M) v = factor * (m.transposed ? m.G[(long long)c * m.ldg + i] : m.G[(long long)i * m.ldg + c]);
             else if (c - m.Mp == i) v = 1.0f;
         }
-        m.W[0][(size_t)i * m.ldw + c] = v;
+        m.W0[(size_t)i * m.ldw + c] = v;
     }
 }
 
@@ -125,14 +125,16 @@ __global__ __launch_bounds__(256) void svd_gram(const SvdMat* mats, const Work* 
     if (FULL) {
         if (!refreshing(m)) return;
         const int cur = m.state[ST_CUR] & 1;
-        W = m.W[m.state[ST_FIRST] ? cur : cur ^ 1];              // what svd_apply has just written
+        const float* const w0 = m.W0;
+        const float* const w1 = m.W1;
+        W = ((m.state[ST_FIRST] ? cur : cur ^ 1) != 0) ? w1 : w0;    // what svd_apply has just written
         const int ti = wk.a, tj = wk.b, nt = m.nb2 / 2;
         rowA0 = ti * PR; rowA1 = rowA0 + BS; rowB0 = tj * PR; rowB1 = rowB0 + BS;
         chunk = wk.c;
         out_index = ti * nt - ti * (ti - 1) / 2 + (tj - ti);
     } else {
         if (m.gs || skip_step(m, tick, max_sweeps)) return;
-        W = m.W[0];
+        W = m.W0;
         int bi, bj;
         pair_blocks(m.nb2, tick % m.R, wk.a, bi, bj);
         rowA0 = rowB0 = bi * BS; rowA1 = rowB1 = bj * BS;
@@ -155,27 +157,28 @@ __global__ __launch_bounds__(256) void svd_gram(const SvdMat* mats, const Work* 
     for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 
     for (int c0 = c_begin; c0 < c_end; c0 += 64) {
-        float4 ld[FULL ? 8 : 4];
+        // (native vector type: an array of the float4 class ended up in scratch memory here)
+        floatx4 ld[FULL ? 8 : 4];
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
             const int lr = lrow + 16 * p;                        // 0..63
             const int grow = (lr < BS ? rowA0 + lr : rowA1 + lr - BS);
-            ld[p] = *(const float4*)(W + (size_t)grow * m.ldw + c0 + lc4);
+            ld[p] = *(const floatx4*)(W + (size_t)grow * m.ldw + c0 + lc4);
         }
         if (FULL && !same) {
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
                 const int lr = lrow + 16 * p;
                 const int grow = (lr < BS ? rowB0 + lr : rowB1 + lr - BS);
-                ld[4 + p] = *(const float4*)(W + (size_t)grow * m.ldw + c0 + lc4);
+                ld[4 + p] = *(const floatx4*)(W + (size_t)grow * m.ldw + c0 + lc4);
             }
         }
         __syncthreads();                                         // previous tile fully consumed
 #pragma unroll
-        for (int p = 0; p < 4; ++p) *(float4*)&tile[lrow + 16 * p][lc4] = ld[p];
+        for (int p = 0; p < 4; ++p) *(floatx4*)&tile[lrow + 16 * p][lc4] = ld[p];
         if (FULL && !same) {
 #pragma unroll
-            for (int p = 0; p < 4; ++p) *(float4*)&tile[PR + lrow + 16 * p][lc4] = ld[4 + p];
+            for (int p = 0; p < 4; ++p) *(floatx4*)&tile[PR + lrow + 16 * p][lc4] = ld[4 + p];
         }
         __syncthreads();
 #pragma unroll
@@ -307,8 +310,8 @@ __global__ __launch_bounds__(256) void svd_rowop(const SvdMat* mats, const Work*
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[e][ib][v] = 0.0f;
 
-    float* rowI = m.W[0] + (size_t)bi * BS * m.ldw + c0 + 2 * l32;
-    float* rowJ = m.W[0] + (size_t)bj * BS * m.ldw + c0 + 2 * l32;
+    float* rowI = m.W0 + (size_t)bi * BS * m.ldw + c0 + 2 * l32;
+    float* rowJ = m.W0 + (size_t)bj * BS * m.ldw + c0 + 2 * l32;
 #pragma unroll 4
     for (int s = 0; s < 32; ++s) {
         const int k = 2 * s + h;                                 // local row of the pair, 0..63
@@ -408,8 +411,10 @@ __global__ __launch_bounds__(256) void svd_apply(const SvdMat* mats, const Work*
     const SvdMat m = mats[wk.mat];
     if (!refreshing(m) || m.state[ST_FIRST]) return;
     const int cur = m.state[ST_CUR] & 1;
-    const float* src = m.W[cur];
-    float* dst = m.W[cur ^ 1];
+    float* const w0 = m.W0;
+    float* const w1 = m.W1;
+    const float* src = cur ? w1 : w0;
+    float* dst = cur ? w0 : w1;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int h = lane >> 5, l32 = lane & 31;
     const int row0 = wk.a * PR;
@@ -607,8 +612,8 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
         const int nt = m.nb2 / 2;
         m.ntiles = nt * (nt + 1) / 2;
         m.ldc = 2 * m.rows_alloc;
-        m.W[0] = carve.take<float>((size_t)m.rows_alloc * m.ldw);
-        m.W[1] = m.gs ? carve.take<float>((size_t)m.rows_alloc * m.ldw) : nullptr;
+        m.W0 = carve.take<float>((size_t)m.rows_alloc * m.ldw);
+        m.W1 = m.gs ? carve.take<float>((size_t)m.rows_alloc * m.ldw) : nullptr;
         m.CT = m.gs ? carve.take<float>((size_t)m.rows_alloc * m.ldc) : nullptr;
         m.C2 = nullptr;
         m.gram = carve.take<float>((size_t)(m.gs ? m.ntiles : m.npairs) * m.nchg * QSZ);

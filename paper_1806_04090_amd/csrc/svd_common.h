@@ -16,6 +16,7 @@ constexpr int MAX_R = ALG1_MAX;
 constexpr int GS_MIN_BLOCKS = 8;  // matrices with at least this many row blocks iterate in Gram space
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 // Per-matrix state words (device, int32).
 enum {
@@ -45,7 +46,8 @@ enum { MODE_NEED_REFRESH = 0, MODE_SWEEPS = 1, MODE_DONE = 2 };
 constexpr float ZERO_REL = 3.64e-12f;       // (32 * 2^-24)^2
 
 struct SvdMat {
-    float* W[2];             // rows_alloc x ldw each: [A | T]; W[1] only for Gram-space matrices
+    float* W0;               // rows_alloc x ldw: [A | T]
+    float* W1;               // second buffer of the same shape, Gram-space matrices only (else null)
     float* CT;               // Gram space: rows_alloc x ldc, [C | Tgs]
     float* C2;               // Gram space: rows_alloc x rows_alloc scratch for the two-sided update
     int ldw, ldc, r, M, Mp, rows_alloc;
@@ -91,7 +93,15 @@ __device__ inline bool skip_step(const SvdMat& m, int tick, int max_sweeps)
 }
 
 // The buffer that currently holds [A | T].
-__device__ inline float* current_w(const SvdMat& m) { return m.W[m.gs ? (m.state[ST_CUR] & 1) : 0]; }
+// Both pointers are read into values before the choice: a conditional between the two fields themselves is
+// an address computed at run time, which moves a by-value copy of the descriptor into scratch memory (a
+// per-lane store of the whole struct at the top of every kernel).
+__device__ inline float* current_w(const SvdMat& m)
+{
+    float* const w0 = m.W0;
+    float* const w1 = m.W1;
+    return (m.gs && (m.state[ST_CUR] & 1)) ? w1 : w0;
+}
 
 // Enqueues svd_eig for one tick (defined in svd_eig.hip).
 void launch_svd_eig(const SvdMat* d_mats, const Work* d_work, int n_items, int tick, int max_sweeps,
