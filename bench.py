@@ -40,15 +40,16 @@ def layer_geometry(m, n):
     return r, M, nb2 >= 8
 
 
-def executed_work(shapes, sweeps, refreshes, pair_visits, inner_sweeps, n_elem, kept_atoms):
+def executed_work(shapes, sweeps, refreshes, pair_visits, jacobi_steps, n_elem, kept_atoms):
     """Arithmetic and bytes the algorithm executes on real data (no padding) per step, by kernel class.
 
     Data-space layers (r < 225), per sweep: block-pair Gram matrices 4 M r^2, rotation of [A | T] 4 M r^2 + 4 r^3.
     Gram-space layers, per refresh: upper-triangular tiles of A A^T  M r (r + 64), and (every refresh but
     the first) A <- T A and T <- T T_old, 2 r^2 (M + r); per sweep: two-sided rotation of C 8 r^3 and
     accumulation into T 4 r^3.
-    64 x 64 eigen-solves: 2016 rotations per inner sweep, each 3 x 64 x 6 flops on the vector ALU (rows and
-    columns of the block, columns of the accumulator), plus a Newton-Schulz step of two 64^3 products.
+    64 x 64 eigen-solves: 32 rotations per Jacobi step (63 steps when every index pair is rotated, 32 when only
+    the pairs that couple the two blocks are), each 3 x 64 x 6 flops on the vector ALU (rows and columns of the
+    block, columns of the accumulator), plus a Newton-Schulz step of two 64^3 products per solve.
     """
     gram = upd = refresh = 0.0
     for (m, n), sw, rf in zip(shapes, sweeps, refreshes):
@@ -59,7 +60,7 @@ def executed_work(shapes, sweeps, refreshes, pair_visits, inner_sweeps, n_elem, 
         else:
             gram += sw * 4.0 * M * r * r
             upd += sw * (4.0 * M * r * r + 4.0 * r ** 3)
-    eig = inner_sweeps * 2016 * 3 * 64 * 6 + pair_visits * 2 * 2 * 64 ** 3
+    eig = jacobi_steps * 32 * 3 * 64 * 6 + pair_visits * 2 * 2 * 64 ** 3
     decode_bytes = 4.0 * n_elem + sum(4.0 * k * (m + n + 1) for (m, n), k in zip(shapes, kept_atoms))
     return {
         "svd_gram": ("mfma", gram, PEAK_FP32_MFMA_TFLOPS, "TFLOP/s"),
@@ -149,12 +150,12 @@ def main():
     ctx.status()
     step()                                      # one step between two status reads: counters of exactly one step
     ctx.status()
-    pair_visits, inner_sweeps = ctx.last_counters()
+    pair_visits, jacobi_steps = ctx.last_counters()
 
     per_step_ms = {k: v[0] / args.steps for k, v in prof.items() if v[1]}
     launches = {k: v[1] / args.steps for k, v in prof.items() if v[1]}
     dominant = max(per_step_ms, key=per_step_ms.get)
-    work = executed_work(shapes, sweeps, refreshes, pair_visits, inner_sweeps, n_elem, kept_atoms)
+    work = executed_work(shapes, sweeps, refreshes, pair_visits, jacobi_steps, n_elem, kept_atoms)
     bound, amount, peak, unit = work[dominant]
     dom_ms = per_step_ms[dominant]
     achieved = amount / (dom_ms * 1e-3) / (1e12 if unit == "TFLOP/s" else 1e9)
@@ -175,7 +176,7 @@ def main():
         "ms_per_step_with_events": round(ms_per_step_profiled, 4),
         "jacobi_sweeps_per_layer": sweeps,
         "gram_refreshes_per_layer": refreshes,
-        "eigen_solves_per_step": pair_visits, "inner_sweeps_per_step": inner_sweeps,
+        "eigen_solves_per_step": pair_visits, "jacobi_steps_per_step": jacobi_steps,
         "encode_contraction": {
             "executed_flops_per_step": contraction,
             "tflops_over_mfma_kernels": round(contraction / (contraction_ms * 1e-3) / 1e12, 3),

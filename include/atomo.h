@@ -97,6 +97,10 @@ typedef struct atomo_svd_options {
     int32_t max_inner_sweeps;        /* default 1 (0 = default): most Jacobi sweeps per 64x64 block-pair problem */
     float   inner_reduction;         /* default 0.01 (0 = default): a block-pair problem stops sweeping once */
                                      /* its largest |cos| is below inner_reduction x the value it started at */
+    int32_t full_period;             /* default 8 (0 = default): a block-pair problem rotates all 2016 index     */
+                                     /* pairs in the rounds of an outer sweep whose number is a multiple of this */
+                                     /* and only the 1024 pairs that couple its two blocks in the other rounds;  */
+                                     /* 1: all 2016 pairs in every round                                         */
 } atomo_svd_options;
 
 /* -------- context ------------------------------------------------------------------------------ */
@@ -119,8 +123,8 @@ int atomo_last_hip_error(const atomo_ctx* ctx);
 
 /* Work counters as read by the most recent atomo_status call (host-side only): how many 64x64
  * block-pair eigenproblems the Jacobi SVD solved since the status call before it, and how many
- * inner Jacobi sweeps those took in total. */
-int atomo_last_counters(const atomo_ctx* ctx, int32_t* pair_visits /*host*/, int32_t* inner_sweeps /*host*/);
+ * Jacobi steps (32 disjoint plane rotations each) those took in total. */
+int atomo_last_counters(const atomo_ctx* ctx, int32_t* pair_visits /*host*/, int32_t* jacobi_steps /*host*/);
 
 /* Waits for `stream`, then copies the number of Jacobi sweeps each matrix of the last
  * atomo_encode_svd took into sweeps[0 .. n_mats) (HOST) and, if refreshes is not NULL, how many

@@ -43,7 +43,7 @@ class atomo_ew_msg(C.Structure):
 
 class atomo_svd_options(C.Structure):
     _fields_ = [("max_sweeps", C.c_int32), ("stop_cosine", C.c_float), ("max_inner_sweeps", C.c_int32),
-                ("inner_reduction", C.c_float)]
+                ("inner_reduction", C.c_float), ("full_period", C.c_int32)]
 
 
 _lib = None
@@ -210,7 +210,7 @@ class Context:
         return {name: (ms[i], cnt[i]) for i, name in enumerate(self.KERNEL_CLASSES)}
 
     def last_counters(self):
-        """(block-pair eigenproblems solved, inner Jacobi sweeps taken) as of the last status() call."""
+        """(block-pair eigenproblems solved, Jacobi steps of 32 rotations taken) as of the last status() call."""
         a, b = C.c_int32(0), C.c_int32(0)
         _check(lib().atomo_last_counters(self._h, C.byref(a), C.byref(b)), "atomo_last_counters")
         return int(a.value), int(b.value)
@@ -252,7 +252,7 @@ def atomo_encode_svd(ctx: Context, mats: Sequence[torch.Tensor], s: float, seed:
                      msgs: Optional[List[SvdMessage]] = None, sigma_out: Optional[torch.Tensor] = None,
                      p_out: Optional[torch.Tensor] = None, max_sweeps: Optional[int] = None,
                      stop_cosine: Optional[float] = None, max_inner_sweeps: int = 0, inner_reduction: float = 0.0,
-                     stream=None) -> List[SvdMessage]:
+                     full_period: int = 0, stream=None) -> List[SvdMessage]:
     """Spectral-ATOMO encode of a list of 2-D float32 CUDA tensors (row stride = tensor stride)."""
     n = len(mats)
     c_mats = (atomo_mat * n)()
@@ -265,10 +265,10 @@ def atomo_encode_svd(ctx: Context, mats: Sequence[torch.Tensor], s: float, seed:
         msgs = [alloc_svd_message(g.shape[0], g.shape[1], default_capacity(s, min(g.shape)), g.device) for g in mats]
     c_msgs = (atomo_svd_msg * n)(*[m.c_struct() for m in msgs])
     opt = None
-    if max_sweeps is not None or stop_cosine is not None or max_inner_sweeps or inner_reduction:
+    if max_sweeps is not None or stop_cosine is not None or max_inner_sweeps or inner_reduction or full_period:
         opt = C.byref(atomo_svd_options(12 if max_sweeps is None else max_sweeps,
                                         1e-4 if stop_cosine is None else stop_cosine,
-                                        max_inner_sweeps, inner_reduction))
+                                        max_inner_sweeps, inner_reduction, int(full_period)))
     _check(lib().atomo_encode_svd(ctx._h, c_mats, n, float(s), int(seed) & (2 ** 64 - 1),
                                   int(stream_base) & (2 ** 64 - 1), opt, c_msgs,
                                   None if sigma_out is None else sigma_out.data_ptr(),

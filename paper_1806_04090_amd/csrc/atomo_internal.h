@@ -37,6 +37,9 @@ struct atomo_ctx {
     atomo::StageSlot ring[8];
     int ring_next = 0;
     std::vector<int*> svd_state;         // per matrix of the last SVD encode: device state words
+    // streams and events of the SVD encoder's internal fork/join (created on first use, default priority)
+    hipStream_t side = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     // optional event bracketing of kernel launches (atomo_profile_*)
     bool profiling = false;
     std::vector<hipEvent_t> ev_pool;     // pairs: [2k] start, [2k+1] stop
@@ -57,6 +60,9 @@ namespace atomo {
 
 // Grows the workspace to at least `bytes` (contents are not preserved).
 int ensure_workspace(atomo_ctx* ctx, size_t bytes);
+
+// Creates ctx->side and the fork/join events if they do not exist yet.
+int ensure_side_streams(atomo_ctx* ctx);
 
 // Copies `bytes` of host data to device address `dst` on `stream` through a pinned staging slot,
 // so the caller's host buffer may be reused as soon as this returns.

@@ -27,6 +27,15 @@ int ensure_workspace(atomo_ctx* ctx, size_t bytes)
     return ATOMO_OK;
 }
 
+int ensure_side_streams(atomo_ctx* ctx)
+{
+    if (!ctx->side) ATOMO_HIP(ctx, hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking));
+    hipEvent_t* events[] = {&ctx->ev_fork, &ctx->ev_join};
+    for (hipEvent_t* e : events)
+        if (!*e) ATOMO_HIP(ctx, hipEventCreateWithFlags(e, hipEventDisableTiming));
+    return ATOMO_OK;
+}
+
 int upload(atomo_ctx* ctx, void* dst, const void* src, size_t bytes, hipStream_t stream)
 {
     if (bytes == 0) return ATOMO_OK;
@@ -113,6 +122,9 @@ int atomo_destroy(atomo_ctx* ctx)
         if (slot.host) (void)hipHostFree(slot.host);
     }
     for (hipEvent_t e : ctx->ev_pool) (void)hipEventDestroy(e);
+    for (hipEvent_t e : {ctx->ev_fork, ctx->ev_join})
+        if (e) (void)hipEventDestroy(e);
+    if (ctx->side) (void)hipStreamDestroy(ctx->side);
     if (ctx->ws) (void)hipFree(ctx->ws);
     if (ctx->d_flags) (void)hipFree(ctx->d_flags);
     if (ctx->h_flags) (void)hipHostFree(ctx->h_flags);
@@ -196,11 +208,11 @@ int atomo_profile_read(atomo_ctx* ctx, double* total_ms, int64_t* launches)
 
 int atomo_last_hip_error(const atomo_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
 
-int atomo_last_counters(const atomo_ctx* ctx, int32_t* pair_visits, int32_t* inner_sweeps)
+int atomo_last_counters(const atomo_ctx* ctx, int32_t* pair_visits, int32_t* jacobi_steps)
 {
-    if (!ctx || !pair_visits || !inner_sweeps) return ATOMO_EINVAL;
+    if (!ctx || !pair_visits || !jacobi_steps) return ATOMO_EINVAL;
     *pair_visits = ctx->h_flags[FLAG_EIG_VISITS];
-    *inner_sweeps = ctx->h_flags[FLAG_EIG_INNER];
+    *jacobi_steps = ctx->h_flags[FLAG_EIG_INNER];
     return ATOMO_OK;
 }
 

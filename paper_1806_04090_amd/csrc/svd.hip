@@ -335,70 +335,12 @@ __global__ __launch_bounds__(256) void svd_rowop(const SvdMat* mats, const Work*
     }
 }
 
-// Gram-space matrices: the two-sided update  C <- D^T C D  (D = the block rotations of the round) and
-// Tgs <- D^T Tgs, one 64x64 tile per workgroup, in place.
-//   kind 1: tile (pair a, pair b) of C:  Qa^T * C[rows of a, columns of b] * Qb
-//   kind 2: 64 rows of pair a x 64 columns of Tgs:  Qa^T * Tgs[rows of a, chunk]
-__global__ __launch_bounds__(256) void svd_twosided(const SvdMat* mats, const Work* work, int tick)
+// Gram-space matrices: one tile of the two-sided update per workgroup (see twosided_tile).
+__global__ __launch_bounds__(256) void svd_twosided(const SvdMat* mats, const Work* work, int n_items, int tick,
+                                                    int phase)
 {
-    __shared__ float xs[PR][PR + 1];
-    __shared__ float ys[PR][PR + 1];
-    const Work wk = work[blockIdx.x];
-    const SvdMat m = mats[wk.mat];
-    if (m.state[ST_QTICK] != tick + 1) return;                   // svd_eig did not run for this matrix in this tick
-    const int kind = wk.c;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int qi = wave >> 1, qj = wave & 1, h = lane >> 5, l32 = lane & 31;
-    int ai, aj, bi = 0, bj = 0;
-    pair_blocks(m.nb2, tick % m.R, wk.a, ai, aj);
-    if (kind == 1) pair_blocks(m.nb2, tick % m.R, wk.b, bi, bj);
-    const float* qa = m.Q + (size_t)wk.a * QSZ;
-    const float* qb = m.Q + (size_t)wk.b * QSZ;
-    // column of local index j: inside C the columns of pair b, inside Tgs a plain 64-column chunk
-    auto col_of = [&](int j) { return kind == 1 ? (j < BS ? bi * BS + j : bj * BS + j - BS) : m.rows_alloc + wk.b * PR + j; };
-    auto row_of = [&](int i) { return i < BS ? ai * BS + i : aj * BS + i - BS; };
-
-    // every global load of the workgroup is issued before the first use: the tile, and the MFMA
-    // operands that come from Qa and Qb
-    float tile_regs[QSZ / 256], qa_regs[PR / 2], qb_regs[PR / 2];
-#pragma unroll
-    for (int p = 0; p < QSZ / 256; ++p) {
-        const int e = tid + 256 * p, i = e >> 6, j = e & 63;
-        tile_regs[p] = m.CT[(size_t)row_of(i) * m.ldc + col_of(j)];
-    }
-#pragma unroll
-    for (int s = 0; s < PR / 2; ++s) {
-        qa_regs[s] = qa[(2 * s + h) * PR + qi * BS + l32];       // (Qa^T)[i][k]
-        qb_regs[s] = kind == 1 ? qb[(2 * s + h) * PR + qj * BS + l32] : 0.0f;    // Qb[k][j]
-    }
-#pragma unroll
-    for (int p = 0; p < QSZ / 256; ++p) {
-        const int e = tid + 256 * p;
-        xs[e >> 6][e & 63] = tile_regs[p];
-    }
-    __syncthreads();
-    floatx16 acc;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-#pragma unroll
-    for (int s = 0; s < PR / 2; ++s)
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(qa_regs[s], xs[2 * s + h][qj * BS + l32], acc, 0, 0, 0);
-    if (kind == 1) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) ys[qi * BS + 8 * (v >> 2) + 4 * h + (v & 3)][qj * BS + l32] = acc[v];
-        __syncthreads();
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-#pragma unroll
-        for (int s = 0; s < PR / 2; ++s)
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(ys[qi * BS + l32][2 * s + h], qb_regs[s], acc, 0, 0, 0);
-    }
-    const int c = col_of(qj * BS + l32);
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const int i = qi * BS + 8 * (v >> 2) + 4 * h + (v & 3);
-        m.CT[(size_t)row_of(i) * m.ldc + c] = acc[v];
-    }
+    __shared__ float xs[PR * TLD];
+    twosided_tile(mats, work, (int)blockIdx.x, n_items, tick, phase, xs, (int)threadIdx.x);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -570,7 +512,7 @@ __global__ __launch_bounds__(256) void svd_pack(const SvdMat* mats, const Work* 
 
 struct Plan {
     std::vector<SvdMat> mats;
-    std::vector<Work> prep, gram, fullgram, tiles, apply, eig, rowop1, twosided, norms, pack;
+    std::vector<Work> prep, gram, fullgram, tiles, apply, eig_gs, eig_ds, rowop1, twosided, norms, pack;
     std::vector<int> gs_periods;     // distinct R of the Gram-space matrices
     int max_R = 1;
     int max_R_ds = 1;                // largest R among the data-space matrices
@@ -579,7 +521,7 @@ struct Plan {
     Work* d_work = nullptr;
     size_t n_work() const
     {
-        return prep.size() + gram.size() + fullgram.size() + tiles.size() + apply.size() + eig.size() +
+        return prep.size() + gram.size() + fullgram.size() + tiles.size() + apply.size() + eig_gs.size() + eig_ds.size() +
                rowop1.size() + twosided.size() + norms.size() + pack.size();
     }
 };
@@ -617,7 +559,7 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
         m.CT = m.gs ? carve.take<float>((size_t)m.rows_alloc * m.ldc) : nullptr;
         m.C2 = nullptr;
         m.gram = carve.take<float>((size_t)(m.gs ? m.ntiles : m.npairs) * m.nchg * QSZ);
-        m.Q = carve.take<float>((size_t)m.npairs * QSZ);
+        m.Q = carve.take<float>((size_t)(m.gs ? 2 : 1) * m.npairs * QSZ);
         m.state = carve.take<int>(ST_WORDS);
         m.sig_raw = carve.take<float>(m.rows_alloc);
         m.G = a.data; m.ldg = a.ld;
@@ -639,7 +581,7 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
         for (int b = 0; b < m.nb2; ++b)
             for (int c = 0; c < (m.ldw + 255) / 256; ++c) plan.prep.push_back(Work{j, b, c, 0});
         for (int k = 0; k < m.npairs; ++k) {
-            plan.eig.push_back(Work{j, k, 0, 0});
+            (m.gs ? plan.eig_gs : plan.eig_ds).push_back(Work{j, k, 0, 0});
             if (m.gs) {
                 for (int k2 = 0; k2 < m.npairs; ++k2) plan.twosided.push_back(Work{j, k, k2, 1});
                 for (int c = 0; c < m.rows_alloc / PR; ++c) plan.twosided.push_back(Work{j, k, c, 2});
@@ -690,6 +632,7 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     const int max_inner = opt && opt->max_inner_sweeps > 0 ? opt->max_inner_sweeps : 1;
     const float inner_reduction = opt && opt->inner_reduction > 0.0f ? opt->inner_reduction : 0.01f;
     const float fresh_stop = 0.25f * stop_cosine;
+    const int full_period = opt && opt->full_period > 0 ? opt->full_period : 8;
 
     Plan sizing;
     build_plan(mats, n_mats, msgs, sigma_out, p_out, stream_base, nullptr, sizing);
@@ -714,7 +657,8 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     const Work* w_fullgram = place(plan.fullgram);
     const Work* w_tiles = place(plan.tiles);
     const Work* w_apply = place(plan.apply);
-    const Work* w_eig = place(plan.eig);
+    const Work* w_eig_gs = place(plan.eig_gs);
+    const Work* w_eig_ds = place(plan.eig_ds);
     const Work* w_rowop1 = place(plan.rowop1);
     const Work* w_twosided = place(plan.twosided);
     const Work* w_norms = place(plan.norms);
@@ -733,35 +677,73 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
         svd_prepare<<<grid(plan.prep), 256, 0, stream>>>(d_mats, w_prep);
         svd_norms<<<grid(plan.norms), 256, 0, stream>>>(d_mats, w_norms, 1);
     }
-    const int n_ticks = max_sweeps * plan.max_R + 1;
-    for (int tick = 0; tick < n_ticks; ++tick) {
-        bool boundary = false;
-        for (int period : plan.gs_periods) boundary = boundary || tick % period == 0;
-        if (boundary) {
-            ProfScope ps(ctx, ATOMO_K_SVD_REFRESH, stream);
-            svd_apply<<<grid(plan.apply), 256, 0, stream>>>(d_mats, w_apply);
-            svd_gram<true><<<grid(plan.fullgram), 256, 0, stream>>>(d_mats, w_fullgram, tick, max_sweeps);
-            svd_fullgram_reduce<<<grid(plan.tiles), 256, 0, stream>>>(d_mats, w_tiles);
-            svd_fresh_check<<<grid(plan.tiles), 256, 0, stream>>>(d_mats, w_tiles, tick, max_sweeps, stop_cosine,
-                                                                  fresh_stop, ctx->d_flags);
+    // The data-space matrices iterate on a stream of their own from here to the end (one fork, one join).
+    // The Gram-space matrices iterate on the caller's stream, two launches per tick: svd_eig, then the part
+    // of the two-sided update that the next svd_eig reads (phase 1).  The rest of the update (phase 2) rides
+    // in the next tick's svd_eig launch as extra workgroups.  Rotations and their tick stamps are
+    // double-buffered by tick parity, so tick t+1 can produce rotations while tick t's are still applied.
+    const bool have_ds = !plan.gram.empty(), have_gs = !plan.twosided.empty();
+    const int n_two = (int)plan.twosided.size();
+    if (have_ds) {
+        rc = ensure_side_streams(ctx);
+        if (rc != ATOMO_OK) return rc;
+        hipStream_t s_ds = ctx->side;
+        ATOMO_HIP(ctx, hipEventRecord(ctx->ev_fork, stream));
+        ATOMO_HIP(ctx, hipStreamWaitEvent(s_ds, ctx->ev_fork, 0));
+        const int ds_ticks = max_sweeps * plan.max_R_ds;
+        for (int tick = 0; tick < ds_ticks; ++tick) {
+            {
+                ProfScope ps(ctx, ATOMO_K_SVD_GRAM, s_ds);
+                svd_gram<false><<<grid(plan.gram), 256, 0, s_ds>>>(d_mats, w_gram, tick, max_sweeps);
+            }
+            {
+                ProfScope ps(ctx, ATOMO_K_SVD_EIG, s_ds);
+                launch_svd_eig(d_mats, w_eig_ds, (int)plan.eig_ds.size(), nullptr, 0, tick, max_sweeps, stop_cosine,
+                               max_inner, inner_reduction, full_period, ctx->d_flags, s_ds);
+            }
+            {
+                ProfScope ps(ctx, ATOMO_K_SVD_UPDATE, s_ds);
+                svd_rowop<<<grid(plan.rowop1), 256, 0, s_ds>>>(d_mats, w_rowop1, tick, max_sweeps);
+            }
         }
-        const bool ds_active = !plan.gram.empty() && tick < max_sweeps * plan.max_R_ds;
-        if (ds_active) {
-            ProfScope ps(ctx, ATOMO_K_SVD_GRAM, stream);
-            svd_gram<false><<<grid(plan.gram), 256, 0, stream>>>(d_mats, w_gram, tick, max_sweeps);
+        ATOMO_HIP(ctx, hipEventRecord(ctx->ev_join, s_ds));
+    }
+    if (have_gs) {
+        const int n_ticks = max_sweeps * plan.max_R + 1;
+        bool rest_pending = false;                               // phase 2 of the previous tick not yet enqueued
+        for (int tick = 0; tick < n_ticks; ++tick) {
+            bool boundary = false;
+            for (int period : plan.gs_periods) boundary = boundary || tick % period == 0;
+            if (boundary) {
+                if (rest_pending) {                              // the refresh reads Tgs and rewrites C
+                    ProfScope ps(ctx, ATOMO_K_SVD_UPDATE, stream);
+                    svd_twosided<<<(unsigned)n_two, 256, 0, stream>>>(d_mats, w_twosided, n_two, tick - 1, 2);
+                    rest_pending = false;
+                }
+                ProfScope ps(ctx, ATOMO_K_SVD_REFRESH, stream);
+                svd_apply<<<grid(plan.apply), 256, 0, stream>>>(d_mats, w_apply);
+                svd_gram<true><<<grid(plan.fullgram), 256, 0, stream>>>(d_mats, w_fullgram, tick, max_sweeps);
+                svd_fullgram_reduce<<<grid(plan.tiles), 256, 0, stream>>>(d_mats, w_tiles);
+                svd_fresh_check<<<grid(plan.tiles), 256, 0, stream>>>(d_mats, w_tiles, tick, max_sweeps, stop_cosine,
+                                                                      fresh_stop, ctx->d_flags);
+            }
+            {
+                ProfScope ps(ctx, ATOMO_K_SVD_EIG, stream);
+                launch_svd_eig(d_mats, w_eig_gs, (int)plan.eig_gs.size(), w_twosided, rest_pending ? n_two : 0, tick,
+                               max_sweeps, stop_cosine, max_inner, inner_reduction, full_period, ctx->d_flags, stream);
+            }
+            {
+                ProfScope ps(ctx, ATOMO_K_SVD_UPDATE, stream);
+                svd_twosided<<<(unsigned)n_two, 256, 0, stream>>>(d_mats, w_twosided, n_two, tick, 1);
+            }
+            rest_pending = true;
         }
-        {
-            ProfScope ps(ctx, ATOMO_K_SVD_EIG, stream);
-            launch_svd_eig(d_mats, w_eig, (int)plan.eig.size(), tick, max_sweeps, stop_cosine, max_inner,
-                           inner_reduction, ctx->d_flags, stream);
-        }
-        {
+        if (rest_pending) {
             ProfScope ps(ctx, ATOMO_K_SVD_UPDATE, stream);
-            if (ds_active) svd_rowop<<<grid(plan.rowop1), 256, 0, stream>>>(d_mats, w_rowop1, tick, max_sweeps);
-            if (!plan.twosided.empty())
-                svd_twosided<<<grid(plan.twosided), 256, 0, stream>>>(d_mats, w_twosided, tick);
+            svd_twosided<<<(unsigned)n_two, 256, 0, stream>>>(d_mats, w_twosided, n_two, n_ticks - 1, 2);
         }
     }
+    if (have_ds) ATOMO_HIP(ctx, hipStreamWaitEvent(stream, ctx->ev_join, 0));
     {
         ProfScope ps(ctx, ATOMO_K_SVD_FINALIZE, stream);
         svd_norms<<<grid(plan.norms), 256, 0, stream>>>(d_mats, w_norms, 0);

@@ -12,6 +12,11 @@
 // double-buffered, so a step is: read buffer X, rotate, write buffer Y permuted, barrier.  Every
 // lane computes the rotation of its own column pair from the diagonal 2x2 block (redundantly in
 // every wave, so no second barrier) and fetches the rotations of its row pairs with lane reads.
+//
+// Cross schedule.  The two diagonal 32x32 blocks of the pair only need to be diagonalised once per outer
+// sweep (cyclic Jacobi rotates every index pair once per sweep); in the other rounds the kernel rotates
+// only the 32 x 32 pairs that couple the two blocks: block a sits in the even slots, block b in the odd
+// slots, the even slots stay and the odd slots move on by one pair per step, 32 steps instead of 63.
 #include <cfloat>
 
 #include "svd_common.h"
@@ -34,8 +39,14 @@ __device__ inline int next_slot(int s)
     return s == 62 ? 63 : s + 2;
 }
 
+// the cross schedule: even slots stay, odd slot 2k+1 moves to 2(k+1 mod 32)+1
+__device__ inline int next_slot_cross(int s) { return (s & 1) ? ((((s >> 1) + 1) & 31) << 1) | 1 : s; }
+
 // column of slot s inside a row: even slots first, then odd slots
 __device__ inline int mem_col(int s) { return (s >> 1) + 32 * (s & 1); }
+
+// slot in which index i of the pair starts (and ends) a sweep
+__device__ inline int home_slot(int i, bool cross) { return cross ? (i < 32 ? 2 * i : 2 * (i - 32) + 1) : i; }
 
 // Largest |A_ij| / max(sqrt(A_ii A_jj), z2) over i < j, and largest diagonal entry.  All threads call.
 __device__ inline float2 max_cosine(const float* A, float z2, float* red)
@@ -88,8 +99,12 @@ __device__ inline float2 pair_rotation(const float* A, int k, float z2)
     return make_float2(c, s);
 }
 
-__global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* work, int step, int max_sweeps,
-                                              float stop_cosine, int max_inner, float inner_reduction, int* flags)
+// Workgroups 0 .. n_eig-1 solve block pairs.  Workgroups beyond take no pair: each applies four tiles of the
+// previous tick's phase-2 two-sided update (one tile per group of four waves, staged in the LDS arrays a
+// pair problem would use), work that neither feeds this tick's pair problems nor touches what they write.
+__global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* work, int n_eig, const Work* two_work,
+                                              int n_two, int step, int max_sweeps, float stop_cosine, int max_inner,
+                                              float inner_reduction, int full_period, int* flags)
 {
     __shared__ float As[2][PR * ELD];
     __shared__ float Qs[2][PR * ELD];
@@ -97,6 +112,13 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
     __shared__ int dest[PR];
     __shared__ float red[32];
 
+    if ((int)blockIdx.x >= n_eig) {
+        const int group = threadIdx.x >> 8;
+        float* tile = group == 0 ? As[0] : group == 1 ? As[1] : group == 2 ? Qs[0] : Qs[1];
+        twosided_tile(mats, two_work, ((int)blockIdx.x - n_eig) * 4 + group, n_two, step - 1, 2, tile,
+                      (int)(threadIdx.x & 255));
+        return;
+    }
     const Work wk = work[blockIdx.x];
     const SvdMat m = mats[wk.mat];
     if (m.gs) {
@@ -108,13 +130,14 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
     int bi, bj;
     pair_blocks(m.nb2, round, wk.a, bi, bj);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const bool cross = round % full_period != 0;
 
     // 1. the Gram matrix of the pair: its block of C (Gram-space matrices), or the partial sums in a
     //    fixed order (data-space matrices); symmetrise (the two triangles were accumulated in
     //    different orders); Q = I
     {
         const float* g = m.gram + (size_t)wk.a * m.nchg * QSZ;
-        if (m.gs && tid == 0) m.state[ST_QTICK] = step + 1;
+        if (m.gs && tid == 0) m.state[(step & 1) ? ST_QTICK_ODD : ST_QTICK] = step + 1;
         for (int e = tid; e < QSZ; e += NT) {
             const int i = e >> 6, j = e & 63;
             float sum = 0.0f;
@@ -125,16 +148,17 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
             } else {
                 for (int c = 0; c < m.nchg; ++c) sum += g[(size_t)c * QSZ + e];
             }
-            As[0][i * ELD + mem_col(j)] = sum;
-            Qs[0][i * ELD + mem_col(j)] = (i == j) ? 1.0f : 0.0f;
+            As[0][home_slot(i, cross) * ELD + mem_col(home_slot(j, cross))] = sum;
+            Qs[0][i * ELD + mem_col(home_slot(j, cross))] = (i == j) ? 1.0f : 0.0f;
         }
         __syncthreads();
         for (int e = tid; e < QSZ; e += NT) {
             const int i = e >> 6, j = e & 63;
             if (i < j) {
-                const float v = 0.5f * (As[0][i * ELD + mem_col(j)] + As[0][j * ELD + mem_col(i)]);
-                As[0][i * ELD + mem_col(j)] = v;
-                As[0][j * ELD + mem_col(i)] = v;
+                const int si = home_slot(i, cross), sj = home_slot(j, cross);
+                const float v = 0.5f * (As[0][si * ELD + mem_col(sj)] + As[0][sj * ELD + mem_col(si)]);
+                As[0][si * ELD + mem_col(sj)] = v;
+                As[0][sj * ELD + mem_col(si)] = v;
             }
         }
     }
@@ -152,7 +176,14 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
     // 3. Jacobi sweeps.  Thread (b, g): slot pair b of the columns, row pairs g*RP_PER.. of A, rows
     //    g*QR_PER.. of Q.  Its two outputs per row go to the columns of slots next(2b), next(2b+1).
     const int b = tid & 31, grp = tid >> 5;
-    const int wc0 = mem_col(next_slot(2 * b)), wc1 = mem_col(next_slot(2 * b + 1));
+    auto advance = [&](int s) { return cross ? next_slot_cross(s) : next_slot(s); };
+    const int wc0 = mem_col(advance(2 * b)), wc1 = mem_col(advance(2 * b + 1));
+    int wr0[RP_PER], wr1[RP_PER];
+#pragma unroll
+    for (int e = 0; e < RP_PER; ++e) {
+        wr0[e] = advance(2 * (grp * RP_PER + e)) * ELD;
+        wr1[e] = advance(2 * (grp * RP_PER + e) + 1) * ELD;
+    }
     int cur = 0;
     int inner_done = 0;
     if (entry.x > 0.0f) {
@@ -188,7 +219,7 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
                 const float x00 = xa[e][0], x01 = xa[e][1], x10 = xa[e][2], x11 = xa[e][3];
                 const float y00 = pa.x * x00 - pa.y * x10, y01 = pa.x * x01 - pa.y * x11;
                 const float y10 = pa.y * x00 + pa.x * x10, y11 = pa.y * x01 + pa.x * x11;
-                const int r0 = next_slot(2 * a) * ELD, r1 = next_slot(2 * a + 1) * ELD;
+                const int r0 = wr0[e], r1 = wr1[e];
                 Y[r0 + wc0] = pb.x * y00 - pb.y * y01;
                 Y[r0 + wc1] = pb.y * y00 + pb.x * y01;
                 Y[r1 + wc0] = pb.x * y10 - pb.y * y11;
@@ -208,12 +239,14 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
             float* A1 = As[cur ^ 1];
             float* Q0 = Qs[cur];
             float* Q1 = Qs[cur ^ 1];
-            for (int t = 0; t < 62; t += 2) {
+            for (int t = 0; t < (cross ? 32 : 62); t += 2) {
                 jacobi_step(A0, A1, Q0, Q1);
                 jacobi_step(A1, A0, Q1, Q0);
             }
-            jacobi_step(A0, A1, Q0, Q1);
-            cur ^= 1;
+            if (!cross) {                                        // 63 steps: one more, into the other buffer
+                jacobi_step(A0, A1, Q0, Q1);
+                cur ^= 1;
+            }
             ++inner_done;
             if (isw + 1 < max_inner) {
                 const float2 now = max_cosine(As[cur], z2, red);
@@ -226,7 +259,7 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
     float* F = Qs[cur ^ 1];                                      // scratch for the Newton-Schulz factor
     for (int e = tid; e < QSZ; e += NT) {
         const int i = e >> 6, j = e & 63;
-        Qm[i * ELD + j] = Qs[cur][i * ELD + mem_col(j)];
+        Qm[i * ELD + j] = Qs[cur][i * ELD + mem_col(home_slot(j, cross))];
     }
 
     // 4. eigenvalues, and where each eigenvector goes: decreasing eigenvalue over the live rows of
@@ -234,7 +267,8 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
     const int nI = max(0, min(BS, m.r - bi * BS)), nJ = max(0, min(BS, m.r - bj * BS));
     if (tid < PR) {
         const bool live = tid < BS ? tid < nI : tid - BS < nJ;
-        ev[tid] = live ? Acur[tid * ELD + mem_col(tid)] : -FLT_MAX;
+        const int sl = home_slot(tid, cross);
+        ev[tid] = live ? Acur[sl * ELD + mem_col(sl)] : -FLT_MAX;
     }
     __syncthreads();
     if (tid < PR) {
@@ -283,7 +317,7 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
             acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bq, acc, 0, 0, 0);
         }
         // 6. write Q with its columns permuted to their destination rows
-        float* qout = m.Q + (size_t)wk.a * QSZ;
+        float* qout = m.Q + ((size_t)(m.gs ? (step & 1) * m.npairs : 0) + wk.a) * QSZ;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int i = qi * BS + 8 * (v >> 2) + 4 * h + (v & 3), j = qj * BS + l32;
@@ -293,7 +327,7 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
 
     if (tid == 0) {
         atomicAdd(&flags[FLAG_EIG_VISITS], 1);
-        atomicAdd(&flags[FLAG_EIG_INNER], inner_done);
+        atomicAdd(&flags[FLAG_EIG_INNER], inner_done * (cross ? 32 : 63));
     }
 
     // 7. end of a sweep: the last pair to arrive decides whether the matrix is finished
@@ -325,11 +359,15 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
 
 }  // namespace
 
-void launch_svd_eig(const SvdMat* d_mats, const Work* d_work, int n_items, int step, int max_sweeps,
-                    float stop_cosine, int max_inner, float inner_reduction, int* d_flags, hipStream_t stream)
+void launch_svd_eig(const SvdMat* d_mats, const Work* d_work, int n_items, const Work* d_two_work, int n_two, int step,
+                    int max_sweeps, float stop_cosine, int max_inner, float inner_reduction, int full_period,
+                    int* d_flags, hipStream_t stream)
 {
-    svd_eig<<<(unsigned)n_items, NT, 0, stream>>>(d_mats, d_work, step, max_sweeps, stop_cosine, max_inner,
-                                                  inner_reduction, d_flags);
+    static_assert(PR * ELD == PR * TLD, "the two-sided tiles are staged in the LDS arrays of the pair problem");
+    const unsigned grid = (unsigned)(n_items + (n_two + 3) / 4);
+    if (grid == 0) return;
+    svd_eig<<<grid, NT, 0, stream>>>(d_mats, d_work, n_items, d_two_work, n_two, step, max_sweeps, stop_cosine,
+                                     max_inner, inner_reduction, full_period, d_flags);
 }
 
 }  // namespace svd
