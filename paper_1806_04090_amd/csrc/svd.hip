@@ -200,7 +200,7 @@ __global__ __launch_bounds__(256) void svd_gram(const SvdMat* mats, const Work* 
 }
 
 // Sums the partial tiles of the full Gram matrix into C (both triangles) and resets Tgs to I.
-__global__ __launch_bounds__(256) void svd_fullgram_reduce(const SvdMat* mats, const Work* work)
+__global__ __launch_bounds__(256) void svd_fullgram_reduce(const SvdMat* mats, const Work* work, int tick)
 {
     __shared__ float t[PR][PR + 1];
     const Work wk = work[blockIdx.x];
@@ -217,13 +217,14 @@ __global__ __launch_bounds__(256) void svd_fullgram_reduce(const SvdMat* mats, c
     }
     __syncthreads();
     const int Rp = m.rows_alloc;
+    float* C = c_of_parity(m, tick);                             // the C that this tick's svd_eig reads
     for (int e = tid; e < QSZ; e += 256) {
         const int i = e >> 6, j = e & 63;
         const float v = ti == tj ? 0.5f * (t[i][j] + t[j][i]) : t[i][j];
-        m.CT[(size_t)(ti * PR + i) * m.ldc + tj * PR + j] = v;
+        C[(size_t)(ti * PR + i) * m.ldc + tj * PR + j] = v;
         m.CT[(size_t)(ti * PR + i) * m.ldc + Rp + tj * PR + j] = (ti == tj && i == j) ? 1.0f : 0.0f;
         if (ti != tj) {                                          // mirrored tile: row index runs over j
-            m.CT[(size_t)(tj * PR + i) * m.ldc + ti * PR + j] = t[j][i];
+            C[(size_t)(tj * PR + i) * m.ldc + ti * PR + j] = t[j][i];
             m.CT[(size_t)(tj * PR + i) * m.ldc + Rp + ti * PR + j] = 0.0f;
         }
     }
@@ -241,15 +242,16 @@ __global__ __launch_bounds__(256) void svd_fresh_check(const SvdMat* mats, const
     const int ti = wk.a, tj = wk.b;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float z2 = ZERO_REL * __int_as_float(m.state[ST_SCALE]);
+    const float* C = c_of_parity(m, tick);
     float mx = 0.0f, dmax = 0.0f;
     for (int e = tid; e < QSZ; e += 256) {
         const int gi = ti * PR + (e >> 6), gj = tj * PR + (e & 63);
         if (gi < gj) {
-            const float dii = m.CT[(size_t)gi * m.ldc + gi], djj = m.CT[(size_t)gj * m.ldc + gj];
+            const float dii = C[(size_t)gi * m.ldc + gi], djj = C[(size_t)gj * m.ldc + gj];
             if (dii > 0.0f && djj > 0.0f)
-                mx = fmaxf(mx, fabsf(m.CT[(size_t)gi * m.ldc + gj]) / fmaxf(sqrtf(dii * djj), z2));
+                mx = fmaxf(mx, fabsf(C[(size_t)gi * m.ldc + gj]) / fmaxf(sqrtf(dii * djj), z2));
         } else if (gi == gj) {
-            dmax = fmaxf(dmax, m.CT[(size_t)gi * m.ldc + gi]);
+            dmax = fmaxf(dmax, C[(size_t)gi * m.ldc + gi]);
         }
     }
     for (int o = 32; o > 0; o >>= 1) {
@@ -278,6 +280,7 @@ __global__ __launch_bounds__(256) void svd_fresh_check(const SvdMat* mats, const
         if (!(fresh < stop_cosine)) atomicMax(&flags[FLAG_NOCONV], 1);
     } else {
         m.state[ST_MODE] = MODE_SWEEPS;
+        m.state[ST_FRESH_AT] = tick + 1;
     }
     m.state[ST_FRESH] = 0;
     m.state[ST_ARRIVE2] = 0;
@@ -336,11 +339,10 @@ __global__ __launch_bounds__(256) void svd_rowop(const SvdMat* mats, const Work*
 }
 
 // Gram-space matrices: one tile of the two-sided update per workgroup (see twosided_tile).
-__global__ __launch_bounds__(256) void svd_twosided(const SvdMat* mats, const Work* work, int n_items, int tick,
-                                                    int phase)
+__global__ __launch_bounds__(256) void svd_twosided(const SvdMat* mats, const Work* work, int n_items, int tick)
 {
     __shared__ float xs[PR * TLD];
-    twosided_tile(mats, work, (int)blockIdx.x, n_items, tick, phase, xs, (int)threadIdx.x);
+    twosided_tile(mats, work, (int)blockIdx.x, n_items, tick, xs, (int)threadIdx.x);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -557,7 +559,7 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
         m.W0 = carve.take<float>((size_t)m.rows_alloc * m.ldw);
         m.W1 = m.gs ? carve.take<float>((size_t)m.rows_alloc * m.ldw) : nullptr;
         m.CT = m.gs ? carve.take<float>((size_t)m.rows_alloc * m.ldc) : nullptr;
-        m.C2 = nullptr;
+        m.CT2 = m.gs ? carve.take<float>((size_t)m.rows_alloc * m.ldc) : nullptr;
         m.gram = carve.take<float>((size_t)(m.gs ? m.ntiles : m.npairs) * m.nchg * QSZ);
         m.Q = carve.take<float>((size_t)(m.gs ? 2 : 1) * m.npairs * QSZ);
         m.state = carve.take<int>(ST_WORDS);
@@ -678,10 +680,11 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
         svd_norms<<<grid(plan.norms), 256, 0, stream>>>(d_mats, w_norms, 1);
     }
     // The data-space matrices iterate on a stream of their own from here to the end (one fork, one join).
-    // The Gram-space matrices iterate on the caller's stream, two launches per tick: svd_eig, then the part
-    // of the two-sided update that the next svd_eig reads (phase 1).  The rest of the update (phase 2) rides
-    // in the next tick's svd_eig launch as extra workgroups.  Rotations and their tick stamps are
-    // double-buffered by tick parity, so tick t+1 can produce rotations while tick t's are still applied.
+    // The Gram-space matrices iterate on the caller's stream, one launch per tick: svd_eig of tick t, which
+    // carries the two-sided update of tick t-1 as extra workgroups.  That works because C alternates between
+    // two buffers: the update of tick t-1 reads the C of parity t-1 and writes parity t, while svd_eig of tick
+    // t forms its own 64x64 block from the C of parity t-1 and the rotations of tick t-1, which are
+    // double-buffered by tick parity as well.
     const bool have_ds = !plan.gram.empty(), have_gs = !plan.twosided.empty();
     const int n_two = (int)plan.twosided.size();
     if (have_ds) {
@@ -699,7 +702,7 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
             {
                 ProfScope ps(ctx, ATOMO_K_SVD_EIG, s_ds);
                 launch_svd_eig(d_mats, w_eig_ds, (int)plan.eig_ds.size(), nullptr, 0, tick, max_sweeps, stop_cosine,
-                               max_inner, inner_reduction, full_period, ctx->d_flags, s_ds);
+                               max_inner, inner_reduction, full_period, 0, ctx->d_flags, s_ds);
             }
             {
                 ProfScope ps(ctx, ATOMO_K_SVD_UPDATE, s_ds);
@@ -710,37 +713,35 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     }
     if (have_gs) {
         const int n_ticks = max_sweeps * plan.max_R + 1;
-        bool rest_pending = false;                               // phase 2 of the previous tick not yet enqueued
         for (int tick = 0; tick < n_ticks; ++tick) {
+            // the matrices that sweep on, and the previous tick's update for every matrix
+            if (tick > 0) {
+                ProfScope ps(ctx, ATOMO_K_SVD_EIG, stream);
+                launch_svd_eig(d_mats, w_eig_gs, (int)plan.eig_gs.size(), w_twosided, n_two, tick, max_sweeps,
+                               stop_cosine, max_inner, inner_reduction, full_period, 0, ctx->d_flags, stream);
+            }
             bool boundary = false;
             for (int period : plan.gs_periods) boundary = boundary || tick % period == 0;
-            if (boundary) {
-                if (rest_pending) {                              // the refresh reads Tgs and rewrites C
-                    ProfScope ps(ctx, ATOMO_K_SVD_UPDATE, stream);
-                    svd_twosided<<<(unsigned)n_two, 256, 0, stream>>>(d_mats, w_twosided, n_two, tick - 1, 2);
-                    rest_pending = false;
-                }
+            if (!boundary) continue;
+            // a sweep boundary of some matrix: those that asked for it get a fresh Gram matrix (their Tgs is
+            // complete now), and their pair problems of this tick run in a launch of their own
+            {
                 ProfScope ps(ctx, ATOMO_K_SVD_REFRESH, stream);
                 svd_apply<<<grid(plan.apply), 256, 0, stream>>>(d_mats, w_apply);
                 svd_gram<true><<<grid(plan.fullgram), 256, 0, stream>>>(d_mats, w_fullgram, tick, max_sweeps);
-                svd_fullgram_reduce<<<grid(plan.tiles), 256, 0, stream>>>(d_mats, w_tiles);
+                svd_fullgram_reduce<<<grid(plan.tiles), 256, 0, stream>>>(d_mats, w_tiles, tick);
                 svd_fresh_check<<<grid(plan.tiles), 256, 0, stream>>>(d_mats, w_tiles, tick, max_sweeps, stop_cosine,
                                                                       fresh_stop, ctx->d_flags);
             }
             {
                 ProfScope ps(ctx, ATOMO_K_SVD_EIG, stream);
-                launch_svd_eig(d_mats, w_eig_gs, (int)plan.eig_gs.size(), w_twosided, rest_pending ? n_two : 0, tick,
-                               max_sweeps, stop_cosine, max_inner, inner_reduction, full_period, ctx->d_flags, stream);
+                launch_svd_eig(d_mats, w_eig_gs, (int)plan.eig_gs.size(), nullptr, 0, tick, max_sweeps, stop_cosine,
+                               max_inner, inner_reduction, full_period, 1, ctx->d_flags, stream);
             }
-            {
-                ProfScope ps(ctx, ATOMO_K_SVD_UPDATE, stream);
-                svd_twosided<<<(unsigned)n_two, 256, 0, stream>>>(d_mats, w_twosided, n_two, tick, 1);
-            }
-            rest_pending = true;
         }
-        if (rest_pending) {
+        {
             ProfScope ps(ctx, ATOMO_K_SVD_UPDATE, stream);
-            svd_twosided<<<(unsigned)n_two, 256, 0, stream>>>(d_mats, w_twosided, n_two, n_ticks - 1, 2);
+            svd_twosided<<<(unsigned)n_two, 256, 0, stream>>>(d_mats, w_twosided, n_two, n_ticks - 1);
         }
     }
     if (have_ds) ATOMO_HIP(ctx, hipStreamWaitEvent(stream, ctx->ev_join, 0));

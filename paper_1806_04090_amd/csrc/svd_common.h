@@ -36,7 +36,8 @@ enum {
     ST_REFRESHES = 14,  // Gram-space matrices: fresh Gram matrices formed so far
     ST_QTICK = 13,      // Gram-space matrices: 1 + the last even tick in which svd_eig produced rotations
     ST_QTICK_ODD = 15,  //                      the same for odd ticks (rotations are double-buffered by tick parity)
-    ST_WORDS = 16
+    ST_FRESH_AT = 16,   // Gram-space matrices: 1 + the tick whose refresh wrote C from the data (svd_eig reads it as is)
+    ST_WORDS = 24
 };
 
 enum { MODE_NEED_REFRESH = 0, MODE_SWEEPS = 1, MODE_DONE = 2 };
@@ -50,7 +51,7 @@ struct SvdMat {
     float* W0;               // rows_alloc x ldw: [A | T]
     float* W1;               // second buffer of the same shape, Gram-space matrices only (else null)
     float* CT;               // Gram space: rows_alloc x ldc, [C | Tgs]
-    float* C2;               // Gram space: rows_alloc x rows_alloc scratch for the two-sided update
+    float* CT2;              // Gram space: second buffer of the same shape; its C half alternates with CT's by tick parity
     int ldw, ldc, r, M, Mp, rows_alloc;
     int nb2, R, npairs, nchg, nchu, gs, ntiles;
     float* gram;             // data space: [npairs][nchg][64*64]; Gram space: [ntiles][nchg][64*64]
@@ -95,27 +96,6 @@ __device__ inline void pair_blocks(int nb2, int round, int k, int& bi, int& bj)
 }
 
 // Data-space matrices: true if work for `tick` should be skipped (finished earlier, or past the sweep limit).
-// The block that shares a pair with block x in `round`.
-__device__ inline int partner_block(int nb2, int round, int x)
-{
-    int a, b;
-    pair_blocks(nb2, round, pair_of_block(nb2, round, x), a, b);
-    return a == x ? b : a;
-}
-
-// Gram-space tile (pair k1, pair k2) of `round`: does the next round's svd_eig read any of it?  The next
-// round's pair (a', b') reads the blocks (a',a'), (a',b'), (b',a'), (b',b') of C.
-__device__ inline bool tile_feeds_next_round(int nb2, int R, int round, int k1, int k2)
-{
-    if (k1 == k2) return true;
-    const int next = (round + 1) % R;
-    int x0, x1, y0, y1;
-    pair_blocks(nb2, round, k1, x0, x1);
-    pair_blocks(nb2, round, k2, y0, y1);
-    const int p0 = partner_block(nb2, next, x0), p1 = partner_block(nb2, next, x1);
-    return p0 == y0 || p0 == y1 || p1 == y0 || p1 == y1;
-}
-
 __device__ inline bool skip_step(const SvdMat& m, int tick, int max_sweeps)
 {
     const int done_at = m.state[ST_DONE_AT];
@@ -134,27 +114,30 @@ __device__ inline float* current_w(const SvdMat& m)
     return (m.gs && (m.state[ST_CUR] & 1)) ? w1 : w0;
 }
 
+// Gram-space matrices: the buffer whose C half holds the Gram matrix of tick parity `parity`.
+__device__ inline float* c_of_parity(const SvdMat& m, int parity)
+{
+    float* const c0 = m.CT;
+    float* const c1 = m.CT2;
+    return (parity & 1) ? c1 : c0;
+}
+
 constexpr int TLD = PR + 1;      // row stride of a 64x64 tile staged in LDS
 
 // Gram-space matrices: the two-sided update  C <- D^T C D  (D = the block rotations of the round) and
-// Tgs <- D^T Tgs, one 64x64 tile at a time, in place, by 256 threads (tid 0..255) that own the LDS tile xs:
-//   kind 1: tile (pair a, pair b) of C:  Qa^T * C[rows of a, columns of b] * Qb
-//   kind 2: 64 rows of pair a x 64 columns of Tgs:  Qa^T * Tgs[rows of a, chunk]
-// phase 1 updates only the tiles of C that the next round's svd_eig reads, phase 2 all the others (and
-// Tgs), so that phase 2 can run beside the next svd_eig; every tile is updated by exactly one of the two.
+// Tgs <- D^T Tgs, one 64x64 tile at a time, by 256 threads (tid 0..255) that own the LDS tile xs:
+//   kind 1: tile (pair a, pair b) of C:  Qa^T * C[rows of a, columns of b] * Qb, read from the C of this tick's
+//           parity and written to the C of the other parity (svd_eig of the next tick still reads the old one)
+//   kind 2: 64 rows of pair a x 64 columns of Tgs:  Qa^T * Tgs[rows of a, chunk], in place
 // Every thread of the workgroup must call this (three workgroup barriers), with item >= n_items for none.
-__device__ inline void twosided_tile(const SvdMat* mats, const Work* work, int item, int n_items, int tick, int phase,
-                                     float* xs, int tid)
+__device__ inline void twosided_tile(const SvdMat* mats, const Work* work, int item, int n_items, int tick, float* xs,
+                                     int tid)
 {
     bool active = item < n_items;
     const Work wk = active ? work[item] : Work{0, 0, 0, 0};
     const SvdMat m = mats[wk.mat];
     const int kind = wk.c;
     if (active) active = m.state[(tick & 1) ? ST_QTICK_ODD : ST_QTICK] == tick + 1;   // did svd_eig rotate in this tick?
-    if (active) {
-        const bool feeds = kind == 1 && tile_feeds_next_round(m.nb2, m.R, tick % m.R, wk.a, wk.b);
-        active = feeds == (phase == 1);
-    }
     const int lane = tid & 63, wave = tid >> 6;
     const int qi = wave >> 1, qj = wave & 1, h = lane >> 5, l32 = lane & 31;
     int ai = 0, aj = 0, bi = 0, bj = 0;
@@ -164,6 +147,8 @@ __device__ inline void twosided_tile(const SvdMat* mats, const Work* work, int i
     }
     const float* qa = m.Q + ((size_t)(tick & 1) * m.npairs + wk.a) * QSZ;
     const float* qb = m.Q + ((size_t)(tick & 1) * m.npairs + wk.b) * QSZ;
+    const float* src = kind == 1 ? c_of_parity(m, tick) : m.CT;
+    float* dst = kind == 1 ? c_of_parity(m, tick + 1) : m.CT;
     // column of local index j: inside C the columns of pair b, inside Tgs a plain 64-column chunk
     auto col_of = [&](int j) { return kind == 1 ? (j < BS ? bi * BS + j : bj * BS + j - BS) : m.rows_alloc + wk.b * PR + j; };
     auto row_of = [&](int i) { return i < BS ? ai * BS + i : aj * BS + i - BS; };
@@ -174,7 +159,7 @@ __device__ inline void twosided_tile(const SvdMat* mats, const Work* work, int i
 #pragma unroll
         for (int p = 0; p < QSZ / 256; ++p) {
             const int e = tid + 256 * p, i = e >> 6, j = e & 63;
-            tile_regs[p] = m.CT[(size_t)row_of(i) * m.ldc + col_of(j)];
+            tile_regs[p] = src[(size_t)row_of(i) * m.ldc + col_of(j)];
         }
 #pragma unroll
         for (int s = 0; s < PR / 2; ++s) {
@@ -214,15 +199,16 @@ __device__ inline void twosided_tile(const SvdMat* mats, const Work* work, int i
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
         const int i = qi * BS + 8 * (v >> 2) + 4 * h + (v & 3);
-        m.CT[(size_t)row_of(i) * m.ldc + c] = acc[v];
+        dst[(size_t)row_of(i) * m.ldc + c] = acc[v];
     }
 }
 
 // Enqueues svd_eig for one tick (defined in svd_eig.hip): n_items pair problems, plus, when n_two > 0, the
-// phase-2 two-sided update of tick - 1 over the n_two tiles of d_two_work.
+// two-sided update of tick - 1 over the n_two tiles of d_two_work.  fresh_only selects, among the Gram-space
+// matrices, those whose Gram matrix was formed in this very tick (1) or all the others (0).
 void launch_svd_eig(const SvdMat* d_mats, const Work* d_work, int n_items, const Work* d_two_work, int n_two, int tick,
                     int max_sweeps, float stop_cosine, int max_inner, float inner_reduction, int full_period,
-                    int* d_flags, hipStream_t stream);
+                    int fresh_only, int* d_flags, hipStream_t stream);
 
 }  // namespace svd
 }  // namespace atomo

@@ -27,6 +27,7 @@ namespace svd {
 namespace {
 
 constexpr int NT = 1024;                // threads per workgroup
+constexpr int TILES_PER_WG = NT / 256;  // two-sided tiles a workgroup without a pair problem applies
 constexpr int ELD = 65;                 // LDS row stride
 constexpr int GROUPS = NT / 32;         // thread groups of 32 (one slot pair of columns per thread)
 constexpr int RP_PER = 32 / GROUPS;     // row pairs of A per thread
@@ -100,11 +101,12 @@ __device__ inline float2 pair_rotation(const float* A, int k, float z2)
 }
 
 // Workgroups 0 .. n_eig-1 solve block pairs.  Workgroups beyond take no pair: each applies four tiles of the
-// previous tick's phase-2 two-sided update (one tile per group of four waves, staged in the LDS arrays a
-// pair problem would use), work that neither feeds this tick's pair problems nor touches what they write.
+// previous tick's two-sided update (one tile per group of four waves, staged in the LDS arrays a pair problem
+// would use).  The update writes the C of this tick's parity; the pair problems read the C of the previous
+// parity and bring their own 64x64 block up to date themselves (step 1 below), so the two do not meet.
 __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* work, int n_eig, const Work* two_work,
                                               int n_two, int step, int max_sweeps, float stop_cosine, int max_inner,
-                                              float inner_reduction, int full_period, int* flags)
+                                              float inner_reduction, int full_period, int fresh_only, int* flags)
 {
     __shared__ float As[2][PR * ELD];
     __shared__ float Qs[2][PR * ELD];
@@ -115,7 +117,7 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
     if ((int)blockIdx.x >= n_eig) {
         const int group = threadIdx.x >> 8;
         float* tile = group == 0 ? As[0] : group == 1 ? As[1] : group == 2 ? Qs[0] : Qs[1];
-        twosided_tile(mats, two_work, ((int)blockIdx.x - n_eig) * 4 + group, n_two, step - 1, 2, tile,
+        twosided_tile(mats, two_work, ((int)blockIdx.x - n_eig) * TILES_PER_WG + group, n_two, step - 1, tile,
                       (int)(threadIdx.x & 255));
         return;
     }
@@ -123,6 +125,9 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
     const SvdMat m = mats[wk.mat];
     if (m.gs) {
         if (m.state[ST_DONE_AT] != 0 || m.state[ST_MODE] != MODE_SWEEPS) return;
+        // a tick with a refresh has two launches: before it, the matrices that sweep on; after it, those
+        // whose Gram matrix the refresh has just formed
+        if ((m.state[ST_FRESH_AT] == step + 1) != (fresh_only != 0)) return;
     } else if (skip_step(m, step, max_sweeps)) {
         return;
     }
@@ -132,34 +137,107 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const bool cross = round % full_period != 0;
 
-    // 1. the Gram matrix of the pair: its block of C (Gram-space matrices), or the partial sums in a
-    //    fixed order (data-space matrices); symmetrise (the two triangles were accumulated in
-    //    different orders); Q = I
-    {
+    // 1. the Gram matrix of the pair into As[0] (home slots), Q = I into Qs[0].
+    //    Data-space matrices: the partial sums, added in a fixed order.
+    //    Gram-space matrices, first tick after a refresh: the pair's block of C as it is.
+    //    Gram-space matrices otherwise: C (previous parity) does not contain the previous tick's rotations yet.
+    //    With the pair's blocks a (then in pair k1, half s1) and b (pair k2, half s2) of the previous round,
+    //        [aa ab; ba bb] = [Q1s^T C11 Q1s, Q1s^T C12 Q2s; ., Q2s^T C22 Q2s],   Qks = columns 32 s .. of Q_k,
+    //    three 32x32 blocks, each two chained MFMA products (32x64x64, then 32x32x64); ba mirrors ab.
+    const bool fresh = m.gs && m.state[ST_FRESH_AT] == step + 1;
+    if (m.gs && tid == 0) m.state[(step & 1) ? ST_QTICK_ODD : ST_QTICK] = step + 1;
+    for (int e = tid; e < QSZ; e += NT) {
+        const int i = e >> 6, j = e & 63;
+        Qs[0][i * ELD + mem_col(home_slot(j, cross))] = (i == j) ? 1.0f : 0.0f;
+    }
+    if (!m.gs || fresh) {
         const float* g = m.gram + (size_t)wk.a * m.nchg * QSZ;
-        if (m.gs && tid == 0) m.state[(step & 1) ? ST_QTICK_ODD : ST_QTICK] = step + 1;
+        const float* C = m.gs ? c_of_parity(m, step) : nullptr;
         for (int e = tid; e < QSZ; e += NT) {
             const int i = e >> 6, j = e & 63;
             float sum = 0.0f;
             if (m.gs) {
                 const int gi = i < BS ? bi * BS + i : bj * BS + i - BS;
                 const int gj = j < BS ? bi * BS + j : bj * BS + j - BS;
-                sum = m.CT[(size_t)gi * m.ldc + gj];
+                sum = C[(size_t)gi * m.ldc + gj];
             } else {
                 for (int c = 0; c < m.nchg; ++c) sum += g[(size_t)c * QSZ + e];
             }
             As[0][home_slot(i, cross) * ELD + mem_col(home_slot(j, cross))] = sum;
-            Qs[0][i * ELD + mem_col(home_slot(j, cross))] = (i == j) ? 1.0f : 0.0f;
+        }
+    } else {
+        const int prev = (step - 1) % m.R, pp = (step - 1) & 1;
+        const float* C = c_of_parity(m, pp);
+        const int k1 = pair_of_block(m.nb2, prev, bi), k2 = pair_of_block(m.nb2, prev, bj);
+        int x0, x1, y0, y1;
+        pair_blocks(m.nb2, prev, k1, x0, x1);
+        pair_blocks(m.nb2, prev, k2, y0, y1);
+        const int s1 = bi == x0 ? 0 : 1, s2 = bj == y0 ? 0 : 1;
+        const float* Q1 = m.Q + ((size_t)pp * m.npairs + k1) * QSZ;
+        const float* Q2 = m.Q + ((size_t)pp * m.npairs + k2) * QSZ;
+        const int h = lane >> 5, l32 = lane & 31;
+        float* P = As[1];                                        // three 32 x 64 intermediates, row stride ELD
+        float* P2 = Qs[1];
+        float qb[PR / 2];                                        // operand of the second product, loaded up front
+        if (wave < 3) {
+            const float* QR = wave == 0 ? Q1 : Q2;
+            const int sR = wave == 0 ? s1 : s2;
+#pragma unroll
+            for (int s = 0; s < PR / 2; ++s) qb[s] = QR[(2 * s + h) * PR + sR * BS + l32];
+        }
+        // product 1: waves 0..5 = (block sb, column half): Qs^T (32 x 64) * C tile (64 x 32 of its 64 columns)
+        if (wave < 6) {
+            const int sb = wave >> 1, half = wave & 1;           // sb 0: aa, 1: ab, 2: bb
+            const float* QL = sb == 2 ? Q2 : Q1;
+            const int sL = sb == 2 ? s2 : s1;
+            const int r0 = sb == 2 ? y0 : x0, r1 = sb == 2 ? y1 : x1;       // row blocks of the tile
+            const int c0 = sb == 0 ? x0 : y0, c1 = sb == 0 ? x1 : y1;       // column blocks of the tile
+            const int col = (half == 0 ? c0 : c1) * BS + l32;
+            float qa[PR / 2], cb[PR / 2];
+#pragma unroll
+            for (int s = 0; s < PR / 2; ++s) {
+                const int k = 2 * s + h;
+                qa[s] = QL[k * PR + sL * BS + l32];
+                cb[s] = C[(size_t)(k < BS ? r0 * BS + k : r1 * BS + k - BS) * m.ldc + col];
+            }
+            floatx16 acc;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+#pragma unroll
+            for (int s = 0; s < PR / 2; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(qa[s], cb[s], acc, 0, 0, 0);
+            float* out = sb == 0 ? P : sb == 1 ? P + BS * ELD : P2;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) out[(8 * (v >> 2) + 4 * h + (v & 3)) * ELD + half * BS + l32] = acc[v];
         }
         __syncthreads();
-        for (int e = tid; e < QSZ; e += NT) {
-            const int i = e >> 6, j = e & 63;
-            if (i < j) {
-                const int si = home_slot(i, cross), sj = home_slot(j, cross);
-                const float v = 0.5f * (As[0][si * ELD + mem_col(sj)] + As[0][sj * ELD + mem_col(si)]);
-                As[0][si * ELD + mem_col(sj)] = v;
-                As[0][sj * ELD + mem_col(si)] = v;
+        // product 2: waves 0..2 = block sb: intermediate (32 x 64) * Qs (64 x 32)
+        if (wave < 3) {
+            const int sb = wave;
+            const float* in = sb == 0 ? P : sb == 1 ? P + BS * ELD : P2;
+            floatx16 acc;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+#pragma unroll
+            for (int s = 0; s < PR / 2; ++s)
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(in[l32 * ELD + 2 * s + h], qb[s], acc, 0, 0, 0);
+            const int ro = sb == 2 ? BS : 0, co = sb == 0 ? 0 : BS;         // where the block sits in the 64 x 64
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int si = home_slot(ro + 8 * (v >> 2) + 4 * h + (v & 3), cross), sj = home_slot(co + l32, cross);
+                As[0][si * ELD + mem_col(sj)] = acc[v];
+                if (sb == 1) As[0][sj * ELD + mem_col(si)] = acc[v];
             }
+        }
+    }
+    __syncthreads();
+    // symmetrise (the two triangles were accumulated in different orders)
+    for (int e = tid; e < QSZ; e += NT) {
+        const int i = e >> 6, j = e & 63;
+        if (i < j) {
+            const int si = home_slot(i, cross), sj = home_slot(j, cross);
+            const float v = 0.5f * (As[0][si * ELD + mem_col(sj)] + As[0][sj * ELD + mem_col(si)]);
+            As[0][si * ELD + mem_col(sj)] = v;
+            As[0][sj * ELD + mem_col(si)] = v;
         }
     }
     __syncthreads();
@@ -361,13 +439,17 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
 
 void launch_svd_eig(const SvdMat* d_mats, const Work* d_work, int n_items, const Work* d_two_work, int n_two, int step,
                     int max_sweeps, float stop_cosine, int max_inner, float inner_reduction, int full_period,
-                    int* d_flags, hipStream_t stream)
+                    int fresh_only, int* d_flags, hipStream_t stream)
 {
     static_assert(PR * ELD == PR * TLD, "the two-sided tiles are staged in the LDS arrays of the pair problem");
-    const unsigned grid = (unsigned)(n_items + (n_two + 3) / 4);
+    const unsigned grid = (unsigned)(n_items + (n_two + TILES_PER_WG - 1) / TILES_PER_WG);
     if (grid == 0) return;
-    svd_eig<<<grid, NT, 0, stream>>>(d_mats, d_work, n_items, d_two_work, n_two, step, max_sweeps, stop_cosine,
-                                     max_inner, inner_reduction, full_period, d_flags);
+    // A compute unit has room for two of these workgroups.  While the chip has a unit for every workgroup of
+    // the launch, unused dynamic LDS keeps them apart: a pair problem is a latency chain and runs slower
+    // when it shares its SIMDs.
+    const size_t pad = n_items <= 200 ? 20 * 1024 : 0;
+    svd_eig<<<grid, NT, pad, stream>>>(d_mats, d_work, n_items, d_two_work, n_two, step, max_sweeps, stop_cosine,
+                                     max_inner, inner_reduction, full_period, fresh_only, d_flags);
 }
 
 }  // namespace svd
