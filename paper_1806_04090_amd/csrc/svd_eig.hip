@@ -194,11 +194,17 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
             const int c0 = sb == 0 ? x0 : y0, c1 = sb == 0 ? x1 : y1;       // column blocks of the tile
             const int col = (half == 0 ? c0 : c1) * BS + l32;
             float qa[PR / 2], cb[PR / 2];
+            // row k = 2 s + h of the tile: block r0 for s < 16, block r1 above; constant strides per half
+            const float* qlp = QL + h * PR + sL * BS + l32;
+            const float* c_lo = C + (size_t)(r0 * BS + h) * m.ldc + col;
+            const float* c_hi = C + (size_t)(r1 * BS + h) * m.ldc + col;
+            const size_t two_rows = 2 * (size_t)m.ldc;
 #pragma unroll
-            for (int s = 0; s < PR / 2; ++s) {
-                const int k = 2 * s + h;
-                qa[s] = QL[k * PR + sL * BS + l32];
-                cb[s] = C[(size_t)(k < BS ? r0 * BS + k : r1 * BS + k - BS) * m.ldc + col];
+            for (int s = 0; s < PR / 4; ++s) {
+                qa[s] = qlp[s * 2 * PR];
+                cb[s] = c_lo[s * two_rows];
+                qa[PR / 4 + s] = qlp[(PR / 4 + s) * 2 * PR];
+                cb[PR / 4 + s] = c_hi[s * two_rows];
             }
             floatx16 acc;
 #pragma unroll
@@ -230,22 +236,37 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
         }
     }
     __syncthreads();
-    // symmetrise (the two triangles were accumulated in different orders)
-    for (int e = tid; e < QSZ; e += NT) {
-        const int i = e >> 6, j = e & 63;
-        if (i < j) {
-            const int si = home_slot(i, cross), sj = home_slot(j, cross);
-            const float v = 0.5f * (As[0][si * ELD + mem_col(sj)] + As[0][sj * ELD + mem_col(si)]);
-            As[0][si * ELD + mem_col(sj)] = v;
-            As[0][sj * ELD + mem_col(si)] = v;
-        }
-    }
-    __syncthreads();
-
-    // 2. largest |cos| between two rows of the pair before rotating (rows at the rounding floor are
-    //    measured against the floor instead of their own length), and the largest squared norm
+    // 2. symmetrise (the two triangles were accumulated in different orders) and, in the same pass, the
+    //    largest |cos| between two rows of the pair before rotating (rows at the rounding floor are
+    //    measured against the floor instead of their own length) and the largest squared norm
     const float z2 = ZERO_REL * __int_as_float(m.state[ST_SCALE]);
-    const float2 entry = max_cosine(As[0], z2, red);
+    float2 entry;
+    {
+        float mx = 0.0f, dmax = 0.0f;
+        for (int e = tid; e < QSZ; e += NT) {
+            const int i = e >> 6, j = e & 63;                    // slot of the row, memory column
+            const int js = j < 32 ? 2 * j : 2 * (j - 32) + 1;    // slot of the column
+            if (i < js) {
+                const float v = 0.5f * (As[0][i * ELD + j] + As[0][js * ELD + mem_col(i)]);
+                As[0][i * ELD + j] = v;
+                As[0][js * ELD + mem_col(i)] = v;
+                const float dii = As[0][i * ELD + mem_col(i)], djj = As[0][js * ELD + j];
+                if (dii > 0.0f && djj > 0.0f)
+                    mx = fmaxf(mx, fabsf(v) * __builtin_amdgcn_rcpf(fmaxf(__builtin_amdgcn_sqrtf(dii * djj), z2)));
+            } else if (i == js) {
+                dmax = fmaxf(dmax, As[0][i * ELD + j]);
+            }
+        }
+        for (int o = 32; o > 0; o >>= 1) {
+            mx = fmaxf(mx, __shfl_down(mx, o));
+            dmax = fmaxf(dmax, __shfl_down(dmax, o));
+        }
+        if (lane == 0) { red[wave] = mx; red[16 + wave] = dmax; }
+        __syncthreads();
+        mx = 0.0f; dmax = 0.0f;
+        for (int w = 0; w < NT / 64; ++w) { mx = fmaxf(mx, red[w]); dmax = fmaxf(dmax, red[16 + w]); }
+        entry = make_float2(mx, dmax);
+    }
     if (tid == 0) {
         atomicMax((unsigned int*)&m.state[ST_OFFMAX], __float_as_uint(entry.x));
         atomicMax((unsigned int*)&m.state[ST_SCALE_NEXT], __float_as_uint(entry.y));
@@ -333,12 +354,10 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
         }
     }
     const float* Acur = As[cur];
-    float* Qm = As[cur ^ 1];                                     // Q in natural column order
-    float* F = Qs[cur ^ 1];                                      // scratch for the Newton-Schulz factor
-    for (int e = tid; e < QSZ; e += NT) {
-        const int i = e >> 6, j = e & 63;
-        Qm[i * ELD + j] = Qs[cur][i * ELD + mem_col(home_slot(j, cross))];
-    }
+    const float* Qc = Qs[cur];                                   // Q, columns in slot order
+    float* F0 = As[cur ^ 1];                                     // scratch for the Newton-Schulz factor
+    // memory column of natural column j of Q
+    auto qcol = [&](int j) { return mem_col(home_slot(j, cross)); };
 
     // 4. eigenvalues, and where each eigenvector goes: decreasing eigenvalue over the live rows of
     //    the pair, padding rows stay padding rows
@@ -349,23 +368,26 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
         ev[tid] = live ? Acur[sl * ELD + mem_col(sl)] : -FLT_MAX;
     }
     __syncthreads();
-    if (tid < PR) {
-        const float mine = ev[tid];
-        int rank = 0;
-        for (int j = 0; j < PR; ++j) {
-            const float o = ev[j];
-            rank += (o > mine) || (o == mine && j < tid);
+    {
+        constexpr int PER_WAVE = PR / (NT / 64);                 // every wave ranks a few eigenvalues by ballot
+        const float other = ev[lane];
+#pragma unroll
+        for (int q = 0; q < PER_WAVE; ++q) {
+            const int i = wave * PER_WAVE + q;
+            const float mine = ev[i];
+            const int rank = __popcll(__ballot((other > mine) || (other == mine && lane < i)));
+            if (lane == 0) {
+                int slot;
+                if (rank < nI) slot = rank;
+                else if (rank < nI + nJ) slot = BS + rank - nI;
+                else {
+                    const int pad = rank - nI - nJ;              // padding rows, in order
+                    slot = pad < BS - nI ? nI + pad : BS + nJ + pad - (BS - nI);
+                }
+                dest[i] = slot;
+            }
         }
-        int slot;
-        if (rank < nI) slot = rank;
-        else if (rank < nI + nJ) slot = BS + rank - nI;
-        else {
-            const int pad = rank - nI - nJ;                      // padding rows, in order
-            slot = pad < BS - nI ? nI + pad : BS + nJ + pad - (BS - nI);
-        }
-        dest[tid] = slot;
     }
-    __syncthreads();
 
     // 5. one Newton-Schulz step  Q <- Q (1.5 I - 0.5 Q^T Q): removes the drift that thousands of
     //    fp32 rotations leave in the orthogonality of Q (waves 0..3, one 32x32 quadrant each)
@@ -374,24 +396,27 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
     if (wave < 4) {
+        const int ci = qcol(qi * BS + l32), cj = qcol(qj * BS + l32);
+#pragma unroll
         for (int k = 0; k < PR; k += 2) {
-            const float a = Qm[(k + h) * ELD + qi * BS + l32];   // (Q^T)[i][k]
-            const float bq = Qm[(k + h) * ELD + qj * BS + l32];  // Q[k][j]
+            const float a = Qc[(k + h) * ELD + ci];              // (Q^T)[i][k]
+            const float bq = Qc[(k + h) * ELD + cj];             // Q[k][j]
             acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bq, acc, 0, 0, 0);
         }
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int i = qi * BS + 8 * (v >> 2) + 4 * h + (v & 3), j = qj * BS + l32;
-            F[i * ELD + j] = (i == j ? 1.5f : 0.0f) - 0.5f * acc[v];
+            F0[i * ELD + j] = (i == j ? 1.5f : 0.0f) - 0.5f * acc[v];
         }
     }
     __syncthreads();
     if (wave < 4) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+#pragma unroll
         for (int k = 0; k < PR; k += 2) {
-            const float a = Qm[(qi * BS + l32) * ELD + k + h];   // Q[i][k]
-            const float bq = F[(k + h) * ELD + qj * BS + l32];   // F[k][j]
+            const float a = Qc[(qi * BS + l32) * ELD + qcol(k + h)];   // Q[i][k]
+            const float bq = F0[(k + h) * ELD + qj * BS + l32];        // F[k][j]
             acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bq, acc, 0, 0, 0);
         }
         // 6. write Q with its columns permuted to their destination rows
@@ -436,6 +461,7 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
 }
 
 }  // namespace
+
 
 void launch_svd_eig(const SvdMat* d_mats, const Work* d_work, int n_items, const Work* d_two_work, int n_two, int step,
                     int max_sweeps, float stop_cosine, int max_inner, float inner_reduction, int full_period,
