@@ -33,9 +33,6 @@ constexpr int NBUCKET = 1 << L0_BITS;        // the largest level
 constexpr int HIST_WGS = 1024;
 constexpr int CHUNK = 4096;                  // elements per sampling workgroup (256 threads x 4 float4)
 
-constexpr int ARRIVE_FANOUT = 64;            // arrival counters per launch, plus one on top of them
-constexpr int ARRIVE_WORDS = ARRIVE_FANOUT + 8;
-
 struct EwState {
     unsigned int cnt[3][NBUCKET];
     unsigned long long sig[3][NBUCKET];
@@ -48,40 +45,7 @@ struct EwState {
     double budget;                // final: s - n_s
     double ratio;                 // final: budget / tail, +inf if tail == 0
     unsigned long long total_kept;
-    unsigned int arrive[4][ARRIVE_WORDS];   // arrival counters (see last_workgroup): histogram levels 0..2, count pass
 };
-
-// A value another workgroup of the same launch wrote (read past the non-coherent caches).
-template <typename T>
-__device__ inline T peer_load(const T* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-
-// A value for another workgroup of the same launch (written past the non-coherent caches).
-template <typename T>
-__device__ inline void peer_store(T* p, T v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-
-// True in exactly one workgroup of the launch: the one whose threads all arrive here last.  What the other
-// workgroups published before their call with device-scope atomics or peer_store is visible to it
-// afterwards through peer_load.  The fence only waits for this thread's own memory operations to complete:
-// a device-scope release fence would write the whole L2 back, once per workgroup.
-// Arrivals are counted in two levels (workgroup b on counter b mod 64, the last one of each on a counter on
-// top): thousands of atomics on one address would queue for longer than the kernels run.
-__device__ inline bool last_workgroup(unsigned int* counters /* ARRIVE_WORDS, zero */, int* lds_flag)
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const unsigned int grid = gridDim.x, sub = blockIdx.x % ARRIVE_FANOUT;
-        const unsigned int expected = (grid - sub + ARRIVE_FANOUT - 1) / ARRIVE_FANOUT;      // workgroups on this counter
-        bool last = false;
-        if (atomicAdd(&counters[sub], 1u) == expected - 1) {
-            const unsigned int groups = grid < ARRIVE_FANOUT ? grid : ARRIVE_FANOUT;
-            last = atomicAdd(&counters[ARRIVE_FANOUT], 1u) == groups - 1;
-        }
-        *lds_flag = last;
-    }
-    __syncthreads();
-    return *lds_flag != 0;
-}
 
 
 // value of an integer significand sum for elements whose biased exponent is e
@@ -100,21 +64,15 @@ __global__ __launch_bounds__(256) void ew_clear(EwState* st)
 {
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i < 3 * NBUCKET) { (&st->cnt[0][0])[i] = 0u; (&st->sig[0][0])[i] = 0ull; }
-    if (i < 4 * ARRIVE_WORDS) (&st->arrive[0][0])[i] = 0u;
     if (i == 0) {
         st->resolved = 0; st->prefix = 0u; st->n_above = 0ull; st->sum_below = 0.0;
         st->n_s = 0ull; st->tail = 0.0; st->budget = 0.0; st->ratio = 0.0; st->total_kept = 0ull;
     }
 }
 
+// Histogram of one level.  Elements are visited as float4 where the pointer allows.
 template <int LEVEL>
-__device__ void ew_solve_level(EwState* st, double s, unsigned long long* cpart, double* spart, int* best);
-
-// Histogram of one level; the workgroup that finishes last then solves the level (ew_solve_level).
-// Elements are visited as float4 where the pointer allows.
-template <int LEVEL>
-__global__ __launch_bounds__(LEVEL == 0 ? 1024 : 256) void ew_hist(const float* __restrict__ g, long long n, EwState* st,
-                                                                  double s)
+__global__ __launch_bounds__(LEVEL == 0 ? 1024 : 256) void ew_hist(const float* __restrict__ g, long long n, EwState* st)
 {
     // Level 0 sees every element and most of them fall into a few dozen buckets: four copies of the
     // histogram (one per lane mod 4) keep lanes of a wave from queueing on the same LDS word.
@@ -145,19 +103,9 @@ __global__ __launch_bounds__(LEVEL == 0 ? 1024 : 256) void ew_hist(const float* 
     const bool vec = (((size_t)g) & 15) == 0;
     const long long n4 = vec ? n / 4 : 0;
     const long long stride = (long long)gridDim.x * TPB;
-    // four independent float4 loads in flight per thread before the first use: the loop is otherwise bound
-    // by load latency, not by the LDS atomics
-    for (long long q0 = (long long)blockIdx.x * TPB + threadIdx.x; q0 < n4; q0 += 4 * stride) {
-        float4 x[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const long long q = q0 + u * stride;
-            x[u] = q < n4 ? ((const float4*)g)[q] : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            if (q0 + u * stride < n4) { visit(x[u].x); visit(x[u].y); visit(x[u].z); visit(x[u].w); }
-        }
+    for (long long q = (long long)blockIdx.x * TPB + threadIdx.x; q < n4; q += stride) {
+        const float4 x = ((const float4*)g)[q];
+        visit(x.x); visit(x.y); visit(x.z); visit(x.w);
     }
     for (long long i = n4 * 4 + (long long)blockIdx.x * TPB + threadIdx.x; i < n; i += stride) visit(g[i]);
     __syncthreads();
@@ -175,25 +123,18 @@ __global__ __launch_bounds__(LEVEL == 0 ? 1024 : 256) void ew_hist(const float* 
             atomicAdd(&st->sig[LEVEL][b], sg);
         }
     }
-    __shared__ int last;
-    if (!last_workgroup(st->arrive[LEVEL], &last)) return;
-    // the LDS histogram is spent: its memory serves the solver
-    unsigned long long* cpart = acc;
-    double* spart = (double*)(acc + 256);
-    ew_solve_level<LEVEL>(st, s, cpart, spart, &last);
 }
-// Solves one histogram level: finds the bucket in which h changes sign and either finishes (n_s, tail) or
-// narrows the key prefix for the next level.  Called by every thread of one workgroup (256 threads or
-// more; threads 0..255 work), after every workgroup's histogram has reached global memory.
 template <int LEVEL>
-__device__ void ew_solve_level(EwState* st, double s, unsigned long long* cpart, double* spart, int* best_p)
+__global__ __launch_bounds__(256) void ew_solve(EwState* st, double s)
 {
-    int& best = *best_p;
+    __shared__ unsigned long long cpart[256];
+    __shared__ double spart[256];
+    __shared__ int best;
+    if (st->resolved) return;
     constexpr int NB = LEVEL == 0 ? (1 << L0_BITS) : (1 << L1_BITS);
     constexpr int SHIFT = LEVEL == 0 ? 20 : LEVEL == 1 ? 10 : 0;
     constexpr int PER = NB / 256;
-    const bool worker = threadIdx.x < 256;      // a larger workgroup only lends its barriers
-    const int tid = threadIdx.x & 255;
+    const int tid = threadIdx.x;
     const unsigned int prefix = st->prefix;
     const unsigned long long n_above0 = st->n_above;
     const double sum_below0 = st->sum_below;
@@ -215,27 +156,22 @@ __device__ void ew_solve_level(EwState* st, double s, unsigned long long* cpart,
 #pragma unroll
     for (int e = 0; e < PER; ++e) {
         const int b = tid * PER + e;
-        cnt_r[e] = peer_load(&st->cnt[LEVEL][b]);
-        sum_r[e] = sig_value(peer_load(&st->sig[LEVEL][b]), bucket_exp(b));
+        cnt_r[e] = st->cnt[LEVEL][b];
+        sum_r[e] = sig_value(st->sig[LEVEL][b], bucket_exp(b));
         c_mine += cnt_r[e];
         s_mine += sum_r[e];
     }
-    __syncthreads();                            // the caller's LDS arrays are free from here
-    if (worker) {
-        cpart[tid] = c_mine;
-        spart[tid] = s_mine;
-        if (tid == 0) best = 0;
-    }
+    cpart[tid] = c_mine;
+    spart[tid] = s_mine;
+    if (tid == 0) best = 0;
     __syncthreads();
     // suffix scan of the counts and prefix scan of the sums over the 256 threads (log-step, in LDS)
     for (int off = 1; off < 256; off <<= 1) {
         const unsigned long long cv = tid + off < 256 ? cpart[tid + off] : 0ull;
         const double sv = tid >= off ? spart[tid - off] : 0.0;
         __syncthreads();
-        if (worker) {
-            cpart[tid] += cv;
-            spart[tid] += sv;
-        }
+        cpart[tid] += cv;
+        spart[tid] += sv;
         __syncthreads();
     }
     const unsigned long long c_after = tid < 255 ? cpart[tid + 1] : 0ull;   // count in buckets owned by later threads
@@ -254,11 +190,11 @@ __device__ void ew_solve_level(EwState* st, double s, unsigned long long* cpart,
             at_or_above -= cnt_r[e];
             below += sum_r[e];
         }
-        if (worker && mine_best >= 0) atomicMax(&best, mine_best);
+        if (mine_best >= 0) atomicMax(&best, mine_best);
     }
     __syncthreads();
     const int bs = best;
-    if (worker && tid == bs / PER) {            // the owner of the chosen bucket finishes from its registers
+    if (tid == bs / PER) {                      // the owner of the chosen bucket finishes from its registers
         unsigned long long above = c_after;
         double below = s_before;
         unsigned int c = 0;
@@ -344,49 +280,16 @@ __device__ inline float4 load4(const float* g, long long q, long long n, bool ve
     return x;
 }
 
-// Exclusive scan of the chunk counts by one workgroup of 256 threads (the last one of ew_count).
-__device__ void ew_scan_chunks(const unsigned int* chunk_count, long long n_chunks, unsigned long long* chunk_base,
-                               EwState* st, long long* count_out, long long capacity, int* flags,
-                               unsigned long long* part /* LDS, 256 words */)
-{
-    const int tid = threadIdx.x;
-    const long long per = (n_chunks + 255) / 256;
-    const long long lo = min(n_chunks, tid * per), hi = min(n_chunks, lo + per);
-    unsigned long long mine = 0ull;
-    for (long long c = lo; c < hi; ++c) mine += peer_load(&chunk_count[c]);
-    part[tid] = mine;
-    __syncthreads();
-    for (int off = 1; off < 256; off <<= 1) {
-        const unsigned long long v = tid >= off ? part[tid - off] : 0ull;
-        __syncthreads();
-        part[tid] += v;
-        __syncthreads();
-    }
-    unsigned long long base = tid > 0 ? part[tid - 1] : 0ull;
-    for (long long c = lo; c < hi; ++c) {
-        chunk_base[c] = base;
-        base += peer_load(&chunk_count[c]);
-    }
-    if (tid == 255) {
-        st->total_kept = base;
-        *count_out = (long long)base;
-        if ((long long)base > capacity) atomicMax(&flags[FLAG_CAPACITY], 1);
-    }
-}
-
 // Kept coordinates per chunk, and their keep bits.  Wave w of a chunk owns float4 [w*256, (w+1)*256) of the
 // chunk, in four iterations of 64 lanes: order inside a chunk is (wave, iteration, lane, component) =
 // ascending index.  keep[((chunk*4 + wave)*4 + iteration)*4 + component] holds one bit per lane, so that the
 // writer neither draws the random numbers again nor reads the gradient outside the kept coordinates.
 __global__ __launch_bounds__(256) void ew_count(const float* __restrict__ g, long long n, const EwState* st,
                                                 unsigned long long stream_id, unsigned long long seed,
-                                                unsigned int* chunk_count, unsigned long long* __restrict__ keep,
-                                                unsigned long long* chunk_base, EwState* st_rw, long long* count_out,
-                                                long long capacity, int* flags)
+                                                unsigned int* __restrict__ chunk_count,
+                                                unsigned long long* __restrict__ keep)
 {
     __shared__ unsigned int wsum[4];
-    __shared__ unsigned long long part[256];
-    __shared__ int last;
     const double ratio = st->ratio;
     const bool vec = (((size_t)g) & 15) == 0;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -412,10 +315,38 @@ __global__ __launch_bounds__(256) void ew_count(const float* __restrict__ g, lon
     }
     if (lane == 0) wsum[wave] = kept;
     __syncthreads();
-    if (threadIdx.x == 0) peer_store(&chunk_count[blockIdx.x], wsum[0] + wsum[1] + wsum[2] + wsum[3]);
-    // the workgroup that finishes last turns the counts into the chunks' offsets in the message
-    if (!last_workgroup(st_rw->arrive[3], &last)) return;
-    ew_scan_chunks(chunk_count, gridDim.x, chunk_base, st_rw, count_out, capacity, flags, part);
+    if (threadIdx.x == 0) chunk_count[blockIdx.x] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+}
+
+// Exclusive scan of the chunk counts (single workgroup).
+__global__ __launch_bounds__(256) void ew_scan(const unsigned int* __restrict__ chunk_count, long long n_chunks,
+                                               unsigned long long* __restrict__ chunk_base, EwState* st,
+                                               long long* count_out, long long capacity, int* flags)
+{
+    __shared__ unsigned long long part[256];
+    const int tid = threadIdx.x;
+    const long long per = (n_chunks + 255) / 256;
+    const long long lo = min(n_chunks, tid * per), hi = min(n_chunks, lo + per);
+    unsigned long long mine = 0ull;
+    for (long long c = lo; c < hi; ++c) mine += chunk_count[c];
+    part[tid] = mine;
+    __syncthreads();
+    for (int off = 1; off < 256; off <<= 1) {
+        const unsigned long long v = tid >= off ? part[tid - off] : 0ull;
+        __syncthreads();
+        part[tid] += v;
+        __syncthreads();
+    }
+    unsigned long long base = tid > 0 ? part[tid - 1] : 0ull;
+    for (long long c = lo; c < hi; ++c) {
+        chunk_base[c] = base;
+        base += chunk_count[c];
+    }
+    if (tid == 255) {
+        st->total_kept = base;
+        *count_out = (long long)base;
+        if ((long long)base > capacity) atomicMax(&flags[FLAG_CAPACITY], 1);
+    }
 }
 
 // Writes the kept coordinates of one chunk in ascending order.  The keep bits give every kept coordinate
@@ -525,7 +456,7 @@ EwLayout ew_layout(void* base, int64_t n)
     return l;
 }
 
-// Enqueues the three histogram levels; afterwards st->{n_s, tail, budget, ratio} are final.
+// Enqueues the three histogram / solve levels; afterwards st->{n_s, tail, budget} are final.
 void enqueue_water_level(atomo_ctx* ctx, const float* x, int64_t n, double s, EwState* st, hipStream_t stream)
 {
     // No workgroup may visit 2^16 elements or more (field widths of the packed histogram word).
@@ -533,10 +464,12 @@ void enqueue_water_level(atomo_ctx* ctx, const float* x, int64_t n, double s, Ew
     const int wgs = (int)std::max<int64_t>(std::min<int64_t>(HIST_WGS, (n + 1023) / 1024), floor_wgs);
     const int wgs0 = (int)std::max<int64_t>(std::min<int64_t>(256, (n + 4095) / 4096), floor_wgs);
     { ProfScope ps(ctx, ATOMO_K_EW_SOLVE, stream); ew_clear<<<(3 * NBUCKET + 255) / 256, 256, 0, stream>>>(st); }
-    ProfScope ps(ctx, ATOMO_K_EW_HIST, stream);                  // each level ends with its solve, in its last workgroup
-    ew_hist<0><<<wgs0, 1024, 0, stream>>>(x, n, st, s);
-    ew_hist<1><<<wgs, 256, 0, stream>>>(x, n, st, s);
-    ew_hist<2><<<wgs, 256, 0, stream>>>(x, n, st, s);
+    { ProfScope ps(ctx, ATOMO_K_EW_HIST, stream); ew_hist<0><<<wgs0, 1024, 0, stream>>>(x, n, st); }
+    { ProfScope ps(ctx, ATOMO_K_EW_SOLVE, stream); ew_solve<0><<<1, 256, 0, stream>>>(st, s); }
+    { ProfScope ps(ctx, ATOMO_K_EW_HIST, stream); ew_hist<1><<<wgs, 256, 0, stream>>>(x, n, st); }
+    { ProfScope ps(ctx, ATOMO_K_EW_SOLVE, stream); ew_solve<1><<<1, 256, 0, stream>>>(st, s); }
+    { ProfScope ps(ctx, ATOMO_K_EW_HIST, stream); ew_hist<2><<<wgs, 256, 0, stream>>>(x, n, st); }
+    { ProfScope ps(ctx, ATOMO_K_EW_SOLVE, stream); ew_solve<2><<<1, 256, 0, stream>>>(st, s); }
 }
 
 }  // namespace
@@ -555,9 +488,9 @@ int encode_entrywise(atomo_ctx* ctx, const float* g, double s, uint64_t seed, ui
     enqueue_water_level(ctx, g, n, s, l.st, stream);
     {
         ProfScope ps(ctx, ATOMO_K_EW_SAMPLE, stream);
-        ew_count<<<(unsigned)n_chunks, 256, 0, stream>>>(g, n, l.st, stream_id, seed, l.chunk_count, l.keep, l.chunk_base,
-                                                         l.st, (long long*)msg->count, (long long)msg->capacity,
-                                                         ctx->d_flags);
+        ew_count<<<(unsigned)n_chunks, 256, 0, stream>>>(g, n, l.st, stream_id, seed, l.chunk_count, l.keep);
+        ew_scan<<<1, 256, 0, stream>>>(l.chunk_count, n_chunks, l.chunk_base, l.st, (long long*)msg->count,
+                                       (long long)msg->capacity, ctx->d_flags);
         ew_write<<<(unsigned)n_chunks, 256, 0, stream>>>(g, l.st, l.keep, l.chunk_base, (long long)msg->capacity,
                                                          msg->idx, msg->val);
         if (p_out) ew_write_p<<<(int)std::min<int64_t>(4096, (n + 255) / 256), 256, 0, stream>>>(g, n, l.st, p_out);
