@@ -13,7 +13,7 @@ constexpr int KCG = 512;        // columns per Gram work item
 constexpr int KCU = 256;        // columns per row-update / apply work item (4 waves x 64)
 constexpr int QSZ = PR * PR;
 constexpr int MAX_R = ALG1_MAX;
-constexpr int GS_MIN_BLOCKS = 8;  // matrices with at least this many row blocks iterate in Gram space
+constexpr int GS_MIN_BLOCKS = 16; // matrices with at least this many row blocks iterate in Gram space
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
