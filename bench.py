@@ -94,7 +94,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-entrywise", action="store_true", help="skip the entry-wise leg")
+    ap.add_argument("--no-entrywise", action="store_true", help="skip the entry-wise and 16-worker decode legs")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run five plain device copies of 1 GiB, the known-size reference that scales the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
@@ -201,6 +201,7 @@ def main():
         },
     }
     entrywise = None if args.no_entrywise else entrywise_leg(ctx, torch, binding, inputs)
+    aggregate = None if args.no_entrywise else aggregate_decode_leg(ctx, torch, binding, inputs, shapes, S, SEED)
     if args.calibration_copy:
         src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
@@ -223,8 +224,48 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "entrywise": entrywise,
+        "decode_average_16_workers": aggregate,
     }
     print(json.dumps(line))
+
+
+def aggregate_decode_leg(ctx, torch, binding, inputs, shapes, s, seed, workers=16, reps=20):
+    """Parameter-server side of the 16-worker configuration, outside the timed steps of the headline metric:
+    every layer decoded from its 16 messages (data seeds 0..15, about 48 atoms per layer) and averaged, all 21
+    layers in one launch.  GPU time of the decode launch from HIP events; the rank-K update runs on the matrix
+    cores (2 m n K flops) and writes each output once (4 B per element)."""
+    msgs = []
+    for w in range(workers):
+        mats = [torch.from_numpy(g).cuda() for g in inputs.resnet18_layer_set(w)]
+        msgs.append(binding.atomo_encode_svd(ctx, mats, s, seed, inputs.worker_stream(w, 0)))
+    torch.cuda.synchronize()
+    if ctx.status()[0] != 0:
+        return None
+    groups = [[msgs[w][j] for w in range(workers)] for j in range(len(shapes))]
+    outs = [torch.empty(m, n, dtype=torch.float32, device="cuda") for m, n in shapes]
+    atoms = [sum(int(x.count.item()) for x in g) for g in groups]
+    for _ in range(3):
+        binding.atomo_decode_svd_batch(ctx, groups, 1.0 / workers, outs=outs)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        binding.atomo_decode_svd_batch(ctx, groups, 1.0 / workers, outs=outs)
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / reps
+    ctx.profile_enable(True)
+    ctx.profile_read()
+    for _ in range(reps):
+        binding.atomo_decode_svd_batch(ctx, groups, 1.0 / workers, outs=outs)
+    gpu_ms = ctx.profile_read()["decode_svd"][0] / reps
+    ctx.profile_enable(False)
+    flops = sum(2.0 * m * n * k for (m, n), k in zip(shapes, atoms))
+    nbytes = 4.0 * sum(m * n for m, n in shapes)
+    return {"workload": "21 ResNet-18 layers, 16 messages each (s=3), decode + average in one launch",
+            "kept_atoms": sum(atoms), "gpu_us_per_call": round(gpu_ms * 1e3, 2), "wall_us_per_call": round(wall * 1e6, 2),
+            "mfma_tflops": round(flops / (gpu_ms * 1e-3) / 1e12, 3),
+            "mfma_frac": round(flops / (gpu_ms * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS, 5),
+            "hbm_write_gbs": round(nbytes / (gpu_ms * 1e-3) / 1e9, 1),
+            "hbm_frac": round(nbytes / (gpu_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
 
 
 def entrywise_leg(ctx, torch, binding, inputs, reps=40, sets=8):

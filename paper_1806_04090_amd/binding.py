@@ -122,8 +122,13 @@ class SvdMessage:
     V: torch.Tensor       # float32 [capacity, cols]
 
     def c_struct(self) -> atomo_svd_msg:
-        return atomo_svd_msg(self.rows, self.cols, self.capacity, self.count.data_ptr(), self.idx.data_ptr(),
-                             self.w.data_ptr(), self.U.data_ptr(), self.V.data_ptr())
+        """The C descriptor, built once (the buffers of a message are not replaced after allocation)."""
+        c = self.__dict__.get("_c")
+        if c is None:
+            c = atomo_svd_msg(self.rows, self.cols, self.capacity, self.count.data_ptr(), self.idx.data_ptr(),
+                              self.w.data_ptr(), self.U.data_ptr(), self.V.data_ptr())
+            self.__dict__["_c"] = c
+        return c
 
     def to_host(self) -> dict:
         k = min(int(self.count.item()), self.capacity)

@@ -1,9 +1,11 @@
 // Decoders (eq. (vhat) of arXiv 1806.04090): g_hat = sum over kept atoms of (lambda_i / p_i) a_i.
 //
 // SVD messages: out = scale * sum_msgs sum_k w_k u_k v_k^T, a dense rank-(sum k) update written once.
-// Each workgroup owns a 64 x 256 tile of one output and walks the atoms of every message summed into
-// it.  Few atoms (one worker, budget 3): the kernel is bound by the HBM write of the tile.
+// Each workgroup owns a 64 x 256 tile of one output and contracts the atoms of every message summed into
+// it on the matrix cores.  Few atoms (one worker, budget 3): bound by the HBM write of the tile.  Many
+// (the average over 16 workers, rank ~ 48): near the ridge between the two.
 // Entry-wise messages: zero fill, then scatter (atomic add when several messages overlap).
+#include <algorithm>
 #include <vector>
 
 #include "atomo_internal.h"
@@ -31,63 +33,97 @@ struct DecOut {
 struct DecWork { int out, tile_r, tile_c, pad; };
 
 constexpr int TR = 64, TC = 256;
+constexpr int ATOMS_MAX = 512;     // atoms listed in LDS per batch of messages (a message holds at most 512)
 
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+// out tile (64 x 256) = sum over messages and kept atoms of (scale w_k u_k) v_k^T as a rank-K update on the
+// matrix cores: A operand (row i, atom k) = scale w_k U[k][i], B operand (atom k, column j) = V[k][j],
+// v_mfma_f32_32x32x2f32, two atoms per instruction.  Wave w owns columns 64 w .. 64 w + 63 of the tile as
+// 2 x 2 blocks of 32 x 32.  The kept atoms of a batch of messages (`batch` x largest capacity <= ATOMS_MAX,
+// chosen by the host) are first listed in LDS, one round trip for all counts and weights, so that the
+// contraction loop only chases pointers it already holds; operands come straight from global memory
+// (every atom's u and v are contiguous rows of its message).  An odd atom count pads with a zero weight.
 __global__ __launch_bounds__(256) void decode_svd_tiles(const DecOut* outs, const DecMsg* msgs, const DecWork* work,
-                                                        float scale)
+                                                        float scale, int batch)
 {
-    __shared__ float us[TR];
+    __shared__ const float* up[ATOMS_MAX];
+    __shared__ const float* vp[ATOMS_MAX];
+    __shared__ float wv[ATOMS_MAX];
+    __shared__ int kept_of[ATOMS_MAX];
+    __shared__ int total_sh;
     const DecWork wk = work[blockIdx.x];
     const DecOut o = outs[wk.out];
-    const int tid = threadIdx.x;
-    const int r0 = wk.tile_r * TR, c0 = wk.tile_c * TC;
-    const int cq = tid & 63;                    // float4 column inside the tile
-    const int rg = tid >> 6;                    // row group: rows rg*16 .. rg*16+15
-    const int col = c0 + cq * 4;
-    float4 acc[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int h = lane >> 5, l32 = lane & 31;
+    const int r0 = wk.tile_r * TR, c0 = wk.tile_c * TC + wave * 64;
+    const int row_a = r0 + l32, row_b = r0 + 32 + l32;          // rows this lane feeds as A operands
+    const int col_a = c0 + l32, col_b = c0 + 32 + l32;          // columns this lane feeds as B operands
+    const bool ra = row_a < o.rows, rb_ok = row_b < o.rows, ca = col_a < o.cols, cb_ok = col_b < o.cols;
+    floatx16 acc[2][2];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[rb][cb][v] = 0.0f;
 
-    for (int mi = o.first; mi < o.last; ++mi) {
-        const DecMsg m = msgs[mi];
-        const int kept = min(*m.count, m.capacity);
-        for (int k = 0; k < kept; ++k) {
-            __syncthreads();
-            if (tid < TR) {
-                const int row = r0 + tid;
-                us[tid] = row < o.rows ? scale * m.w[k] * m.U[(size_t)k * o.rows + row] : 0.0f;
+    for (int first = o.first; first < o.last; first += batch) {
+        const int nm = min(batch, o.last - first);
+        __syncthreads();                                         // the previous list is spent
+        for (int q = tid; q < nm; q += 256) kept_of[q] = min(*msgs[first + q].count, msgs[first + q].capacity);
+        __syncthreads();
+        for (int q = tid; q < nm; q += 256) {
+            int at = 0;
+            for (int e = 0; e < q; ++e) at += kept_of[e];
+            const DecMsg m = msgs[first + q];
+            const int kept = kept_of[q];
+            for (int k = 0; k < kept && at + k < ATOMS_MAX; ++k) {
+                up[at + k] = m.U + (size_t)k * o.rows;
+                vp[at + k] = m.V + (size_t)k * o.cols;
+                wv[at + k] = scale * m.w[k];
             }
-            __syncthreads();
-            const float* v = m.V + (size_t)k * o.cols;
-            float4 vv;
-            vv.x = col < o.cols ? v[col] : 0.0f;
-            vv.y = col + 1 < o.cols ? v[col + 1] : 0.0f;
-            vv.z = col + 2 < o.cols ? v[col + 2] : 0.0f;
-            vv.w = col + 3 < o.cols ? v[col + 3] : 0.0f;
+            if (q == nm - 1) total_sh = min(at + kept, ATOMS_MAX);
+        }
+        __syncthreads();
+        const int total = total_sh;
+        // four atom pairs per trip: all sixteen operand loads are issued before the first MFMA
+        for (int k0 = 0; k0 < total; k0 += 8) {
+            float a0[4], a1[4], b0[4], b1[4];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const float u = us[rg * 16 + i];
-                acc[i].x += u * vv.x;
-                acc[i].y += u * vv.y;
-                acc[i].z += u * vv.z;
-                acc[i].w += u * vv.w;
+            for (int t = 0; t < 4; ++t) {
+                const int kk = k0 + 2 * t + h;
+                const bool live = kk < total;
+                const float wgt = live ? wv[kk] : 0.0f;
+                const float* u = up[live ? kk : 0];
+                const float* v = vp[live ? kk : 0];
+                a0[t] = live && ra ? wgt * u[row_a] : 0.0f;
+                a1[t] = live && rb_ok ? wgt * u[row_b] : 0.0f;
+                b0[t] = live && ca ? v[col_a] : 0.0f;
+                b1[t] = live && cb_ok ? v[col_b] : 0.0f;
+            }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                if (k0 + 2 * t < total) {                        // uniform: skip pairs past the end
+                    acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[t], b0[t], acc[0][0], 0, 0, 0);
+                    acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[t], b1[t], acc[0][1], 0, 0, 0);
+                    acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[t], b0[t], acc[1][0], 0, 0, 0);
+                    acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[t], b1[t], acc[1][1], 0, 0, 0);
+                }
             }
         }
     }
-    const bool vec_ok = ((o.ld & 3) == 0) && ((((size_t)o.out) & 15) == 0) && (col + 3 < o.cols);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int row = r0 + rg * 16 + i;
-        if (row >= o.rows) continue;
-        float* dst = o.out + (size_t)row * o.ld + col;
-        if (vec_ok) {
-            *(float4*)dst = acc[i];
-        } else {
-            if (col < o.cols) dst[0] = acc[i].x;
-            if (col + 1 < o.cols) dst[1] = acc[i].y;
-            if (col + 2 < o.cols) dst[2] = acc[i].z;
-            if (col + 3 < o.cols) dst[3] = acc[i].w;
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+            const int col = c0 + cb * 32 + l32;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = r0 + rb * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+                if (row < o.rows && col < o.cols) o.out[(size_t)row * o.ld + col] = acc[rb][cb][v];
+            }
         }
-    }
 }
 
 __global__ __launch_bounds__(256) void fill_zero(float* __restrict__ out, long long n)
@@ -156,7 +192,10 @@ int decode_svd_batch(atomo_ctx* ctx, const atomo_svd_msg* msgs, const int32_t* f
     if ((rc = upload(ctx, d_work, hw.data(), hw.size() * sizeof(DecWork), stream)) != ATOMO_OK) return rc;
     {
         ProfScope ps(ctx, ATOMO_K_DECODE_SVD, stream);
-        decode_svd_tiles<<<(unsigned)hw.size(), 256, 0, stream>>>(d_outs, d_msgs, d_work, scale);
+        int max_cap = 1;
+        for (int k = 0; k < n_msgs; ++k) max_cap = std::max(max_cap, (int)msgs[k].capacity);
+        const int batch = std::max(1, ATOMS_MAX / max_cap);      // messages whose atoms fit the LDS list together
+        decode_svd_tiles<<<(unsigned)hw.size(), 256, 0, stream>>>(d_outs, d_msgs, d_work, scale, batch);
     }
     ATOMO_HIP(ctx, hipGetLastError());
     return ATOMO_OK;
