@@ -271,8 +271,8 @@ def atomo_encode_svd(ctx: Context, mats: Sequence[torch.Tensor], s: float, seed:
     c_msgs = (atomo_svd_msg * n)(*[m.c_struct() for m in msgs])
     opt = None
     if max_sweeps is not None or stop_cosine is not None or max_inner_sweeps or inner_reduction or full_period:
-        opt = C.byref(atomo_svd_options(12 if max_sweeps is None else max_sweeps,
-                                        1e-4 if stop_cosine is None else stop_cosine,
+        opt = C.byref(atomo_svd_options(0 if max_sweeps is None else max_sweeps,
+                                        0.0 if stop_cosine is None else stop_cosine,
                                         max_inner_sweeps, inner_reduction, int(full_period)))
     _check(lib().atomo_encode_svd(ctx._h, c_mats, n, float(s), int(seed) & (2 ** 64 - 1),
                                   int(stream_base) & (2 ** 64 - 1), opt, c_msgs,

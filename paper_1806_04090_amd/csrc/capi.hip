@@ -259,7 +259,9 @@ int atomo_encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s
         if (m.rows != a.rows || m.cols != a.cols || m.capacity < 1) return ATOMO_EINVAL;
         if (!m.count || !m.idx || !m.w || !m.U || !m.V) return ATOMO_EINVAL;
     }
-    if (opt && (opt->max_sweeps < 1 || !(opt->stop_cosine > 0.0f))) return ATOMO_EINVAL;
+    if (opt && (opt->max_sweeps < 0 || !(opt->stop_cosine >= 0.0f) || opt->max_inner_sweeps < 0 ||
+                !(opt->inner_reduction >= 0.0f) || opt->full_period < 0))
+        return ATOMO_EINVAL;
     DeviceGuard guard(ctx);
     if (!guard.ok) return ATOMO_EHIP;
     return encode_svd(ctx, mats, n_mats, s, seed, stream_base, opt, msgs, sigma_out, p_out, (hipStream_t)stream);

@@ -222,6 +222,7 @@ __global__ __launch_bounds__(256) void svd_fullgram_reduce(const SvdMat* mats, c
         const int i = e >> 6, j = e & 63;
         const float v = ti == tj ? 0.5f * (t[i][j] + t[j][i]) : t[i][j];
         C[(size_t)(ti * PR + i) * m.ldc + tj * PR + j] = v;
+        if (ti == tj && i == j) m.cref[ti * PR + i] = v;         // the row's squared norm, measured on the data
         m.CT[(size_t)(ti * PR + i) * m.ldc + Rp + tj * PR + j] = (ti == tj && i == j) ? 1.0f : 0.0f;
         if (ti != tj) {                                          // mirrored tile: row index runs over j
             C[(size_t)(tj * PR + i) * m.ldc + ti * PR + j] = t[j][i];
@@ -564,6 +565,7 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
         m.Q = carve.take<float>((size_t)(m.gs ? 2 : 1) * m.npairs * QSZ);
         m.state = carve.take<int>(ST_WORDS);
         m.sig_raw = carve.take<float>(m.rows_alloc);
+        m.cref = m.gs ? carve.take<float>(m.rows_alloc) : nullptr;
         m.G = a.data; m.ldg = a.ld;
         if (msgs) {
             const atomo_svd_msg& g = msgs[j];
@@ -629,8 +631,8 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
                const atomo_svd_options* opt, const atomo_svd_msg* msgs, float* sigma_out, float* p_out,
                hipStream_t stream)
 {
-    const int max_sweeps = opt ? opt->max_sweeps : 12;
-    const float stop_cosine = opt ? opt->stop_cosine : 1e-4f;
+    const int max_sweeps = opt && opt->max_sweeps > 0 ? opt->max_sweeps : 16;
+    const float stop_cosine = opt && opt->stop_cosine > 0.0f ? opt->stop_cosine : 1e-4f;
     const int max_inner = opt && opt->max_inner_sweeps > 0 ? opt->max_inner_sweeps : 1;
     const float inner_reduction = opt && opt->inner_reduction > 0.0f ? opt->inner_reduction : 0.01f;
     const float fresh_stop = 0.25f * stop_cosine;

@@ -37,6 +37,7 @@ enum {
     ST_QTICK = 13,      // Gram-space matrices: 1 + the last even tick in which svd_eig produced rotations
     ST_QTICK_ODD = 15,  //                      the same for odd ticks (rotations are double-buffered by tick parity)
     ST_FRESH_AT = 16,   // Gram-space matrices: 1 + the tick whose refresh wrote C from the data (svd_eig reads it as is)
+    ST_SAT_OUT = 17,    // Gram-space matrices: 1 if a row sat out of some pair problem in the current sweep (GS_RELIABLE)
     ST_WORDS = 24
 };
 
@@ -46,6 +47,17 @@ enum { MODE_NEED_REFRESH = 0, MODE_SWEEPS = 1, MODE_DONE = 2 };
 // residue of the fp32 updates (about 32 ulp of the dominant rows): their directions carry no
 // information, so they neither count in the convergence test nor get rotated among themselves.
 constexpr float ZERO_REL = 3.64e-12f;       // (32 * 2^-24)^2
+
+// Gram space.  A diagonal entry of C that has shrunk far below what it was when C was last formed from the
+// data is the difference of nearly equal numbers: what is left is rounding noise of the size of the old
+// value times the unit roundoff times the number of updates.  Every row therefore carries a reference value
+// (its squared norm at the last refresh, pushed through the rotations like the diagonal itself, without the
+// off-diagonal terms), and a row whose diagonal entry is below GS_RELIABLE x reference sits out: it is not
+// rotated and does not count in the convergence test until the next refresh measures it on the data again.
+constexpr float GS_RELIABLE = 1.0e-5f;
+// While rows sit out, finishing the sweeps on the others first would be wasted work: the refresh they wait
+// for is asked for as soon as the others are this close to orthogonal, and everything converges together.
+constexpr float GS_EARLY_REFRESH = 3.0e-2f;
 
 struct SvdMat {
     float* W0;               // rows_alloc x ldw: [A | T]
@@ -58,6 +70,7 @@ struct SvdMat {
     float* Q;                // [npairs][64*64]; Gram space: [2][npairs][64*64], indexed by tick parity
     int* state;              // [ST_WORDS]
     float* sig_raw;          // [rows_alloc]
+    float* cref;             // Gram space: [rows_alloc] reference squared norm of every row, see GS_RELIABLE
     const float* G;
     long long ldg;
     int rows, cols, transposed;
@@ -129,7 +142,7 @@ constexpr int TLD = PR + 1;      // row stride of a 64x64 tile staged in LDS
 //   kind 1: tile (pair a, pair b) of C:  Qa^T * C[rows of a, columns of b] * Qb, read from the C of this tick's
 //           parity and written to the C of the other parity (svd_eig of the next tick still reads the old one)
 //   kind 2: 64 rows of pair a x 64 columns of Tgs:  Qa^T * Tgs[rows of a, chunk], in place
-// Every thread of the workgroup must call this (three workgroup barriers), with item >= n_items for none.
+// Every thread of the workgroup must call this (it has workgroup barriers), with item >= n_items for none.
 __device__ inline void twosided_tile(const SvdMat* mats, const Work* work, int item, int n_items, int tick, float* xs,
                                      int tid)
 {
@@ -138,6 +151,7 @@ __device__ inline void twosided_tile(const SvdMat* mats, const Work* work, int i
     const SvdMat m = mats[wk.mat];
     const int kind = wk.c;
     if (active) active = m.state[(tick & 1) ? ST_QTICK_ODD : ST_QTICK] == tick + 1;   // did svd_eig rotate in this tick?
+    if (!__syncthreads_or(active)) return;                       // nothing to do in this workgroup (finished matrices)
     const int lane = tid & 63, wave = tid >> 6;
     const int qi = wave >> 1, qj = wave & 1, h = lane >> 5, l32 = lane & 31;
     int ai = 0, aj = 0, bi = 0, bj = 0;

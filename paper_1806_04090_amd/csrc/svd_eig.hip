@@ -112,6 +112,8 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
     __shared__ float Qs[2][PR * ELD];
     __shared__ float ev[PR];
     __shared__ int dest[PR];
+    __shared__ float ref[PR];            // Gram space: reference squared norm of the pair's rows (natural index)
+    __shared__ int sits_out[PR];         // Gram space: by slot, rows whose diagonal entry is rounding noise
     __shared__ float red[32];
 
     if ((int)blockIdx.x >= n_eig) {
@@ -150,6 +152,7 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
         const int i = e >> 6, j = e & 63;
         Qs[0][i * ELD + mem_col(home_slot(j, cross))] = (i == j) ? 1.0f : 0.0f;
     }
+    if (tid < PR) ref[tid] = m.gs ? m.cref[tid < BS ? bi * BS + tid : bj * BS + tid - BS] : 0.0f;
     if (!m.gs || fresh) {
         const float* g = m.gram + (size_t)wk.a * m.nchg * QSZ;
         const float* C = m.gs ? c_of_parity(m, step) : nullptr;
@@ -240,6 +243,14 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
     //    largest |cos| between two rows of the pair before rotating (rows at the rounding floor are
     //    measured against the floor instead of their own length) and the largest squared norm
     const float z2 = ZERO_REL * __int_as_float(m.state[ST_SCALE]);
+    if (tid < PR) {
+        const int sl = home_slot(tid, cross);
+        const bool out = m.gs && As[0][sl * ELD + mem_col(sl)] < GS_RELIABLE * ref[tid];
+        sits_out[sl] = out;
+        // (rows at the rounding floor of the data are not waiting for anything: they are finished)
+        if (out && ref[tid] > z2) atomicMax(&m.state[ST_SAT_OUT], 1);
+    }
+    __syncthreads();
     float2 entry;
     {
         float mx = 0.0f, dmax = 0.0f;
@@ -247,7 +258,9 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
             const int i = e >> 6, j = e & 63;                    // slot of the row, memory column
             const int js = j < 32 ? 2 * j : 2 * (j - 32) + 1;    // slot of the column
             if (i < js) {
-                const float v = 0.5f * (As[0][i * ELD + j] + As[0][js * ELD + mem_col(i)]);
+                // a row that sits out is cut loose: no rotation touches it, nothing is measured against it
+                const float v = (sits_out[i] | sits_out[js]) ? 0.0f
+                                                             : 0.5f * (As[0][i * ELD + j] + As[0][js * ELD + mem_col(i)]);
                 As[0][i * ELD + j] = v;
                 As[0][js * ELD + mem_col(i)] = v;
                 const float dii = As[0][i * ELD + mem_col(i)], djj = As[0][js * ELD + j];
@@ -389,6 +402,20 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
         }
     }
 
+    // Gram space: the reference values follow the rows, ref'_j = sum_i Q_ij^2 ref_i
+    __syncthreads();                                             // dest[] is complete
+    if (m.gs && tid < PR) {
+        const int cj = qcol(tid);
+        float r = 0.0f;
+#pragma unroll 8
+        for (int i = 0; i < PR; ++i) {
+            const float q = Qc[i * ELD + cj];
+            r = fmaf(q * q, ref[i], r);
+        }
+        const int d = dest[tid];
+        m.cref[d < BS ? bi * BS + d : bj * BS + d - BS] = r;
+    }
+
     // 5. one Newton-Schulz step  Q <- Q (1.5 I - 0.5 Q^T Q): removes the drift that thousands of
     //    fp32 rotations leave in the orthogonality of Q (waves 0..3, one 32x32 quadrant each)
     const int qi = (wave >> 1) & 1, qj = wave & 1, h = lane >> 5, l32 = lane & 31;
@@ -446,7 +473,10 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
             if (m.gs) {
                 // Gram space: diagonal to the threshold (or out of sweeps) -> apply the rotations to the
                 // data and look at a fresh Gram matrix at the next tick
-                if (worst < stop_cosine || sweeps >= max_sweeps) m.state[ST_MODE] = MODE_NEED_REFRESH;
+                const bool waiting = atomicAdd(&m.state[ST_SAT_OUT], 0) != 0;
+                if (worst < stop_cosine || sweeps >= max_sweeps || (waiting && worst < GS_EARLY_REFRESH))
+                    m.state[ST_MODE] = MODE_NEED_REFRESH;
+                m.state[ST_SAT_OUT] = 0;
             } else if (worst < stop_cosine) {
                 m.state[ST_DONE_AT] = step + 1;
             } else if (sweeps >= max_sweeps) {

@@ -34,6 +34,17 @@ def test_svd_decode_matches_oracle(rows, cols, ks):
     np.testing.assert_allclose(out, want, rtol=0, atol=1e-5 * max(np.abs(want).max(), 1e-30))
 
 
+@pytest.mark.parametrize("rows,cols,capacity,ks", [(40, 130, 100, [7, 0, 99, 100, 1, 33, 2, 2, 2, 50, 5, 64]),   # batches of 5 messages
+                                                   (96, 70, 512, [512, 3]),                                     # one message fills the atom list
+                                                   (33, 33, 6, [5] * 90)])                                      # 85 messages per batch, then 5
+def test_svd_decode_many_messages_across_batches(rows, cols, capacity, ks):
+    rng = np.random.default_rng(len(ks) * 7 + rows)
+    pairs = [make_msg(rng, rows, cols, k, capacity) for k in ks]
+    out = binding.atomo_decode(ctx(), [m for m, _ in pairs], scale=0.5).cpu().numpy()
+    want = oracle.decode_svd([h for _, h in pairs], rows, cols, scale=0.5)
+    assert np.linalg.norm(out - want) <= 1e-5 * max(np.linalg.norm(want), 1e-30)
+
+
 def test_svd_decode_into_strided_output_and_batch():
     rng = np.random.default_rng(1)
     m1, h1 = make_msg(rng, 33, 50, 2, 4)

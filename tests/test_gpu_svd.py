@@ -112,6 +112,60 @@ def test_rank_deficient_and_zero_matrices():
     np.testing.assert_allclose(out, e11, atol=1e-6)
 
 
+@pytest.mark.parametrize("shape", [(512, 600), (600, 512), (500, 700), (481, 481)])
+def test_gram_space_shapes(shape):
+    # 16 row blocks or more: the sweeps run on the Gram matrix, the data is only touched by the refreshes
+    rng = np.random.default_rng(shape[0] * 31 + shape[1])
+    G = inputs.low_rank_plus_noise(rng, shape[0], shape[1], [1.0, 0.6, 0.3, 0.1], 0.003)
+    msgs, per, status, sweeps = encode([G], 3.0, 21, stream_base=9, capacity=16)
+    assert status == 0
+    assert ctx().svd_refreshes(1)[0] >= 2
+    full_parity(G, 3.0, 21, 9, msgs[0], *per[0])
+
+
+def test_gram_space_rank_deficient_and_mixed_batch():
+    rng = np.random.default_rng(77)
+    exact = inputs.low_rank_plus_noise(rng, 512, 640, [2.0, 1.0, 0.5], 0.0)        # rank 3, 509 zero singular values
+    ones = np.ones((520, 600), dtype=np.float32)
+    small = inputs.low_rank_plus_noise(rng, 64, 200, [1.0, 0.2], 0.01)             # data-space neighbour in the same call
+    msgs, per, status, _ = encode([exact, ones, small], 2.0, 4, capacity=8)
+    assert status == 0
+    sig = per[0][0]
+    np.testing.assert_allclose(sig[:3], np.linalg.svd(exact.astype(np.float64), compute_uv=False)[:3], rtol=1e-4)
+    assert np.abs(sig[3:]).max() < 1e-4 * sig[0]
+    np.testing.assert_allclose(per[1][0][0], np.sqrt(520 * 600), rtol=1e-5)
+    assert np.abs(per[1][0][1:]).max() < 1e-4 * np.sqrt(520 * 600)
+    full_parity(small, 2.0, 4, 2, msgs[2], *per[2])
+    # s = 2 with three nonzero singular values: the kept atoms rebuild a rank <= 3 matrix whose atoms are singular pairs
+    check_svd_message_against_matrix(exact.astype(np.float64), msgs[0].to_host(), per[0][0], per[0][1])
+
+
+def test_gram_space_graded_spectrum():
+    # singular values over five decades: rows that shrink far below their size at the last refresh must wait
+    # for the next one, and still come out to the same tolerance
+    rng = np.random.default_rng(5)
+    r, n = 512, 700
+    sig = 10.0 ** (-5.0 * np.arange(r) / (r - 1))                 # (about 27 sweeps; the default limit of 16 covers three decades)
+    U, _ = np.linalg.qr(rng.standard_normal((r, r)))
+    V, _ = np.linalg.qr(rng.standard_normal((n, r)))
+    G = ((U * sig) @ V.T).astype(np.float32)
+    msgs, per, status, sweeps = encode([G], 4.0, 3, capacity=16, max_sweeps=32)
+    assert status == 0
+    ref = np.linalg.svd(G.astype(np.float64), compute_uv=False)
+    assert sigma_tolerance_ok(per[0][0], ref).all(), float(np.abs(per[0][0] - ref).max())
+    check_svd_message_against_matrix(G.astype(np.float64), msgs[0].to_host(), per[0][0], per[0][1])
+
+
+@pytest.mark.parametrize("options", [dict(full_period=1), dict(full_period=3), dict(max_inner_sweeps=2),
+                                     dict(stop_cosine=3e-5)])
+def test_jacobi_schedule_options_reach_the_same_decomposition(options):
+    mats = inputs.resnet18_layer_set(2, shapes=[(128, 576), (512, 256), (512, 1024)])
+    msgs, per, status, sweeps = encode(mats, 3.0, 13, **options)
+    assert status == 0 and sweeps <= 12
+    for j, G in enumerate(mats):
+        full_parity(G, 3.0, 13, j, msgs[j], *per[j])
+
+
 def test_capacity_overflow_is_latched_not_fatal():
     rng = np.random.default_rng(4)
     G = inputs.low_rank_plus_noise(rng, 40, 60, [1.0], 0.1)
