@@ -14,7 +14,8 @@
 // One Jacobi "tick" visits, for every matrix of the call at once, one round of a round-robin
 // tournament over its row blocks.  A sweep is R = (#blocks - 1) rounds.
 //
-// Small matrices (fewer than 8 row blocks) iterate in data space; per tick and block pair (64 rows):
+// Small matrices (fewer than 16 row blocks) iterate in data space, on a forked stream of the context;
+// per tick and block pair (64 rows):
 //     svd_gram<false> : partial 64x64 Gram matrices of the pair over column chunks          (MFMA)
 //     svd_eig         : sums the partials and diagonalises the Gram matrix (see svd_eig.hip)
 //     svd_rowop       : rows <- Q^T rows over all of W                                      (MFMA)
@@ -22,14 +23,16 @@
 //
 // Large matrices iterate in Gram space: the rotations of a pair depend on the rows only through
 // their Gram matrix, so the r x r matrix C = A A^T is formed once (svd_gram<true>, MFMA), the sweeps
-// rotate C two-sidedly and accumulate the rotations in Tgs (svd_eig reads its 64x64 block straight
-// from C; svd_twosided computes C <- D^T C D tile by tile, D being the block rotations of the round,
-// and Tgs <- D^T Tgs), and only when a sweep finds C diagonal to the threshold are the accumulated
-// rotations applied to the data as one contraction W <- Tgs * W (svd_apply, MFMA).  fp32 rounding
-// makes C drift from the true Gram matrix of the rotated rows, so after every application C is
-// formed afresh from the data (svd_gram<true> again); the matrix is finished when that fresh C is
-// diagonal to a quarter of the threshold, otherwise the sweeps continue from it.  The O(M r^2) work
-// thus happens in two or three large contractions instead of in every round.
+// rotate C two-sidedly and accumulate the rotations in Tgs, and only when a sweep finds C diagonal to
+// the threshold are the accumulated rotations applied to the data as one contraction W <- Tgs * W
+// (svd_apply, MFMA).  fp32 rounding makes C drift from the true Gram matrix of the rotated rows, so
+// after every application C is formed afresh from the data (svd_gram<true> again); the matrix is
+// finished when that fresh C is diagonal to a quarter of the threshold, otherwise the sweeps continue
+// from it.  The O(M r^2) work thus happens in two or three large contractions instead of in every
+// round.  A Gram-space tick is one launch of svd_eig: the pair problems of the tick, and as extra
+// workgroups the two-sided update C <- D^T C D, Tgs <- D^T Tgs of the previous tick (twosided_tile in
+// svd_common.h; D = the block rotations of that round).  C alternates between two buffers by tick
+// parity and every pair problem brings its own 64x64 block up to date (svd_eig.hip, step 1).
 #include <cfloat>
 #include <cmath>
 #include <vector>
