@@ -110,7 +110,11 @@ typedef struct atomo_svd_options {
 
 /* -------- context ------------------------------------------------------------------------------ */
 
-/* Creates a context on HIP device `device`.  *out is set on success. */
+/* Creates a context on HIP device `device`.  *out is set on success.
+ * A context owns one workspace and (for the SVD encoder) one helper stream that is forked from and joined
+ * back into the caller's stream inside every call: calls that share a context must be issued from one host
+ * thread at a time and onto one stream, or onto streams the caller has ordered among themselves; use one
+ * context per concurrent stream. */
 int atomo_create(atomo_ctx** out, int device);
 int atomo_destroy(atomo_ctx* ctx);
 
