@@ -213,10 +213,18 @@ __global__ __launch_bounds__(256) void svd_fullgram_reduce(const SvdMat* mats, c
     const int tile_index = ti * nt - ti * (ti - 1) / 2 + (tj - ti);
     const float* g = m.gram + (size_t)tile_index * m.nchg * QSZ;
     const int tid = threadIdx.x;
-    for (int e = tid; e < QSZ; e += 256) {
-        float sum = 0.0f;
-        for (int c = 0; c < m.nchg; ++c) sum += g[(size_t)c * QSZ + e];
-        t[e >> 6][e & 63] = sum;
+    // sixteen independent sums per thread, chunk after chunk in a fixed order: sixteen loads in flight
+    float sums[QSZ / 256];
+#pragma unroll
+    for (int p = 0; p < QSZ / 256; ++p) sums[p] = 0.0f;
+    for (int c = 0; c < m.nchg; ++c) {
+#pragma unroll
+        for (int p = 0; p < QSZ / 256; ++p) sums[p] += g[(size_t)c * QSZ + tid + 256 * p];
+    }
+#pragma unroll
+    for (int p = 0; p < QSZ / 256; ++p) {
+        const int e = tid + 256 * p;
+        t[e >> 6][e & 63] = sums[p];
     }
     __syncthreads();
     const int Rp = m.rows_alloc;
