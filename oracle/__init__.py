@@ -57,6 +57,12 @@ def _L():
         lib.oracle_decode_svd_accumulate.restype = None
         lib.oracle_decode_entrywise_accumulate.argtypes = [c.c_int64, i64p, dp, c.c_double, dp]
         lib.oracle_decode_entrywise_accumulate.restype = None
+        lib.oracle_lq_norm.argtypes = [dp, c.c_int64, c.c_double, c.c_int]
+        lib.oracle_lq_norm.restype = c.c_double
+        lib.oracle_lq_probabilities.argtypes = [dp, c.c_int64, c.c_double, c.c_int, dp]
+        lib.oracle_lq_probabilities.restype = c.c_double
+        lib.oracle_decode_lq_accumulate.argtypes = [c.c_int64, i64p, c.POINTER(c.c_int8), c.c_double, c.c_double, dp]
+        lib.oracle_decode_lq_accumulate.restype = None
         _lib = lib
     return _lib
 
@@ -157,6 +163,29 @@ def decode_entrywise(messages, n: int, scale: float = 1.0):
     return out
 
 
+def lq_probabilities(g, q: float):
+    """(p, ||g||_q) of l_q quantisation, p_i = |g_i| / ||g||_q (Section 4); q = float('inf') is the maximum norm."""
+    g = np.ascontiguousarray(np.asarray(g, dtype=np.float64).ravel())
+    p = np.empty_like(g)
+    is_inf = 1 if np.isinf(q) else 0
+    norm = _L().oracle_lq_probabilities(_ptr(g, ctypes.c_double), g.size, 0.0 if is_inf else float(q), is_inf,
+                                        _ptr(p, ctypes.c_double))
+    return p, float(norm)
+
+
+def decode_lq(messages, n: int, scale: float = 1.0):
+    """Dense length-n float64 sum of l_q messages {'idx', 'sign', 'norm'}, times scale."""
+    out = np.zeros(n)
+    for msg in messages:
+        idx = np.ascontiguousarray(msg["idx"], dtype=np.int64)
+        sign = np.ascontiguousarray(msg["sign"], dtype=np.int8)
+        if idx.size:
+            assert idx.min() >= 0 and idx.max() < n and set(np.unique(sign)) <= {-1, 1}
+            _L().oracle_decode_lq_accumulate(idx.size, _ptr(idx, ctypes.c_int64), _ptr(sign, ctypes.c_int8),
+                                             float(msg["norm"]), float(scale), _ptr(out, ctypes.c_double))
+    return out
+
+
 # ----------------------------------------------------------------- chains ----
 
 def encode_svd(G, s: float, seed: int, stream: int, sigma_UV=None, p32=None):
@@ -182,3 +211,14 @@ def encode_entrywise(g, s: float, seed: int, stream: int, p32=None):
     p_for_w = p if p32 is None else p_used32.astype(np.float64)
     idx, val = pack_weights(g, p_for_w, mask)
     return {"p": p, "mask": mask, "idx": idx, "val": val}
+
+
+def encode_lq(g, q: float, seed: int, stream: int, p32=None):
+    """l_q quantisation of a flat gradient (Section 4): kept coordinates (ascending), their signs, ||g||_q."""
+    g = np.asarray(g, dtype=np.float64).ravel()
+    p, norm = lq_probabilities(g, q)
+    p_used32 = p.astype(np.float32) if p32 is None else np.asarray(p32, dtype=np.float32)
+    mask = bernoulli_mask(p_used32, seed, stream)
+    idx = np.flatnonzero(mask)
+    return {"p": p, "mask": mask, "idx": idx, "sign": np.sign(g[idx]).astype(np.int8), "norm": norm}
+

@@ -317,3 +317,48 @@ void oracle_decode_entrywise_accumulate(int64_t k, const int64_t* idx, const dou
 {
     for (int64_t a = 0; a < k; ++a) out[idx[a]] += scale * val[a];
 }
+
+/* ------------------------------------------------------------------------ */
+/* l_q quantisation (Section 4): 1-bit QSGD (q = 2), TernGrad (q = inf).      */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * ||g||_q for q in (0, inf]; q_is_inf != 0 selects the maximum norm.
+ * Plain left-to-right sums in double.
+ */
+double oracle_lq_norm(const double* g, int64_t n, double q, int q_is_inf)
+{
+    double acc = 0.0;
+    if (q_is_inf) {
+        for (int64_t i = 0; i < n; ++i) { double a = fabs(g[i]); if (a > acc) acc = a; }
+        return acc;
+    }
+    if (q == 2.0) {
+        for (int64_t i = 0; i < n; ++i) acc += g[i] * g[i];
+        return sqrt(acc);
+    }
+    if (q == 1.0) {
+        for (int64_t i = 0; i < n; ++i) acc += fabs(g[i]);
+        return acc;
+    }
+    for (int64_t i = 0; i < n; ++i) if (g[i] != 0.0) acc += pow(fabs(g[i]), q);
+    return pow(acc, 1.0 / q);
+}
+
+/*
+ * The probabilities of l_q quantisation, p_i = |g_i| / ||g||_q (text before
+ * Theorem (lqgrad)); an all-zero g gives p = 0.  Returns the norm.
+ */
+double oracle_lq_probabilities(const double* g, int64_t n, double q, int q_is_inf, double* p)
+{
+    double norm = oracle_lq_norm(g, n, q, q_is_inf);
+    for (int64_t i = 0; i < n; ++i) p[i] = norm > 0.0 ? fabs(g[i]) / norm : 0.0;
+    return norm;
+}
+
+/* L_q(g)_i = ||g||_q sign(g_i) zeta_i:  out[idx[k]] += scale * sign[k] * norm. */
+void oracle_decode_lq_accumulate(int64_t k, const int64_t* idx, const int8_t* sign, double norm, double scale, double* out)
+{
+    for (int64_t a = 0; a < k; ++a) out[idx[a]] += scale * (double)sign[a] * norm;
+}
+
