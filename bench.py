@@ -307,11 +307,36 @@ def entrywise_leg(ctx, torch, binding, inputs, reps=40, sets=8):
                 prof[name] = prof.get(name, 0.0) + ms
     ctx.profile_enable(False)
     nbytes = 12.0 * n + 20.0 * kept
+    # l_q quantisation of the same gradient (1-bit QSGD, TernGrad): norm pass instead of the histograms
+    lq = {}
+    for name, q in (("qsgd_1bit_q2", 2.0), ("terngrad_qinf", float("inf"))):
+        lmsgs = [binding.alloc_lq_message(n, binding.lq_capacity(n, q), "cuda") for _ in range(sets)]
+
+        def lstep(i):
+            k = i % sets
+            binding.atomo_encode_lq(ctx, gs[k], q, 0, 0, msg=lmsgs[k])
+            binding.atomo_decode(ctx, [lmsgs[k]], out=outs[k])
+
+        for i in range(sets):
+            lstep(i)
+        torch.cuda.synchronize()
+        if ctx.status()[0] != 0:
+            continue
+        t0 = time.perf_counter()
+        for i in range(reps):
+            lstep(i)
+        torch.cuda.synchronize()
+        ldt = (time.perf_counter() - t0) / reps
+        lkept = int(lmsgs[0].count.item())
+        lbytes = 12.0 * n + 8.0 * lkept
+        lq[name] = {"us_per_step": round(ldt * 1e6, 2), "kept": lkept, "elements_per_s": n / ldt,
+                    "hbm_gbs": round(lbytes / ldt / 1e9, 1), "hbm_frac": round(lbytes / ldt / 1e9 / PEAK_HBM_GBS, 4)}
     return {"workload": "flat_heavy_tail: N=11,173,962 fp32, N(0,1e-3^2) + 11,173 entries x100, s=N/100, encode + decode",
             "elements_per_s": n / dt, "us_per_step": round(dt * 1e6, 2), "kept": kept,
             "roofline": {"bound": "hbm", "achieved": round(nbytes / dt / 1e9, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                          "frac": round(nbytes / dt / 1e9 / PEAK_HBM_GBS, 4), "algorithmic_bytes_per_step": nbytes},
-            "us_per_step_by_kernel_class": {k: round(v / reps * 1e3, 2) for k, v in sorted(prof.items())}}
+            "us_per_step_by_kernel_class": {k: round(v / reps * 1e3, 2) for k, v in sorted(prof.items())},
+            "lq_quantisation": lq}
 
 
 def cpu_baseline(host_mats, s, seed):

@@ -55,7 +55,7 @@ typedef enum atomo_status_code {
     ATOMO_ENOMEM = -5      /* the workspace could not be allocated                                  */
 } atomo_status_code;
 
-enum { ATOMO_KIND_SVD = 0, ATOMO_KIND_ENTRYWISE = 1 };
+enum { ATOMO_KIND_SVD = 0, ATOMO_KIND_ENTRYWISE = 1, ATOMO_KIND_LQ = 2 };
 
 typedef struct atomo_ctx atomo_ctx;   /* opaque: device, workspace, latched device-side flags */
 
@@ -88,6 +88,16 @@ typedef struct atomo_ew_msg {
     uint32_t* idx;                   /* [capacity] kept coordinates, ascending                       */
     float* val;                      /* [capacity] g_i / p_i                                         */
 } atomo_ew_msg;
+
+/* One l_q-quantised gradient (Section 4: L_q(g)_i = |g|_q sign(g_i) zeta_i; q = 2 is 1-bit QSGD, q = inf
+ * TernGrad): the kept coordinates with their signs, and the one magnitude they all share. */
+typedef struct atomo_lq_msg {
+    int64_t n;                       /* length of the encoded gradient, 0 < n < 2^31                 */
+    int64_t capacity;                /* room for this many kept coordinates                          */
+    int64_t* count;                  /* [1]  number kept (may exceed capacity: see status)           */
+    uint32_t* idx;                   /* [capacity] kept coordinates, ascending, in bits 0..30; bit 31 is set where g_i < 0 */
+    float* norm;                     /* [1]  |g|_q                                                   */
+} atomo_lq_msg;
 
 /* Tuning knobs of the Jacobi SVD; pass NULL to the encoder for the defaults. */
 typedef struct atomo_svd_options {
@@ -184,6 +194,16 @@ int atomo_encode_entrywise(atomo_ctx* ctx, const float* g, double s, uint64_t se
                            const atomo_ew_msg* msg /*host*/, float* p_out, void* stream);
 
 /*
+ * l_q quantisation (Section 4, Theorem (lqgrad)): p_i = |g_i| / |g|_q, the variance-optimal entry-wise
+ * probabilities for the budget s = |g|_1 / |g|_q, computed without Algorithm 1 (every g is balanced for
+ * that budget).  Coordinate i is kept iff u_i < p_i (Philox stream (seed, stream_id)); a kept coordinate
+ * decodes to sign(g_i) |g|_q.  q > 0; pass INFINITY for the maximum norm (TernGrad), 2 for 1-bit QSGD.
+ *   g : device float32 [msg->n];  p_out : optional device float32 [msg->n].
+ */
+int atomo_encode_lq(atomo_ctx* ctx, const float* g, double q, uint64_t seed, uint64_t stream_id,
+                    const atomo_lq_msg* msg /*host*/, float* p_out, void* stream);
+
+/*
  * Decode (eq. (vhat)): out = scale * sum over the n_msgs messages of sum_k w_k a_k.  With
  * scale = 1/P and the P workers' messages this is the parameter server's averaged gradient
  * (Section 2).  `out` is overwritten.
@@ -191,6 +211,7 @@ int atomo_encode_entrywise(atomo_ctx* ctx, const float* g, double s, uint64_t se
  *                                out is the dense rows x cols row-major matrix with row stride ld.
  *   kind = ATOMO_KIND_ENTRYWISE: msgs is a HOST array of n_msgs atomo_ew_msg with equal n;
  *                                out is the dense vector of n floats (ld is ignored).
+ *   kind = ATOMO_KIND_LQ:        msgs is a HOST array of n_msgs atomo_lq_msg with equal n; out as above.
  * A message whose count exceeds its capacity contributes its first `capacity` atoms.
  */
 int atomo_decode(atomo_ctx* ctx, int kind, const void* msgs, int n_msgs, float scale,

@@ -12,13 +12,14 @@ import os
 from dataclasses import dataclass
 from typing import List, Optional, Sequence
 
+import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libatomo.so")
 
 ATOMO_OK, ATOMO_EINVAL, ATOMO_ECAPACITY, ATOMO_ENOCONV, ATOMO_EHIP, ATOMO_ENOMEM = 0, -1, -2, -3, -4, -5
-ATOMO_KIND_SVD, ATOMO_KIND_ENTRYWISE = 0, 1
+ATOMO_KIND_SVD, ATOMO_KIND_ENTRYWISE, ATOMO_KIND_LQ = 0, 1, 2
 
 
 class AtomoError(RuntimeError):
@@ -39,6 +40,11 @@ class atomo_svd_msg(C.Structure):
 class atomo_ew_msg(C.Structure):
     _fields_ = [("n", C.c_int64), ("capacity", C.c_int64), ("count", C.c_void_p), ("idx", C.c_void_p),
                 ("val", C.c_void_p)]
+
+
+class atomo_lq_msg(C.Structure):
+    _fields_ = [("n", C.c_int64), ("capacity", C.c_int64), ("count", C.c_void_p), ("idx", C.c_void_p),
+                ("norm", C.c_void_p)]
 
 
 class atomo_svd_options(C.Structure):
@@ -72,6 +78,7 @@ def lib() -> C.CDLL:
                                        C.POINTER(atomo_svd_options), C.POINTER(atomo_svd_msg), vp, vp, vp]
         L.atomo_encode_entrywise.argtypes = [vp, vp, C.c_double, C.c_uint64, C.c_uint64, C.POINTER(atomo_ew_msg),
                                              vp, vp]
+        L.atomo_encode_lq.argtypes = [vp, vp, C.c_double, C.c_uint64, C.c_uint64, C.POINTER(atomo_lq_msg), vp, vp]
         L.atomo_decode.argtypes = [vp, C.c_int, vp, C.c_int, C.c_float, vp, C.c_int64, vp]
         L.atomo_decode_svd_batch.argtypes = [vp, C.POINTER(atomo_svd_msg), C.POINTER(C.c_int32), C.c_int, C.c_float,
                                              C.POINTER(vp), C.POINTER(C.c_int64), vp]
@@ -81,7 +88,8 @@ def lib() -> C.CDLL:
         L.atomo_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         for name in ("atomo_last_counters", "atomo_svd_sweeps", "atomo_profile_enable", "atomo_profile_read", "atomo_create", "atomo_destroy", "atomo_reserve", "atomo_svd_workspace_bytes",
                      "atomo_entrywise_workspace_bytes", "atomo_status", "atomo_last_hip_error", "atomo_probabilities",
-                     "atomo_encode_svd", "atomo_encode_entrywise", "atomo_decode", "atomo_decode_svd_batch"):
+                     "atomo_encode_svd", "atomo_encode_entrywise", "atomo_encode_lq", "atomo_decode",
+                     "atomo_decode_svd_batch"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -153,6 +161,25 @@ class EntrywiseMessage:
                 "val": self.val[:k].cpu().numpy()}
 
 
+@dataclass
+class LqMessage:
+    """One l_q-quantised gradient: kept coordinates (sign in bit 31 of the index) and the shared magnitude."""
+    n: int
+    capacity: int
+    count: torch.Tensor   # int64 [1]
+    idx: torch.Tensor     # uint32 stored as int32 bits [capacity]
+    norm: torch.Tensor    # float32 [1]
+
+    def c_struct(self) -> atomo_lq_msg:
+        return atomo_lq_msg(self.n, self.capacity, self.count.data_ptr(), self.idx.data_ptr(), self.norm.data_ptr())
+
+    def to_host(self) -> dict:
+        k = min(int(self.count.item()), self.capacity)
+        words = self.idx[:k].cpu().numpy().view("uint32")
+        return {"count": int(self.count.item()), "idx": (words & 0x7FFFFFFF).astype("int64"),
+                "sign": np.where(words >> 31, -1, 1).astype("int8"), "norm": float(self.norm.item())}
+
+
 def default_capacity(s: float, n_atoms: int) -> int:
     """Room for the expected s kept atoms plus a wide margin (the count is Poisson-binomial with mean <= s)."""
     return int(min(n_atoms, math.ceil(s) + 8 * math.ceil(math.sqrt(s)) + 8))
@@ -172,6 +199,20 @@ def alloc_entrywise_message(n: int, capacity: int, device) -> EntrywiseMessage:
                             torch.zeros(1, dtype=torch.int64, device=device),
                             torch.zeros(capacity, dtype=torch.int32, device=device),
                             torch.zeros(capacity, dtype=torch.float32, device=device))
+
+
+def alloc_lq_message(n: int, capacity: int, device) -> LqMessage:
+    return LqMessage(n, capacity,
+                     torch.zeros(1, dtype=torch.int64, device=device),
+                     torch.zeros(capacity, dtype=torch.int32, device=device),
+                     torch.zeros(1, dtype=torch.float32, device=device))
+
+
+def lq_capacity(n: int, q: float) -> int:
+    """Room for an l_q message of a length-n gradient: the budget |g|_1 / |g|_q is at most n^(1 - 1/q) for
+    q >= 1 (Hoelder), n otherwise, plus a margin for the spread of the count."""
+    s = float(n) if (q < 1.0 or math.isinf(q)) else float(n) ** (1.0 - 1.0 / q)
+    return default_capacity(s, n)
 
 
 # -------------------------------------------------------------------------------------- context
@@ -300,8 +341,26 @@ def atomo_encode_entrywise(ctx: Context, g: torch.Tensor, s: float, seed: int, s
     return msg
 
 
+def atomo_encode_lq(ctx: Context, g: torch.Tensor, q: float, seed: int, stream_id: int = 0,
+                    msg: Optional[LqMessage] = None, p_out: Optional[torch.Tensor] = None, stream=None) -> LqMessage:
+    """l_q quantisation of a flat float32 CUDA tensor: q = 2 is 1-bit QSGD, q = float('inf') TernGrad."""
+    g = _f32_cuda(g, "g")
+    if not g.is_contiguous():
+        raise ValueError("g must be contiguous")
+    n = g.numel()
+    if msg is None:
+        msg = alloc_lq_message(n, lq_capacity(n, q), g.device)
+    cm = msg.c_struct()
+    _check(lib().atomo_encode_lq(ctx._h, g.data_ptr(), float(q), int(seed) & (2 ** 64 - 1),
+                                 int(stream_id) & (2 ** 64 - 1), C.byref(cm),
+                                 None if p_out is None else p_out.data_ptr(), _stream_handle(stream)),
+           "atomo_encode_lq")
+    return msg
+
+
 def atomo_decode(ctx: Context, msgs, scale: float = 1.0, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
-    """Sums the messages (all SvdMessage of one shape, or all EntrywiseMessage of one length) into a dense tensor."""
+    """Sums the messages (all SvdMessage of one shape, or all EntrywiseMessage / LqMessage of one length) into a
+    dense tensor."""
     msgs = list(msgs)
     first = msgs[0]
     if isinstance(first, SvdMessage):
@@ -312,6 +371,14 @@ def atomo_decode(ctx: Context, msgs, scale: float = 1.0, out: Optional[torch.Ten
         _check(lib().atomo_decode(ctx._h, ATOMO_KIND_SVD, C.cast(c_msgs, C.c_void_p), len(msgs), float(scale),
                                   out.data_ptr(), out.stride(0) if out.shape[0] > 1 else out.shape[1],
                                   _stream_handle(stream)), "atomo_decode")
+        return out
+    if isinstance(first, LqMessage):
+        if out is None:
+            out = torch.empty(first.n, dtype=torch.float32, device=first.idx.device)
+        _f32_cuda(out, "out")
+        c_msgs = (atomo_lq_msg * len(msgs))(*[m.c_struct() for m in msgs])
+        _check(lib().atomo_decode(ctx._h, ATOMO_KIND_LQ, C.cast(c_msgs, C.c_void_p), len(msgs), float(scale),
+                                  out.data_ptr(), 0, _stream_handle(stream)), "atomo_decode")
         return out
     if out is None:
         out = torch.empty(first.n, dtype=torch.float32, device=first.val.device)

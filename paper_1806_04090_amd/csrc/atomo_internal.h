@@ -154,6 +154,8 @@ int svd_sweeps(atomo_ctx* ctx, hipStream_t stream, int32_t* sweeps, int32_t* ref
 size_t entrywise_workspace_bytes(int64_t n);
 int encode_entrywise(atomo_ctx* ctx, const float* g, double s, uint64_t seed, uint64_t stream_id,
                      const atomo_ew_msg* msg, float* p_out, hipStream_t stream);
+int encode_lq(atomo_ctx* ctx, const float* g, double q, uint64_t seed, uint64_t stream_id, const atomo_lq_msg* msg,
+              float* p_out, hipStream_t stream);
 int probabilities(atomo_ctx* ctx, const float* lambda, const int64_t* offsets, int n_seg, double s, float* p,
                   hipStream_t stream);
 
@@ -161,5 +163,6 @@ int decode_svd_batch(atomo_ctx* ctx, const atomo_svd_msg* msgs, const int32_t* f
                      float* const* outs, const int64_t* lds, hipStream_t stream);
 int decode_entrywise(atomo_ctx* ctx, const atomo_ew_msg* msgs, int n_msgs, float scale, float* out,
                      hipStream_t stream);
+int decode_lq(atomo_ctx* ctx, const atomo_lq_msg* msgs, int n_msgs, float scale, float* out, hipStream_t stream);
 
 }  // namespace atomo

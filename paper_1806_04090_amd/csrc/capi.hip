@@ -278,6 +278,17 @@ int atomo_encode_entrywise(atomo_ctx* ctx, const float* g, double s, uint64_t se
     return encode_entrywise(ctx, g, s, seed, stream_id, msg, p_out, (hipStream_t)stream);
 }
 
+int atomo_encode_lq(atomo_ctx* ctx, const float* g, double q, uint64_t seed, uint64_t stream_id,
+                    const atomo_lq_msg* msg, float* p_out, void* stream)
+{
+    if (!ctx || !g || !msg || !(q > 0.0)) return ATOMO_EINVAL;                      // (NaN fails the comparison)
+    if (msg->n <= 0 || msg->n >= ((int64_t)1 << 31) || msg->capacity < 1) return ATOMO_EINVAL;
+    if (!msg->count || !msg->idx || !msg->norm) return ATOMO_EINVAL;
+    DeviceGuard guard(ctx);
+    if (!guard.ok) return ATOMO_EHIP;
+    return encode_lq(ctx, g, q, seed, stream_id, msg, p_out, (hipStream_t)stream);
+}
+
 int atomo_decode_svd_batch(atomo_ctx* ctx, const atomo_svd_msg* msgs, const int32_t* first, int n_out, float scale,
                            float* const* outs, const int64_t* lds, void* stream)
 {
@@ -318,6 +329,16 @@ int atomo_decode(atomo_ctx* ctx, int kind, const void* msgs, int n_msgs, float s
         DeviceGuard guard(ctx);
         if (!guard.ok) return ATOMO_EHIP;
         return decode_entrywise(ctx, m, n_msgs, scale, out, (hipStream_t)stream);
+    }
+    if (kind == ATOMO_KIND_LQ) {
+        const atomo_lq_msg* m = (const atomo_lq_msg*)msgs;
+        for (int k = 0; k < n_msgs; ++k) {
+            if (m[k].n != m[0].n || m[k].n <= 0 || m[k].n >= ((int64_t)1 << 31) || m[k].capacity < 1) return ATOMO_EINVAL;
+            if (!m[k].count || !m[k].idx || !m[k].norm) return ATOMO_EINVAL;
+        }
+        DeviceGuard guard(ctx);
+        if (!guard.ok) return ATOMO_EHIP;
+        return decode_lq(ctx, m, n_msgs, scale, out, (hipStream_t)stream);
     }
     return ATOMO_EINVAL;
 }

@@ -159,6 +159,31 @@ __global__ __launch_bounds__(256) void scatter_entrywise(const EwDecMsg* msgs, i
     }
 }
 
+struct LqDecMsg {
+    const long long* count;
+    const unsigned int* idx;
+    const float* norm;
+    long long capacity;
+};
+
+// l_q messages (Section 4): a kept coordinate decodes to sign * |g|_q, the sign in bit 31 of its index.
+__global__ __launch_bounds__(256) void scatter_lq(const LqDecMsg* msgs, int n_msgs, float scale, float* __restrict__ out,
+                                                  long long n)
+{
+    const LqDecMsg m = msgs[blockIdx.y];
+    const long long kept = min(*m.count, m.capacity);
+    const float mag = scale * *m.norm;
+    const long long stride = (long long)gridDim.x * 256;
+    for (long long k = (long long)blockIdx.x * 256 + threadIdx.x; k < kept; k += stride) {
+        const unsigned int word = m.idx[k];
+        const unsigned int i = word & 0x7FFFFFFFu;
+        if ((long long)i >= n) continue;
+        const float v = (word >> 31) ? -mag : mag;
+        if (n_msgs == 1) out[i] = v;
+        else atomicAdd(&out[i], v);
+    }
+}
+
 }  // namespace
 
 int decode_svd_batch(atomo_ctx* ctx, const atomo_svd_msg* msgs, const int32_t* first, int n_out, float scale,
@@ -221,6 +246,30 @@ int decode_entrywise(atomo_ctx* ctx, const atomo_ew_msg* msgs, int n_msgs, float
         ProfScope ps(ctx, ATOMO_K_EW_DECODE, stream);
         fill_zero<<<fill_wgs, 256, 0, stream>>>(out, n);
         scatter_entrywise<<<dim3(sc_wgs, n_msgs), 256, 0, stream>>>(d_msgs, n_msgs, scale, out, n);
+    }
+    ATOMO_HIP(ctx, hipGetLastError());
+    return ATOMO_OK;
+}
+
+int decode_lq(atomo_ctx* ctx, const atomo_lq_msg* msgs, int n_msgs, float scale, float* out, hipStream_t stream)
+{
+    const int64_t n = msgs[0].n;
+    std::vector<LqDecMsg> hm(n_msgs);
+    int64_t max_cap = 1;
+    for (int k = 0; k < n_msgs; ++k) {
+        hm[k] = LqDecMsg{(const long long*)msgs[k].count, msgs[k].idx, msgs[k].norm, (long long)msgs[k].capacity};
+        if (msgs[k].capacity > max_cap) max_cap = msgs[k].capacity;
+    }
+    int rc = ensure_workspace(ctx, align_up(hm.size() * sizeof(LqDecMsg), 256));
+    if (rc != ATOMO_OK) return rc;
+    LqDecMsg* d_msgs = (LqDecMsg*)ctx->ws;
+    if ((rc = upload(ctx, d_msgs, hm.data(), hm.size() * sizeof(LqDecMsg), stream)) != ATOMO_OK) return rc;
+    const int fill_wgs = (int)std::min<int64_t>(2048, (n / 4 + 255) / 256 + 1);
+    const int sc_wgs = (int)std::min<int64_t>(1024, (max_cap + 255) / 256);
+    {
+        ProfScope ps(ctx, ATOMO_K_EW_DECODE, stream);
+        fill_zero<<<fill_wgs, 256, 0, stream>>>(out, n);
+        scatter_lq<<<dim3(sc_wgs, n_msgs), 256, 0, stream>>>(d_msgs, n_msgs, scale, out, n);
     }
     ATOMO_HIP(ctx, hipGetLastError());
     return ATOMO_OK;

@@ -355,7 +355,7 @@ __global__ __launch_bounds__(256) void ew_scan(const unsigned int* __restrict__ 
 __global__ __launch_bounds__(256) void ew_write(const float* __restrict__ g, const EwState* st,
                                                 const unsigned long long* __restrict__ keep,
                                                 const unsigned long long* __restrict__ chunk_base, long long capacity,
-                                                unsigned int* __restrict__ idx, float* __restrict__ val)
+                                                unsigned int* __restrict__ idx, float* __restrict__ val /* null: signs in idx */)
 {
     __shared__ unsigned int wsum[4];
     __shared__ unsigned short local[CHUNK];    // coordinate offsets inside the chunk, by rank
@@ -404,8 +404,12 @@ __global__ __launch_bounds__(256) void ew_write(const float* __restrict__ g, con
         if ((long long)pos < capacity) {
             const long long i = i0 + local[t];
             const float x = g[i];
-            idx[pos] = (unsigned int)i;
-            val[pos] = x / ew_probability(x, ratio);
+            if (val) {
+                idx[pos] = (unsigned int)i;
+                val[pos] = x / ew_probability(x, ratio);
+            } else {                                             // l_q message: the sign rides in bit 31
+                idx[pos] = (unsigned int)i | (x < 0.0f ? 0x80000000u : 0u);
+            }
         }
     }
 }
@@ -435,11 +439,81 @@ __global__ __launch_bounds__(256) void prob_small(const float* __restrict__ lam,
     for (int i = tid; i < n; i += 256) p[seg.begin + src[i]] = alg1_probability(key[i], i, ns, s, tail_ns);
 }
 
+// ---- l_q quantisation (Section 4) -------------------------------------------------------------------
+enum { LQ_MAX = 0, LQ_TWO = 1, LQ_ONE = 2, LQ_POW = 3 };
+constexpr int LQ_WGS = 1024;
+
+// Per-workgroup part of |g|_q: max |g_i|, or the sum of g_i^2, |g_i| or |g_i|^q in double (fixed thread ->
+// element map and fixed reduction tree, so the norm is the same bits in every run).
+__global__ __launch_bounds__(256) void lq_norm_partial(const float* __restrict__ g, long long n, int mode, double q,
+                                                       double* __restrict__ partial)
+{
+    __shared__ double wpart[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    double acc = 0.0;
+    auto visit = [&](float x) {
+        const double a = (double)fabsf(x);
+        if (mode == LQ_MAX) acc = fmax(acc, a);
+        else if (mode == LQ_TWO) acc = fma(a, a, acc);
+        else if (mode == LQ_ONE) acc += a;
+        else if (a > 0.0) acc += pow(a, q);
+    };
+    const bool vec = (((size_t)g) & 15) == 0;
+    const long long n4 = vec ? n / 4 : 0;
+    const long long stride = (long long)gridDim.x * 256;
+    for (long long q0 = (long long)blockIdx.x * 256 + tid; q0 < n4; q0 += 4 * stride) {
+        float4 x[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const long long qq = q0 + u * stride;
+            x[u] = qq < n4 ? ((const float4*)g)[qq] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { visit(x[u].x); visit(x[u].y); visit(x[u].z); visit(x[u].w); }
+    }
+    for (long long i = n4 * 4 + (long long)blockIdx.x * 256 + tid; i < n; i += stride) visit(g[i]);
+    for (int o = 32; o > 0; o >>= 1) {
+        const double other = __shfl_down(acc, o);
+        acc = mode == LQ_MAX ? fmax(acc, other) : acc + other;
+    }
+    if (lane == 0) wpart[wave] = acc;
+    __syncthreads();
+    if (tid == 0) {
+        double t = wpart[0];
+        for (int w = 1; w < 4; ++w) t = mode == LQ_MAX ? fmax(t, wpart[w]) : t + wpart[w];
+        partial[blockIdx.x] = t;
+    }
+}
+
+// |g|_q from the partial results (one workgroup), 1 / |g|_q as the sampler's ratio, and the message's norm.
+__global__ __launch_bounds__(256) void lq_norm_final(const double* __restrict__ partial, int n_partial, int mode, double q,
+                                                     EwState* st, float* norm_out)
+{
+    __shared__ double tree[256];
+    const int tid = threadIdx.x;
+    double t = 0.0;
+    for (int k = tid; k < n_partial; k += 256) t = mode == LQ_MAX ? fmax(t, partial[k]) : t + partial[k];
+    tree[tid] = t;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if (tid < off) tree[tid] = mode == LQ_MAX ? fmax(tree[tid], tree[tid + off]) : tree[tid] + tree[tid + off];
+        __syncthreads();
+    }
+    if (tid == 0) {
+        const double acc = tree[0];
+        const double norm = mode == LQ_MAX || mode == LQ_ONE ? acc : mode == LQ_TWO ? sqrt(acc) : pow(acc, 1.0 / q);
+        st->ratio = norm > 0.0 ? 1.0 / norm : 0.0;               // p_i = min(1, |g_i| / |g|_q)
+        st->n_s = 0ull; st->tail = norm; st->budget = 1.0; st->resolved = 1; st->total_kept = 0ull;
+        *norm_out = (float)norm;
+    }
+}
+
 struct EwLayout {
     EwState* st;
     unsigned int* chunk_count;
     unsigned long long* chunk_base;
     unsigned long long* keep;     // [n_chunks][64] keep bits, see ew_count
+    double* lq_partial;           // [LQ_WGS] per-workgroup parts of |g|_q
     size_t bytes;
 };
 
@@ -452,6 +526,7 @@ EwLayout ew_layout(void* base, int64_t n)
     l.chunk_count = carve.take<unsigned int>(n_chunks);
     l.chunk_base = carve.take<unsigned long long>(n_chunks);
     l.keep = carve.take<unsigned long long>(n_chunks * 64);
+    l.lq_partial = carve.take<double>(LQ_WGS);
     l.bytes = carve.off;
     return l;
 }
@@ -493,6 +568,34 @@ int encode_entrywise(atomo_ctx* ctx, const float* g, double s, uint64_t seed, ui
                                        (long long)msg->capacity, ctx->d_flags);
         ew_write<<<(unsigned)n_chunks, 256, 0, stream>>>(g, l.st, l.keep, l.chunk_base, (long long)msg->capacity,
                                                          msg->idx, msg->val);
+        if (p_out) ew_write_p<<<(int)std::min<int64_t>(4096, (n + 255) / 256), 256, 0, stream>>>(g, n, l.st, p_out);
+    }
+    ATOMO_HIP(ctx, hipGetLastError());
+    return ATOMO_OK;
+}
+
+int encode_lq(atomo_ctx* ctx, const float* g, double q, uint64_t seed, uint64_t stream_id, const atomo_lq_msg* msg,
+              float* p_out, hipStream_t stream)
+{
+    const int64_t n = msg->n;
+    int rc = ensure_workspace(ctx, entrywise_workspace_bytes(n));
+    if (rc != ATOMO_OK) return rc;
+    const EwLayout l = ew_layout(ctx->ws, n);
+    const long long n_chunks = (n + CHUNK - 1) / CHUNK;
+    const int mode = std::isinf(q) ? LQ_MAX : q == 2.0 ? LQ_TWO : q == 1.0 ? LQ_ONE : LQ_POW;
+    const int wgs = (int)std::min<int64_t>(LQ_WGS, (n + 4095) / 4096);
+    {
+        ProfScope ps(ctx, ATOMO_K_EW_HIST, stream);              // the norm pass takes the place of the histograms
+        lq_norm_partial<<<wgs, 256, 0, stream>>>(g, n, mode, q, l.lq_partial);
+    }
+    { ProfScope ps(ctx, ATOMO_K_EW_SOLVE, stream); lq_norm_final<<<1, 256, 0, stream>>>(l.lq_partial, wgs, mode, q, l.st, msg->norm); }
+    {
+        ProfScope ps(ctx, ATOMO_K_EW_SAMPLE, stream);
+        ew_count<<<(unsigned)n_chunks, 256, 0, stream>>>(g, n, l.st, stream_id, seed, l.chunk_count, l.keep);
+        ew_scan<<<1, 256, 0, stream>>>(l.chunk_count, n_chunks, l.chunk_base, l.st, (long long*)msg->count,
+                                       (long long)msg->capacity, ctx->d_flags);
+        ew_write<<<(unsigned)n_chunks, 256, 0, stream>>>(g, l.st, l.keep, l.chunk_base, (long long)msg->capacity,
+                                                         msg->idx, nullptr);
         if (p_out) ew_write_p<<<(int)std::min<int64_t>(4096, (n + 255) / 256), 256, 0, stream>>>(g, n, l.st, p_out);
     }
     ATOMO_HIP(ctx, hipGetLastError());

@@ -1,0 +1,96 @@
+"""GPU parity: l_q quantisation (atomo_encode_lq, Section 4) against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1806_04090_amd import binding, inputs
+from gpu_common import ctx, dev
+
+pytestmark = pytest.mark.gpu
+
+INF = float("inf")
+
+
+def encode(g, q, seed, stream, capacity=None):
+    n = g.size
+    p = torch.zeros(n, dtype=torch.float32, device="cuda")
+    msg = None if capacity is None else binding.alloc_lq_message(n, capacity, "cuda")
+    msg = binding.atomo_encode_lq(ctx(), dev(g), q, seed, stream, msg=msg, p_out=p)
+    return msg, p.cpu().numpy()
+
+
+def parity(g, q, seed, stream, capacity=None):
+    msg, p_gpu = encode(g, q, seed, stream, capacity)
+    assert ctx().status()[0] == 0
+    p_ref, norm_ref = oracle.lq_probabilities(g.astype(np.float64), q)
+    np.testing.assert_allclose(p_gpu, p_ref, rtol=1e-6, atol=1e-30)
+    h = msg.to_host()
+    np.testing.assert_allclose(h["norm"], norm_ref, rtol=1e-6)
+    ref = oracle.encode_lq(g, q, seed, stream, p32=p_gpu)          # the mask is bit-exact given the GPU's float32 p
+    assert h["count"] == ref["idx"].size and np.array_equal(h["idx"], ref["idx"]) and np.array_equal(h["sign"], ref["sign"])
+    out = binding.atomo_decode(ctx(), [msg]).cpu().numpy()
+    want = oracle.decode_lq([dict(ref, norm=h["norm"])], g.size)   # same float32 magnitude on both sides
+    np.testing.assert_array_equal(out, want.astype(np.float32))
+    return msg, h
+
+
+@pytest.mark.parametrize("q", [2.0, INF, 1.0, 3.5, 0.7])
+@pytest.mark.parametrize("n", [1, 5, 4097, 70_001])
+def test_against_the_oracle(q, n):
+    rng = np.random.default_rng(n * 13 + int(min(q, 99) * 10))
+    g = (rng.standard_normal(n) * np.exp(rng.standard_normal(n))).astype(np.float32)
+    g[rng.random(n) < 0.05] = 0
+    parity(g, q, seed=5, stream=n)
+
+
+def test_budget_and_second_moment_of_theorem_lqgrad():
+    # s = sum p = |g|_1 / |g|_q, and E |L_q(g)|^2 = |g|_1 |g|_q: the count of kept coordinates times norm^2
+    g = inputs.flat_heavy_tail(2, n=200_000)
+    a = np.abs(g.astype(np.float64))
+    for q, norm in ((2.0, np.sqrt((a ** 2).sum())), (INF, a.max())):
+        kept = []
+        for t in range(40):
+            msg, _ = encode(g, q, 3, t)
+            kept.append(int(msg.count.item()))
+        s = a.sum() / norm
+        var = (a / norm * (1 - a / norm)).sum()
+        assert abs(np.mean(kept) - s) < 5 * np.sqrt(var / len(kept))
+        np.testing.assert_allclose(np.mean(kept) * norm ** 2, a.sum() * norm, rtol=5 * np.sqrt(var / len(kept)) / s)
+
+
+def test_full_size_qsgd_and_terngrad():
+    g = inputs.flat_heavy_tail(0)
+    for q in (2.0, INF):
+        parity(g, q, seed=0, stream=0)
+
+
+def test_degenerate_inputs_unaligned_pointer_and_average():
+    zero = np.zeros(1000, dtype=np.float32)
+    msg, p = encode(zero, 2.0, 1, 0)
+    assert ctx().status()[0] == 0 and int(msg.count.item()) == 0 and (p == 0).all() and float(msg.norm.item()) == 0.0
+    one = np.zeros(33, dtype=np.float32); one[7] = -2.5
+    msg, h = parity(one, INF, 1, 0)
+    assert h["count"] == 1 and h["idx"][0] == 7 and h["sign"][0] == -1 and h["norm"] == 2.5
+    # unaligned start, and the average of several workers' messages
+    rng = np.random.default_rng(8)
+    base = dev(rng.standard_normal(10_003).astype(np.float32))
+    view = base[3:]
+    msgs = [binding.atomo_encode_lq(ctx(), view, 2.0, 4, w) for w in range(5)]
+    hosts = [m.to_host() for m in msgs]
+    for w, h in enumerate(hosts):
+        ref = oracle.encode_lq(view.cpu().numpy(), 2.0, 4, w)
+        assert len(set(ref["idx"].tolist()) ^ set(h["idx"].tolist())) <= 2      # oracle's own fp64 p vs the GPU's
+    out = binding.atomo_decode(ctx(), msgs, scale=0.2).cpu().numpy()
+    want = oracle.decode_lq(hosts, view.numel(), scale=0.2)
+    np.testing.assert_allclose(out, want, rtol=1e-6, atol=1e-7)
+
+
+def test_capacity_overflow_is_latched():
+    rng = np.random.default_rng(9)
+    g = rng.standard_normal(5000).astype(np.float32)
+    msg, p = encode(g, INF, 2, 0, capacity=10)
+    assert ctx().status()[0] == binding.ATOMO_ECAPACITY
+    h = msg.to_host()
+    mask = oracle.bernoulli_mask(p, 2, 0)
+    assert h["count"] == int(mask.sum()) > 10 and np.array_equal(h["idx"], np.flatnonzero(mask)[:10])

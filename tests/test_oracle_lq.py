@@ -23,8 +23,7 @@ def test_norm_matches_numpy_and_probabilities_are_valid(q):
     want = np.abs(g).max() if np.isinf(q) else (np.abs(g) ** q).sum() ** (1.0 / q)
     np.testing.assert_allclose(norm, want, rtol=1e-12)
     assert (p >= 0).all() and (p[g == 0] == 0).all()
-    if q >= 1:                                    # |g_i| <= ||g||_inf <= ||g||_q: a valid probability (Section 4)
-        assert p.max() <= 1.0
+    assert p.max() <= 1.0                         # |g_i| <= ||g||_inf <= ||g||_q: a valid probability (Section 4)
     np.testing.assert_allclose(p.sum(), np.abs(g).sum() / norm, rtol=1e-12)      # s = ||g||_1 / ||g||_q
 
 
