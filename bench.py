@@ -43,7 +43,8 @@ def layer_geometry(m, n):
 def executed_work(shapes, sweeps, refreshes, pair_visits, jacobi_steps, n_elem, kept_atoms):
     """Arithmetic and bytes the algorithm executes on real data (no padding) per step, by kernel class.
 
-    Data-space layers (r <= 480), per sweep: block-pair Gram matrices 4 M r^2 (svd_gram), rotation of [A | T]
+    Thin layers (r <= 32) are streaming passes over the data (svd_thin), priced by their bytes.
+    Data-space layers (32 < r <= 480), per sweep: block-pair Gram matrices 4 M r^2 (svd_gram), rotation of [A | T]
     4 M r^2 + 4 r^3 (svd_update).
     Gram-space layers, per refresh (svd_refresh): upper-triangular tiles of A A^T  M r (r + 64), and (every
     refresh but the first) A <- T A and T <- T T_old, 2 r^2 (M + r); per sweep, inside the svd_eig launches:
@@ -55,10 +56,13 @@ def executed_work(shapes, sweeps, refreshes, pair_visits, jacobi_steps, n_elem, 
     svd_eig class is priced as a whole (vector-ALU rotations + the MFMA work its launches carry) against the
     157.3 TFLOP/s that is both the fp32 vector and the fp32 matrix peak.
     """
-    gram = upd = refresh = twosided = catchup = 0.0
+    gram = upd = refresh = twosided = catchup = thin_bytes = 0.0
     for (m, n), sw, rf in zip(shapes, sweeps, refreshes):
         r, M, gs = layer_geometry(m, n)
-        if gs:
+        if r <= 32:
+            # thin layers: largest-entry pass, first Gram pass, one read + write per rotation, gather of the kept atoms
+            thin_bytes += 4.0 * M * r * (3 + 2 * sw)
+        elif gs:
             nb = -(-r // 32)
             nb2 = nb + (nb & 1)
             visits = sw * (nb2 - 1) * (nb2 // 2)
@@ -78,6 +82,7 @@ def executed_work(shapes, sweeps, refreshes, pair_visits, jacobi_steps, n_elem, 
         "svd_eig": ("alu", eig, PEAK_FP32_VALU_TFLOPS, "TFLOP/s"),
         "svd_prepare": ("hbm", 12.0 * n_elem, PEAK_HBM_GBS, "GB/s"),
         "svd_finalize": ("hbm", 4.0 * n_elem, PEAK_HBM_GBS, "GB/s"),
+        "svd_thin": ("hbm", thin_bytes, PEAK_HBM_GBS, "GB/s"),
         "decode_svd": ("hbm", decode_bytes, PEAK_HBM_GBS, "GB/s"),
     }
 
@@ -202,6 +207,7 @@ def main():
     }
     entrywise = None if args.no_entrywise else entrywise_leg(ctx, torch, binding, inputs)
     aggregate = None if args.no_entrywise else aggregate_decode_leg(ctx, torch, binding, inputs, shapes, S, SEED)
+    section6 = None if args.no_entrywise else section6_leg(ctx, torch, binding, inputs, S, SEED)
     if args.calibration_copy:
         src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
@@ -225,6 +231,7 @@ def main():
         "cpu_baseline": cpu,
         "entrywise": entrywise,
         "decode_average_16_workers": aggregate,
+        "section6_reshape": section6,
     }
     print(json.dumps(line))
 
@@ -266,6 +273,52 @@ def aggregate_decode_leg(ctx, torch, binding, inputs, shapes, s, seed, workers=1
             "mfma_frac": round(flops / (gpu_ms * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS, 5),
             "hbm_write_gbs": round(nbytes / (gpu_ms * 1e-3) / 1e9, 1),
             "hbm_frac": round(nbytes / (gpu_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+
+
+def section6_leg(ctx, torch, binding, inputs, s, seed, reps=20):
+    """The same encode + decode on the layer sets in the reshape of Section 6 ([x*y/2, 2*k*k] per convolution):
+    ResNet-18 (every matrix has at most 18 columns, all on the thin path) and VGG-11-BN (eight such matrices
+    plus two 512 x 512 fully connected layers, which take the Gram-space iteration).  Wall time per step, and
+    the GPU time of the thin kernels against the bytes they have to move (see executed_work)."""
+    out = {}
+    for name, shapes in (("resnet18", inputs.RESNET18_SECTION6_SHAPES), ("vgg11bn", inputs.VGG11BN_SECTION6_SHAPES)):
+        host = inputs.section6_layer_set(0, shapes)
+        mats = [torch.from_numpy(g).cuda() for g in host]
+        n_elem = sum(g.size for g in host)
+        msgs = [binding.alloc_svd_message(m, n, binding.default_capacity(s, min(m, n)), "cuda") for m, n in shapes]
+        outs = [torch.empty(m, n, dtype=torch.float32, device="cuda") for m, n in shapes]
+        groups = [[m] for m in msgs]
+
+        def step():
+            binding.atomo_encode_svd(ctx, mats, s, seed, 0, msgs=msgs)
+            binding.atomo_decode_svd_batch(ctx, groups, 1.0, outs=outs)
+
+        for _ in range(3):
+            step()
+        torch.cuda.synchronize()
+        status, _ = ctx.status()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            step()
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / reps
+        sweeps = ctx.svd_sweeps(len(shapes))
+        ctx.profile_enable(True)
+        prof = {}
+        for _ in range(reps):
+            step()
+            for k, (ms, cnt) in ctx.profile_read().items():
+                if cnt:
+                    prof[k] = prof.get(k, 0.0) + ms
+        ctx.profile_enable(False)
+        thin_bytes = sum(4.0 * m * n * (3 + 2 * sw) for (m, n), sw in zip(shapes, sweeps) if min(m, n) <= 32)
+        thin_ms = prof.get("svd_thin", 0.0) / reps
+        out[name] = {"elements": n_elem, "status": status, "us_per_step": round(dt * 1e6, 1),
+                     "elements_per_s": n_elem / dt,
+                     "gpu_us_by_kernel_class": {k: round(v / reps * 1e3, 1) for k, v in sorted(prof.items())},
+                     "thin_hbm_gbs": round(thin_bytes / (thin_ms * 1e-3) / 1e9, 1) if thin_ms > 0 else None,
+                     "thin_hbm_frac": round(thin_bytes / (thin_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4) if thin_ms > 0 else None}
+    return out
 
 
 def entrywise_leg(ctx, torch, binding, inputs, reps=40, sets=8):

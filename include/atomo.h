@@ -235,6 +235,7 @@ enum {
     ATOMO_K_SVD_PREPARE = 0, ATOMO_K_SVD_GRAM, ATOMO_K_SVD_EIG, ATOMO_K_SVD_UPDATE, ATOMO_K_SVD_REFRESH,
     ATOMO_K_SVD_FINALIZE,
     ATOMO_K_DECODE_SVD, ATOMO_K_EW_HIST, ATOMO_K_EW_SOLVE, ATOMO_K_EW_SAMPLE, ATOMO_K_EW_DECODE,
+    ATOMO_K_SVD_THIN,
     ATOMO_K_COUNT
 };
 

@@ -242,7 +242,7 @@ class Context:
         _check(lib().atomo_reserve(self._h, nbytes), "atomo_reserve")
 
     KERNEL_CLASSES = ("svd_prepare", "svd_gram", "svd_eig", "svd_update", "svd_refresh", "svd_finalize", "decode_svd",
-                      "ew_hist", "ew_solve", "ew_sample", "ew_decode")
+                      "ew_hist", "ew_solve", "ew_sample", "ew_decode", "svd_thin")
 
     def profile_enable(self, enable: bool):
         _check(lib().atomo_profile_enable(self._h, 1 if enable else 0), "atomo_profile_enable")

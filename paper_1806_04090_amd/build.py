@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libatomo.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["capi.hip", "svd.hip", "svd_eig.hip", "entrywise.hip", "decode.hip"]
+SOURCES = ["capi.hip", "svd.hip", "svd_eig.hip", "svd_thin.hip", "entrywise.hip", "decode.hip"]
 
 # packed-fp32 instructions are switched off on purpose: the compiler would otherwise form them
 # from ordinary float code.

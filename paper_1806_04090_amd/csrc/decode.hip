@@ -33,6 +33,7 @@ struct DecOut {
 struct DecWork { int out, tile_r, tile_c, pad; };
 
 constexpr int TR = 64, TC = 256;
+constexpr int TALL_ROWS = 256;     // rows per workgroup for outputs of at most 32 columns
 constexpr int ATOMS_MAX = 512;     // atoms listed in LDS per batch of messages (a message holds at most 512)
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
@@ -44,9 +45,13 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 // chosen by the host) are first listed in LDS, one round trip for all counts and weights, so that the
 // contraction loop only chases pointers it already holds; operands come straight from global memory
 // (every atom's u and v are contiguous rows of its message).  An odd atom count pads with a zero weight.
+// TALL: outputs of at most 32 columns (the [x*y/2, 2*k*k] reshape of Section 6).  The workgroup owns 256 rows,
+// wave w rows 64 w .. 64 w + 63, one 32-column block.
+template <bool TALL>
 __global__ __launch_bounds__(256) void decode_svd_tiles(const DecOut* outs, const DecMsg* msgs, const DecWork* work,
                                                         float scale, int batch)
 {
+    constexpr int NCB = TALL ? 1 : 2;
     __shared__ const float* up[ATOMS_MAX];
     __shared__ const float* vp[ATOMS_MAX];
     __shared__ float wv[ATOMS_MAX];
@@ -56,15 +61,16 @@ __global__ __launch_bounds__(256) void decode_svd_tiles(const DecOut* outs, cons
     const DecOut o = outs[wk.out];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int h = lane >> 5, l32 = lane & 31;
-    const int r0 = wk.tile_r * TR, c0 = wk.tile_c * TC + wave * 64;
+    const int r0 = TALL ? wk.tile_r * TALL_ROWS + wave * 64 : wk.tile_r * TR;
+    const int c0 = TALL ? 0 : wk.tile_c * TC + wave * 64;
     const int row_a = r0 + l32, row_b = r0 + 32 + l32;          // rows this lane feeds as A operands
     const int col_a = c0 + l32, col_b = c0 + 32 + l32;          // columns this lane feeds as B operands
-    const bool ra = row_a < o.rows, rb_ok = row_b < o.rows, ca = col_a < o.cols, cb_ok = col_b < o.cols;
-    floatx16 acc[2][2];
+    const bool ra = row_a < o.rows, rb_ok = row_b < o.rows, ca = col_a < o.cols, cb_ok = !TALL && col_b < o.cols;
+    floatx16 acc[2][NCB];
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb)
+        for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[rb][cb][v] = 0.0f;
 
@@ -106,9 +112,11 @@ __global__ __launch_bounds__(256) void decode_svd_tiles(const DecOut* outs, cons
             for (int t = 0; t < 4; ++t) {
                 if (k0 + 2 * t < total) {                        // uniform: skip pairs past the end
                     acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[t], b0[t], acc[0][0], 0, 0, 0);
-                    acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[t], b1[t], acc[0][1], 0, 0, 0);
                     acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[t], b0[t], acc[1][0], 0, 0, 0);
-                    acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[t], b1[t], acc[1][1], 0, 0, 0);
+                    if (!TALL) {
+                        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[t], b1[t], acc[0][1], 0, 0, 0);
+                        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[t], b1[t], acc[1][1], 0, 0, 0);
+                    }
                 }
             }
         }
@@ -116,7 +124,7 @@ __global__ __launch_bounds__(256) void decode_svd_tiles(const DecOut* outs, cons
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb) {
+        for (int cb = 0; cb < NCB; ++cb) {
             const int col = c0 + cb * 32 + l32;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
@@ -192,16 +200,22 @@ int decode_svd_batch(atomo_ctx* ctx, const atomo_svd_msg* msgs, const int32_t* f
     const int n_msgs = first[n_out];
     std::vector<DecMsg> hm(n_msgs);
     std::vector<DecOut> ho(n_out);
-    std::vector<DecWork> hw;
+    std::vector<DecWork> hw, hw_tall;
     for (int k = 0; k < n_msgs; ++k)
         hm[k] = DecMsg{msgs[k].count, msgs[k].w, msgs[k].U, msgs[k].V, msgs[k].capacity, 0};
     for (int o = 0; o < n_out; ++o) {
         const atomo_svd_msg& m0 = msgs[first[o]];
         ho[o] = DecOut{outs[o], (long long)lds[o], m0.rows, m0.cols, first[o], first[o + 1]};
+        if (m0.cols <= 32 && m0.rows > TR) {
+            for (int a = 0; a < (m0.rows + TALL_ROWS - 1) / TALL_ROWS; ++a) hw_tall.push_back(DecWork{o, a, 0, 0});
+            continue;
+        }
         const int tr = (m0.rows + TR - 1) / TR, tc = (m0.cols + TC - 1) / TC;
         for (int a = 0; a < tr; ++a)
             for (int b = 0; b < tc; ++b) hw.push_back(DecWork{o, a, b, 0});
     }
+    const size_t n_wide = hw.size();
+    hw.insert(hw.end(), hw_tall.begin(), hw_tall.end());
     Carver size_only(nullptr);
     size_only.take<DecMsg>(hm.size());
     size_only.take<DecOut>(ho.size());
@@ -220,7 +234,9 @@ int decode_svd_batch(atomo_ctx* ctx, const atomo_svd_msg* msgs, const int32_t* f
         int max_cap = 1;
         for (int k = 0; k < n_msgs; ++k) max_cap = std::max(max_cap, (int)msgs[k].capacity);
         const int batch = std::max(1, ATOMS_MAX / max_cap);      // messages whose atoms fit the LDS list together
-        decode_svd_tiles<<<(unsigned)hw.size(), 256, 0, stream>>>(d_outs, d_msgs, d_work, scale, batch);
+        if (n_wide > 0) decode_svd_tiles<false><<<(unsigned)n_wide, 256, 0, stream>>>(d_outs, d_msgs, d_work, scale, batch);
+        if (!hw_tall.empty())
+            decode_svd_tiles<true><<<(unsigned)hw_tall.size(), 256, 0, stream>>>(d_outs, d_msgs, d_work + n_wide, scale, batch);
     }
     ATOMO_HIP(ctx, hipGetLastError());
     return ATOMO_OK;

@@ -34,6 +34,7 @@
 // svd_common.h; D = the block rotations of that round).  C alternates between two buffers by tick
 // parity and every pair problem brings its own 64x64 block up to date (svd_eig.hip, step 1).
 #include <cfloat>
+#include <algorithm>
 #include <cmath>
 #include <vector>
 
@@ -81,15 +82,6 @@ __global__ __launch_bounds__(256) void svd_absmax(const SvdMat* mats, const Work
         mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
         if (mx > 0.0f && mx <= FLT_MAX) atomicMax((unsigned int*)&m.state[ST_ABSMAX], __float_as_uint(mx));
     }
-}
-
-// exponent e such that absmax * 2^-e lies in [1, 2); 0 for an all-zero matrix
-__device__ inline int scale_exponent(const SvdMat& m)
-{
-    const unsigned int bits = (unsigned int)m.state[ST_ABSMAX];
-    if (bits == 0u) return 0;
-    const int e = (int)(bits >> 23) - 127;
-    return e < -126 ? -126 : e;
 }
 
 __global__ __launch_bounds__(256) void svd_prepare(const SvdMat* mats, const Work* work)
@@ -527,6 +519,8 @@ __global__ __launch_bounds__(256) void svd_pack(const SvdMat* mats, const Work* 
 struct Plan {
     std::vector<SvdMat> mats;
     std::vector<Work> prep, gram, fullgram, tiles, apply, eig_gs, eig_ds, rowop1, twosided, norms, pack;
+    std::vector<Work> thin_chunks, thin_list;      // thin matrices: (matrix, chunk of positions); (matrix)
+    std::vector<Work> thin_direct, thin_copied;    // the chunks again, split by whether G is used in place
     std::vector<int> gs_periods;     // distinct R of the Gram-space matrices
     int max_R = 1;
     int max_R_ds = 1;                // largest R among the data-space matrices
@@ -536,7 +530,7 @@ struct Plan {
     size_t n_work() const
     {
         return prep.size() + gram.size() + fullgram.size() + tiles.size() + apply.size() + eig_gs.size() + eig_ds.size() +
-               rowop1.size() + twosided.size() + norms.size() + pack.size();
+               rowop1.size() + twosided.size() + norms.size() + pack.size() + 2 * thin_chunks.size() + thin_list.size();
     }
 };
 
@@ -555,6 +549,44 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
         m.transposed = a.rows > a.cols;
         m.r = m.transposed ? a.cols : a.rows;
         m.M = m.transposed ? a.rows : a.cols;
+        m.thin = m.r <= THIN_R;
+        m.stream_id = stream_base + (uint64_t)j;
+        m.G = a.data; m.ldg = a.ld;
+        if (msgs) {
+            const atomo_svd_msg& g = msgs[j];
+            m.count = g.count; m.idx = g.idx; m.w = g.w; m.U = g.U; m.V = g.V;
+            m.capacity = g.capacity < m.r ? g.capacity : m.r;
+        } else {
+            m.count = nullptr; m.idx = nullptr; m.w = nullptr; m.U = nullptr; m.V = nullptr; m.capacity = 1;
+        }
+        m.sigma_out = sigma_out ? sigma_out + atom_off : nullptr;
+        m.p_out = p_out ? p_out + atom_off : nullptr;
+        atom_off += m.r;
+        if (m.thin) {
+            // chunks of 1024 positions, larger only to keep a matrix under 128 chunks
+            const int64_t per = ((int64_t)m.M + 128 * 1024 - 1) / (128 * 1024);
+            m.tchunk = m.M <= 1024 ? (int)align_up(m.M, 256) : (int)(1024 * per);
+            m.nchg = (m.M + m.tchunk - 1) / m.tchunk;
+            m.Mp = m.M; m.ldw = 0; m.nb2 = 0; m.rows_alloc = THIN_R; m.R = 1; m.npairs = 0; m.nchu = 0; m.gs = 0;
+            m.ntiles = 0; m.ldc = 0;
+            m.W0 = nullptr; m.W1 = nullptr; m.CT = nullptr; m.CT2 = nullptr; m.cref = nullptr;
+            m.gram = carve.take<float>((size_t)m.nchg * THIN_R * THIN_R);
+            m.Q = carve.take<float>(2 * THIN_R * THIN_R);
+            m.B = carve.take<float>((size_t)m.M * m.r);
+            m.state = carve.take<int>(ST_WORDS);
+            m.sig_raw = carve.take<float>(THIN_R);
+            m.src_row = carve.take<int>(m.capacity);
+            m.src_inv = carve.take<float>(m.capacity);
+            const bool direct = m.transposed && m.ldg == m.r;
+            m.X = direct ? m.G : m.B;
+            for (int c = 0; c < m.nchg; ++c) {
+                plan.thin_chunks.push_back(Work{j, c, 0, 0});
+                (direct ? plan.thin_direct : plan.thin_copied).push_back(Work{j, c, 0, 0});
+            }
+            plan.thin_list.push_back(Work{j, 0, 0, 0});
+            continue;
+        }
+        m.tchunk = 0; m.B = nullptr; m.X = nullptr;
         m.Mp = (int)align_up(m.M, 64);
         m.ldw = m.Mp + (int)align_up(m.r, 64);
         const int nb = (m.r + BS - 1) / BS;
@@ -577,20 +609,8 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
         m.state = carve.take<int>(ST_WORDS);
         m.sig_raw = carve.take<float>(m.rows_alloc);
         m.cref = m.gs ? carve.take<float>(m.rows_alloc) : nullptr;
-        m.G = a.data; m.ldg = a.ld;
-        if (msgs) {
-            const atomo_svd_msg& g = msgs[j];
-            m.count = g.count; m.idx = g.idx; m.w = g.w; m.U = g.U; m.V = g.V;
-            m.capacity = g.capacity < m.r ? g.capacity : m.r;
-        } else {
-            m.count = nullptr; m.idx = nullptr; m.w = nullptr; m.U = nullptr; m.V = nullptr; m.capacity = 1;
-        }
         m.src_row = carve.take<int>(m.capacity);
         m.src_inv = carve.take<float>(m.capacity);
-        m.sigma_out = sigma_out ? sigma_out + atom_off : nullptr;
-        m.p_out = p_out ? p_out + atom_off : nullptr;
-        atom_off += m.r;
-        m.stream_id = stream_base + (uint64_t)j;
         if (m.R > plan.max_R) plan.max_R = m.R;
         if (!m.gs && m.R > plan.max_R_ds) plan.max_R_ds = m.R;
         for (int b = 0; b < m.nb2; ++b)
@@ -678,6 +698,10 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     const Work* w_twosided = place(plan.twosided);
     const Work* w_norms = place(plan.norms);
     const Work* w_pack = place(plan.pack);
+    const Work* w_thin_chunks = place(plan.thin_chunks);
+    const Work* w_thin_list = place(plan.thin_list);
+    const Work* w_thin_direct = place(plan.thin_direct);
+    const Work* w_thin_copied = place(plan.thin_copied);
 
     rc = upload(ctx, d_mats, plan.mats.data(), plan.mats.size() * sizeof(SvdMat), stream);
     if (rc != ATOMO_OK) return rc;
@@ -688,9 +712,11 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     {
         ProfScope ps(ctx, ATOMO_K_SVD_PREPARE, stream);
         svd_reset<<<(unsigned)((n_mats * ST_WORDS + 255) / 256), 256, 0, stream>>>(d_mats, n_mats);
-        svd_absmax<<<grid(plan.prep), 256, 0, stream>>>(d_mats, w_prep);
-        svd_prepare<<<grid(plan.prep), 256, 0, stream>>>(d_mats, w_prep);
-        svd_norms<<<grid(plan.norms), 256, 0, stream>>>(d_mats, w_norms, 1);
+        if (!plan.prep.empty()) {
+            svd_absmax<<<grid(plan.prep), 256, 0, stream>>>(d_mats, w_prep);
+            svd_prepare<<<grid(plan.prep), 256, 0, stream>>>(d_mats, w_prep);
+            svd_norms<<<grid(plan.norms), 256, 0, stream>>>(d_mats, w_norms, 1);
+        }
     }
     // The data-space matrices iterate on a stream of their own from here to the end (one fork, one join).
     // The Gram-space matrices iterate on the caller's stream, one launch per tick: svd_eig of tick t, which
@@ -698,14 +724,29 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     // two buffers: the update of tick t-1 reads the C of parity t-1 and writes parity t, while svd_eig of tick
     // t forms its own 64x64 block from the C of parity t-1 and the rotations of tick t-1, which are
     // double-buffered by tick parity as well.
-    const bool have_ds = !plan.gram.empty(), have_gs = !plan.twosided.empty();
+    // Thin matrices share that stream when there are Gram-space matrices to overlap with.
+    const bool have_ds = !plan.gram.empty(), have_gs = !plan.twosided.empty(), have_thin = !plan.thin_list.empty();
+    const bool use_side = have_ds || (have_thin && have_gs);
     const int n_two = (int)plan.twosided.size();
-    if (have_ds) {
+    if (use_side) {
         rc = ensure_side_streams(ctx);
         if (rc != ATOMO_OK) return rc;
-        hipStream_t s_ds = ctx->side;
         ATOMO_HIP(ctx, hipEventRecord(ctx->ev_fork, stream));
-        ATOMO_HIP(ctx, hipStreamWaitEvent(s_ds, ctx->ev_fork, 0));
+        ATOMO_HIP(ctx, hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0));
+    }
+    if (have_thin) {
+        hipStream_t s_thin = have_gs ? ctx->side : stream;
+        // one pass over the data does the work of several sweeps of the blocked iteration: a quarter of the limit
+        const int passes = std::max(2, std::min(THIN_PASSES, (max_sweeps + 3) / 4));
+        ProfScope ps(ctx, ATOMO_K_SVD_THIN, s_thin);
+        launch_thin_absmax(d_mats, w_thin_direct, (int)plan.thin_direct.size(), w_thin_copied, (int)plan.thin_copied.size(),
+                           s_thin);
+        for (int pass = 0; pass < passes; ++pass)
+            launch_thin_pass(d_mats, w_thin_chunks, (int)plan.thin_chunks.size(), w_thin_list, (int)plan.thin_list.size(),
+                             pass, passes - 1, stop_cosine, ctx->d_flags, s_thin);
+    }
+    if (have_ds) {
+        hipStream_t s_ds = ctx->side;
         const int ds_ticks = max_sweeps * plan.max_R_ds;
         for (int tick = 0; tick < ds_ticks; ++tick) {
             {
@@ -722,8 +763,8 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
                 svd_rowop<<<grid(plan.rowop1), 256, 0, s_ds>>>(d_mats, w_rowop1, tick, max_sweeps);
             }
         }
-        ATOMO_HIP(ctx, hipEventRecord(ctx->ev_join, s_ds));
     }
+    if (use_side) ATOMO_HIP(ctx, hipEventRecord(ctx->ev_join, ctx->side));
     if (have_gs) {
         const int n_ticks = max_sweeps * plan.max_R + 1;
         for (int tick = 0; tick < n_ticks; ++tick) {
@@ -757,12 +798,13 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
             svd_twosided<<<(unsigned)n_two, 256, 0, stream>>>(d_mats, w_twosided, n_two, n_ticks - 1);
         }
     }
-    if (have_ds) ATOMO_HIP(ctx, hipStreamWaitEvent(stream, ctx->ev_join, 0));
+    if (use_side) ATOMO_HIP(ctx, hipStreamWaitEvent(stream, ctx->ev_join, 0));
     {
         ProfScope ps(ctx, ATOMO_K_SVD_FINALIZE, stream);
-        svd_norms<<<grid(plan.norms), 256, 0, stream>>>(d_mats, w_norms, 0);
+        if (!plan.norms.empty()) svd_norms<<<grid(plan.norms), 256, 0, stream>>>(d_mats, w_norms, 0);
         svd_select<<<(unsigned)n_mats, 256, 0, stream>>>(d_mats, s, (unsigned long long)seed, ctx->d_flags);
-        svd_pack<<<grid(plan.pack), 256, 0, stream>>>(d_mats, w_pack);
+        if (!plan.pack.empty()) svd_pack<<<grid(plan.pack), 256, 0, stream>>>(d_mats, w_pack);
+        if (have_thin) launch_thin_pack(d_mats, w_thin_chunks, (int)plan.thin_chunks.size(), stream);
     }
     ATOMO_HIP(ctx, hipGetLastError());
     return ATOMO_OK;

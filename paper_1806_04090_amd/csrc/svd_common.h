@@ -14,6 +14,8 @@ constexpr int KCU = 256;        // columns per row-update / apply work item (4 w
 constexpr int QSZ = PR * PR;
 constexpr int MAX_R = ALG1_MAX;
 constexpr int GS_MIN_BLOCKS = 16; // matrices with at least this many row blocks iterate in Gram space
+constexpr int THIN_R = 32;        // matrices with at most this many vectors on the shorter side take the thin path (svd_thin.hip)
+constexpr int THIN_PASSES = 8;    // at most this many passes over the data for a thin matrix
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
@@ -85,6 +87,11 @@ struct SvdMat {
     unsigned long long stream_id;
     int* src_row;            // [capacity]
     float* src_inv;          // [capacity]
+    // thin matrices (r <= THIN_R): Q = [V | rotation of the next pass], 32 x 32 each; gram = [nchg][32 x 32]
+    int thin;
+    int tchunk;              // positions per work item (a multiple of 256)
+    float* B;                // M x r, position-major: the rotated data
+    const float* X;          // the data before the first rotation, position-major with row stride r: G itself, or its copy in B
 };
 
 struct Work { int mat, a, b, c; };
@@ -106,6 +113,15 @@ __device__ inline void pair_blocks(int nb2, int round, int k, int& bi, int& bj)
     else { a = (round + k) % n1; b = (round - k + n1) % n1; }
     bi = a < b ? a : b;
     bj = a < b ? b : a;
+}
+
+// exponent e such that absmax * 2^-e lies in [1, 2); 0 for an all-zero matrix
+__device__ inline int scale_exponent(const SvdMat& m)
+{
+    const unsigned int bits = (unsigned int)m.state[ST_ABSMAX];
+    if (bits == 0u) return 0;
+    const int e = (int)(bits >> 23) - 127;
+    return e < -126 ? -126 : e;
 }
 
 // Data-space matrices: true if work for `tick` should be skipped (finished earlier, or past the sweep limit).
@@ -223,6 +239,16 @@ __device__ inline void twosided_tile(const SvdMat* mats, const Work* work, int i
 void launch_svd_eig(const SvdMat* d_mats, const Work* d_work, int n_items, const Work* d_two_work, int n_two, int tick,
                     int max_sweeps, float stop_cosine, int max_inner, float inner_reduction, int full_period,
                     int fresh_only, int* d_flags, hipStream_t stream);
+
+// Thin matrices (defined in svd_thin.hip).  d_chunks lists (matrix, chunk of positions), d_list the thin matrices.
+// d_direct: chunks of the matrices used in place (largest |entry| only); d_copied: chunks of those copied into B first.
+void launch_thin_absmax(const SvdMat* d_mats, const Work* d_direct, int n_direct, const Work* d_copied, int n_copied,
+                        hipStream_t stream);
+// One pass over the data (rotate, Gram matrix) followed by the r x r problem of every thin matrix.
+void launch_thin_pass(const SvdMat* d_mats, const Work* d_chunks, int n_chunks, const Work* d_list, int n_list, int pass,
+                      int last_pass, float stop_cosine, int* d_flags, hipStream_t stream);
+// After svd_select: the kept atoms' vectors into the message.
+void launch_thin_pack(const SvdMat* d_mats, const Work* d_chunks, int n_chunks, hipStream_t stream);
 
 }  // namespace svd
 }  // namespace atomo

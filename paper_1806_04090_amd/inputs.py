@@ -25,6 +25,30 @@ RESNET18_SHAPES = (
 RESNET18_ELEMENTS = sum(m * n for m, n in RESNET18_SHAPES)        # 11,164,352
 RESNET18_PARAMETERS = 11_173_962                                   # with the 9,610 BN / bias scalars
 
+# Convolution weights [out, in, k, k] of the two CIFAR-10 models of Table "datasets", in network order, and their
+# fully connected layers [out, in].
+RESNET18_CONVS = (
+    [(64, 3, 3)] + [(64, 64, 3)] * 4
+    + [(128, 64, 3)] + [(128, 128, 3)] * 3 + [(128, 64, 1)]
+    + [(256, 128, 3)] + [(256, 256, 3)] * 3 + [(256, 128, 1)]
+    + [(512, 256, 3)] + [(512, 512, 3)] * 3 + [(512, 256, 1)]
+)
+RESNET18_FCS = [(10, 512)]
+VGG11BN_CONVS = [(64, 3, 3), (128, 64, 3), (256, 128, 3), (256, 256, 3),
+                 (512, 256, 3), (512, 512, 3), (512, 512, 3), (512, 512, 3)]
+VGG11BN_FCS = [(512, 512), (512, 512), (10, 512)]
+VGG11BN_PARAMETERS = 9_756_426                                     # with the BN / bias scalars
+
+
+def section6_reshape(convs, fcs):
+    """Matrix shapes under the reshape of Section 6: a conv gradient [x, y, k, k] is viewed as
+    [x*y/2, 2*k*k] (same memory, no copy); fully connected layers stay [out, in]."""
+    return [(x * y // 2, 2 * k * k) for (x, y, k) in convs] + list(fcs)
+
+
+RESNET18_SECTION6_SHAPES = section6_reshape(RESNET18_CONVS, RESNET18_FCS)
+VGG11BN_SECTION6_SHAPES = section6_reshape(VGG11BN_CONVS, VGG11BN_FCS)
+
 
 def _orthonormal(rng: np.random.Generator, dim: int, k: int) -> np.ndarray:
     """dim x k matrix with orthonormal columns: Q factor of a Gaussian matrix."""
@@ -51,6 +75,14 @@ def single_conv_layer(seed: int = 0) -> np.ndarray:
 
 def resnet18_layer_set(seed: int = 0, shapes=RESNET18_SHAPES):
     """The 21 ResNet-18 matrices: rank-8 geometric signal 0.5^k (k = 0..7) plus N(0, 1e-3^2)."""
+    rng = np.random.default_rng(seed)
+    sig = 0.5 ** np.arange(8)
+    return [low_rank_plus_noise(rng, m, n, sig, 1e-3) for (m, n) in shapes]
+
+
+def section6_layer_set(seed: int = 0, shapes=RESNET18_SECTION6_SHAPES):
+    """One matrix per layer in the Section 6 reshape: rank-min(8, cols, rows) geometric signal 0.5^k plus
+    N(0, 1e-3^2), generated directly in the reshaped view."""
     rng = np.random.default_rng(seed)
     sig = 0.5 ** np.arange(8)
     return [low_rank_plus_noise(rng, m, n, sig, 1e-3) for (m, n) in shapes]
