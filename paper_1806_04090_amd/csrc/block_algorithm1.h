@@ -57,8 +57,9 @@ __device__ inline int block_algorithm1(const float* key, int n, double s, Alg1Sc
     sc.part[tid] = mine;
     if (tid == 0) { sc.first_true = n; sc.tail_ns = 0.0; }
     __syncthreads();
+    const int owners = per > 0 ? (n + per - 1) / per : 0;         // threads whose slice is not empty
     double after = 0.0;
-    for (int t = 255; t > tid; --t) after += sc.part[t];
+    for (int t = owners - 1; t > tid; --t) after += sc.part[t];
     {
         double tail = after + mine;
         int found = n;

@@ -475,8 +475,9 @@ __global__ __launch_bounds__(256) void svd_select(const SvdMat* mats, double s, 
     }
     ipart[tid] = kept_local;
     __syncthreads();
+    const int owners = (r + per - 1) / per;                        // threads whose slice is not empty
     int pos = 0;
-    for (int t = 0; t < tid; ++t) pos += ipart[t];
+    for (int t = 0; t < min(tid, owners); ++t) pos += ipart[t];
     if (tid == 255) {
         const int total = pos + kept_local;
         *m.count = total;

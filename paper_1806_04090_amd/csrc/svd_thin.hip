@@ -113,7 +113,23 @@ __global__ __launch_bounds__(TNT) void thin_absmax(const SvdMat* mats, const Wor
     const long long lo = (long long)wk.a * m.tchunk * m.r;
     const long long hi = min((long long)m.M, (long long)(wk.a + 1) * m.tchunk) * m.r;
     float mx = 0.0f;
-    for (long long e = lo + threadIdx.x; e < hi; e += TNT) mx = fmaxf(mx, fabsf(m.X[e]));
+    const float* x = m.X + lo;
+    const long long len = hi - lo;
+    long long done = 0;
+    if ((((size_t)x) & 15) == 0) {                                  // 16-byte loads, four in flight per thread
+        const float4* x4 = (const float4*)x;
+        const long long n4 = len / 4;
+        for (long long q = threadIdx.x; q < n4; q += 4 * TNT) {
+            float4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = q + u * TNT < n4 ? x4[q + u * TNT] : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                mx = fmaxf(fmaxf(mx, fmaxf(fabsf(v[u].x), fabsf(v[u].y))), fmaxf(fabsf(v[u].z), fabsf(v[u].w)));
+        }
+        done = n4 * 4;
+    }
+    for (long long e = done + threadIdx.x; e < len; e += TNT) mx = fmaxf(mx, fabsf(x[e]));
     publish_absmax(m, mx, red);
 }
 

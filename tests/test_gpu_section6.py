@@ -16,18 +16,6 @@ from test_gpu_svd import encode, full_parity
 pytestmark = pytest.mark.gpu
 
 
-def test_reshape_is_a_view_of_the_same_memory():
-    # [x, y, k, k] -> [x*y/2, 2*k*k] keeps the element order: row-major memory is unchanged
-    for convs, fcs, shapes in ((inputs.RESNET18_CONVS, inputs.RESNET18_FCS, inputs.RESNET18_SECTION6_SHAPES),
-                               (inputs.VGG11BN_CONVS, inputs.VGG11BN_FCS, inputs.VGG11BN_SECTION6_SHAPES)):
-        for (x, y, k), (rows, cols) in zip(convs, shapes):
-            assert rows * cols == x * y * k * k and cols == 2 * k * k
-            t = torch.arange(x * y * k * k).reshape(x, y, k, k)
-            assert t.view(rows, cols).data_ptr() == t.data_ptr()
-        assert list(shapes[len(convs):]) == list(fcs)
-    assert sum(m * n for m, n in inputs.RESNET18_SECTION6_SHAPES) == inputs.RESNET18_ELEMENTS
-
-
 @pytest.mark.parametrize("shape", [(96, 18), (2048, 18), (4096, 2), (1024 + 37, 18), (3000, 32), (5000, 31), (700, 7),
                                    (18, 2048), (2, 4096), (27, 1500), (257, 1), (1, 257)])
 def test_thin_shapes_against_the_oracle(shape):
