@@ -106,7 +106,11 @@ typedef struct atomo_svd_options {
                                      /* 27.  Every sweep allowed costs launches even when unused (they return at   */
                                      /* once, about 0.08 ms per sweep for 512-row matrices).  Hitting the limit    */
                                      /* reports ATOMO_ENOCONV; the message is then still an exact decomposition of */
-                                     /* the input, with atoms that are not yet orthogonal to the tolerance         */
+                                     /* the input, with atoms that are not yet orthogonal to the tolerance.        */
+                                     /* Matrices with min(rows, cols) <= 32 (the [x*y/2, 2*k*k] reshape of Section */
+                                     /* 6) solve their whole r x r problem per pass over the data: they get        */
+                                     /* max(2, min(8, ceil(max_sweeps / 4))) passes (two are the rule), and their  */
+                                     /* atomo_svd_sweeps count is the number of passes that rotated                */
     float   stop_cosine;             /* default 1e-4 (0 = default): stop after the first sweep whose largest */
                                      /* |<a_i,a_j>| / (|a_i||a_j|), measured before rotating, is below */
     int32_t max_inner_sweeps;        /* default 1 (0 = default): most Jacobi sweeps per 64x64 block-pair problem */
