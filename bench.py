@@ -264,6 +264,11 @@ def aggregate_decode_leg(ctx, torch, binding, inputs, shapes, s, seed, workers=1
     for _ in range(reps):
         binding.atomo_decode_svd_batch(ctx, groups, 1.0 / workers, outs=outs)
     gpu_ms = ctx.profile_read()["decode_svd"][0] / reps
+    # the whole parameter-server step in the same launch: params += (-gamma / P) * sum of the messages
+    params = [torch.zeros(m, n, dtype=torch.float32, device="cuda") for m, n in shapes]
+    for _ in range(reps):
+        binding.atomo_apply_svd_batch(ctx, groups, -0.01 / workers, params)
+    apply_ms = ctx.profile_read()["decode_svd"][0] / reps
     ctx.profile_enable(False)
     flops = sum(2.0 * m * n * k for (m, n), k in zip(shapes, atoms))
     nbytes = 4.0 * sum(m * n for m, n in shapes)
@@ -272,7 +277,9 @@ def aggregate_decode_leg(ctx, torch, binding, inputs, shapes, s, seed, workers=1
             "mfma_tflops": round(flops / (gpu_ms * 1e-3) / 1e12, 3),
             "mfma_frac": round(flops / (gpu_ms * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS, 5),
             "hbm_write_gbs": round(nbytes / (gpu_ms * 1e-3) / 1e9, 1),
-            "hbm_frac": round(nbytes / (gpu_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+            "hbm_frac": round(nbytes / (gpu_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+            "fused_sgd_update_gpu_us_per_call": round(apply_ms * 1e3, 2),
+            "fused_sgd_update_hbm_gbs": round(2.0 * nbytes / (apply_ms * 1e-3) / 1e9, 1)}
 
 
 def section6_leg(ctx, torch, binding, inputs, s, seed, reps=20):

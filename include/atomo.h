@@ -75,8 +75,11 @@ typedef struct atomo_svd_msg {
     int32_t capacity;                /* room for this many kept atoms, 1 <= capacity                 */
     int32_t* count;                  /* [1]  number of atoms kept (may exceed capacity: see status)  */
     int32_t* idx;                    /* [capacity] atom indices, ascending                           */
-    float*   w;                      /* [capacity] weights sigma_i / p_i                             */
-    float*   U;                      /* [capacity][rows]  U[k*rows + i] = (u of k-th kept atom)_i, unit norm */
+    float*   w;                      /* [capacity] weights sigma_i / p_i; NULL selects the folded form below */
+    float*   U;                      /* [capacity][rows]  U[k*rows + i] = (u of k-th kept atom)_i, unit norm;  */
+                                     /* folded form (w == NULL): (sigma_i / p_i) u, the "weighted singular     */
+                                     /* vectors" of Section 6, rows + cols reals per atom as in the cost        */
+                                     /* s(n+m) of Table "matrix_sparse"                                         */
     float*   V;                      /* [capacity][cols]  V[k*cols + j] = (v of k-th kept atom)_j, unit norm */
 } atomo_svd_msg;
 
@@ -229,6 +232,16 @@ int atomo_decode(atomo_ctx* ctx, int kind, const void* msgs, int n_msgs, float s
  */
 int atomo_decode_svd_batch(atomo_ctx* ctx, const atomo_svd_msg* msgs, const int32_t* first, int n_out,
                            float scale, float* const* outs, const int64_t* lds, void* stream);
+
+/*
+ * The parameter server's step (Section 2: w_{k+1} = w_k - gamma g_hat; Section 6: the PS combines the
+ * workers' messages and updates the model with the average gradient) without materialising the gradient:
+ *     params[o] += alpha * sum over msgs[first[o] .. first[o+1]) of sum_k w_k u_k v_k^T
+ * for each of n_out parameter matrices, in one launch; alpha = -gamma / P for P workers.  Arguments as for
+ * atomo_decode_svd_batch, except that params[o] (device, rows x cols, row stride lds[o]) is read and updated.
+ */
+int atomo_apply_svd_batch(atomo_ctx* ctx, const atomo_svd_msg* msgs, const int32_t* first, int n_out,
+                          float alpha, float* const* params, const int64_t* lds, void* stream);
 
 /* -------- measurement -------------------------------------------------------------------------- */
 

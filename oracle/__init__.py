@@ -135,10 +135,12 @@ def pack_weights(lam, p, mask):
 def decode_svd(messages, m: int, n: int, scale: float = 1.0):
     """Dense m x n float64 sum of the messages' kept rank-1 atoms, times scale.
 
-    Each message is a dict with 'w' (k,), 'U' (m, k), 'V' (n, k)."""
+    Each message is a dict with 'w' (k,), 'U' (m, k), 'V' (n, k); 'w' None marks the folded form, whose U
+    columns are the weighted singular vectors (sigma / p) u (Section 6)."""
     out = np.zeros((m, n))
     for msg in messages:
-        w = np.ascontiguousarray(msg["w"], dtype=np.float64)
+        k = np.asarray(msg["U"]).shape[1] if np.asarray(msg["U"]).ndim == 2 else 0
+        w = np.ones(k) if msg["w"] is None else np.ascontiguousarray(msg["w"], dtype=np.float64)
         k = w.size
         if k == 0:
             continue
@@ -200,6 +202,27 @@ def encode_svd(G, s: float, seed: int, stream: int, sigma_UV=None, p32=None):
     idx, w = pack_weights(sigma, p_for_w, mask)
     return {"sigma": sigma, "p": p, "mask": mask, "idx": idx, "w": w,
             "U": np.asarray(U)[:, idx], "V": np.asarray(V)[:, idx]}
+
+
+def fold_svd_message(msg):
+    """The same message with the weight inside U: columns (sigma / p) u, no separate weights; rows + cols reals
+    per kept atom, the communication cost s(n + m) of Table "matrix_sparse"."""
+    out = dict(msg)
+    out["U"] = np.asarray(msg["U"], dtype=np.float64) * np.asarray(msg["w"], dtype=np.float64)[None, :]
+    out["w"] = None
+    return out
+
+
+def ps_update(params, worker_messages, gamma: float):
+    """The parameter server's step of Section 2, w <- w - gamma * g_hat, with g_hat the average over the P
+    workers of their decoded messages (Section 6).  params: list of m x n arrays, one per layer;
+    worker_messages[l]: the P messages of layer l.  Returns the new float64 parameters."""
+    out = []
+    for w, msgs in zip(params, worker_messages):
+        w = np.asarray(w, dtype=np.float64)
+        g_hat = decode_svd(msgs, w.shape[0], w.shape[1], 1.0 / len(msgs))
+        out.append(w - gamma * g_hat)
+    return out
 
 
 def encode_entrywise(g, s: float, seed: int, stream: int, p32=None):

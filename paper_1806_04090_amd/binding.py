@@ -82,6 +82,7 @@ def lib() -> C.CDLL:
         L.atomo_decode.argtypes = [vp, C.c_int, vp, C.c_int, C.c_float, vp, C.c_int64, vp]
         L.atomo_decode_svd_batch.argtypes = [vp, C.POINTER(atomo_svd_msg), C.POINTER(C.c_int32), C.c_int, C.c_float,
                                              C.POINTER(vp), C.POINTER(C.c_int64), vp]
+        L.atomo_apply_svd_batch.argtypes = L.atomo_decode_svd_batch.argtypes
         L.atomo_svd_sweeps.argtypes = [vp, vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int]
         L.atomo_last_counters.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         L.atomo_profile_enable.argtypes = [vp, C.c_int]
@@ -89,7 +90,7 @@ def lib() -> C.CDLL:
         for name in ("atomo_last_counters", "atomo_svd_sweeps", "atomo_profile_enable", "atomo_profile_read", "atomo_create", "atomo_destroy", "atomo_reserve", "atomo_svd_workspace_bytes",
                      "atomo_entrywise_workspace_bytes", "atomo_status", "atomo_last_hip_error", "atomo_probabilities",
                      "atomo_encode_svd", "atomo_encode_entrywise", "atomo_encode_lq", "atomo_decode",
-                     "atomo_decode_svd_batch"):
+                     "atomo_decode_svd_batch", "atomo_apply_svd_batch"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -125,7 +126,7 @@ class SvdMessage:
     capacity: int
     count: torch.Tensor   # int32 [1]
     idx: torch.Tensor     # int32 [capacity]
-    w: torch.Tensor       # float32 [capacity]
+    w: Optional[torch.Tensor]   # float32 [capacity]; None: folded form, U holds (sigma / p) u
     U: torch.Tensor       # float32 [capacity, rows]
     V: torch.Tensor       # float32 [capacity, cols]
 
@@ -134,13 +135,14 @@ class SvdMessage:
         c = self.__dict__.get("_c")
         if c is None:
             c = atomo_svd_msg(self.rows, self.cols, self.capacity, self.count.data_ptr(), self.idx.data_ptr(),
-                              self.w.data_ptr(), self.U.data_ptr(), self.V.data_ptr())
+                              None if self.w is None else self.w.data_ptr(), self.U.data_ptr(), self.V.data_ptr())
             self.__dict__["_c"] = c
         return c
 
     def to_host(self) -> dict:
         k = min(int(self.count.item()), self.capacity)
-        return {"count": int(self.count.item()), "idx": self.idx[:k].cpu().numpy(), "w": self.w[:k].cpu().numpy(),
+        return {"count": int(self.count.item()), "idx": self.idx[:k].cpu().numpy(),
+                "w": None if self.w is None else self.w[:k].cpu().numpy(),
                 "U": self.U[:k].cpu().numpy().T.copy(), "V": self.V[:k].cpu().numpy().T.copy()}
 
 
@@ -185,11 +187,12 @@ def default_capacity(s: float, n_atoms: int) -> int:
     return int(min(n_atoms, math.ceil(s) + 8 * math.ceil(math.sqrt(s)) + 8))
 
 
-def alloc_svd_message(rows: int, cols: int, capacity: int, device) -> SvdMessage:
+def alloc_svd_message(rows: int, cols: int, capacity: int, device, folded: bool = False) -> SvdMessage:
+    """folded: no weight array; the encoder writes (sigma / p) u into U (rows + cols reals per atom)."""
     return SvdMessage(rows, cols, capacity,
                       torch.zeros(1, dtype=torch.int32, device=device),
                       torch.zeros(capacity, dtype=torch.int32, device=device),
-                      torch.zeros(capacity, dtype=torch.float32, device=device),
+                      None if folded else torch.zeros(capacity, dtype=torch.float32, device=device),
                       torch.zeros(capacity, rows, dtype=torch.float32, device=device),
                       torch.zeros(capacity, cols, dtype=torch.float32, device=device))
 
@@ -365,7 +368,7 @@ def atomo_decode(ctx: Context, msgs, scale: float = 1.0, out: Optional[torch.Ten
     first = msgs[0]
     if isinstance(first, SvdMessage):
         if out is None:
-            out = torch.empty(first.rows, first.cols, dtype=torch.float32, device=first.w.device)
+            out = torch.empty(first.rows, first.cols, dtype=torch.float32, device=first.U.device)
         _f32_cuda(out, "out")
         c_msgs = (atomo_svd_msg * len(msgs))(*[m.c_struct() for m in msgs])
         _check(lib().atomo_decode(ctx._h, ATOMO_KIND_SVD, C.cast(c_msgs, C.c_void_p), len(msgs), float(scale),
@@ -397,7 +400,7 @@ def atomo_decode_svd_batch(ctx: Context, groups: Sequence[Sequence[SvdMessage]],
     for grp in groups:
         first.append(first[-1] + len(grp))
     if outs is None:
-        outs = [torch.empty(grp[0].rows, grp[0].cols, dtype=torch.float32, device=grp[0].w.device) for grp in groups]
+        outs = [torch.empty(grp[0].rows, grp[0].cols, dtype=torch.float32, device=grp[0].U.device) for grp in groups]
     c_msgs = (atomo_svd_msg * len(flat))(*[m.c_struct() for m in flat])
     c_first = (C.c_int32 * len(first))(*first)
     c_outs = (C.c_void_p * len(outs))(*[o.data_ptr() for o in outs])
@@ -405,3 +408,22 @@ def atomo_decode_svd_batch(ctx: Context, groups: Sequence[Sequence[SvdMessage]],
     _check(lib().atomo_decode_svd_batch(ctx._h, c_msgs, c_first, len(outs), float(scale), c_outs, c_lds,
                                         _stream_handle(stream)), "atomo_decode_svd_batch")
     return outs
+
+
+def atomo_apply_svd_batch(ctx: Context, groups: Sequence[Sequence[SvdMessage]], alpha: float,
+                          params: List[torch.Tensor], stream=None) -> List[torch.Tensor]:
+    """params[o] += alpha * (sum of the decoded messages of groups[o]), in place, one launch for the layer set."""
+    flat = [m for grp in groups for m in grp]
+    first = [0]
+    for grp in groups:
+        first.append(first[-1] + len(grp))
+    for p, grp in zip(params, groups):
+        if p.dtype != torch.float32 or tuple(p.shape) != (grp[0].rows, grp[0].cols) or p.stride(1) != 1:
+            raise ValueError("params must be float32 rows x cols tensors with unit column stride")
+    c_msgs = (atomo_svd_msg * len(flat))(*[m.c_struct() for m in flat])
+    c_first = (C.c_int32 * len(first))(*first)
+    c_params = (C.c_void_p * len(params))(*[p.data_ptr() for p in params])
+    c_lds = (C.c_int64 * len(params))(*[p.stride(0) if p.shape[0] > 1 else p.shape[1] for p in params])
+    _check(lib().atomo_apply_svd_batch(ctx._h, c_msgs, c_first, len(params), float(alpha), c_params, c_lds,
+                                       _stream_handle(stream)), "atomo_apply_svd_batch")
+    return params

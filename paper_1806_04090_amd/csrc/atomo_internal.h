@@ -159,8 +159,9 @@ int encode_lq(atomo_ctx* ctx, const float* g, double q, uint64_t seed, uint64_t 
 int probabilities(atomo_ctx* ctx, const float* lambda, const int64_t* offsets, int n_seg, double s, float* p,
                   hipStream_t stream);
 
+// accumulate: outs[o] += ... instead of outs[o] = ...
 int decode_svd_batch(atomo_ctx* ctx, const atomo_svd_msg* msgs, const int32_t* first, int n_out, float scale,
-                     float* const* outs, const int64_t* lds, hipStream_t stream);
+                     float* const* outs, const int64_t* lds, bool accumulate, hipStream_t stream);
 int decode_entrywise(atomo_ctx* ctx, const atomo_ew_msg* msgs, int n_msgs, float scale, float* out,
                      hipStream_t stream);
 int decode_lq(atomo_ctx* ctx, const atomo_lq_msg* msgs, int n_msgs, float scale, float* out, hipStream_t stream);

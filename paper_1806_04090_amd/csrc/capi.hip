@@ -257,7 +257,7 @@ int atomo_encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s
         if (!a.data || a.rows <= 0 || a.cols <= 0 || a.ld < a.cols) return ATOMO_EINVAL;
         if ((a.rows < a.cols ? a.rows : a.cols) > 2048) return ATOMO_EINVAL;
         if (m.rows != a.rows || m.cols != a.cols || m.capacity < 1) return ATOMO_EINVAL;
-        if (!m.count || !m.idx || !m.w || !m.U || !m.V) return ATOMO_EINVAL;
+        if (!m.count || !m.idx || !m.U || !m.V) return ATOMO_EINVAL;         // w may be null: folded form
     }
     if (opt && (opt->max_sweeps < 0 || !(opt->stop_cosine >= 0.0f) || opt->max_inner_sweeps < 0 ||
                 !(opt->inner_reduction >= 0.0f) || opt->full_period < 0))
@@ -289,8 +289,8 @@ int atomo_encode_lq(atomo_ctx* ctx, const float* g, double q, uint64_t seed, uin
     return encode_lq(ctx, g, q, seed, stream_id, msg, p_out, (hipStream_t)stream);
 }
 
-int atomo_decode_svd_batch(atomo_ctx* ctx, const atomo_svd_msg* msgs, const int32_t* first, int n_out, float scale,
-                           float* const* outs, const int64_t* lds, void* stream)
+static int svd_batch(atomo_ctx* ctx, const atomo_svd_msg* msgs, const int32_t* first, int n_out, float scale,
+                     float* const* outs, const int64_t* lds, bool accumulate, void* stream)
 {
     if (!ctx || !first || !outs || !lds || n_out <= 0) return ATOMO_EINVAL;
     if (first[0] != 0) return ATOMO_EINVAL;
@@ -302,12 +302,24 @@ int atomo_decode_svd_batch(atomo_ctx* ctx, const atomo_svd_msg* msgs, const int3
         for (int k = first[o]; k < first[o + 1]; ++k) {
             const atomo_svd_msg& m = msgs[k];
             if (m.rows != m0.rows || m.cols != m0.cols || m.capacity < 1) return ATOMO_EINVAL;
-            if (!m.count || !m.idx || !m.w || !m.U || !m.V) return ATOMO_EINVAL;
+            if (!m.count || !m.idx || !m.U || !m.V) return ATOMO_EINVAL;     // w may be null: folded form
         }
     }
     DeviceGuard guard(ctx);
     if (!guard.ok) return ATOMO_EHIP;
-    return decode_svd_batch(ctx, msgs, first, n_out, scale, outs, lds, (hipStream_t)stream);
+    return decode_svd_batch(ctx, msgs, first, n_out, scale, outs, lds, accumulate, (hipStream_t)stream);
+}
+
+int atomo_decode_svd_batch(atomo_ctx* ctx, const atomo_svd_msg* msgs, const int32_t* first, int n_out, float scale,
+                           float* const* outs, const int64_t* lds, void* stream)
+{
+    return svd_batch(ctx, msgs, first, n_out, scale, outs, lds, false, stream);
+}
+
+int atomo_apply_svd_batch(atomo_ctx* ctx, const atomo_svd_msg* msgs, const int32_t* first, int n_out, float alpha,
+                          float* const* params, const int64_t* lds, void* stream)
+{
+    return svd_batch(ctx, msgs, first, n_out, alpha, params, lds, true, stream);
 }
 
 int atomo_decode(atomo_ctx* ctx, int kind, const void* msgs, int n_msgs, float scale, float* out, int64_t ld,

@@ -4,6 +4,8 @@
 // Each workgroup owns a 64 x 256 tile of one output and contracts the atoms of every message summed into
 // it on the matrix cores.  Few atoms (one worker, budget 3): bound by the HBM write of the tile.  Many
 // (the average over 16 workers, rank ~ 48): near the ridge between the two.
+// The same kernel adds the update to what `out` holds instead of overwriting it (the parameter server's step,
+// params += alpha * average gradient), and takes messages in the folded form (weight inside U).
 // Entry-wise messages: zero fill, then scatter (atomic add when several messages overlap).
 #include <algorithm>
 #include <vector>
@@ -47,7 +49,7 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 // (every atom's u and v are contiguous rows of its message).  An odd atom count pads with a zero weight.
 // TALL: outputs of at most 32 columns (the [x*y/2, 2*k*k] reshape of Section 6).  The workgroup owns 256 rows,
 // wave w rows 64 w .. 64 w + 63, one 32-column block.
-template <bool TALL>
+template <bool TALL, bool ACCUMULATE>
 __global__ __launch_bounds__(256) void decode_svd_tiles(const DecOut* outs, const DecMsg* msgs, const DecWork* work,
                                                         float scale, int batch)
 {
@@ -87,7 +89,7 @@ __global__ __launch_bounds__(256) void decode_svd_tiles(const DecOut* outs, cons
             for (int k = 0; k < kept && at + k < ATOMS_MAX; ++k) {
                 up[at + k] = m.U + (size_t)k * o.rows;
                 vp[at + k] = m.V + (size_t)k * o.cols;
-                wv[at + k] = scale * m.w[k];
+                wv[at + k] = m.w ? scale * m.w[k] : scale;         // folded messages carry the weight in U
             }
             if (q == nm - 1) total_sh = min(at + kept, ATOMS_MAX);
         }
@@ -129,7 +131,10 @@ __global__ __launch_bounds__(256) void decode_svd_tiles(const DecOut* outs, cons
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int row = r0 + rb * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
-                if (row < o.rows && col < o.cols) o.out[(size_t)row * o.ld + col] = acc[rb][cb][v];
+                if (row < o.rows && col < o.cols) {
+                    float* dst = o.out + (size_t)row * o.ld + col;
+                    *dst = ACCUMULATE ? *dst + acc[rb][cb][v] : acc[rb][cb][v];
+                }
             }
         }
 }
@@ -195,7 +200,7 @@ __global__ __launch_bounds__(256) void scatter_lq(const LqDecMsg* msgs, int n_ms
 }  // namespace
 
 int decode_svd_batch(atomo_ctx* ctx, const atomo_svd_msg* msgs, const int32_t* first, int n_out, float scale,
-                     float* const* outs, const int64_t* lds, hipStream_t stream)
+                     float* const* outs, const int64_t* lds, bool accumulate, hipStream_t stream)
 {
     const int n_msgs = first[n_out];
     std::vector<DecMsg> hm(n_msgs);
@@ -234,9 +239,15 @@ int decode_svd_batch(atomo_ctx* ctx, const atomo_svd_msg* msgs, const int32_t* f
         int max_cap = 1;
         for (int k = 0; k < n_msgs; ++k) max_cap = std::max(max_cap, (int)msgs[k].capacity);
         const int batch = std::max(1, ATOMS_MAX / max_cap);      // messages whose atoms fit the LDS list together
-        if (n_wide > 0) decode_svd_tiles<false><<<(unsigned)n_wide, 256, 0, stream>>>(d_outs, d_msgs, d_work, scale, batch);
-        if (!hw_tall.empty())
-            decode_svd_tiles<true><<<(unsigned)hw_tall.size(), 256, 0, stream>>>(d_outs, d_msgs, d_work + n_wide, scale, batch);
+        const unsigned n_tall = (unsigned)hw_tall.size();
+        if (n_wide > 0) {
+            if (accumulate) decode_svd_tiles<false, true><<<(unsigned)n_wide, 256, 0, stream>>>(d_outs, d_msgs, d_work, scale, batch);
+            else decode_svd_tiles<false, false><<<(unsigned)n_wide, 256, 0, stream>>>(d_outs, d_msgs, d_work, scale, batch);
+        }
+        if (n_tall > 0) {
+            if (accumulate) decode_svd_tiles<true, true><<<n_tall, 256, 0, stream>>>(d_outs, d_msgs, d_work + n_wide, scale, batch);
+            else decode_svd_tiles<true, false><<<n_tall, 256, 0, stream>>>(d_outs, d_msgs, d_work + n_wide, scale, batch);
+        }
     }
     ATOMO_HIP(ctx, hipGetLastError());
     return ATOMO_OK;

@@ -490,10 +490,13 @@ __global__ __launch_bounds__(256) void svd_select(const SvdMat* mats, double s, 
         const uint32_t word = (i & 3) == 0 ? rnd.x : (i & 3) == 1 ? rnd.y : (i & 3) == 2 ? rnd.z : rnd.w;
         if (u01(word) < p) {
             if (pos < m.capacity) {
+                const float weight = key[i] / p;
+                const float fold = m.w ? 1.0f : weight;         // folded message: the weight goes into U
                 m.idx[pos] = i;
-                m.w[pos] = key[i] / p;
+                if (m.w) m.w[pos] = weight;
                 m.src_row[pos] = src[i];
-                m.src_inv[pos] = 1.0f / (key[i] * unscale);
+                m.src_inv[pos] = (m.transposed ? fold : 1.0f) / (key[i] * unscale);   // U is the long side iff rows > cols
+                m.src_fold[pos] = m.transposed ? 1.0f : fold;
             }
             ++pos;
         }
@@ -514,7 +517,8 @@ __global__ __launch_bounds__(256) void svd_pack(const SvdMat* mats, const Work* 
     float* long_out = m.transposed ? m.U + (size_t)slot * m.rows : m.V + (size_t)slot * m.cols;
     float* short_out = m.transposed ? m.V + (size_t)slot * m.cols : m.U + (size_t)slot * m.rows;
     for (int c = threadIdx.x; c < m.M; c += 256) long_out[c] = a[c] * inv;
-    for (int c = threadIdx.x; c < m.r; c += 256) short_out[c] = a[m.Mp + c];
+    const float fold = m.src_fold[slot];
+    for (int c = threadIdx.x; c < m.r; c += 256) short_out[c] = a[m.Mp + c] * fold;
 }
 
 struct Plan {
@@ -578,6 +582,7 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
             m.sig_raw = carve.take<float>(THIN_R);
             m.src_row = carve.take<int>(m.capacity);
             m.src_inv = carve.take<float>(m.capacity);
+            m.src_fold = carve.take<float>(m.capacity);
             const bool direct = m.transposed && m.ldg == m.r;
             m.X = direct ? m.G : m.B;
             for (int c = 0; c < m.nchg; ++c) {
@@ -612,6 +617,7 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
         m.cref = m.gs ? carve.take<float>(m.rows_alloc) : nullptr;
         m.src_row = carve.take<int>(m.capacity);
         m.src_inv = carve.take<float>(m.capacity);
+        m.src_fold = carve.take<float>(m.capacity);
         if (m.R > plan.max_R) plan.max_R = m.R;
         if (!m.gs && m.R > plan.max_R_ds) plan.max_R_ds = m.R;
         for (int b = 0; b < m.nb2; ++b)

@@ -86,7 +86,9 @@ struct SvdMat {
     float* p_out;            // may be null
     unsigned long long stream_id;
     int* src_row;            // [capacity]
-    float* src_inv;          // [capacity]
+    float* src_inv;          // [capacity] what the long vector of the kept atom is multiplied by: 1 / its norm
+    float* src_fold;         // [capacity] what the short vector is multiplied by: 1
+                             //   (a folded message, w == null, has the weight sigma / p in the factor of its U side)
     // thin matrices (r <= THIN_R): Q = [V | rotation of the next pass], 32 x 32 each; gram = [nchg][32 x 32]
     int thin;
     int tchunk;              // positions per work item (a multiple of 256)

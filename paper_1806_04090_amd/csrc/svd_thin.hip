@@ -413,7 +413,7 @@ __global__ __launch_bounds__(TNT) void thin_pack(const SvdMat* mats, const Work*
 {
     __shared__ float xs_all[TWAVES][THIN_R * XLD];
     __shared__ int col_of[THIN_R];
-    __shared__ float inv_of[THIN_R];
+    __shared__ float inv_of[THIN_R], fold_of[THIN_R];
     const Work wk = work[blockIdx.x];
     const SvdMat m = mats[wk.mat];
     const int kept = min(*m.count, m.capacity);
@@ -426,6 +426,7 @@ __global__ __launch_bounds__(TNT) void thin_pack(const SvdMat* mats, const Work*
     if (tid < kept) {
         col_of[tid] = m.src_row[tid];
         inv_of[tid] = m.src_inv[tid];
+        fold_of[tid] = m.src_fold[tid];
     }
     float* const mu = m.U;
     float* const mv = m.V;
@@ -448,7 +449,7 @@ __global__ __launch_bounds__(TNT) void thin_pack(const SvdMat* mats, const Work*
         __syncthreads();
         for (int e = tid; e < kept * r; e += TNT) {
             const int slot = e / r, c = e % r;
-            short_out[(size_t)slot * r + c] = m.Q[c * THIN_R + col_of[slot]];
+            short_out[(size_t)slot * r + c] = m.Q[c * THIN_R + col_of[slot]] * fold_of[slot];
         }
     }
 }

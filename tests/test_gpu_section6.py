@@ -23,7 +23,7 @@ def test_thin_shapes_against_the_oracle(shape):
     G = inputs.low_rank_plus_noise(rng, shape[0], shape[1], [1.0, 0.5, 0.25, 0.1], 0.01)
     r = min(shape)
     msgs, per, status, sweeps = encode([G], 3.0, 5, stream_base=9, capacity=r)
-    assert status == 0 and sweeps <= 3
+    assert status == 0 and ctx().svd_sweeps(1)[0] <= 3
     h = full_parity(G, 3.0, 5, 9, msgs[0], *per[0])
     out = binding.atomo_decode(ctx(), msgs).cpu().numpy()
     want = oracle.decode_svd([h], *shape)

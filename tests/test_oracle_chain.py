@@ -122,3 +122,53 @@ def test_same_seed_same_message_and_ascending_indices():
     c = oracle.encode_entrywise(g, 200.0, seed=0, stream=1)
     assert not np.array_equal(a["idx"], c["idx"])
     assert abs(a["idx"].size - 200) < 6 * np.sqrt(200)
+
+
+def test_folded_message_decodes_to_the_same_matrix_and_costs_s_times_n_plus_m():
+    # Table "matrix_sparse": the SVD sparsification communicates s(n + m) reals in expectation
+    G = inputs.single_conv_layer(0).astype(np.float64)
+    msg = oracle.encode_svd(G, 2.0, 0, 0)
+    folded = oracle.fold_svd_message(msg)
+    assert folded["w"] is None
+    np.testing.assert_allclose(oracle.decode_svd([folded], *G.shape), oracle.decode_svd([msg], *G.shape), atol=1e-14)
+    np.testing.assert_allclose(np.linalg.norm(folded["U"], axis=0), msg["w"], rtol=1e-12)
+    reals = folded["U"].size + folded["V"].size
+    assert reals == msg["idx"].size * (G.shape[0] + G.shape[1])
+    assert abs(msg["p"].sum() - 2.0) < 1e-12                      # so E[reals] = s (n + m)
+
+
+def test_ps_update_with_full_budget_is_plain_minibatch_sgd():
+    # s >= rank: every atom is kept with p = 1 (KKT appendix), each message decodes to its gradient, and the
+    # step of Section 2 becomes w - gamma * mean of the workers' gradients
+    rng = np.random.default_rng(3)
+    shapes = [(12, 20), (30, 7)]
+    P, gamma = 4, 0.1
+    params = [rng.standard_normal(sh) for sh in shapes]
+    grads = [[rng.standard_normal(sh) for _ in range(P)] for sh in shapes]
+    msgs = [[oracle.encode_svd(g, float(min(sh)), 5, 100 * l + k) for k, g in enumerate(gl)]
+            for l, (sh, gl) in enumerate(zip(shapes, grads))]
+    new = oracle.ps_update(params, msgs, gamma)
+    for w, gl, got in zip(params, grads, new):
+        np.testing.assert_allclose(got, w - gamma * np.mean(gl, axis=0), atol=1e-12)
+    # folded messages give the same step
+    folded = [[oracle.fold_svd_message(m) for m in ml] for ml in msgs]
+    for a, b in zip(oracle.ps_update(params, folded, gamma), new):
+        np.testing.assert_allclose(a, b, atol=1e-13)
+
+
+def test_ps_update_is_unbiased_in_expectation():
+    # E[g_hat] = g (unbiasedness, Section 3): averaged over many seeds the sparsified step approaches the dense one
+    rng = np.random.default_rng(8)
+    G = inputs.low_rank_plus_noise(rng, 16, 24, [1.0, 0.5, 0.25], 0.05).astype(np.float64)
+    w0 = rng.standard_normal(G.shape)
+    svd_parts = oracle.svd(G)
+    trials = 4000
+    acc = np.zeros_like(G)
+    for t in range(trials):
+        msg = oracle.encode_svd(G, 2.0, t, 0, sigma_UV=svd_parts)
+        acc += oracle.ps_update([w0], [[msg]], 0.5)[0]
+    mean_step = acc / trials
+    # standard error of the mean of the step: gamma * sqrt(E|g_hat - g|^2 / trials), bounded by the variance term
+    sig, p = svd_parts[0], oracle.probabilities(svd_parts[0], 2.0)
+    var = np.sum(sig ** 2 * (1.0 / np.maximum(p, 1e-300) - 1.0) * (p > 0))
+    assert np.linalg.norm(mean_step - (w0 - 0.5 * G)) <= 0.5 * 4.0 * np.sqrt(var / trials)
