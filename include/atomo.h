@@ -184,7 +184,7 @@ int atomo_probabilities(atomo_ctx* ctx, const float* lambda, const int64_t* offs
  *   mats, msgs : HOST arrays of n_mats descriptors; msgs[j].rows/cols must equal mats[j].rows/cols.
  *   sigma_out, p_out : optional device float32, all matrices concatenated, min(rows, cols) values
  *                      each, descending sigma order (atom order).  Pass NULL to skip.
- * Supported shapes: min(rows, cols) <= 2048.
+ * Supported shapes: min(rows, cols) <= 2048, max(rows, cols) <= 2^30.
  */
 int atomo_encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s,
                      uint64_t seed, uint64_t stream_base, const atomo_svd_options* opt /*host, optional*/,

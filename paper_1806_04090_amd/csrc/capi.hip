@@ -256,6 +256,7 @@ int atomo_encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s
         const atomo_svd_msg& m = msgs[j];
         if (!a.data || a.rows <= 0 || a.cols <= 0 || a.ld < a.cols) return ATOMO_EINVAL;
         if ((a.rows < a.cols ? a.rows : a.cols) > 2048) return ATOMO_EINVAL;
+        if ((a.rows > a.cols ? a.rows : a.cols) > (1 << 30)) return ATOMO_EINVAL;   // position indices stay in int32
         if (m.rows != a.rows || m.cols != a.cols || m.capacity < 1) return ATOMO_EINVAL;
         if (!m.count || !m.idx || !m.U || !m.V) return ATOMO_EINVAL;         // w may be null: folded form
     }
