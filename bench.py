@@ -208,6 +208,20 @@ def main():
     entrywise = None if args.no_entrywise else entrywise_leg(ctx, torch, binding, inputs)
     aggregate = None if args.no_entrywise else aggregate_decode_leg(ctx, torch, binding, inputs, shapes, S, SEED)
     section6 = None if args.no_entrywise else section6_leg(ctx, torch, binding, inputs, S, SEED)
+    # What a plain device-to-device copy reaches on this GPU (1 GiB, so nothing is served from a cache): context for
+    # the HBM fractions above, which are all taken against the published 8 TB/s.
+    copy_gbs = None
+    if not args.no_entrywise:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        copy_gbs = round(5 * 2.0 * src.numel() * 4 / (time.perf_counter() - t0) / 1e9, 1)
+        del src, dst
     if args.calibration_copy:
         src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
@@ -232,6 +246,7 @@ def main():
         "entrywise": entrywise,
         "decode_average_16_workers": aggregate,
         "section6_reshape": section6,
+        "plain_copy_read_plus_write_gbs": copy_gbs,
     }
     print(json.dumps(line))
 
