@@ -458,6 +458,16 @@ __global__ __launch_bounds__(256) void svd_select(const SvdMat* mats, double s, 
     }
     __syncthreads();
     block_sort_desc(key, src, P);
+    // Rows at the rounding floor of the fp32 iteration (ZERO_REL) were left as they were: what they hold is residue
+    // of the updates, not atoms of the matrix.  Their singular value is reported as 0 (which is within that floor
+    // of the truth), so p = 0 and they are never sampled.
+    {
+        const float floor = sqrtf(ZERO_REL) * key[0];
+        __syncthreads();
+        for (int i = tid; i < r; i += 256)
+            if (key[i] <= floor) key[i] = 0.0f;
+        __syncthreads();
+    }
     const int ns = block_algorithm1(key, r, s, sc);
     const double tail_ns = sc.tail_ns;
 
