@@ -61,12 +61,19 @@ __device__ inline int block_algorithm1(const float* key, int n, double s, Alg1Sc
     double after = 0.0;
     for (int t = owners - 1; t > tid; --t) after += sc.part[t];
     {
-        double tail = after + mine;
-        int found = n;
-        for (int i = lo; i < hi; ++i) {
-            if ((double)key[i] * (s - (double)i) <= tail) { found = i; break; }
-            tail -= (double)key[i];
+        // tail sums of the slice, each accumulated from the small end: subtracting the large leading values from
+        // one total instead would cancel (a slice that holds 1e30 and 1 would lose the 1)
+        double suffix[ALG1_MAX / 256];
+        double run = after;
+#pragma unroll
+        for (int k = ALG1_MAX / 256 - 1; k >= 0; --k) {
+            if (lo + k < hi) run += (double)key[lo + k];
+            suffix[k] = run;
         }
+        int found = n;
+#pragma unroll
+        for (int k = ALG1_MAX / 256 - 1; k >= 0; --k)
+            if (lo + k < hi && (double)key[lo + k] * (s - (double)(lo + k)) <= suffix[k]) found = lo + k;
         if (found < n) atomicMin(&sc.first_true, found);
     }
     __syncthreads();

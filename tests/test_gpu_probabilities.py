@@ -76,3 +76,16 @@ def test_quantisation_presets_closed_form():
     for norm in (np.sqrt((a ** 2).sum()), a.max()):
         p = run(g, [0, g.size], a.sum() / norm)
         np.testing.assert_allclose(p, np.minimum(1.0, a / norm), rtol=2e-6, atol=1e-12)
+
+
+@pytest.mark.parametrize("n", [11, 1635, 2048, 2049, 60_000])
+def test_wide_dynamic_range(n):
+    # magnitudes from 1e-30 to 1e30 in one segment: the tail sums behind the forced atoms must keep the small
+    # values (sort path up to 2048 atoms, histogram path above)
+    rng = np.random.default_rng(n)
+    lam = rng.choice(np.array([0.0, 1.0, 1.0000001, 2.0, 1e-30, 1e30], dtype=np.float32), n)
+    lam[:6] = [1e30, 2.0, 1.0, 1e-30, 0.0, 1.0000001]
+    for s in (0.5, float((lam == np.float32(1e30)).sum()) + 2.0, n / 3.0):
+        p = run(lam, [0, n], s)
+        want = oracle.probabilities(lam.astype(np.float64), s)
+        np.testing.assert_allclose(p, want, rtol=1e-6, atol=1e-44)

@@ -179,3 +179,14 @@ def test_equivariance_scaling_and_degenerate_cases():
         pred = [a[i] * (s - i) <= tail[i] for i in range(n) if s - i > 0]
         first = pred.index(True)
         assert all(pred[first:])
+
+
+def test_wide_dynamic_range_closed_form():
+    # three atoms of 1e30 are forced to p = 1 (Algorithm 1); the remaining budget 2 is spread over the others in
+    # proportion to their size (eq. (p_i) of the KKT appendix): tail = 3*2 + 3*1 + 2e-30, so p(2) = 4/9, p(1) = 2/9.
+    # A tail sum formed by subtracting the large values from the total would lose the small ones entirely.
+    lam = np.array([1e30] * 3 + [2.0] * 3 + [1.0] * 3 + [1e-30] * 2)
+    want = np.array([1.0] * 3 + [4 / 9] * 3 + [2 / 9] * 3 + [2e-30 / 9] * 2)
+    np.testing.assert_allclose(oracle.probabilities(lam, 5.0), want, rtol=1e-14)
+    perm = np.random.default_rng(0).permutation(lam.size)
+    np.testing.assert_allclose(oracle.probabilities(lam[perm], 5.0), want[perm], rtol=1e-14)
