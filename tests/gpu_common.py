@@ -29,7 +29,9 @@ def sigma_tolerance_ok(got, want):
 def check_svd_message_against_matrix(G, host_msg, sigma_gpu, p_gpu, tol=1e-4):
     """Properties any correct Spectral-ATOMO message has, whatever basis was picked inside sigma clusters."""
     G = np.asarray(G, dtype=np.float64)
-    idx, w, U, V = host_msg["idx"], host_msg["w"], host_msg["U"], host_msg["V"]
+    idx, w = host_msg["idx"], host_msg["w"]
+    # float64 copies: numpy would otherwise add up the squares of a million float32 entries in float32
+    U, V = np.asarray(host_msg["U"], dtype=np.float64), np.asarray(host_msg["V"], dtype=np.float64)
     s1 = float(sigma_gpu[0])
     assert (np.diff(idx) > 0).all()
     if idx.size == 0:

@@ -111,3 +111,20 @@ def test_thin_pass_count_is_reported_and_limited():
     msgs, per, status, sweeps = encode([G], 3.0, 1, max_sweeps=1)
     assert ctx().svd_sweeps(1)[0] == 1
     assert status in (0, binding.ATOMO_ENOCONV)
+
+
+@pytest.mark.parametrize("shape", [(300_001, 18), (2, 700_000)])
+def test_more_than_131072_positions(shape):
+    # beyond 128 chunks of 1024 positions the chunks grow instead: several blocks per wave and chunk
+    rng = np.random.default_rng(shape[0])
+    G = inputs.low_rank_plus_noise(rng, shape[0], shape[1], [1.0, 0.5], 1e-3)
+    msgs, per, status, sweeps = encode([G], 3.0, 1, capacity=min(shape))
+    assert status == 0
+    ref = np.linalg.svd(G.astype(np.float64), compute_uv=False)
+    assert sigma_tolerance_ok(per[0][0], ref).all()
+    h = msgs[0].to_host()
+    assert np.array_equal(h["idx"], np.flatnonzero(oracle.bernoulli_mask(per[0][1], 1, 0)))
+    check_svd_message_against_matrix(G.astype(np.float64), h, *per[0])
+    out = binding.atomo_decode(ctx(), msgs).cpu().numpy()
+    want = oracle.decode_svd([h], *shape)
+    assert np.linalg.norm(out - want) <= 1e-5 * max(np.linalg.norm(want), 1e-30)
