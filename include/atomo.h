@@ -105,8 +105,9 @@ typedef struct atomo_lq_msg {
 /* Tuning knobs of the Jacobi SVD; pass NULL to the encoder for the defaults. */
 typedef struct atomo_svd_options {
     int32_t max_sweeps;              /* default 16 (0 = default).  Noise-dominated gradients take about 9 sweeps,  */
-                                     /* singular values graded over two decades 13, three decades 16, five decades */
-                                     /* 27.  Every sweep allowed costs launches even when unused (they return at   */
+                                     /* exactly low-rank ones (rank 128 in 600 x 700) 14, singular values graded   */
+                                     /* over two decades 13, three 16, five 17; a matrix half of whose rows are    */
+                                     /* copies of the other half 20.  Every sweep allowed costs launches even when unused (they return at   */
                                      /* once, about 0.08 ms per sweep for 512-row matrices).  Hitting the limit    */
                                      /* reports ATOMO_ENOCONV; the message is then still an exact decomposition of */
                                      /* the input, with atoms that are not yet orthogonal to the tolerance.        */

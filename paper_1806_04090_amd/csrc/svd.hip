@@ -58,7 +58,7 @@ __global__ __launch_bounds__(256) void svd_reset(const SvdMat* mats, int n_mats)
 {
     const int t = blockIdx.x * 256 + threadIdx.x;
     const int j = t / ST_WORDS, w = t % ST_WORDS;
-    if (j < n_mats) mats[j].state[w] = (w == ST_FIRST) ? 1 : 0;
+    if (j < n_mats) mats[j].state[w] = (w == ST_FIRST) ? 1 : (w == ST_DMIN) ? 0x7f800000 : 0;
 }
 
 __global__ __launch_bounds__(256) void svd_absmax(const SvdMat* mats, const Work* work)
@@ -239,7 +239,7 @@ __global__ __launch_bounds__(256) void svd_fullgram_reduce(const SvdMat* mats, c
 __global__ __launch_bounds__(256) void svd_fresh_check(const SvdMat* mats, const Work* work, int tick, int max_sweeps,
                                                        float stop_cosine, float fresh_stop, int* flags)
 {
-    __shared__ float red[8];
+    __shared__ float red[12];
     const Work wk = work[blockIdx.x];
     const SvdMat m = mats[wk.mat];
     if (!refreshing(m)) return;
@@ -247,7 +247,7 @@ __global__ __launch_bounds__(256) void svd_fresh_check(const SvdMat* mats, const
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float z2 = ZERO_REL * __int_as_float(m.state[ST_SCALE]);
     const float* C = c_of_parity(m, tick);
-    float mx = 0.0f, dmax = 0.0f;
+    float mx = 0.0f, dmax = 0.0f, dmin = __int_as_float(0x7f800000);
     for (int e = tid; e < QSZ; e += 256) {
         const int gi = ti * PR + (e >> 6), gj = tj * PR + (e & 63);
         if (gi < gj) {
@@ -255,20 +255,25 @@ __global__ __launch_bounds__(256) void svd_fresh_check(const SvdMat* mats, const
             if (dii > 0.0f && djj > 0.0f)
                 mx = fmaxf(mx, fabsf(C[(size_t)gi * m.ldc + gj]) / fmaxf(sqrtf(dii * djj), z2));
         } else if (gi == gj) {
-            dmax = fmaxf(dmax, C[(size_t)gi * m.ldc + gi]);
+            const float d = C[(size_t)gi * m.ldc + gi];
+            dmax = fmaxf(dmax, d);
+            if (d > z2) dmin = fminf(dmin, d);
         }
     }
     for (int o = 32; o > 0; o >>= 1) {
         mx = fmaxf(mx, __shfl_down(mx, o));
         dmax = fmaxf(dmax, __shfl_down(dmax, o));
+        dmin = fminf(dmin, __shfl_down(dmin, o));
     }
-    if (lane == 0) { red[wave] = mx; red[4 + wave] = dmax; }
+    if (lane == 0) { red[wave] = mx; red[4 + wave] = dmax; red[8 + wave] = dmin; }
     __syncthreads();
     if (tid != 0) return;
     mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
     dmax = fmaxf(fmaxf(red[4], red[5]), fmaxf(red[6], red[7]));
+    dmin = fminf(fminf(red[8], red[9]), fminf(red[10], red[11]));
     atomicMax((unsigned int*)&m.state[ST_FRESH], __float_as_uint(mx));
     atomicMax((unsigned int*)&m.state[ST_SCALE_NEXT], __float_as_uint(dmax));
+    atomicMin((unsigned int*)&m.state[ST_DMIN], __float_as_uint(dmin));
     __threadfence();
     const int arrived = atomicAdd(&m.state[ST_ARRIVE2], 1);
     if (arrived != m.ntiles - 1) return;
@@ -291,6 +296,12 @@ __global__ __launch_bounds__(256) void svd_fresh_check(const SvdMat* mats, const
     m.state[ST_OFFMAX] = 0;
     const unsigned int grown = atomicAdd((unsigned int*)&m.state[ST_SCALE_NEXT], 0u);
     if (grown > (unsigned int)m.state[ST_SCALE]) m.state[ST_SCALE] = (int)grown;
+    // how far apart the rows are, for the resolution of the sweeps that follow (GS_NOISE)
+    const float lo = __uint_as_float(atomicAdd((unsigned int*)&m.state[ST_DMIN], 0u));
+    const float hi = __uint_as_float(grown);
+    const float noise = (lo > 0.0f && lo <= hi) ? fminf(GS_NOISE * sqrtf(hi / lo), GS_NOISE_CAP) : 0.0f;
+    m.state[ST_NOISE] = __float_as_int(noise);
+    m.state[ST_DMIN] = 0x7f800000;
 }
 
 // ------------------------------------------------------------------------------------------------

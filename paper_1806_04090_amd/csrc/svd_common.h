@@ -40,6 +40,8 @@ enum {
     ST_QTICK_ODD = 15,  //                      the same for odd ticks (rotations are double-buffered by tick parity)
     ST_FRESH_AT = 16,   // Gram-space matrices: 1 + the tick whose refresh wrote C from the data (svd_eig reads it as is)
     ST_SAT_OUT = 17,    // Gram-space matrices: 1 if a row sat out of some pair problem in the current sweep (GS_RELIABLE)
+    ST_DMIN = 18,       // Gram-space matrices: smallest squared row norm above the floor seen by the running refresh (float bits)
+    ST_NOISE = 19,      // Gram-space matrices: cosines below this are not resolved by the Gram arithmetic (float bits), see GS_NOISE
     ST_WORDS = 24
 };
 
@@ -57,9 +59,15 @@ constexpr float ZERO_REL = 3.64e-12f;       // (32 * 2^-24)^2
 // off-diagonal terms), and a row whose diagonal entry is below GS_RELIABLE x reference sits out: it is not
 // rotated and does not count in the convergence test until the next refresh measures it on the data again.
 constexpr float GS_RELIABLE = 1.0e-5f;
-// While rows sit out, finishing the sweeps on the others first would be wasted work: the refresh they wait
-// for is asked for as soon as the others are this close to orthogonal, and everything converges together.
-constexpr float GS_EARLY_REFRESH = 3.0e-2f;
+// A sweep in which some row sat out ends with a refresh: the rows that wait are measured again at once (a
+// refresh costs about a tenth of a sweep), so a row can shrink by GS_RELIABLE per sweep, not per several sweeps.
+// Gradients of low rank (a fully connected layer sees at most batch-size atoms) converge in two thirds of the sweeps.
+
+// Between a row of squared norm d_max and one of squared norm d_min the updates of C leave rounding errors of the
+// order of GS_NOISE * sqrt(d_max / d_min) in the cosine.  Sweeping on C below that level is wasted: the refresh is
+// asked for as soon as the largest cosine of a sweep is under it (capped at GS_NOISE_CAP).
+constexpr float GS_NOISE = 1.0e-6f;
+constexpr float GS_NOISE_CAP = 3.0e-2f;
 
 struct SvdMat {
     float* W0;               // rows_alloc x ldw: [A | T]

@@ -224,3 +224,19 @@ def test_unbiased_over_streams():
     assert np.abs(z).max() < 5.0
     counts = np.array([m.to_host()["count"] for m in msgs[:100]])
     assert abs(counts.mean() - 2.0) < 5 * np.sqrt(per[0][1].dot(1 - per[0][1]) / 100)
+
+
+def test_gram_space_low_rank_gradients_with_default_options():
+    # the gradient of a fully connected layer has at most batch-size atoms: rank 128 in 600 x 700, and rank 16 plus
+    # a little noise in 512 x 512, within the default sweep limit
+    rng = np.random.default_rng(5)
+    exact = (rng.standard_normal((600, 128)) @ rng.standard_normal((128, 700))).astype(np.float32)
+    noisy = (rng.standard_normal((512, 16)) @ rng.standard_normal((16, 512)) + 1e-3 * rng.standard_normal((512, 512))).astype(np.float32)
+    msgs, per, status, sweeps = encode([exact, noisy], 4.0, 2, capacity=32)
+    assert status == 0 and sweeps <= 16
+    for G, m, (sig, p) in zip([exact, noisy], msgs, per):
+        ref = np.linalg.svd(G.astype(np.float64), compute_uv=False)
+        floor = 32 * 2.0 ** -24 * ref[0] * 1.01
+        assert (sigma_tolerance_ok(sig, ref) | ((sig <= floor) & (ref <= floor))).all()
+        check_svd_message_against_matrix(G.astype(np.float64), m.to_host(), sig, p)
+    assert (per[0][0][128:] == 0).all() and (per[0][1][128:] == 0).all()
