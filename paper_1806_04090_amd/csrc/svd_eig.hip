@@ -474,7 +474,9 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
                 // Gram space: diagonal to the threshold (or out of sweeps) -> apply the rotations to the
                 // data and look at a fresh Gram matrix at the next tick
                 const bool waiting = atomicAdd(&m.state[ST_SAT_OUT], 0) != 0;
-                const float resolved = fmaxf(stop_cosine, __int_as_float(m.state[ST_NOISE]));
+                // convergence is quadratic: a sweep that started below ten times the threshold has ended well below
+                // it, which the fresh Gram matrix then confirms (or the sweeps go on)
+                const float resolved = fmaxf(10.0f * stop_cosine, __int_as_float(m.state[ST_NOISE]));
                 if (worst < resolved || sweeps >= max_sweeps || waiting)
                     m.state[ST_MODE] = MODE_NEED_REFRESH;
                 m.state[ST_SAT_OUT] = 0;
