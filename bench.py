@@ -247,6 +247,7 @@ def main():
         "decode_average_16_workers": aggregate,
         "section6_reshape": section6,
         "plain_copy_read_plus_write_gbs": copy_gbs,
+        "fp32_mfma_loop_tflops": round(ctx.measure_mfma_fp32(), 1),
     }
     print(json.dumps(line))
 

@@ -265,6 +265,11 @@ int atomo_profile_enable(atomo_ctx* ctx, int enable);
  * each kernel class since the last read. */
 int atomo_profile_read(atomo_ctx* ctx, double* total_ms, int64_t* launches);
 
+/* What a loop of nothing but fp32 matrix-core instructions (v_mfma_f32_32x32x2f32, four independent accumulators
+ * per wave, 16 waves per compute unit) reaches on this GPU, in TFLOP/s: the achievable figure to set beside the
+ * published peak.  Runs two short kernels on `stream` and waits for them (about a millisecond). */
+int atomo_measure_mfma_fp32(atomo_ctx* ctx, double* tflops /*host*/, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -85,12 +85,13 @@ def lib() -> C.CDLL:
         L.atomo_apply_svd_batch.argtypes = L.atomo_decode_svd_batch.argtypes
         L.atomo_svd_sweeps.argtypes = [vp, vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int]
         L.atomo_last_counters.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+        L.atomo_measure_mfma_fp32.argtypes = [vp, C.POINTER(C.c_double), vp]
         L.atomo_profile_enable.argtypes = [vp, C.c_int]
         L.atomo_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         for name in ("atomo_last_counters", "atomo_svd_sweeps", "atomo_profile_enable", "atomo_profile_read", "atomo_create", "atomo_destroy", "atomo_reserve", "atomo_svd_workspace_bytes",
                      "atomo_entrywise_workspace_bytes", "atomo_status", "atomo_last_hip_error", "atomo_probabilities",
                      "atomo_encode_svd", "atomo_encode_entrywise", "atomo_encode_lq", "atomo_decode",
-                     "atomo_decode_svd_batch", "atomo_apply_svd_batch"):
+                     "atomo_decode_svd_batch", "atomo_apply_svd_batch", "atomo_measure_mfma_fp32"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -246,6 +247,12 @@ class Context:
 
     KERNEL_CLASSES = ("svd_prepare", "svd_gram", "svd_eig", "svd_update", "svd_refresh", "svd_finalize", "decode_svd",
                       "ew_hist", "ew_solve", "ew_sample", "ew_decode", "svd_thin")
+
+    def measure_mfma_fp32(self) -> float:
+        """TFLOP/s of a loop of fp32 matrix-core instructions on this GPU (blocks for about a millisecond)."""
+        out = C.c_double(0.0)
+        _check(lib().atomo_measure_mfma_fp32(self._h, C.byref(out), _stream_handle(None)), "atomo_measure_mfma_fp32")
+        return out.value
 
     def profile_enable(self, enable: bool):
         _check(lib().atomo_profile_enable(self._h, 1 if enable else 0), "atomo_profile_enable")

@@ -206,6 +206,61 @@ int atomo_profile_read(atomo_ctx* ctx, double* total_ms, int64_t* launches)
     return ATOMO_OK;
 }
 
+namespace {
+
+typedef float probe_floatx16 __attribute__((ext_vector_type(16)));
+
+// Nothing but fp32 matrix-core instructions: four independent accumulators per wave, `iters` rounds.
+__global__ __launch_bounds__(256) void mfma_fp32_loop(float* sink, int iters)
+{
+    probe_floatx16 acc[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[q][v] = 0.0f;
+    const float a = 1.0f + 1e-3f * (float)(threadIdx.x & 63), b = 1.0f - 1e-3f * (float)(threadIdx.x >> 6);
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc[q] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[q], 0, 0, 0);
+    }
+    float sum = 0.0f;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sum += acc[q][v];
+    if (sum == -1.0f) sink[0] = sum;                             // never true; keeps the loop alive
+}
+
+}  // namespace
+
+int atomo_measure_mfma_fp32(atomo_ctx* ctx, double* tflops, void* stream)
+{
+    if (!ctx || !tflops) return ATOMO_EINVAL;
+    DeviceGuard guard(ctx);
+    if (!guard.ok) return ATOMO_EHIP;
+    hipStream_t st = (hipStream_t)stream;
+    int rc = ensure_workspace(ctx, 256);
+    if (rc != ATOMO_OK) return rc;
+    hipDeviceProp_t prop;
+    ATOMO_HIP(ctx, hipGetDeviceProperties(&prop, ctx->device));
+    const int wgs = prop.multiProcessorCount * 4, iters = 4000;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    ATOMO_HIP(ctx, hipEventCreate(&e0));
+    ATOMO_HIP(ctx, hipEventCreate(&e1));
+    mfma_fp32_loop<<<wgs, 256, 0, st>>>((float*)ctx->ws, 16);     // warm-up
+    ATOMO_HIP(ctx, hipEventRecord(e0, st));
+    mfma_fp32_loop<<<wgs, 256, 0, st>>>((float*)ctx->ws, iters);
+    ATOMO_HIP(ctx, hipEventRecord(e1, st));
+    ATOMO_HIP(ctx, hipEventSynchronize(e1));
+    float ms = 0.0f;
+    ATOMO_HIP(ctx, hipEventElapsedTime(&ms, e0, e1));
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    // waves x rounds x 4 instructions x (32 x 32 x 2 multiply-adds = 4096 flop)
+    *tflops = (double)wgs * 4.0 * (double)iters * 4.0 * 4096.0 / ((double)ms * 1e-3) / 1e12;
+    return ATOMO_OK;
+}
+
 int atomo_last_hip_error(const atomo_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
 
 int atomo_last_counters(const atomo_ctx* ctx, int32_t* pair_visits, int32_t* jacobi_steps)
