@@ -124,6 +124,9 @@ typedef struct atomo_svd_options {
                                      /* pairs in the rounds of an outer sweep whose number is a multiple of this */
                                      /* and only the 1024 pairs that couple its two blocks in the other rounds;  */
                                      /* 1: all 2016 pairs in every round                                         */
+    const uint64_t* stream_ids;      /* HOST array of n_mats Philox stream ids, or NULL for stream_base + j: lets */
+                                     /* one call encode the gradients of several workers (stream = worker, layer) */
+                                     /* and produce the messages that separate calls would                        */
 } atomo_svd_options;
 
 /* -------- context ------------------------------------------------------------------------------ */

@@ -49,7 +49,7 @@ class atomo_lq_msg(C.Structure):
 
 class atomo_svd_options(C.Structure):
     _fields_ = [("max_sweeps", C.c_int32), ("stop_cosine", C.c_float), ("max_inner_sweeps", C.c_int32),
-                ("inner_reduction", C.c_float), ("full_period", C.c_int32)]
+                ("inner_reduction", C.c_float), ("full_period", C.c_int32), ("stream_ids", C.POINTER(C.c_uint64))]
 
 
 _lib = None
@@ -308,8 +308,9 @@ def atomo_encode_svd(ctx: Context, mats: Sequence[torch.Tensor], s: float, seed:
                      msgs: Optional[List[SvdMessage]] = None, sigma_out: Optional[torch.Tensor] = None,
                      p_out: Optional[torch.Tensor] = None, max_sweeps: Optional[int] = None,
                      stop_cosine: Optional[float] = None, max_inner_sweeps: int = 0, inner_reduction: float = 0.0,
-                     full_period: int = 0, stream=None) -> List[SvdMessage]:
-    """Spectral-ATOMO encode of a list of 2-D float32 CUDA tensors (row stride = tensor stride)."""
+                     full_period: int = 0, stream_ids: Optional[Sequence[int]] = None, stream=None) -> List[SvdMessage]:
+    """Spectral-ATOMO encode of a list of 2-D float32 CUDA tensors (row stride = tensor stride).
+    stream_ids: one Philox stream id per matrix instead of stream_base + index."""
     n = len(mats)
     c_mats = (atomo_mat * n)()
     for j, g in enumerate(mats):
@@ -321,10 +322,16 @@ def atomo_encode_svd(ctx: Context, mats: Sequence[torch.Tensor], s: float, seed:
         msgs = [alloc_svd_message(g.shape[0], g.shape[1], default_capacity(s, min(g.shape)), g.device) for g in mats]
     c_msgs = (atomo_svd_msg * n)(*[m.c_struct() for m in msgs])
     opt = None
-    if max_sweeps is not None or stop_cosine is not None or max_inner_sweeps or inner_reduction or full_period:
+    if (max_sweeps is not None or stop_cosine is not None or max_inner_sweeps or inner_reduction or full_period
+            or stream_ids is not None):
+        ids = None
+        if stream_ids is not None:
+            if len(stream_ids) != n:
+                raise ValueError("stream_ids needs one entry per matrix")
+            ids = (C.c_uint64 * n)(*[int(x) & (2 ** 64 - 1) for x in stream_ids])
         opt = C.byref(atomo_svd_options(0 if max_sweeps is None else max_sweeps,
                                         0.0 if stop_cosine is None else stop_cosine,
-                                        max_inner_sweeps, inner_reduction, int(full_period)))
+                                        max_inner_sweeps, inner_reduction, int(full_period), ids))
     _check(lib().atomo_encode_svd(ctx._h, c_mats, n, float(s), int(seed) & (2 ** 64 - 1),
                                   int(stream_base) & (2 ** 64 - 1), opt, c_msgs,
                                   None if sigma_out is None else sigma_out.data_ptr(),

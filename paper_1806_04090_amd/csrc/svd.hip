@@ -562,7 +562,7 @@ struct Plan {
 
 // Lays the workspace out (base == nullptr: sizes only).
 void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, float* sigma_out, float* p_out,
-                uint64_t stream_base, void* base, Plan& plan)
+                uint64_t stream_base, const uint64_t* stream_ids, void* base, Plan& plan)
 {
     Carver carve(base);
     plan.mats.resize(n_mats);
@@ -576,7 +576,7 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
         m.r = m.transposed ? a.cols : a.rows;
         m.M = m.transposed ? a.rows : a.cols;
         m.thin = m.r <= THIN_R;
-        m.stream_id = stream_base + (uint64_t)j;
+        m.stream_id = stream_ids ? stream_ids[j] : stream_base + (uint64_t)j;
         m.G = a.data; m.ldg = a.ld;
         if (msgs) {
             const atomo_svd_msg& g = msgs[j];
@@ -681,7 +681,7 @@ int svd_workspace_bytes(const atomo_mat* mats, int n_mats, size_t* bytes)
         if ((mats[j].rows < mats[j].cols ? mats[j].rows : mats[j].cols) > MAX_R) return ATOMO_EINVAL;
     }
     Plan plan;
-    build_plan(mats, n_mats, nullptr, nullptr, nullptr, 0, nullptr, plan);
+    build_plan(mats, n_mats, nullptr, nullptr, nullptr, 0, nullptr, nullptr, plan);
     *bytes = plan.bytes;
     return ATOMO_OK;
 }
@@ -698,12 +698,13 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     const int full_period = opt && opt->full_period > 0 ? opt->full_period : 8;
 
     Plan sizing;
-    build_plan(mats, n_mats, msgs, sigma_out, p_out, stream_base, nullptr, sizing);
+    const uint64_t* stream_ids = opt ? opt->stream_ids : nullptr;
+    build_plan(mats, n_mats, msgs, sigma_out, p_out, stream_base, stream_ids, nullptr, sizing);
     int rc = ensure_workspace(ctx, sizing.bytes);
     if (rc != ATOMO_OK) return rc;
 
     Plan plan;
-    build_plan(mats, n_mats, msgs, sigma_out, p_out, stream_base, ctx->ws, plan);
+    build_plan(mats, n_mats, msgs, sigma_out, p_out, stream_base, stream_ids, ctx->ws, plan);
     SvdMat* d_mats = plan.d_mats;
     ctx->svd_state.clear();
     for (const SvdMat& m : plan.mats) ctx->svd_state.push_back(m.state);

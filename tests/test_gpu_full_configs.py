@@ -124,6 +124,38 @@ def test_sixteen_worker_aggregate():
     del flat
 
 
+def test_workers_in_one_call_give_the_messages_of_separate_calls():
+    # four workers' gradients (a thin, two blocked and a Gram-space layer each) in one call with per-matrix stream
+    # ids (worker, layer): bit for bit what worker-by-worker calls produce
+    shapes = [(64, 27), (64, 576), (256, 1152), (512, 600)]
+    workers = 4
+    grads = [inputs.resnet18_layer_set(50 + w, shapes=shapes) for w in range(workers)]
+    separate = []
+    for w in range(workers):
+        msgs, per, status, _ = encode_set(grads[w], 3.0, 7, inputs.worker_stream(w, 0))
+        assert status == 0
+        separate.append((msgs, per))
+    mats = [dev(g) for w in range(workers) for g in grads[w]]
+    ids = [inputs.worker_stream(w, j) for w in range(workers) for j in range(len(shapes))]
+    total = workers * sum(min(sh) for sh in shapes)
+    sigma = torch.zeros(total, device="cuda")
+    p = torch.zeros(total, device="cuda")
+    batched = binding.atomo_encode_svd(ctx(), mats, 3.0, 7, 0, sigma_out=sigma, p_out=p, stream_ids=ids)
+    assert ctx().status()[0] == 0
+    sig_h, p_h = sigma.cpu().numpy(), p.cpu().numpy()
+    off = 0
+    for w in range(workers):
+        for j, sh in enumerate(shapes):
+            r = min(sh)
+            a, b = separate[w][0][j].to_host(), batched[w * len(shapes) + j].to_host()
+            assert a["count"] == b["count"] and np.array_equal(a["idx"], b["idx"])
+            for key in ("w", "U", "V"):
+                assert np.array_equal(a[key], b[key]), (w, j, key)
+            assert np.array_equal(separate[w][1][j][0], sig_h[off:off + r])
+            assert np.array_equal(separate[w][1][j][1], p_h[off:off + r])
+            off += r
+
+
 def test_entrywise_full_gradient():
     n = inputs.RESNET18_PARAMETERS
     g = inputs.flat_heavy_tail(seed=0)
