@@ -107,10 +107,11 @@ typedef struct atomo_svd_options {
     int32_t max_sweeps;              /* default 16 (0 = default).  Noise-dominated gradients take about 9 sweeps,  */
                                      /* exactly low-rank ones (rank 128 in 600 x 700) 14, singular values graded   */
                                      /* over two decades 13, three 16, five 17; a matrix half of whose rows are    */
-                                     /* copies of the other half 20.  Every sweep allowed costs launches even when unused (they return at   */
-                                     /* once, about 0.08 ms per sweep for 512-row matrices).  Hitting the limit    */
-                                     /* reports ATOMO_ENOCONV; the message is then still an exact decomposition of */
-                                     /* the input, with atoms that are not yet orthogonal to the tolerance.        */
+                                     /* copies of the other half 20.  Every sweep allowed costs launches even when */
+                                     /* unused (they return at once, about 0.08 ms per sweep for 512-row           */
+                                     /* matrices).  Hitting the limit reports ATOMO_ENOCONV; the message is then   */
+                                     /* still an exact decomposition of the input, with atoms that are not yet     */
+                                     /* orthogonal to the tolerance.                                               */
                                      /* Matrices with min(rows, cols) <= 32 (the [x*y/2, 2*k*k] reshape of Section */
                                      /* 6) solve their whole r x r problem per pass over the data: they get        */
                                      /* max(2, min(8, ceil(max_sweeps / 4))) passes (two are the rule), and their  */
@@ -159,7 +160,8 @@ int atomo_last_counters(const atomo_ctx* ctx, int32_t* pair_visits /*host*/, int
 /* Waits for `stream`, then copies the number of Jacobi sweeps each matrix of the last
  * atomo_encode_svd took into sweeps[0 .. n_mats) (HOST) and, if refreshes is not NULL, how many
  * times the full Gram matrix of the matrix was formed from the data (0 for matrices small enough
- * to iterate directly on the data).  n_mats must match that call. */
+ * to iterate directly on the data).  n_mats must match that call; the counts stay readable until the
+ * next atomo_encode_svd on the context. */
 int atomo_svd_sweeps(atomo_ctx* ctx, void* stream, int32_t* sweeps /*host*/, int32_t* refreshes /*host, optional*/,
                      int n_mats);
 const char* atomo_strerror(int status);

@@ -36,7 +36,11 @@ struct atomo_ctx {
     int last_hip = 0;
     atomo::StageSlot ring[8];
     int ring_next = 0;
-    std::vector<int*> svd_state;         // per matrix of the last SVD encode: device state words
+    // sweep and refresh counts of the last SVD encode, [2 * report_n] on the device, outside the workspace (which the
+    // next call of any kind overwrites)
+    int32_t* d_report = nullptr;
+    size_t report_cap = 0;               // pairs allocated
+    size_t report_n = 0;                 // matrices of the last SVD encode
     // streams and events of the SVD encoder's internal fork/join (created on first use, default priority)
     hipStream_t side = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;

@@ -126,6 +126,7 @@ int atomo_destroy(atomo_ctx* ctx)
         if (e) (void)hipEventDestroy(e);
     if (ctx->side) (void)hipStreamDestroy(ctx->side);
     if (ctx->ws) (void)hipFree(ctx->ws);
+    if (ctx->d_report) (void)hipFree(ctx->d_report);
     if (ctx->d_flags) (void)hipFree(ctx->d_flags);
     if (ctx->h_flags) (void)hipHostFree(ctx->h_flags);
     delete ctx;

@@ -499,6 +499,10 @@ __global__ __launch_bounds__(256) void svd_select(const SvdMat* mats, double s, 
     const int owners = (r + per - 1) / per;                        // threads whose slice is not empty
     int pos = 0;
     for (int t = 0; t < min(tid, owners); ++t) pos += ipart[t];
+    if (tid == 0) {
+        m.report[0] = m.state[ST_SWEEPS];
+        m.report[1] = m.state[ST_REFRESHES];
+    }
     if (tid == 255) {
         const int total = pos + kept_local;
         *m.count = total;
@@ -697,6 +701,14 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     const float fresh_stop = 0.25f * stop_cosine;
     const int full_period = opt && opt->full_period > 0 ? opt->full_period : 8;
 
+    if ((size_t)n_mats > ctx->report_cap) {                      // (hipFree waits for the device)
+        if (ctx->d_report) ATOMO_HIP(ctx, hipFree(ctx->d_report));
+        ctx->d_report = nullptr;
+        ctx->report_cap = 0;
+        const size_t want = align_up((size_t)n_mats, 256);
+        if (hipMalloc((void**)&ctx->d_report, want * 2 * sizeof(int32_t)) != hipSuccess) return ATOMO_ENOMEM;
+        ctx->report_cap = want;
+    }
     Plan sizing;
     const uint64_t* stream_ids = opt ? opt->stream_ids : nullptr;
     build_plan(mats, n_mats, msgs, sigma_out, p_out, stream_base, stream_ids, nullptr, sizing);
@@ -706,8 +718,8 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     Plan plan;
     build_plan(mats, n_mats, msgs, sigma_out, p_out, stream_base, stream_ids, ctx->ws, plan);
     SvdMat* d_mats = plan.d_mats;
-    ctx->svd_state.clear();
-    for (const SvdMat& m : plan.mats) ctx->svd_state.push_back(m.state);
+    for (int j = 0; j < n_mats; ++j) plan.mats[j].report = ctx->d_report + 2 * j;
+    ctx->report_n = (size_t)n_mats;
 
     std::vector<Work> all;
     all.reserve(plan.n_work());
@@ -841,13 +853,13 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
 
 int svd_sweeps(atomo_ctx* ctx, hipStream_t stream, int32_t* sweeps, int32_t* refreshes, int n_mats)
 {
-    if ((size_t)n_mats != ctx->svd_state.size()) return ATOMO_EINVAL;
+    if ((size_t)n_mats != ctx->report_n) return ATOMO_EINVAL;
     ATOMO_HIP(ctx, hipStreamSynchronize(stream));
+    std::vector<int32_t> host(2 * (size_t)n_mats);
+    ATOMO_HIP(ctx, hipMemcpy(host.data(), ctx->d_report, host.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
     for (int j = 0; j < n_mats; ++j) {
-        ATOMO_HIP(ctx, hipMemcpy(&sweeps[j], ctx->svd_state[j] + ST_SWEEPS, sizeof(int32_t), hipMemcpyDeviceToHost));
-        if (refreshes)
-            ATOMO_HIP(ctx, hipMemcpy(&refreshes[j], ctx->svd_state[j] + ST_REFRESHES, sizeof(int32_t),
-                                     hipMemcpyDeviceToHost));
+        sweeps[j] = host[2 * j];
+        if (refreshes) refreshes[j] = host[2 * j + 1];
     }
     return ATOMO_OK;
 }

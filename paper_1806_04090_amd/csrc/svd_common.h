@@ -101,6 +101,7 @@ struct SvdMat {
     int thin;
     int tchunk;              // positions per work item (a multiple of 256)
     float* B;                // M x r, position-major: the rotated data
+    int* report;             // [2] sweeps and refreshes of this matrix, written when the message is made
     const float* X;          // the data before the first rotation, position-major with row stride r: G itself, or its copy in B
 };
 

@@ -240,3 +240,16 @@ def test_gram_space_low_rank_gradients_with_default_options():
         assert (sigma_tolerance_ok(sig, ref) | ((sig <= floor) & (ref <= floor))).all()
         check_svd_message_against_matrix(G.astype(np.float64), m.to_host(), sig, p)
     assert (per[0][0][128:] == 0).all() and (per[0][1][128:] == 0).all()
+
+
+def test_sweep_counts_survive_a_decode():
+    # the counts are kept outside the workspace, which a decode of many tiles overwrites from its start
+    shapes = [(96, 18), (2048, 18), (64, 576)]
+    mats = inputs.section6_layer_set(2, shapes)
+    msgs, per, status, _ = encode(mats, 3.0, 4, capacity=8)
+    before = (ctx().svd_sweeps(3), ctx().svd_refreshes(3))
+    big = binding.alloc_svd_message(131072, 18, 2, "cuda")
+    big.count.fill_(0)
+    binding.atomo_decode(ctx(), [big])                          # 512 work items: tens of KB at the head of the workspace
+    assert (ctx().svd_sweeps(3), ctx().svd_refreshes(3)) == before
+    assert all(1 <= s <= 16 for s in before[0])
