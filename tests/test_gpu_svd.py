@@ -253,3 +253,19 @@ def test_sweep_counts_survive_a_decode():
     binding.atomo_decode(ctx(), [big])                          # 512 work items: tens of KB at the head of the workspace
     assert (ctx().svd_sweeps(3), ctx().svd_refreshes(3)) == before
     assert all(1 <= s <= 16 for s in before[0])
+
+
+def test_largest_supported_rank_and_the_first_rejected_one():
+    # min(rows, cols) = 2048 is the limit of the interface (64 row blocks, 63 rounds per sweep)
+    rng = np.random.default_rng(0)
+    G = inputs.low_rank_plus_noise(rng, 2300, 2048, 0.5 ** np.arange(8), 1e-3)
+    msgs, per, status, sweeps = encode([G], 3.0, 1, capacity=16)
+    assert status == 0
+    ref = np.linalg.svd(G.astype(np.float64), compute_uv=False)
+    assert sigma_tolerance_ok(per[0][0], ref).all()
+    np.testing.assert_allclose(per[0][1], oracle.probabilities(ref, 3.0), rtol=1e-4, atol=1e-9)
+    h = msgs[0].to_host()
+    assert np.array_equal(h["idx"], np.flatnonzero(oracle.bernoulli_mask(per[0][1], 1, 0)))
+    check_svd_message_against_matrix(G.astype(np.float64), h, *per[0])
+    with pytest.raises(binding.AtomoError):
+        binding.atomo_encode_svd(ctx(), [torch.zeros(2049, 2049, device="cuda")], 3.0, 1, 0)
