@@ -419,12 +419,42 @@ def entrywise_leg(ctx, torch, binding, inputs, reps=40, sets=8):
         lbytes = 12.0 * n + 8.0 * lkept
         lq[name] = {"us_per_step": round(ldt * 1e6, 2), "kept": lkept, "elements_per_s": n / ldt,
                     "hbm_gbs": round(lbytes / ldt / 1e9, 1), "hbm_frac": round(lbytes / ldt / 1e9 / PEAK_HBM_GBS, 4)}
+    # the same path on a gradient a hundred times larger (2^30 elements, 4.3 GB, generated on the device): the
+    # launches and single-workgroup steps that dominate at 44.7 MB are amortised there
+    large = None
+    try:
+        nl = 1 << 30
+        gl = torch.empty(nl, dtype=torch.float32, device="cuda").normal_(0.0, 1e-3)
+        gl[::1000] *= 100.0
+        sl = nl / 100
+        ml = binding.alloc_entrywise_message(nl, binding.default_capacity(sl, nl), "cuda")
+        ol = torch.empty(nl, dtype=torch.float32, device="cuda")
+        for _ in range(2):
+            binding.atomo_encode_entrywise(ctx, gl, sl, 0, 0, msg=ml)
+            binding.atomo_decode(ctx, [ml], out=ol)
+        torch.cuda.synchronize()
+        if ctx.status()[0] == 0:
+            t0 = time.perf_counter()
+            for _ in range(5):
+                binding.atomo_encode_entrywise(ctx, gl, sl, 0, 0, msg=ml)
+                binding.atomo_decode(ctx, [ml], out=ol)
+            torch.cuda.synchronize()
+            dl = (time.perf_counter() - t0) / 5
+            kl = int(ml.count.item())
+            bl = 12.0 * nl + 20.0 * kl
+            large = {"elements": nl, "kept": kl, "ms_per_step": round(dl * 1e3, 3), "elements_per_s": nl / dl,
+                     "hbm_gbs": round(bl / dl / 1e9, 1), "hbm_frac": round(bl / dl / 1e9 / PEAK_HBM_GBS, 4)}
+        del gl, ml, ol
+        torch.cuda.empty_cache()
+    except RuntimeError:
+        large = None
     return {"workload": "flat_heavy_tail: N=11,173,962 fp32, N(0,1e-3^2) + 11,173 entries x100, s=N/100, encode + decode",
             "elements_per_s": n / dt, "us_per_step": round(dt * 1e6, 2), "kept": kept,
             "roofline": {"bound": "hbm", "achieved": round(nbytes / dt / 1e9, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                          "frac": round(nbytes / dt / 1e9 / PEAK_HBM_GBS, 4), "algorithmic_bytes_per_step": nbytes},
             "us_per_step_by_kernel_class": {k: round(v / reps * 1e3, 2) for k, v in sorted(prof.items())},
-            "lq_quantisation": lq}
+            "lq_quantisation": lq,
+            "same_path_at_2^30_elements": large}
 
 
 def cpu_baseline(host_mats, s, seed):

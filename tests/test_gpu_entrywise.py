@@ -123,3 +123,44 @@ def test_unbiased_over_streams():
     # and the whole vector: sum of the estimates against the sum of the gradient
     total_var = (g.astype(np.float64) ** 2 * (1 - p) / np.maximum(p, 1e-300))[p > 0].sum() / trials
     assert abs(mean.sum() - g.astype(np.float64).sum()) < 5 * np.sqrt(total_var)
+
+
+def test_largest_supported_length():
+    # n just below 2^32 (17 GB of gradient, generated on the device): no oracle pass over that, so the properties
+    # that hold at any size: kept count within 6 sd of s, ascending indices past 2^31, capped entries unchanged
+    # (p = 1), every other kept value of the one magnitude tail / (s - n_s) (eq. (p_i), KKT appendix), which is
+    # also evaluated directly; decode puts the values where they belong and zeros elsewhere
+    n = 2 ** 32 - 4099
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1)
+    g = torch.empty(n, dtype=torch.float32, device="cuda")
+    step = 1 << 28
+    for a in range(0, n, step):
+        g[a:min(n, a + step)].normal_(0.0, 1e-3, generator=gen)
+    g[-1] = 7.0
+    g[2 ** 31 + 5] = -9.0
+    g[0] = 3.0
+    s = n / 1000.0
+    msg = binding.alloc_entrywise_message(n, int(s + 10 * np.sqrt(s) + 64), "cuda")
+    binding.atomo_encode_entrywise(ctx(), g, s, 5, 9, msg=msg)
+    assert ctx().status()[0] == 0
+    k = int(msg.count.item())
+    assert abs(k - s) < 6 * np.sqrt(s)
+    idx = msg.idx[:k].to(torch.int64) & 0xFFFFFFFF
+    val = msg.val[:k]
+    assert bool((idx[1:] > idx[:-1]).all()) and 0 <= int(idx[0]) and int(idx[-1]) < n
+    gv = g[idx]
+    assert bool((torch.sign(gv) == torch.sign(val)).all())
+    capped = val.abs() > 1.0
+    assert sorted(idx[capped].tolist()) == [0, 2 ** 31 + 5, n - 1] and torch.equal(val[capped], gv[capped])
+    tau = val.abs()[~capped]
+    assert float(tau.max() - tau.min()) <= 2e-6 * float(tau.max())
+    l1 = sum(float(g[a:min(n, a + step)].abs().double().sum()) for a in range(0, n, step))
+    assert abs(float(tau.max()) - (l1 - 19.0) / (s - 3)) <= 1e-5 * float(tau.max())
+    del gv
+    out = binding.atomo_decode(ctx(), [msg])
+    assert torch.equal(out[idx], val)
+    total = sum(float(out[a:min(n, a + step)].abs().double().sum()) for a in range(0, n, step))
+    assert abs(total - float(val.abs().double().sum())) <= 1e-9 * total
+    del out, g
+    torch.cuda.empty_cache()
