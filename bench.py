@@ -87,6 +87,30 @@ def executed_work(shapes, sweeps, refreshes, pair_visits, jacobi_steps, n_elem, 
     }
 
 
+def profiled_traffic_bytes(kernel):
+    """HBM-side bytes per launch of `kernel` for this workload, from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE + WRITE_SIZE, each scaled by what the counter reads for a plain copy of known size; section
+    "ResNet-18 steps only" of profiles/bench_resnet18_svd_and_entrywise_hbm_traffic.md).  bench.py cannot run
+    the profiler on itself; None if the summary is not there."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
+                        "bench_resnet18_svd_and_entrywise_hbm_traffic.md")
+    try:
+        text = open(path).read()
+    except OSError:
+        return None
+    marker = text.find("## ResNet-18 steps only")
+    if marker < 0:
+        return None
+    for row in text[marker:].splitlines():
+        cells = [c.strip() for c in row.split("|")]
+        if len(cells) >= 5 and cells[1] == kernel:
+            try:
+                return (float(cells[3]) + float(cells[4])) * 1024.0 * 1024.0
+            except ValueError:
+                return None
+    return None
+
+
 def paper_form_flops(shapes, sweeps):
     """The contraction count of textbook blocked one-sided Jacobi, sweeps x (8 M r^2 + 4 r^3) per layer: what
     the same number of sweeps would cost without the Gram-space reformulation.  For comparison only."""
@@ -187,7 +211,8 @@ def main():
                         "frac": round(rate / kp, 5)}
     roofline = {
         "kernel": dominant, "bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
-        "frac": round(achieved / peak, 5), "traffic": None,
+        "frac": round(achieved / peak, 5), "traffic": profiled_traffic_bytes(dominant),
+        "traffic_unit": "HBM-side bytes per launch (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, scaled; see profiles/)",
         "avg_launch_us": round(dom_ms * 1e3 / launches[dominant], 2), "launches_per_step": launches[dominant],
         "by_kernel": by_kernel,
         "ms_per_step_with_events": round(ms_per_step_profiled, 4),
