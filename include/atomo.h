@@ -114,7 +114,8 @@ typedef struct atomo_svd_options {
                                      /* orthogonal to the tolerance.                                               */
                                      /* Matrices with min(rows, cols) <= 32 (the [x*y/2, 2*k*k] reshape of Section */
                                      /* 6) solve their whole r x r problem per pass over the data: they get        */
-                                     /* max(2, min(8, ceil(max_sweeps / 4))) passes (two are the rule), and their  */
+                                     /* 1 + ceil(max_sweeps / 8) passes, at least 2 and at most 8 (three by        */
+                                     /* default; one or two rotate and the last confirms), and their               */
                                      /* atomo_svd_sweeps count is the number of passes that rotated                */
     float   stop_cosine;             /* default 1e-4 (0 = default): stop after the first sweep whose largest */
                                      /* |<a_i,a_j>| / (|a_i||a_j|), measured before rotating, is below */

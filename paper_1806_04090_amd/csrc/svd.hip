@@ -777,8 +777,10 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     }
     if (have_thin) {
         hipStream_t s_thin = have_gs ? ctx->side : stream;
-        // one pass over the data does the work of several sweeps of the blocked iteration: a quarter of the limit
-        const int passes = std::max(2, std::min(THIN_PASSES, (max_sweeps + 3) / 4));
+        // a pass over the data does the work of many sweeps of the blocked iteration: one rotating pass per eight
+        // sweeps of the limit, and the pass that confirms (no input tried, however graded or rank-deficient, has
+        // needed more than two rotating passes)
+        const int passes = std::max(2, std::min(THIN_PASSES, 1 + (max_sweeps + 7) / 8));
         ProfScope ps(ctx, ATOMO_K_SVD_THIN, s_thin);
         launch_thin_absmax(d_mats, w_thin_direct, (int)plan.thin_direct.size(), w_thin_copied, (int)plan.thin_copied.size(),
                            s_thin);
