@@ -74,3 +74,9 @@ def test_entrywise_decode_matches_oracle():
         msgs.append(m); hosts.append({"idx": idx, "val": val.astype(np.float64)})
     out = binding.atomo_decode(ctx(), msgs, scale=0.5).cpu().numpy()
     np.testing.assert_allclose(out, oracle.decode_entrywise(hosts, n, scale=0.5), rtol=1e-6, atol=1e-9)
+
+
+def test_matrix_core_rate_probe_returns_a_plausible_figure():
+    # the measurement helper of bench.py: between a tenth of and the whole published fp32 matrix-core peak
+    rate = ctx().measure_mfma_fp32()
+    assert 15.0 < rate < 160.0
