@@ -129,8 +129,9 @@ def main():
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (the design note in DESIGN.md says "
-              "how it would shard); run with --gpus 1", file=sys.stderr)
+        print("bench.py measures one GPU: this library has no multi-GPU path (layers are independent units and the "
+              "Philox stream of (worker, layer) makes any assignment reproduce the same masks); run with --gpus 1",
+              file=sys.stderr)
         sys.exit(2)
 
     import torch
