@@ -126,6 +126,11 @@ typedef struct atomo_svd_options {
                                      /* pairs in the rounds of an outer sweep whose number is a multiple of this */
                                      /* and only the 1024 pairs that couple its two blocks in the other rounds;  */
                                      /* 1: all 2016 pairs in every round                                         */
+    int32_t block_order;             /* matrices with 481 or more vectors on the shorter side (they iterate on the */
+                                     /* r x r Gram matrix): 0 (default) pairs the 32-row blocks of every round by  */
+                                     /* the weight of their off-diagonal blocks, heaviest first (dynamic ordering  */
+                                     /* of the parallel block-Jacobi method); 1 keeps the fixed round-robin        */
+                                     /* tournament that the smaller matrices use                                   */
     const uint64_t* stream_ids;      /* HOST array of n_mats Philox stream ids, or NULL for stream_base + j: lets */
                                      /* one call encode the gradients of several workers (stream = worker, layer) */
                                      /* and produce the messages that separate calls would                        */

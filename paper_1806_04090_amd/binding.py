@@ -49,7 +49,8 @@ class atomo_lq_msg(C.Structure):
 
 class atomo_svd_options(C.Structure):
     _fields_ = [("max_sweeps", C.c_int32), ("stop_cosine", C.c_float), ("max_inner_sweeps", C.c_int32),
-                ("inner_reduction", C.c_float), ("full_period", C.c_int32), ("stream_ids", C.POINTER(C.c_uint64))]
+                ("inner_reduction", C.c_float), ("full_period", C.c_int32), ("block_order", C.c_int32),
+                ("stream_ids", C.POINTER(C.c_uint64))]
 
 
 _lib = None
@@ -308,9 +309,11 @@ def atomo_encode_svd(ctx: Context, mats: Sequence[torch.Tensor], s: float, seed:
                      msgs: Optional[List[SvdMessage]] = None, sigma_out: Optional[torch.Tensor] = None,
                      p_out: Optional[torch.Tensor] = None, max_sweeps: Optional[int] = None,
                      stop_cosine: Optional[float] = None, max_inner_sweeps: int = 0, inner_reduction: float = 0.0,
-                     full_period: int = 0, stream_ids: Optional[Sequence[int]] = None, stream=None) -> List[SvdMessage]:
+                     full_period: int = 0, block_order: int = 0, stream_ids: Optional[Sequence[int]] = None,
+                     stream=None) -> List[SvdMessage]:
     """Spectral-ATOMO encode of a list of 2-D float32 CUDA tensors (row stride = tensor stride).
-    stream_ids: one Philox stream id per matrix instead of stream_base + index."""
+    stream_ids: one Philox stream id per matrix instead of stream_base + index.
+    block_order: 0 = block pairs by weight (default), 1 = the fixed tournament, for the matrices that iterate in Gram space."""
     n = len(mats)
     c_mats = (atomo_mat * n)()
     for j, g in enumerate(mats):
@@ -323,7 +326,7 @@ def atomo_encode_svd(ctx: Context, mats: Sequence[torch.Tensor], s: float, seed:
     c_msgs = (atomo_svd_msg * n)(*[m.c_struct() for m in msgs])
     opt = None
     if (max_sweeps is not None or stop_cosine is not None or max_inner_sweeps or inner_reduction or full_period
-            or stream_ids is not None):
+            or block_order or stream_ids is not None):
         ids = None
         if stream_ids is not None:
             if len(stream_ids) != n:
@@ -331,7 +334,7 @@ def atomo_encode_svd(ctx: Context, mats: Sequence[torch.Tensor], s: float, seed:
             ids = (C.c_uint64 * n)(*[int(x) & (2 ** 64 - 1) for x in stream_ids])
         opt = C.byref(atomo_svd_options(0 if max_sweeps is None else max_sweeps,
                                         0.0 if stop_cosine is None else stop_cosine,
-                                        max_inner_sweeps, inner_reduction, int(full_period), ids))
+                                        max_inner_sweeps, inner_reduction, int(full_period), int(block_order), ids))
     _check(lib().atomo_encode_svd(ctx._h, c_mats, n, float(s), int(seed) & (2 ** 64 - 1),
                                   int(stream_base) & (2 ** 64 - 1), opt, c_msgs,
                                   None if sigma_out is None else sigma_out.data_ptr(),

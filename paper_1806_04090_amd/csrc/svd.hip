@@ -61,6 +61,21 @@ __global__ __launch_bounds__(256) void svd_reset(const SvdMat* mats, int n_mats)
     if (j < n_mats) mats[j].state[w] = (w == ST_FIRST) ? 1 : (w == ST_DMIN) ? 0x7f800000 : 0;
 }
 
+// Gram-space matrices: the pairing of the first ticks is that of the fixed tournament (no block weights exist yet).
+__global__ __launch_bounds__(64) void svd_first_pairs(const SvdMat* mats, const Work* list)
+{
+    const SvdMat m = mats[list[blockIdx.x].mat];
+    for (int e = threadIdx.x; e < 3 * m.npairs; e += 64) {
+        const int t = e / m.npairs, k = e - t * m.npairs;
+        int bi, bj;
+        pair_blocks(m.nb2, t % m.R, k, bi, bj);
+        m.sched[(size_t)e * 2] = bi;
+        m.sched[(size_t)e * 2 + 1] = bj;
+        m.where[(size_t)t * m.nb2 + bi] = 2 * k;
+        m.where[(size_t)t * m.nb2 + bj] = 2 * k + 1;
+    }
+}
+
 __global__ __launch_bounds__(256) void svd_absmax(const SvdMat* mats, const Work* work)
 {
     __shared__ float red[4];
@@ -221,11 +236,15 @@ __global__ __launch_bounds__(256) void svd_fullgram_reduce(const SvdMat* mats, c
     __syncthreads();
     const int Rp = m.rows_alloc;
     float* C = c_of_parity(m, tick);                             // the C that this tick's svd_eig reads
+    const bool first = m.state[ST_FIRST] != 0;
     for (int e = tid; e < QSZ; e += 256) {
         const int i = e >> 6, j = e & 63;
         const float v = ti == tj ? 0.5f * (t[i][j] + t[j][i]) : t[i][j];
         C[(size_t)(ti * PR + i) * m.ldc + tj * PR + j] = v;
-        if (ti == tj && i == j) m.cref[ti * PR + i] = v;         // the row's squared norm, measured on the data
+        if (ti == tj && i == j) {
+            m.cref[ti * PR + i] = v;                             // the row's squared norm, measured on the data
+            if (first) m.cref0[ti * PR + i] = v;
+        }
         m.CT[(size_t)(ti * PR + i) * m.ldc + Rp + tj * PR + j] = (ti == tj && i == j) ? 1.0f : 0.0f;
         if (ti != tj) {                                          // mirrored tile: row index runs over j
             C[(size_t)(tj * PR + i) * m.ldc + ti * PR + j] = t[j][i];
@@ -551,6 +570,7 @@ struct Plan {
     std::vector<Work> prep, gram, fullgram, tiles, apply, eig_gs, eig_ds, rowop1, twosided, norms, pack;
     std::vector<Work> thin_chunks, thin_list;      // thin matrices: (matrix, chunk of positions); (matrix)
     std::vector<Work> thin_direct, thin_copied;    // the chunks again, split by whether G is used in place
+    std::vector<Work> gs_list;                     // the Gram-space matrices
     std::vector<int> gs_periods;     // distinct R of the Gram-space matrices
     int max_R = 1;
     int max_R_ds = 1;                // largest R among the data-space matrices
@@ -560,7 +580,8 @@ struct Plan {
     size_t n_work() const
     {
         return prep.size() + gram.size() + fullgram.size() + tiles.size() + apply.size() + eig_gs.size() + eig_ds.size() +
-               rowop1.size() + twosided.size() + norms.size() + pack.size() + 2 * thin_chunks.size() + thin_list.size();
+               rowop1.size() + twosided.size() + norms.size() + pack.size() + 2 * thin_chunks.size() + thin_list.size() +
+               gs_list.size();
     }
 };
 
@@ -599,7 +620,8 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
             m.nchg = (m.M + m.tchunk - 1) / m.tchunk;
             m.Mp = m.M; m.ldw = 0; m.nb2 = 0; m.rows_alloc = THIN_R; m.R = 1; m.npairs = 0; m.nchu = 0; m.gs = 0;
             m.ntiles = 0; m.ldc = 0;
-            m.W0 = nullptr; m.W1 = nullptr; m.CT = nullptr; m.CT2 = nullptr; m.cref = nullptr;
+            m.W0 = nullptr; m.W1 = nullptr; m.CT = nullptr; m.CT2 = nullptr; m.cref = nullptr; m.cref0 = nullptr;
+            m.sched = nullptr; m.where = nullptr; m.bw = nullptr; m.dd = nullptr;
             m.gram = carve.take<float>((size_t)m.nchg * THIN_R * THIN_R);
             m.Q = carve.take<float>(2 * THIN_R * THIN_R);
             m.B = carve.take<float>((size_t)m.M * m.r);
@@ -640,6 +662,11 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
         m.state = carve.take<int>(ST_WORDS);
         m.sig_raw = carve.take<float>(m.rows_alloc);
         m.cref = m.gs ? carve.take<float>(m.rows_alloc) : nullptr;
+        m.cref0 = m.gs ? carve.take<float>(m.rows_alloc) : nullptr;
+        m.sched = m.gs ? carve.take<int>((size_t)3 * m.npairs * 2) : nullptr;
+        m.where = m.gs ? carve.take<int>((size_t)3 * m.nb2) : nullptr;
+        m.bw = m.gs ? carve.take<float>((size_t)2 * m.nb2 * m.nb2) : nullptr;
+        m.dd = m.gs ? carve.take<float>((size_t)2 * m.rows_alloc) : nullptr;
         m.src_row = carve.take<int>(m.capacity);
         m.src_inv = carve.take<float>(m.capacity);
         m.src_fold = carve.take<float>(m.capacity);
@@ -658,6 +685,7 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
             }
         }
         if (m.gs) {
+            plan.gs_list.push_back(Work{j, 0, 0, 0});
             bool seen = false;
             for (int p : plan.gs_periods) seen = seen || p == m.R;
             if (!seen) plan.gs_periods.push_back(m.R);
@@ -700,6 +728,7 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     const float inner_reduction = opt && opt->inner_reduction > 0.0f ? opt->inner_reduction : 0.01f;
     const float fresh_stop = 0.25f * stop_cosine;
     const int full_period = opt && opt->full_period > 0 ? opt->full_period : 8;
+    const int cyclic = opt && opt->block_order == 1 ? 1 : 0;
 
     if ((size_t)n_mats > ctx->report_cap) {                      // (hipFree waits for the device)
         if (ctx->d_report) ATOMO_HIP(ctx, hipFree(ctx->d_report));
@@ -743,6 +772,7 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     const Work* w_thin_list = place(plan.thin_list);
     const Work* w_thin_direct = place(plan.thin_direct);
     const Work* w_thin_copied = place(plan.thin_copied);
+    const Work* w_gs_list = place(plan.gs_list);
 
     rc = upload(ctx, d_mats, plan.mats.data(), plan.mats.size() * sizeof(SvdMat), stream);
     if (rc != ATOMO_OK) return rc;
@@ -753,6 +783,7 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     {
         ProfScope ps(ctx, ATOMO_K_SVD_PREPARE, stream);
         svd_reset<<<(unsigned)((n_mats * ST_WORDS + 255) / 256), 256, 0, stream>>>(d_mats, n_mats);
+        if (!plan.gs_list.empty()) svd_first_pairs<<<grid(plan.gs_list), 64, 0, stream>>>(d_mats, w_gs_list);
         if (!plan.prep.empty()) {
             svd_absmax<<<grid(plan.prep), 256, 0, stream>>>(d_mats, w_prep);
             svd_prepare<<<grid(plan.prep), 256, 0, stream>>>(d_mats, w_prep);
@@ -798,8 +829,8 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
             }
             {
                 ProfScope ps(ctx, ATOMO_K_SVD_EIG, s_ds);
-                launch_svd_eig(d_mats, w_eig_ds, (int)plan.eig_ds.size(), nullptr, 0, tick, max_sweeps, stop_cosine,
-                               max_inner, inner_reduction, full_period, 0, ctx->d_flags, s_ds);
+                launch_svd_eig(d_mats, w_eig_ds, (int)plan.eig_ds.size(), nullptr, 0, nullptr, 0, 0, tick, max_sweeps,
+                               stop_cosine, max_inner, inner_reduction, full_period, 0, ctx->d_flags, s_ds);
             }
             {
                 ProfScope ps(ctx, ATOMO_K_SVD_UPDATE, s_ds);
@@ -814,11 +845,12 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
             // the matrices that sweep on, and the previous tick's update for every matrix
             if (tick > 0) {
                 ProfScope ps(ctx, ATOMO_K_SVD_EIG, stream);
-                launch_svd_eig(d_mats, w_eig_gs, (int)plan.eig_gs.size(), w_twosided, n_two, tick, max_sweeps,
-                               stop_cosine, max_inner, inner_reduction, full_period, 0, ctx->d_flags, stream);
+                launch_svd_eig(d_mats, w_eig_gs, (int)plan.eig_gs.size(), w_twosided, n_two, w_gs_list,
+                               (int)plan.gs_list.size(), cyclic, tick, max_sweeps, stop_cosine, max_inner,
+                               inner_reduction, full_period, 0, ctx->d_flags, stream);
             }
             bool boundary = false;
-            for (int period : plan.gs_periods) boundary = boundary || tick % period == 0;
+            for (int period : plan.gs_periods) boundary = boundary || (tick % period == 0 && tick <= max_sweeps * period);
             if (!boundary) continue;
             // a sweep boundary of some matrix: those that asked for it get a fresh Gram matrix (their Tgs is
             // complete now), and their pair problems of this tick run in a launch of their own
@@ -832,8 +864,8 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
             }
             {
                 ProfScope ps(ctx, ATOMO_K_SVD_EIG, stream);
-                launch_svd_eig(d_mats, w_eig_gs, (int)plan.eig_gs.size(), nullptr, 0, tick, max_sweeps, stop_cosine,
-                               max_inner, inner_reduction, full_period, 1, ctx->d_flags, stream);
+                launch_svd_eig(d_mats, w_eig_gs, (int)plan.eig_gs.size(), nullptr, 0, nullptr, 0, 0, tick, max_sweeps,
+                               stop_cosine, max_inner, inner_reduction, full_period, 1, ctx->d_flags, stream);
             }
         }
         {

@@ -42,6 +42,8 @@ enum {
     ST_SAT_OUT = 17,    // Gram-space matrices: 1 if a row sat out of some pair problem in the current sweep (GS_RELIABLE)
     ST_DMIN = 18,       // Gram-space matrices: smallest squared row norm above the floor seen by the running refresh (float bits)
     ST_NOISE = 19,      // Gram-space matrices: cosines below this are not resolved by the Gram arithmetic (float bits), see GS_NOISE
+    ST_WSTAMP = 20,     // Gram-space matrices: word 20 + (t & 1) holds t + 1 once the block weights of the C after t ticks are written
+    ST_CYCLIC_FROM = 22, // Gram-space matrices: ticks from this one on are paired by the fixed tournament (0 = not set)
     ST_WORDS = 24
 };
 
@@ -63,6 +65,24 @@ constexpr float GS_RELIABLE = 1.0e-5f;
 // refresh costs about a tenth of a sweep), so a row can shrink by GS_RELIABLE per sweep, not per several sweeps.
 // Gradients of low rank (a fully connected layer sees at most batch-size atoms) converge in two thirds of the sweeps.
 
+// Order of the block pairs in Gram space.  The C of a Gram-space matrix is all there, so the pairing of a tick need not
+// follow the fixed tournament: the pairs are chosen greedily by the weight of their off-diagonal block, heaviest first, as in the dynamic ordering of Becka, Oksa and Vajtersic for the parallel
+// block-Jacobi method.  The weights known when tick t + 1 is planned (during tick t) are those of the C after
+// t - 1 ticks; the pairs of ticks t - 1 and t, whose rotations they do not contain yet, count as zero.
+// The largest cosine that decides whether a sweep (still nb - 1 ticks) has resolved the matrix is taken over the
+// pairs of its last GS_WINDOW ticks only: they are the heaviest ones of that moment.
+// The weight of a block is the sum of its squared entries in the scaling of the first refresh, c_ij^2 / (ref_i ref_j)
+// with reference squared norms that follow the rows through the rotations like those of GS_RELIABLE but are never
+// measured again.  With a fixed scaling this is the classical dynamic ordering on D^-1/2 C D^-1/2, and rows that
+// shrink towards the floor (a rank-deficient gradient) lose their weight as they shrink; squared cosines of the
+// current norms would keep them at the top of every tick, at the expense of the pairs of rows that carry the matrix.
+constexpr int GS_WINDOW = 5;
+// The fixed tournament, which visits every pair whatever the weights say, takes over again from this sweep on, and
+// already after the first sweep in which a row sat out (GS_RELIABLE): rows that collapse - a gradient of low rank,
+// duplicated rows, a steeply graded spectrum - have to be brought down by the rows that carry the matrix, and
+// weights cannot rank those rotations against the ones among the large rows.
+constexpr int GS_DYNAMIC_SWEEPS = 10;
+
 // Between a row of squared norm d_max and one of squared norm d_min the updates of C leave rounding errors of the
 // order of GS_NOISE * sqrt(d_max / d_min) in the cosine.  Sweeping on C below that level is wasted: the refresh is
 // asked for as soon as the largest cosine of a sweep is under it (capped at GS_NOISE_CAP).
@@ -81,6 +101,8 @@ struct SvdMat {
     int* state;              // [ST_WORDS]
     float* sig_raw;          // [rows_alloc]
     float* cref;             // Gram space: [rows_alloc] reference squared norm of every row, see GS_RELIABLE
+    float* cref0;            // Gram space: [rows_alloc] the same, but never measured again after the first refresh: the
+                             //   scale of the row for the block weights
     const float* G;
     long long ldg;
     int rows, cols, transposed;
@@ -103,6 +125,12 @@ struct SvdMat {
     float* B;                // M x r, position-major: the rotated data
     int* report;             // [2] sweeps and refreshes of this matrix, written when the message is made
     const float* X;          // the data before the first rotation, position-major with row stride r: G itself, or its copy in B
+    // Gram-space matrices: the pairing of the ticks, tables indexed by tick mod 3
+    int* sched;              // [3][npairs][2]: the two blocks (smaller first) of every pair
+    int* where;              // [3][nb2]: 2 x pair + half for every block
+    float* bw;               // [2][nb2][nb2]: weight of every off-diagonal block, by parity of the tick count of its C
+    float* dd;               // [2][rows_alloc]: the scale of every row for the block weights, by tick parity: cref0
+                             //   after the pair problems of the tick, 0 for rows that sat out or lie under the floor
 };
 
 struct Work { int mat, a, b, c; };
@@ -124,6 +152,18 @@ __device__ inline void pair_blocks(int nb2, int round, int k, int& bi, int& bj)
     else { a = (round + k) % n1; b = (round - k + n1) % n1; }
     bi = a < b ? a : b;
     bj = a < b ? b : a;
+}
+
+// The blocks of pair k in `tick`: from the table for Gram-space matrices, else the fixed tournament.
+__device__ inline void tick_pair(const SvdMat& m, int tick, int k, int& bi, int& bj)
+{
+    if (m.gs) {
+        const int* s = m.sched + ((size_t)(tick % 3) * m.npairs + k) * 2;
+        bi = s[0];
+        bj = s[1];
+    } else {
+        pair_blocks(m.nb2, tick % m.R, k, bi, bj);
+    }
 }
 
 // exponent e such that absmax * 2^-e lies in [1, 2); 0 for an all-zero matrix
@@ -183,8 +223,8 @@ __device__ inline void twosided_tile(const SvdMat* mats, const Work* work, int i
     const int qi = wave >> 1, qj = wave & 1, h = lane >> 5, l32 = lane & 31;
     int ai = 0, aj = 0, bi = 0, bj = 0;
     if (active) {
-        pair_blocks(m.nb2, tick % m.R, wk.a, ai, aj);
-        if (kind == 1) pair_blocks(m.nb2, tick % m.R, wk.b, bi, bj);
+        tick_pair(m, tick, wk.a, ai, aj);
+        if (kind == 1) tick_pair(m, tick, wk.b, bi, bj);
     }
     const float* qa = m.Q + ((size_t)(tick & 1) * m.npairs + wk.a) * QSZ;
     const float* qb = m.Q + ((size_t)(tick & 1) * m.npairs + wk.b) * QSZ;
@@ -196,6 +236,19 @@ __device__ inline void twosided_tile(const SvdMat* mats, const Work* work, int i
 
     // every global load is issued before the first use: the tile, and the MFMA operands from Qa and Qb
     float tile_regs[QSZ / 256], qa_regs[PR / 2], qb_regs[PR / 2];
+    // for the weight of the wave's 32x32 block of the new C: 1 / |row| of its rows and of its column (0: skip the row)
+    float rrow[16], rcol = 0.0f;
+    const int brow = qi ? aj : ai, bcol = qj ? bj : bi;
+    if (active && kind == 1) {
+        const float* d = m.dd + (size_t)(tick & 1) * m.rows_alloc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const float x = d[brow * BS + 8 * (v >> 2) + 4 * h + (v & 3)];
+            rrow[v] = x > 0.0f ? __builtin_amdgcn_rsqf(x) : 0.0f;
+        }
+        const float x = d[bcol * BS + l32];
+        rcol = x > 0.0f ? __builtin_amdgcn_rsqf(x) : 0.0f;
+    }
     if (active) {
 #pragma unroll
         for (int p = 0; p < QSZ / 256; ++p) {
@@ -242,14 +295,32 @@ __device__ inline void twosided_tile(const SvdMat* mats, const Work* work, int i
         const int i = qi * BS + 8 * (v >> 2) + 4 * h + (v & 3);
         dst[(size_t)row_of(i) * m.ldc + c] = acc[v];
     }
+    if (kind == 1) {
+        // the weight of this block of the C after tick + 1 ticks: sum of its squared entries, each divided by the
+        // reference squared norms of its two rows (a diagonal block leaves out its diagonal), summed in a fixed order
+        float sum = 0.0f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const float t = acc[v] * rrow[v] * rcol;
+            if (brow != bcol || 8 * (v >> 2) + 4 * h + (v & 3) != l32) sum = fmaf(t, t, sum);
+        }
+        for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+        if (lane == 0) {
+            m.bw[((size_t)((tick + 1) & 1) * m.nb2 + brow) * m.nb2 + bcol] = sum;
+            if (wk.a == 0 && wk.b == 0 && wave == 0) m.state[ST_WSTAMP + ((tick + 1) & 1)] = tick + 2;
+        }
+    }
 }
 
 // Enqueues svd_eig for one tick (defined in svd_eig.hip): n_items pair problems, plus, when n_two > 0, the
 // two-sided update of tick - 1 over the n_two tiles of d_two_work.  fresh_only selects, among the Gram-space
 // matrices, those whose Gram matrix was formed in this very tick (1) or all the others (0).
-void launch_svd_eig(const SvdMat* d_mats, const Work* d_work, int n_items, const Work* d_two_work, int n_two, int tick,
-                    int max_sweeps, float stop_cosine, int max_inner, float inner_reduction, int full_period,
-                    int fresh_only, int* d_flags, hipStream_t stream);
+// With n_plan > 0 the launch also plans the pairing of tick + 1 for the Gram-space matrices of d_plan_work (one
+// workgroup each): by block weight, or, with cyclic != 0, the fixed tournament.
+void launch_svd_eig(const SvdMat* d_mats, const Work* d_work, int n_items, const Work* d_two_work, int n_two,
+                    const Work* d_plan_work, int n_plan, int cyclic, int tick, int max_sweeps, float stop_cosine,
+                    int max_inner, float inner_reduction, int full_period, int fresh_only, int* d_flags,
+                    hipStream_t stream);
 
 // Thin matrices (defined in svd_thin.hip).  d_chunks lists (matrix, chunk of positions), d_list the thin matrices.
 // d_direct: chunks of the matrices used in place (largest |entry| only); d_copied: chunks of those copied into B first.

@@ -100,22 +100,112 @@ __device__ inline float2 pair_rotation(const float* A, int k, float z2)
     return make_float2(c, s);
 }
 
+// Plans the pairing of tick + 1 for one Gram-space matrix (all NT threads of a workgroup call).
+// Dynamic order: a greedy maximum-weight matching on the block weights of the C after tick - 1 ticks (written by the
+// two-sided update of the previous launch), heaviest pair first, ties to the lower block indices; the pairs of
+// ticks tick - 1 and tick count as zero, their rotations are not in those weights yet.  Without such weights
+// (first ticks, `cyclic`) the round of the fixed tournament.  wsh: nb2 x nb2 floats, redw / rede: 16 words each.
+__device__ inline void plan_next_tick(const SvdMat& m, int tick, int cyclic, float* wsh, float* redw, int* rede)
+{
+    if (!m.gs || m.state[ST_DONE_AT] != 0) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nb = m.nb2, np = m.npairs;
+    int* sch = m.sched + (size_t)((tick + 1) % 3) * np * 2;
+    int* whr = m.where + (size_t)((tick + 1) % 3) * nb;
+    // (ST_CYCLIC_FROM may be set while this launch runs, but then to tick + 2: the answer for tick + 1 is the same)
+    const int cyclic_from = m.state[ST_CYCLIC_FROM];
+    const bool weighted = !cyclic && tick >= 2 && (tick + 1) / m.R < GS_DYNAMIC_SWEEPS &&
+                          !(cyclic_from != 0 && tick + 1 >= cyclic_from) &&
+                          m.state[ST_WSTAMP + ((tick - 1) & 1)] == tick;
+    if (!weighted) {
+        for (int k = tid; k < np; k += NT) {
+            int bi, bj;
+            pair_blocks(nb, (tick + 1) % m.R, k, bi, bj);
+            sch[2 * k] = bi; sch[2 * k + 1] = bj;
+            whr[bi] = 2 * k; whr[bj] = 2 * k + 1;
+        }
+        return;
+    }
+    const float* W = m.bw + (size_t)((tick - 1) & 1) * nb * nb;
+    auto usable = [](float w) { return (w > 0.0f && w <= FLT_MAX) ? w : 0.0f; };
+    for (int e = tid; e < nb * nb; e += NT) {
+        const int i = e / nb, j = e - i * nb;
+        wsh[e] = i < j ? usable(W[i * nb + j]) + usable(W[j * nb + i]) : 0.0f;
+    }
+    __syncthreads();
+    for (int q = tid; q < 2 * np; q += NT) {
+        const int* s = m.sched + ((size_t)((q < np ? tick : tick + 2) % 3) * np + (q < np ? q : q - np)) * 2;
+        wsh[s[0] * nb + s[1]] = 0.0f;
+    }
+    __syncthreads();
+    // this thread's candidates (i < j), at most MAX_R / BS squared over NT of them
+    constexpr int PER = (MAX_R / BS) * (MAX_R / BS) / NT;
+    float cw[PER];
+    int ci[PER], cj[PER];
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        const int e = tid + NT * k;
+        const int i = e < nb * nb ? e / nb : 0, j = e < nb * nb ? e - i * nb : 0;
+        ci[k] = i; cj[k] = j;
+        cw[k] = i < j ? wsh[e] : -1.0f;                        // -1: no candidate
+    }
+    unsigned long long used = 0ull;
+    for (int it = 0; it < np; ++it) {
+        float bw = -1.0f;
+        int be = 0x7fffffff;
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+            const bool free_pair = cw[k] >= 0.0f && !((used >> ci[k]) & 1ull) && !((used >> cj[k]) & 1ull);
+            const int e = tid + NT * k;
+            if (free_pair && (cw[k] > bw || (cw[k] == bw && e < be))) { bw = cw[k]; be = e; }
+        }
+        for (int o = 32; o > 0; o >>= 1) {
+            const float ow = __shfl_xor(bw, o);
+            const int oe = __shfl_xor(be, o);
+            if (ow > bw || (ow == bw && oe < be)) { bw = ow; be = oe; }
+        }
+        if (lane == 0) { redw[wave] = bw; rede[wave] = be; }
+        __syncthreads();
+        bw = -1.0f; be = 0x7fffffff;
+        for (int w = 0; w < NT / 64; ++w) {
+            const float ow = redw[w];
+            const int oe = rede[w];
+            if (ow > bw || (ow == bw && oe < be)) { bw = ow; be = oe; }
+        }
+        __syncthreads();
+        if (be == 0x7fffffff) break;                             // cannot happen: an even number of free blocks is left
+        const int i = be / nb, j = be - i * nb;
+        used |= (1ull << i) | (1ull << j);
+        if (tid == 0) {
+            sch[2 * it] = i; sch[2 * it + 1] = j;
+            whr[i] = 2 * it; whr[j] = 2 * it + 1;
+        }
+    }
+}
+
 // Workgroups 0 .. n_eig-1 solve block pairs.  Workgroups beyond take no pair: each applies four tiles of the
 // previous tick's two-sided update (one tile per group of four waves, staged in the LDS arrays a pair problem
 // would use).  The update writes the C of this tick's parity; the pair problems read the C of the previous
 // parity and bring their own 64x64 block up to date themselves (step 1 below), so the two do not meet.
 __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* work, int n_eig, const Work* two_work,
-                                              int n_two, int step, int max_sweeps, float stop_cosine, int max_inner,
-                                              float inner_reduction, int full_period, int fresh_only, int* flags)
+                                              int n_two, const Work* plan_work, int cyclic, int step, int max_sweeps,
+                                              float stop_cosine, int max_inner, float inner_reduction, int full_period,
+                                              int fresh_only, int* flags)
 {
     __shared__ float As[2][PR * ELD];
     __shared__ float Qs[2][PR * ELD];
     __shared__ float ev[PR];
     __shared__ int dest[PR];
     __shared__ float ref[PR];            // Gram space: reference squared norm of the pair's rows (natural index)
+    __shared__ float ref0[PR];           //             the same in the scaling of the first refresh (cref0)
     __shared__ int sits_out[PR];         // Gram space: by slot, rows whose diagonal entry is rounding noise
     __shared__ float red[32];
 
+    const int two_wgs = (n_two + TILES_PER_WG - 1) / TILES_PER_WG;
+    if ((int)blockIdx.x >= n_eig + two_wgs) {                     // the last workgroups plan the next tick
+        plan_next_tick(mats[plan_work[(int)blockIdx.x - n_eig - two_wgs].mat], step, cyclic, As[0], red, dest);
+        return;
+    }
     if ((int)blockIdx.x >= n_eig) {
         const int group = threadIdx.x >> 8;
         float* tile = group == 0 ? As[0] : group == 1 ? As[1] : group == 2 ? Qs[0] : Qs[1];
@@ -135,7 +225,7 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
     }
     const int round = step % m.R;
     int bi, bj;
-    pair_blocks(m.nb2, round, wk.a, bi, bj);
+    tick_pair(m, step, wk.a, bi, bj);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const bool cross = round % full_period != 0;
 
@@ -152,7 +242,10 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
         const int i = e >> 6, j = e & 63;
         Qs[0][i * ELD + mem_col(home_slot(j, cross))] = (i == j) ? 1.0f : 0.0f;
     }
-    if (tid < PR) ref[tid] = m.gs ? m.cref[tid < BS ? bi * BS + tid : bj * BS + tid - BS] : 0.0f;
+    if (tid < PR) {
+        ref[tid] = m.gs ? m.cref[tid < BS ? bi * BS + tid : bj * BS + tid - BS] : 0.0f;
+        ref0[tid] = m.gs ? m.cref0[tid < BS ? bi * BS + tid : bj * BS + tid - BS] : 0.0f;
+    }
     if (!m.gs || fresh) {
         const float* g = m.gram + (size_t)wk.a * m.nchg * QSZ;
         const float* C = m.gs ? c_of_parity(m, step) : nullptr;
@@ -169,13 +262,14 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
             As[0][home_slot(i, cross) * ELD + mem_col(home_slot(j, cross))] = sum;
         }
     } else {
-        const int prev = (step - 1) % m.R, pp = (step - 1) & 1;
+        const int prev = step - 1, pp = (step - 1) & 1;
         const float* C = c_of_parity(m, pp);
-        const int k1 = pair_of_block(m.nb2, prev, bi), k2 = pair_of_block(m.nb2, prev, bj);
+        const int* was = m.where + (size_t)(prev % 3) * m.nb2;
+        const int k1 = was[bi] >> 1, k2 = was[bj] >> 1;
+        const int s1 = was[bi] & 1, s2 = was[bj] & 1;
         int x0, x1, y0, y1;
-        pair_blocks(m.nb2, prev, k1, x0, x1);
-        pair_blocks(m.nb2, prev, k2, y0, y1);
-        const int s1 = bi == x0 ? 0 : 1, s2 = bj == y0 ? 0 : 1;
+        tick_pair(m, prev, k1, x0, x1);
+        tick_pair(m, prev, k2, y0, y1);
         const float* Q1 = m.Q + ((size_t)pp * m.npairs + k1) * QSZ;
         const float* Q2 = m.Q + ((size_t)pp * m.npairs + k2) * QSZ;
         const int h = lane >> 5, l32 = lane & 31;
@@ -281,7 +375,8 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
         entry = make_float2(mx, dmax);
     }
     if (tid == 0) {
-        atomicMax((unsigned int*)&m.state[ST_OFFMAX], __float_as_uint(entry.x));
+        // (Gram space: the pairs of the last ticks of the sweep are the heaviest of that moment, see GS_WINDOW)
+        if (!m.gs || cyclic || round >= m.R - GS_WINDOW) atomicMax((unsigned int*)&m.state[ST_OFFMAX], __float_as_uint(entry.x));
         atomicMax((unsigned int*)&m.state[ST_SCALE_NEXT], __float_as_uint(entry.y));
     }
 
@@ -406,14 +501,19 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
     __syncthreads();                                             // dest[] is complete
     if (m.gs && tid < PR) {
         const int cj = qcol(tid);
-        float r = 0.0f;
+        float r = 0.0f, r0 = 0.0f;
 #pragma unroll 8
         for (int i = 0; i < PR; ++i) {
             const float q = Qc[i * ELD + cj];
             r = fmaf(q * q, ref[i], r);
+            r0 = fmaf(q * q, ref0[i], r0);
         }
         const int d = dest[tid];
-        m.cref[d < BS ? bi * BS + d : bj * BS + d - BS] = r;
+        const int grow = d < BS ? bi * BS + d : bj * BS + d - BS;
+        m.cref[grow] = r;
+        // the scale of the row for the block weights that the two-sided update forms (rows that are not rotated: 0)
+        m.cref0[grow] = r0;
+        m.dd[(size_t)(step & 1) * m.rows_alloc + grow] = (ev[tid] > z2 && !sits_out[home_slot(tid, cross)]) ? r0 : 0.0f;
     }
 
     // 5. one Newton-Schulz step  Q <- Q (1.5 I - 0.5 Q^T Q): removes the drift that thousands of
@@ -479,6 +579,7 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
                 const float resolved = fmaxf(10.0f * stop_cosine, __int_as_float(m.state[ST_NOISE]));
                 if (worst < resolved || sweeps >= max_sweeps || waiting)
                     m.state[ST_MODE] = MODE_NEED_REFRESH;
+                if (waiting && m.state[ST_CYCLIC_FROM] == 0) m.state[ST_CYCLIC_FROM] = step + 2;
                 m.state[ST_SAT_OUT] = 0;
             } else if (worst < stop_cosine) {
                 m.state[ST_DONE_AT] = step + 1;
@@ -496,19 +597,22 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
 }  // namespace
 
 
-void launch_svd_eig(const SvdMat* d_mats, const Work* d_work, int n_items, const Work* d_two_work, int n_two, int step,
-                    int max_sweeps, float stop_cosine, int max_inner, float inner_reduction, int full_period,
-                    int fresh_only, int* d_flags, hipStream_t stream)
+void launch_svd_eig(const SvdMat* d_mats, const Work* d_work, int n_items, const Work* d_two_work, int n_two,
+                    const Work* d_plan_work, int n_plan, int cyclic, int step, int max_sweeps, float stop_cosine,
+                    int max_inner, float inner_reduction, int full_period, int fresh_only, int* d_flags,
+                    hipStream_t stream)
 {
     static_assert(PR * ELD == PR * TLD, "the two-sided tiles are staged in the LDS arrays of the pair problem");
-    const unsigned grid = (unsigned)(n_items + (n_two + TILES_PER_WG - 1) / TILES_PER_WG);
+    static_assert((MAX_R / BS) * (MAX_R / BS) <= PR * ELD, "the block weights are staged in an LDS array of the pair problem");
+    static_assert((MAX_R / BS) * (MAX_R / BS) % NT == 0 && MAX_R / BS <= 64, "candidate pairs per thread, block mask");
+    const unsigned grid = (unsigned)(n_items + (n_two + TILES_PER_WG - 1) / TILES_PER_WG + n_plan);
     if (grid == 0) return;
     // A compute unit has room for two of these workgroups.  While the chip has a unit for every workgroup of
     // the launch, unused dynamic LDS keeps them apart: a pair problem is a latency chain and runs slower
     // when it shares its SIMDs.
     const size_t pad = n_items <= 200 ? 20 * 1024 : 0;
-    svd_eig<<<grid, NT, pad, stream>>>(d_mats, d_work, n_items, d_two_work, n_two, step, max_sweeps, stop_cosine,
-                                     max_inner, inner_reduction, full_period, fresh_only, d_flags);
+    svd_eig<<<grid, NT, pad, stream>>>(d_mats, d_work, n_items, d_two_work, n_two, d_plan_work, cyclic, step, max_sweeps,
+                                     stop_cosine, max_inner, inner_reduction, full_period, fresh_only, d_flags);
 }
 
 }  // namespace svd
