@@ -104,10 +104,11 @@ typedef struct atomo_lq_msg {
 
 /* Tuning knobs of the Jacobi SVD; pass NULL to the encoder for the defaults. */
 typedef struct atomo_svd_options {
-    int32_t max_sweeps;              /* default 16 (0 = default).  Noise-dominated gradients take about 9 sweeps,  */
-                                     /* exactly low-rank ones (rank 128 in 600 x 700) 14, singular values graded   */
-                                     /* over two decades 13, three 16, five 17; a matrix half of whose rows are    */
-                                     /* copies of the other half 20.  Every sweep allowed costs launches even when */
+    int32_t max_sweeps;              /* default 16 (0 = default).  Noise-dominated gradients take 8 to 10 sweeps   */
+                                     /* (6 or 7 with 481 or more vectors on the shorter side, see block_order),    */
+                                     /* exactly low-rank ones (rank 128 in 600 x 700) 12, singular values graded   */
+                                     /* over two decades 11, three 14, five 16; a matrix half of whose rows are    */
+                                     /* copies of the other half 16.  Every sweep allowed costs launches even when */
                                      /* unused (they return at once, about 0.08 ms per sweep for 512-row           */
                                      /* matrices).  Hitting the limit reports ATOMO_ENOCONV; the message is then   */
                                      /* still an exact decomposition of the input, with atoms that are not yet     */
@@ -129,8 +130,10 @@ typedef struct atomo_svd_options {
     int32_t block_order;             /* matrices with 481 or more vectors on the shorter side (they iterate on the */
                                      /* r x r Gram matrix): 0 (default) pairs the 32-row blocks of every round by  */
                                      /* the weight of their off-diagonal blocks, heaviest first (dynamic ordering  */
-                                     /* of the parallel block-Jacobi method); 1 keeps the fixed round-robin        */
-                                     /* tournament that the smaller matrices use                                   */
+                                     /* of the parallel block-Jacobi method; a matrix falls back to the tournament */
+                                     /* once a row has shrunk by 1e-5, as in gradients of low rank); 1 keeps the   */
+                                     /* fixed round-robin tournament that the smaller matrices use throughout.     */
+                                     /* Either order gives the same result from call to call                      */
     const uint64_t* stream_ids;      /* HOST array of n_mats Philox stream ids, or NULL for stream_base + j: lets */
                                      /* one call encode the gradients of several workers (stream = worker, layer) */
                                      /* and produce the messages that separate calls would                        */

@@ -33,6 +33,9 @@
 // workgroups the two-sided update C <- D^T C D, Tgs <- D^T Tgs of the previous tick (twosided_tile in
 // svd_common.h; D = the block rotations of that round).  C alternates between two buffers by tick
 // parity and every pair problem brings its own 64x64 block up to date (svd_eig.hip, step 1).
+// Which blocks form the pairs of a Gram-space tick is read from a table that a further workgroup of the
+// launch before has written: the heaviest off-diagonal blocks first (GS_WINDOW in svd_common.h), or the
+// rounds of the fixed tournament.
 #include <cfloat>
 #include <algorithm>
 #include <cmath>

@@ -157,13 +157,30 @@ def test_gram_space_graded_spectrum():
 
 
 @pytest.mark.parametrize("options", [dict(full_period=1), dict(full_period=3), dict(max_inner_sweeps=2),
-                                     dict(stop_cosine=3e-5)])
+                                     dict(stop_cosine=3e-5), dict(block_order=1)])
 def test_jacobi_schedule_options_reach_the_same_decomposition(options):
     mats = inputs.resnet18_layer_set(2, shapes=[(128, 576), (512, 256), (512, 1024)])
     msgs, per, status, sweeps = encode(mats, 3.0, 13, **options)
     assert status == 0 and sweeps <= 12
     for j, G in enumerate(mats):
         full_parity(G, 3.0, 13, j, msgs[j], *per[j])
+
+
+def test_block_pairs_by_weight_need_fewer_sweeps_than_the_tournament():
+    # Gram space, a noise-dominated gradient: pairing the blocks of every tick by the weight of their off-diagonal
+    # block reaches the same decomposition in fewer sweeps than the fixed tournament; the result of either order is
+    # the same from call to call
+    G = inputs.resnet18_layer_set(3, shapes=[(512, 2304)])[0]
+    counts = {}
+    for order in (0, 1):
+        msgs, per, status, _ = encode([G], 3.0, 17, block_order=order)
+        assert status == 0
+        counts[order] = ctx().svd_sweeps(1)[0]
+        full_parity(G, 3.0, 17, 0, msgs[0], *per[0])
+        again, per2, status, _ = encode([G], 3.0, 17, block_order=order)
+        np.testing.assert_array_equal(per[0][0], per2[0][0])
+        np.testing.assert_array_equal(msgs[0].to_host()["U"], again[0].to_host()["U"])
+    assert counts[0] < counts[1], counts
 
 
 def test_capacity_overflow_is_latched_not_fatal():
