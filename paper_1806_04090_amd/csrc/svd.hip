@@ -169,9 +169,9 @@ __global__ __launch_bounds__(256) void svd_gram(const SvdMat* mats, const Work* 
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 
-    for (int c0 = c_begin; c0 < c_end; c0 += 64) {
-        // (native vector type: an array of the float4 class ended up in scratch memory here)
-        floatx4 ld[FULL ? 8 : 4];
+    // (native vector type: an array of the float4 class ended up in scratch memory here)
+    floatx4 ld[FULL ? 8 : 4];
+    auto fetch = [&](int c0) {
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
             const int lr = lrow + 16 * p;                        // 0..63
@@ -186,6 +186,9 @@ __global__ __launch_bounds__(256) void svd_gram(const SvdMat* mats, const Work* 
                 ld[4 + p] = *(const floatx4*)(W + (size_t)grow * m.ldw + c0 + lc4);
             }
         }
+    };
+    if (c_begin < c_end) fetch(c_begin);
+    for (int c0 = c_begin; c0 < c_end; c0 += 64) {
         __syncthreads();                                         // previous tile fully consumed
 #pragma unroll
         for (int p = 0; p < 4; ++p) *(floatx4*)&tile[lrow + 16 * p][lc4] = ld[p];
@@ -194,6 +197,7 @@ __global__ __launch_bounds__(256) void svd_gram(const SvdMat* mats, const Work* 
             for (int p = 0; p < 4; ++p) *(floatx4*)&tile[PR + lrow + 16 * p][lc4] = ld[4 + p];
         }
         __syncthreads();
+        if (c0 + 64 < c_end) fetch(c0 + 64);                     // the next tile's loads overlap this tile's products
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
             const float4 a = *(const float4*)&tile[qi * BS + l32][h * 32 + 4 * s];
@@ -352,17 +356,24 @@ __global__ __launch_bounds__(256) void svd_rowop(const SvdMat* mats, const Work*
 
     float* rowI = m.W0 + (size_t)bi * BS * m.ldw + c0 + 2 * l32;
     float* rowJ = m.W0 + (size_t)bj * BS * m.ldw + c0 + 2 * l32;
-#pragma unroll 4
+    // every load of the tile is issued before the first product: the kernel is a chain of memory latencies otherwise
+    float xa[32], xb[32], q0[32], q1[32];
+#pragma unroll
     for (int s = 0; s < 32; ++s) {
         const int k = 2 * s + h;                                 // local row of the pair, 0..63
         const float* p = (k < BS ? rowI + (size_t)k * m.ldw : rowJ + (size_t)(k - BS) * m.ldw);
         const float2 x = *(const float2*)p;
-        const float q0 = q[k * PR + l32];                        // (Q^T)[i][k], i in block 0
-        const float q1 = q[k * PR + BS + l32];                   //              i in block 1
-        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(q0, x.x, acc[0][0], 0, 0, 0);
-        acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(q0, x.y, acc[1][0], 0, 0, 0);
-        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(q1, x.x, acc[0][1], 0, 0, 0);
-        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(q1, x.y, acc[1][1], 0, 0, 0);
+        xa[s] = x.x; xb[s] = x.y;
+        q0[s] = q[k * PR + l32];                                 // (Q^T)[i][k], i in block 0
+        q1[s] = q[k * PR + BS + l32];                            //              i in block 1
+    }
+    __builtin_amdgcn_sched_barrier(0);                           // (keeps the loads above the products)
+#pragma unroll
+    for (int s = 0; s < 32; ++s) {
+        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(q0[s], xa[s], acc[0][0], 0, 0, 0);
+        acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(q0[s], xb[s], acc[1][0], 0, 0, 0);
+        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(q1[s], xa[s], acc[0][1], 0, 0, 0);
+        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(q1[s], xb[s], acc[1][1], 0, 0, 0);
     }
 #pragma unroll
     for (int ib = 0; ib < 2; ++ib) {
