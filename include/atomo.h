@@ -119,7 +119,9 @@ typedef struct atomo_svd_options {
                                      /* default; one or two rotate and the last confirms), and their               */
                                      /* atomo_svd_sweeps count is the number of passes that rotated                */
     float   stop_cosine;             /* default 1e-4 (0 = default): stop after the first sweep whose largest */
-                                     /* |<a_i,a_j>| / (|a_i||a_j|), measured before rotating, is below */
+                                     /* |<a_i,a_j>| / (|a_i||a_j|), measured before rotating, is below; matrices   */
+                                     /* that iterate on their Gram matrix stop once the Gram matrix formed afresh  */
+                                     /* from the rotated data has no cosine above it                               */
     int32_t max_inner_sweeps;        /* default 1 (0 = default): most Jacobi sweeps per 64x64 block-pair problem */
     float   inner_reduction;         /* default 0.01 (0 = default): a block-pair problem stops sweeping once */
                                      /* its largest |cos| is below inner_reduction x the value it started at */

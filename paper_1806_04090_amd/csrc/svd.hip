@@ -27,7 +27,7 @@
 // the threshold are the accumulated rotations applied to the data as one contraction W <- Tgs * W
 // (svd_apply, MFMA).  fp32 rounding makes C drift from the true Gram matrix of the rotated rows, so
 // after every application C is formed afresh from the data (svd_gram<true> again); the matrix is
-// finished when that fresh C is diagonal to a quarter of the threshold, otherwise the sweeps continue
+// finished when that fresh C is diagonal to the threshold, otherwise the sweeps continue
 // from it.  The O(M r^2) work thus happens in two or three large contractions instead of in every
 // round.  A Gram-space tick is one launch of svd_eig: the pair problems of the tick, and as extra
 // workgroups the two-sided update C <- D^T C D, Tgs <- D^T Tgs of the previous tick (twosided_tile in
@@ -740,7 +740,7 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     const float stop_cosine = opt && opt->stop_cosine > 0.0f ? opt->stop_cosine : 1e-4f;
     const int max_inner = opt && opt->max_inner_sweeps > 0 ? opt->max_inner_sweeps : 1;
     const float inner_reduction = opt && opt->inner_reduction > 0.0f ? opt->inner_reduction : 0.01f;
-    const float fresh_stop = 0.25f * stop_cosine;
+    const float fresh_stop = stop_cosine;
     const int full_period = opt && opt->full_period > 0 ? opt->full_period : 8;
     const int cyclic = opt && opt->block_order == 1 ? 1 : 0;
 

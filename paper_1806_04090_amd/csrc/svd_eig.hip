@@ -517,42 +517,37 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
     }
 
     // 5. one Newton-Schulz step  Q <- Q (1.5 I - 0.5 Q^T Q): removes the drift that thousands of
-    //    fp32 rotations leave in the orthogonality of Q (waves 0..3, one 32x32 quadrant each)
-    const int qi = (wave >> 1) & 1, qj = wave & 1, h = lane >> 5, l32 = lane & 31;
-    floatx16 acc;
+    //    fp32 rotations leave in the orthogonality of Q.  Every wave owns one 16x16 tile of the 64x64 result
+    //    (v_mfma_f32_16x16x4f32: lane l holds A[l & 15][l >> 4] and B[l >> 4][l & 15], and four results
+    //    C[4 (l >> 4) + v][l & 15]).
+    {
+        const int ti = wave >> 2, tj = wave & 3, lo = lane & 15, hi = lane >> 4;
+        floatx4 t4 = {0.0f, 0.0f, 0.0f, 0.0f};
+        const int ci = qcol(ti * 16 + lo), cj = qcol(tj * 16 + lo);
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-    if (wave < 4) {
-        const int ci = qcol(qi * BS + l32), cj = qcol(qj * BS + l32);
-#pragma unroll
-        for (int k = 0; k < PR; k += 2) {
-            const float a = Qc[(k + h) * ELD + ci];              // (Q^T)[i][k]
-            const float bq = Qc[(k + h) * ELD + cj];             // Q[k][j]
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bq, acc, 0, 0, 0);
+        for (int k = 0; k < PR; k += 4) {
+            const float a = Qc[(k + hi) * ELD + ci];             // (Q^T)[i][k]
+            const float bq = Qc[(k + hi) * ELD + cj];            // Q[k][j]
+            t4 = __builtin_amdgcn_mfma_f32_16x16x4f32(a, bq, t4, 0, 0, 0);
         }
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int i = qi * BS + 8 * (v >> 2) + 4 * h + (v & 3), j = qj * BS + l32;
-            F0[i * ELD + j] = (i == j ? 1.5f : 0.0f) - 0.5f * acc[v];
+        for (int v = 0; v < 4; ++v) {
+            const int i = ti * 16 + 4 * hi + v, j = tj * 16 + lo;
+            F0[i * ELD + j] = (i == j ? 1.5f : 0.0f) - 0.5f * t4[v];
         }
-    }
-    __syncthreads();
-    if (wave < 4) {
+        __syncthreads();
+        floatx4 q4 = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-#pragma unroll
-        for (int k = 0; k < PR; k += 2) {
-            const float a = Qc[(qi * BS + l32) * ELD + qcol(k + h)];   // Q[i][k]
-            const float bq = F0[(k + h) * ELD + qj * BS + l32];        // F[k][j]
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bq, acc, 0, 0, 0);
+        for (int k = 0; k < PR; k += 4) {
+            const float a = Qc[(ti * 16 + lo) * ELD + qcol(k + hi)];   // Q[i][k]
+            const float bq = F0[(k + hi) * ELD + tj * 16 + lo];        // F[k][j]
+            q4 = __builtin_amdgcn_mfma_f32_16x16x4f32(a, bq, q4, 0, 0, 0);
         }
         // 6. write Q with its columns permuted to their destination rows
         float* qout = m.Q + ((size_t)(m.gs ? (step & 1) * m.npairs : 0) + wk.a) * QSZ;
+        const int dj = dest[tj * 16 + lo];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int i = qi * BS + 8 * (v >> 2) + 4 * h + (v & 3), j = qj * BS + l32;
-            qout[i * PR + dest[j]] = acc[v];
-        }
+        for (int v = 0; v < 4; ++v) qout[(ti * 16 + 4 * hi + v) * PR + dj] = q4[v];
     }
 
     if (tid == 0) {
