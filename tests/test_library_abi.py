@@ -61,3 +61,41 @@ def test_no_fallback_without_a_gpu():
         pytest.skip("a GPU is visible")
     with pytest.raises(RuntimeError):
         binding.Context(0)
+
+
+def test_struct_layouts_match_the_header(tmp_path):
+    """The ctypes mirrors in the binding against include/atomo.h as the host C compiler lays it out."""
+    import shutil
+    import subprocess
+    cc = shutil.which("gcc") or shutil.which("cc")
+    if cc is None:
+        pytest.skip("no host C compiler")
+    structs = [binding.atomo_mat, binding.atomo_svd_msg, binding.atomo_ew_msg, binding.atomo_lq_msg,
+               binding.atomo_svd_options]
+    lines = ["#include <stdio.h>", "#include <stddef.h>", '#include "atomo.h"', "int main(void) {"]
+    for st in structs:
+        lines.append(f'  printf("{st.__name__} size %zu\\n", sizeof({st.__name__}));')
+        for name, _ in st._fields_:
+            lines.append(f'  printf("{st.__name__} {name} %zu\\n", offsetof({st.__name__}, {name}));')
+    lines += ["  return 0;", "}"]
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.run([cc, "-std=c99", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split("\n")
+    seen = {}
+    for line in out:
+        if line:
+            st, field, value = line.split()
+            seen[(st, field)] = int(value)
+    for st in structs:
+        assert seen[(st.__name__, "size")] == C.sizeof(st), st.__name__
+        for name, _ in st._fields_:
+            assert seen[(st.__name__, name)] == getattr(st, name).offset, (st.__name__, name)
+    # and the header declares no field that the binding leaves out
+    text = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "atomo.h")).read(), flags=re.S)
+    for st in structs:
+        body = re.search(r"typedef struct %s \{(.*?)\} %s;" % (st.__name__, st.__name__), text, flags=re.S).group(1)
+        declared = [part.replace("*", " ").split()[-1] for stmt in body.split(";") if stmt.strip()
+                    for part in stmt.split(",")]
+        assert declared == [name for name, _ in st._fields_], st.__name__
