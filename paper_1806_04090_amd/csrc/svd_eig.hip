@@ -104,8 +104,8 @@ __device__ inline float2 pair_rotation(const float* A, int k, float z2)
 // Dynamic order: a greedy maximum-weight matching on the block weights of the C after tick - 1 ticks (written by the
 // two-sided update of the previous launch), heaviest pair first, ties to the lower block indices; the pairs of
 // ticks tick - 1 and tick count as zero, their rotations are not in those weights yet.  Without such weights
-// (first ticks, `cyclic`) the round of the fixed tournament.  wsh: nb2 x nb2 floats, redw / rede: 16 words each.
-__device__ inline void plan_next_tick(const SvdMat& m, int tick, int cyclic, float* wsh, float* redw, int* rede)
+// (first ticks, `cyclic`) the round of the fixed tournament.  wsh: nb2 x (nb2 + 1) floats, ptr / partner: 64 words each.
+__device__ inline void plan_next_tick(const SvdMat& m, int tick, int cyclic, float* wsh, int* ptr, int* partner)
 {
     if (!m.gs || m.state[ST_DONE_AT] != 0) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -128,58 +128,73 @@ __device__ inline void plan_next_tick(const SvdMat& m, int tick, int cyclic, flo
     }
     const float* W = m.bw + (size_t)((tick - 1) & 1) * nb * nb;
     auto usable = [](float w) { return (w > 0.0f && w <= FLT_MAX) ? w : 0.0f; };
+    const int ld = nb + 1;                                       // odd row stride: a column is spread over the LDS banks
     for (int e = tid; e < nb * nb; e += NT) {
         const int i = e / nb, j = e - i * nb;
-        wsh[e] = i < j ? usable(W[i * nb + j]) + usable(W[j * nb + i]) : 0.0f;
+        wsh[i * ld + j] = i != j ? usable(W[i * nb + j]) + usable(W[j * nb + i]) : 0.0f;
     }
+    if (tid < PR) { partner[tid] = -1; ptr[tid] = -1; }
     __syncthreads();
     for (int q = tid; q < 2 * np; q += NT) {
         const int* s = m.sched + ((size_t)((q < np ? tick : tick + 2) % 3) * np + (q < np ? q : q - np)) * 2;
-        wsh[s[0] * nb + s[1]] = 0.0f;
+        wsh[s[0] * ld + s[1]] = 0.0f;
+        wsh[s[1] * ld + s[0]] = 0.0f;
     }
     __syncthreads();
-    // this thread's candidates (i < j), at most MAX_R / BS squared over NT of them
-    constexpr int PER = (MAX_R / BS) * (MAX_R / BS) / NT;
-    float cw[PER];
-    int ci[PER], cj[PER];
+    // The greedy matching (heaviest edge first; edges ordered by weight, then by lower block indices) is the union of
+    // the locally dominant edges of successive rounds: an edge is taken when each of its two blocks is the other's
+    // best free partner, which holds at least for the best free edge of all, so every round makes progress.
+    // Sixteen threads per block look at four candidates each.
+    const int v = tid >> 4, helper = tid & 15;
+    float cw[4];
 #pragma unroll
-    for (int k = 0; k < PER; ++k) {
-        const int e = tid + NT * k;
-        const int i = e < nb * nb ? e / nb : 0, j = e < nb * nb ? e - i * nb : 0;
-        ci[k] = i; cj[k] = j;
-        cw[k] = i < j ? wsh[e] : -1.0f;                        // -1: no candidate
+    for (int k = 0; k < 4; ++k) {
+        const int j = helper + 16 * k;
+        cw[k] = (v < nb && j < nb && j != v) ? wsh[v * ld + j] : -1.0f;      // -1: no candidate
     }
-    unsigned long long used = 0ull;
-    for (int it = 0; it < np; ++it) {
+    for (int round = 0; round < np; ++round) {
+        const bool v_free = v < nb && partner[v] < 0;
         float bw = -1.0f;
-        int be = 0x7fffffff;
+        int be = 0x7fffffff, bj = -1;
+        if (v_free) {
 #pragma unroll
-        for (int k = 0; k < PER; ++k) {
-            const bool free_pair = cw[k] >= 0.0f && !((used >> ci[k]) & 1ull) && !((used >> cj[k]) & 1ull);
-            const int e = tid + NT * k;
-            if (free_pair && (cw[k] > bw || (cw[k] == bw && e < be))) { bw = cw[k]; be = e; }
+            for (int k = 0; k < 4; ++k) {
+                const int j = helper + 16 * k;
+                if (cw[k] >= 0.0f && partner[j] < 0) {
+                    const int e = v < j ? v * nb + j : j * nb + v;
+                    if (cw[k] > bw || (cw[k] == bw && e < be)) { bw = cw[k]; be = e; bj = j; }
+                }
+            }
         }
-        for (int o = 32; o > 0; o >>= 1) {
+        for (int o = 8; o > 0; o >>= 1) {                        // the sixteen helpers of a block sit in one wave
             const float ow = __shfl_xor(bw, o);
-            const int oe = __shfl_xor(be, o);
-            if (ow > bw || (ow == bw && oe < be)) { bw = ow; be = oe; }
+            const int oe = __shfl_xor(be, o), oj = __shfl_xor(bj, o);
+            if (ow > bw || (ow == bw && oe < be)) { bw = ow; be = oe; bj = oj; }
         }
-        if (lane == 0) { redw[wave] = bw; rede[wave] = be; }
+        if (helper == 0 && v < nb) ptr[v] = v_free ? bj : -1;     // (last read before the barrier that ended the round before)
         __syncthreads();
-        bw = -1.0f; be = 0x7fffffff;
-        for (int w = 0; w < NT / 64; ++w) {
-            const float ow = redw[w];
-            const int oe = rede[w];
-            if (ow > bw || (ow == bw && oe < be)) { bw = ow; be = oe; }
-        }
-        __syncthreads();
-        if (be == 0x7fffffff) break;                             // cannot happen: an even number of free blocks is left
-        const int i = be / nb, j = be - i * nb;
-        used |= (1ull << i) | (1ull << j);
-        if (tid == 0) {
-            sch[2 * it] = i; sch[2 * it + 1] = j;
-            whr[i] = 2 * it; whr[j] = 2 * it + 1;
-        }
+        bool taken = false;
+        if (helper == 0 && v_free && bj >= 0 && ptr[bj] == v) { partner[v] = bj; taken = true; }
+        if (!__syncthreads_or(taken)) break;                     // (also orders the writes of partner[] before the next round)
+    }
+    // pair numbers in the order of each pair's lower block; blocks left over (cannot happen) pair up in order
+    if (wave != 0) return;
+    const int mine = lane < nb ? partner[lane] : lane;           // lanes beyond the blocks: out of the way
+    const unsigned long long unmatched = __ballot(lane < nb && mine < 0);
+    int mate = mine;
+    if (lane < nb && mine < 0) {
+        const int rank = __popcll(unmatched & ((1ull << lane) - 1ull));
+        // the r-th unmatched block pairs with the (r ^ 1)-th
+        int seen = 0;
+        for (int b2 = 0; b2 < nb; ++b2)
+            if ((unmatched >> b2) & 1ull) { if (seen == (rank ^ 1)) mate = b2; ++seen; }
+    }
+    const bool leader = lane < nb && mate > lane;
+    const unsigned long long leaders = __ballot(leader);
+    if (leader) {
+        const int k = __popcll(leaders & ((1ull << lane) - 1ull));
+        sch[2 * k] = lane; sch[2 * k + 1] = mate;
+        whr[lane] = 2 * k; whr[mate] = 2 * k + 1;
     }
 }
 
@@ -203,7 +218,7 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
 
     const int two_wgs = (n_two + TILES_PER_WG - 1) / TILES_PER_WG;
     if ((int)blockIdx.x >= n_eig + two_wgs) {                     // the last workgroups plan the next tick
-        plan_next_tick(mats[plan_work[(int)blockIdx.x - n_eig - two_wgs].mat], step, cyclic, As[0], red, dest);
+        plan_next_tick(mats[plan_work[(int)blockIdx.x - n_eig - two_wgs].mat], step, cyclic, As[0], dest, sits_out);
         return;
     }
     if ((int)blockIdx.x >= n_eig) {
