@@ -337,7 +337,7 @@ __global__ __launch_bounds__(256) void svd_rowop(const SvdMat* mats, const Work*
 {
     const Work wk = work[blockIdx.x];
     const SvdMat m = mats[wk.mat];
-    if (m.gs || skip_step(m, tick, max_sweeps)) return;
+    if (m.gs || skip_step(m, tick, max_sweeps) || m.idle[wk.a]) return;
     int bi, bj;
     pair_blocks(m.nb2, tick % m.R, wk.a, bi, bj);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -635,7 +635,7 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
             m.Mp = m.M; m.ldw = 0; m.nb2 = 0; m.rows_alloc = THIN_R; m.R = 1; m.npairs = 0; m.nchu = 0; m.gs = 0;
             m.ntiles = 0; m.ldc = 0;
             m.W0 = nullptr; m.W1 = nullptr; m.CT = nullptr; m.CT2 = nullptr; m.cref = nullptr; m.cref0 = nullptr;
-            m.sched = nullptr; m.where = nullptr; m.bw = nullptr; m.dd = nullptr;
+            m.sched = nullptr; m.where = nullptr; m.bw = nullptr; m.dd = nullptr; m.idle = nullptr;
             m.gram = carve.take<float>((size_t)m.nchg * THIN_R * THIN_R);
             m.Q = carve.take<float>(2 * THIN_R * THIN_R);
             m.B = carve.take<float>((size_t)m.M * m.r);
@@ -673,6 +673,7 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
         m.CT2 = m.gs ? carve.take<float>((size_t)m.rows_alloc * m.ldc) : nullptr;
         m.gram = carve.take<float>((size_t)(m.gs ? m.ntiles : m.npairs) * m.nchg * QSZ);
         m.Q = carve.take<float>((size_t)(m.gs ? 2 : 1) * m.npairs * QSZ);
+        m.idle = m.gs ? nullptr : carve.take<int>(m.npairs);
         m.state = carve.take<int>(ST_WORDS);
         m.sig_raw = carve.take<float>(m.rows_alloc);
         m.cref = m.gs ? carve.take<float>(m.rows_alloc) : nullptr;

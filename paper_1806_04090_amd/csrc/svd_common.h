@@ -96,6 +96,7 @@ struct SvdMat {
     float* CT2;              // Gram space: second buffer of the same shape; its C half alternates with CT's by tick parity
     int ldw, ldc, r, M, Mp, rows_alloc;
     int nb2, R, npairs, nchg, nchu, gs, ntiles;
+    int* idle;               // data space: [npairs] 1 if the pair problem of the running tick left its rows as they are
     float* gram;             // data space: [npairs][nchg][64*64]; Gram space: [ntiles][nchg][64*64]
     float* Q;                // [npairs][64*64]; Gram space: [2][npairs][64*64], indexed by tick parity
     int* state;              // [ST_WORDS]
@@ -201,6 +202,10 @@ __device__ inline float* c_of_parity(const SvdMat& m, int parity)
     float* const c1 = m.CT2;
     return (parity & 1) ? c1 : c0;
 }
+
+// Data space: a pair whose largest cosine is below this fraction of stop_cosine is left alone (no Jacobi steps, and no
+// row update if its rows are in order already): the sweep that only confirms convergence then costs its Gram matrices.
+constexpr float DS_LEAVE = 0.1f;
 
 constexpr int TLD = PR + 1;      // row stride of a 64x64 tile staged in LDS
 

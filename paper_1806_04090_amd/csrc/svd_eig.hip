@@ -408,7 +408,8 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
     }
     int cur = 0;
     int inner_done = 0;
-    if (entry.x > 0.0f) {
+    const bool leave = !m.gs && entry.x <= DS_LEAVE * stop_cosine;
+    if (entry.x > 0.0f && !leave) {
         // inner target: a fixed factor below what came in is enough for the outer iteration
         const float inner_stop = fmaxf(2e-7f, inner_reduction * entry.x);
         // One step: read buffer X, rotate, write buffer Y with the slots advanced.  Written as a lambda
@@ -514,6 +515,12 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
 
     // Gram space: the reference values follow the rows, ref'_j = sum_i Q_ij^2 ref_i
     __syncthreads();                                             // dest[] is complete
+    if (!m.gs) {
+        // a pair that was left alone and whose rows are in order needs no row update
+        const bool in_place = leave && (tid >= PR || dest[tid] == tid);
+        const int all_in_place = __syncthreads_and(in_place);
+        if (tid == 0) m.idle[wk.a] = all_in_place;
+    }
     if (m.gs && tid < PR) {
         const int cj = qcol(tid);
         float r = 0.0f, r0 = 0.0f;
