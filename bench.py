@@ -120,8 +120,8 @@ def paper_form_flops(shapes, sweeps):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-entrywise", action="store_true", help="skip the entry-wise and 16-worker decode legs")
     ap.add_argument("--calibration-copy", action="store_true",
