@@ -298,6 +298,9 @@ def aggregate_decode_leg(ctx, torch, binding, inputs, shapes, s, seed, workers=1
         binding.atomo_encode_svd(ctx, all_mats, s, seed, 0, msgs=flat_msgs, stream_ids=ids)
     torch.cuda.synchronize()
     enc16 = (time.perf_counter() - t0) / 3
+    ctx.status()
+    sweeps16 = ctx.svd_sweeps(len(all_mats))
+    paper16 = paper_form_flops(list(shapes) * workers, sweeps16)
     del all_mats
     msgs = [flat_msgs[w * len(shapes):(w + 1) * len(shapes)] for w in range(workers)]
     groups = [[msgs[w][j] for w in range(workers)] for j in range(len(shapes))]
@@ -332,6 +335,9 @@ def aggregate_decode_leg(ctx, torch, binding, inputs, shapes, s, seed, workers=1
             "hbm_frac": round(nbytes / (gpu_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
             "encode_16_gradients_one_call_ms": round(enc16 * 1e3, 2),
             "encode_16_gradients_elements_per_s": workers * sum(m * n for m, n in shapes) / enc16,
+            # the same sweeps in the textbook data-space form, sweeps x (8 M r^2 + 4 r^3), over the measured time
+            "encode_16_gradients_paper_form_tflops": round(paper16 / enc16 / 1e12, 2),
+            "encode_16_gradients_frac_of_fp32_mfma_peak_paper_form": round(paper16 / enc16 / 1e12 / PEAK_FP32_MFMA_TFLOPS, 4),
             "fused_sgd_update_gpu_us_per_call": round(apply_ms * 1e3, 2),
             "fused_sgd_update_hbm_gbs": round(2.0 * nbytes / (apply_ms * 1e-3) / 1e9, 1)}
 
