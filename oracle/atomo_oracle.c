@@ -102,44 +102,45 @@ static int by_mag_desc(const void* a, const void* b)
 
 /*
  * p = argmin sum lambda_i^2/p_i  s.t. 0 < p_i <= 1, sum p_i = s   (eq. (opt_prob1)).
- * Steps of Algorithm 1 in the paper's order, after sorting |lambda| descending;
- * the result is scattered back to the caller's order.  Readings taken:
- *  - the sums printed in the test and in the update run over |lambda_j|, j = i..n
- *    (the tail sum), as the KKT appendix's closed form for p_i confirms;
- *  - s is decremented in place, so the test uses the budget that remains;
- *  - lambda_i = 0 gets p_i = 0 (KKT appendix, consequence 2); a tail sum of zero
- *    therefore ends the scan with zeros instead of dividing by it.  With
+ * Algorithm 1 reaches this minimiser exactly, and the KKT appendix writes it in
+ * closed form (eq. (p_i)): with |lambda| sorted descending and
+ *     T_k = sum_{j > k} |lambda_j|           (what the atoms after the first k add up to),
+ * n_s is the smallest k for which the largest remaining atom fits under the
+ * remaining budget,  |lambda_{k+1}| (s - k) <= T_k,  and then
+ *     p_i = 1                               for the n_s largest atoms,
+ *     p_i = |lambda_i| (s - n_s) / T_{n_s}  for the others.
+ * The oracle is that definition written out: sort, tail sums, search for n_s,
+ * one pass that fills p (scattered back to the caller's order).  Readings:
+ *  - the sums in Algorithm 1's test and update run over |lambda_j| (the tail
+ *    sum), as eq. (p_i) confirms, and the budget in the test is what remains
+ *    after the atoms already set to 1;
+ *  - lambda_i = 0 gets p_i = 0 (KKT appendix, consequence 2): once T_k = 0 only
+ *    zeros remain and the search stops there instead of dividing by zero.  With
  *    s >= #nonzeros every nonzero atom gets p = 1 (KKT appendix, consequence 1).
- * Returns n_s, the number of atoms with p forced to 1 by the else-branch.
+ * Returns n_s.
  */
 int64_t oracle_probabilities(const double* lambda, int64_t n, double s, double* p)
 {
     if (n <= 0) return 0;
     mag_pos* a = (mag_pos*)malloc((size_t)n * sizeof(mag_pos));
-    double* tail = (double*)malloc((size_t)(n + 1) * sizeof(double));
+    double* T = (double*)malloc((size_t)(n + 1) * sizeof(double));
     for (int64_t i = 0; i < n; ++i) { a[i].mag = fabs(lambda[i]); a[i].pos = i; }
     qsort(a, (size_t)n, sizeof(mag_pos), by_mag_desc);
-    tail[n] = 0.0;
-    for (int64_t i = n - 1; i >= 0; --i) tail[i] = tail[i + 1] + a[i].mag;   /* sum_{j>=i} |lambda_j| */
+    T[n] = 0.0;
+    for (int64_t k = n - 1; k >= 0; --k) T[k] = T[k + 1] + a[k].mag;      /* T[k] = sum of a[k..n) */
 
-    int64_t forced = 0;
-    int64_t i = 0;
-    while (i < n) {
-        if (tail[i] == 0.0) {                       /* only zeros remain */
-            for (int64_t k = i; k < n; ++k) p[a[k].pos] = 0.0;
-            i = n;
-        } else if (a[i].mag * s <= tail[i]) {
-            for (int64_t k = i; k < n; ++k) p[a[k].pos] = a[k].mag * s / tail[i];
-            i = n;
-        } else {
-            p[a[i].pos] = 1.0;
-            s -= 1.0;
-            ++forced;
-            ++i;
-        }
+    /* n_s: first k with T_k = 0 (nothing but zeros left) or |lambda_{k+1}| (s - k) <= T_k; k = n ends it */
+    int64_t n_s = 0;
+    while (n_s < n && T[n_s] > 0.0 && a[n_s].mag * (s - (double)n_s) > T[n_s]) ++n_s;
+
+    const double budget = s - (double)n_s;
+    const double rest = n_s < n ? T[n_s] : 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        if (i < n_s) p[a[i].pos] = 1.0;
+        else p[a[i].pos] = rest > 0.0 ? a[i].mag * budget / rest : 0.0;
     }
-    free(a); free(tail);
-    return forced;
+    free(a); free(T);
+    return n_s;
 }
 
 /* ------------------------------------------------------------------------ */
