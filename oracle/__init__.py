@@ -18,15 +18,22 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "atomo_oracle.c")
-_LIB = os.path.join(_HERE, "libatomo_oracle.so")
+# ATOMO_ORACLE_SANITIZE=undefined builds and loads a second library with gcc's undefined-behaviour sanitizer
+# (traps abort the process), which loads into a running interpreter as it is; the address sanitizer needs its
+# runtime first in the process and is run on sanitize_driver.c instead (tests/test_oracle_sanitizers.py).
+_SANITIZE = os.environ.get("ATOMO_ORACLE_SANITIZE", "")
+_LIB = os.path.join(_HERE, "libatomo_oracle_ubsan.so" if _SANITIZE == "undefined" else "libatomo_oracle.so")
 
 
 def build(force: bool = False) -> str:
     """Compile the C oracle with gcc (a second or two).  Returns the library path."""
+    if _SANITIZE not in ("", "undefined"):
+        raise RuntimeError("ATOMO_ORACLE_SANITIZE supports only 'undefined'")
     stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
     if force or stale:
         tmp = _LIB + ".tmp.%d" % os.getpid()
-        subprocess.check_call(["gcc", "-O2", "-fPIC", "-shared", "-o", tmp, _SRC, "-lm"])
+        flags = ["-O2"] if not _SANITIZE else ["-O1", "-g", "-fsanitize=undefined", "-fno-sanitize-recover=all"]
+        subprocess.check_call(["gcc", *flags, "-fPIC", "-shared", "-o", tmp, _SRC, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
 
