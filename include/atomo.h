@@ -20,8 +20,12 @@
  *    structs (atomo_mat, atomo_svd_msg, atomo_ew_msg) and arrays of them are
  *    HOST memory; they are read during the call and may be freed afterwards.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *    Work is enqueued on it; calls do not wait for the GPU.  Results are
+ *    Work is enqueued on it; calls do not wait for the results.  Results are
  *    valid once the stream has reached the end of the enqueued work.
+ *    Descriptor tables travel to the device through a ring of eight pinned
+ *    staging buffers owned by the context: a call that needs a buffer whose
+ *    previous copy (eight uploads ago) has not been executed yet waits for
+ *    that copy, and for nothing else.
  *  - The caller owns every input, output and message buffer.  Inputs are never
  *    modified.  The context owns a device workspace that grows on demand
  *    (growing it allocates, which synchronises the device; atomo_reserve
@@ -67,8 +71,8 @@ typedef struct atomo_mat {
     const float* data;               /* device */
 } atomo_mat;
 
-/* One Spectral-ATOMO message: the kept singular triplets of one matrix ("weighted singular vectors
- * sampled from the true gradient", Section 6).  Atom index 0 is the largest singular value.
+/* One Spectral-ATOMO message: the kept singular triplets of one matrix with their weights (what a worker
+ * sends to the parameter server in Section 6).  Atom index 0 is the largest singular value.
  * All pointers are caller-owned device memory. */
 typedef struct atomo_svd_msg {
     int32_t rows, cols;              /* shape of the encoded matrix                                   */
@@ -77,8 +81,8 @@ typedef struct atomo_svd_msg {
     int32_t* idx;                    /* [capacity] atom indices, ascending                           */
     float*   w;                      /* [capacity] weights sigma_i / p_i; NULL selects the folded form below */
     float*   U;                      /* [capacity][rows]  U[k*rows + i] = (u of k-th kept atom)_i, unit norm;  */
-                                     /* folded form (w == NULL): (sigma_i / p_i) u, the "weighted singular     */
-                                     /* vectors" of Section 6, rows + cols reals per atom as in the cost        */
+                                     /* folded form (w == NULL): (sigma_i / p_i) u, the weight carried by the   */
+                                     /* left vector (Section 6), rows + cols reals per atom as in the cost      */
                                      /* s(n+m) of Table "matrix_sparse"                                         */
     float*   V;                      /* [capacity][cols]  V[k*cols + j] = (v of k-th kept atom)_j, unit norm */
 } atomo_svd_msg;
@@ -162,11 +166,6 @@ int atomo_entrywise_workspace_bytes(int64_t n, size_t* bytes /*host*/);
  * largest number of Jacobi sweeps any matrix of the last atomo_encode_svd took. */
 int atomo_status(atomo_ctx* ctx, void* stream, int32_t* sweeps /*host, optional*/);
 int atomo_last_hip_error(const atomo_ctx* ctx);
-
-/* Work counters as read by the most recent atomo_status call (host-side only): how many 64x64
- * block-pair eigenproblems the Jacobi SVD solved since the status call before it, and how many
- * Jacobi steps (32 disjoint plane rotations each) those took in total. */
-int atomo_last_counters(const atomo_ctx* ctx, int32_t* pair_visits /*host*/, int32_t* jacobi_steps /*host*/);
 
 /* Waits for `stream`, then copies the number of Jacobi sweeps each matrix of the last
  * atomo_encode_svd took into sweeps[0 .. n_mats) (HOST) and, if refreshes is not NULL, how many
@@ -259,32 +258,6 @@ int atomo_decode_svd_batch(atomo_ctx* ctx, const atomo_svd_msg* msgs, const int3
  */
 int atomo_apply_svd_batch(atomo_ctx* ctx, const atomo_svd_msg* msgs, const int32_t* first, int n_out,
                           float alpha, float* const* params, const int64_t* lds, void* stream);
-
-/* -------- measurement -------------------------------------------------------------------------- */
-
-/* Kernel classes whose GPU time can be measured with HIP events (for benchmarks; not part of the
- * method).  While profiling is on, every launch of these kernels is bracketed by two events on the
- * caller's stream, which costs a few microseconds per launch. */
-enum {
-    ATOMO_K_SVD_PREPARE = 0, ATOMO_K_SVD_GRAM, ATOMO_K_SVD_EIG, ATOMO_K_SVD_UPDATE, ATOMO_K_SVD_REFRESH,
-    ATOMO_K_SVD_FINALIZE,
-    ATOMO_K_DECODE_SVD, ATOMO_K_EW_HIST, ATOMO_K_EW_SOLVE, ATOMO_K_EW_SAMPLE, ATOMO_K_EW_DECODE,
-    ATOMO_K_SVD_THIN,
-    ATOMO_K_COUNT
-};
-
-/* Switches event bracketing on (enable != 0) or off and discards what was collected. */
-int atomo_profile_enable(atomo_ctx* ctx, int enable);
-
-/* Waits for the recorded events, then adds to total_ms[k] / launches[k] (HOST arrays of
- * ATOMO_K_COUNT entries, caller-initialised) the GPU time and the number of bracketed launches of
- * each kernel class since the last read. */
-int atomo_profile_read(atomo_ctx* ctx, double* total_ms, int64_t* launches);
-
-/* What a loop of nothing but fp32 matrix-core instructions (v_mfma_f32_32x32x2f32, four independent accumulators
- * per wave, 16 waves per compute unit) reaches on this GPU, in TFLOP/s: the achievable figure to set beside the
- * published peak.  Runs two short kernels on `stream` and waits for them (about a millisecond). */
-int atomo_measure_mfma_fp32(atomo_ctx* ctx, double* tflops /*host*/, void* stream);
 
 #ifdef __cplusplus
 }

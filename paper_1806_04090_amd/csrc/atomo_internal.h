@@ -8,6 +8,7 @@
 #include <vector>
 
 #include "../../include/atomo.h"
+#include "../../include/atomo_bench.h"
 
 namespace atomo {
 

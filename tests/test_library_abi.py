@@ -1,5 +1,5 @@
-"""CPU-side checks of the C ABI: the library loads, exports what include/atomo.h declares, and the
-host-side argument validation answers without touching a GPU."""
+"""CPU-side checks of the C ABI: the library loads, exports what include/atomo.h and include/atomo_bench.h
+declare, and the host-side argument validation answers without touching a GPU."""
 import ctypes as C
 import os
 import re
@@ -11,8 +11,8 @@ from paper_1806_04090_amd import binding
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "atomo.h")).read()
+def declared_symbols(header="atomo.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(atomo_[a-z_0-9]+)\s*\(", text)))
 
@@ -20,8 +20,11 @@ def declared_symbols():
 def test_every_declared_symbol_is_exported():
     names = declared_symbols()
     assert {"atomo_encode_svd", "atomo_encode_entrywise", "atomo_probabilities", "atomo_decode"} <= set(names)
+    bench = declared_symbols("atomo_bench.h")
+    assert {"atomo_profile_enable", "atomo_profile_read", "atomo_measure_mfma_fp32", "atomo_last_counters"} == set(bench)
+    assert not set(bench) & set(names)                       # the method's header holds no measurement call
     L = binding.lib()
-    for name in names:
+    for name in names + bench:
         assert hasattr(L, name), name
 
 
