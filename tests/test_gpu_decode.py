@@ -35,7 +35,9 @@ def test_svd_decode_matches_oracle(rows, cols, ks):
 
 
 @pytest.mark.parametrize("rows,cols,capacity,ks", [(40, 130, 100, [7, 0, 99, 100, 1, 33, 2, 2, 2, 50, 5, 64]),   # batches of 5 messages
-                                                   (96, 70, 512, [512, 3]),                                     # one message fills the atom list
+                                                   (96, 70, 512, [512, 3]),                                     # the atom list is staged in two pieces
+                                                   (600, 600, 600, [600]),                                      # every atom of a 600 x 600 matrix kept (p = 1)
+                                                   (130, 2048, 130, [130, 129, 1]),
                                                    (33, 33, 6, [5] * 90)])                                      # 85 messages per batch, then 5
 def test_svd_decode_many_messages_across_batches(rows, cols, capacity, ks):
     rng = np.random.default_rng(len(ks) * 7 + rows)

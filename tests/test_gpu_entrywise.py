@@ -101,6 +101,12 @@ def test_determinism_and_multi_message_average():
     out = binding.atomo_decode(ctx(), msgs, scale=0.25).cpu().numpy()
     want = oracle.decode_entrywise([m.to_host() for m in msgs], g.size, scale=0.25)
     np.testing.assert_allclose(out, want, rtol=1e-5, atol=1e-9)
+    # overlapping messages are added in call order, one launch each: the same bits in every run
+    for _ in range(3):
+        again = binding.atomo_decode(ctx(), msgs, scale=0.25).cpu().numpy()
+        assert np.array_equal(out, again)
+    assert (np.count_nonzero(sum((np.bincount(m.to_host()["idx"], minlength=g.size) for m in msgs))) <
+            sum(m.to_host()["count"] for m in msgs))            # the messages do overlap
 
 
 def test_unbiased_over_streams():

@@ -84,6 +84,7 @@ def test_degenerate_inputs_unaligned_pointer_and_average():
     out = binding.atomo_decode(ctx(), msgs, scale=0.2).cpu().numpy()
     want = oracle.decode_lq(hosts, view.numel(), scale=0.2)
     np.testing.assert_allclose(out, want, rtol=1e-6, atol=1e-7)
+    assert np.array_equal(out, binding.atomo_decode(ctx(), msgs, scale=0.2).cpu().numpy())   # same bits in every run
 
 
 def test_capacity_overflow_is_latched():
