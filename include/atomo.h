@@ -56,7 +56,8 @@ typedef enum atomo_status_code {
     ATOMO_ECAPACITY = -2,  /* (atomo_status only) more atoms were kept than a message could hold    */
     ATOMO_ENOCONV = -3,    /* (atomo_status only) the Jacobi SVD stopped at the sweep limit         */
     ATOMO_EHIP = -4,       /* a HIP runtime call failed; atomo_last_hip_error gives its code        */
-    ATOMO_ENOMEM = -5      /* the workspace could not be allocated                                  */
+    ATOMO_ENOMEM = -5,     /* the workspace could not be allocated                                  */
+    ATOMO_ETOOLARGE = -6   /* atomo_encode_entrywise_noalloc: n exceeds what its fixed scratch holds */
 } atomo_status_code;
 
 enum { ATOMO_KIND_SVD = 0, ATOMO_KIND_ENTRYWISE = 1, ATOMO_KIND_LQ = 2 };
@@ -215,6 +216,24 @@ int atomo_encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s
  */
 int atomo_encode_entrywise(atomo_ctx* ctx, const float* g, double s, uint64_t seed, uint64_t stream_id,
                            const atomo_ew_msg* msg /*host*/, float* p_out, void* stream);
+
+/*
+ * atomo_encode_entrywise for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same message, bit for bit; the scratch
+ * memory of the kernels (water-level search state, per-chunk counts, offsets and keep bits) is a fixed array
+ * of 3 MiB that the library holds on every GPU it runs on until the process ends, instead of the context's
+ * growable workspace.  The call allocates nothing (no hipMalloc, hipFree, event or stream creation), on any
+ * path.
+ *   n = msg->n is limited to 2^24 = 16,777,216 elements; a longer gradient returns ATOMO_ETOOLARGE and
+ *   nothing is enqueued.
+ *   All calls on one GPU share that GPU's array, whatever their context or stream: two such calls whose
+ *   kernels overlap in time race on it.  Issue them on one stream, or order the streams.  The array keeps
+ *   the previous call's contents; the call clears what it needs cleared itself, with a kernel.
+ *   atomo_create looks up the array's address on the context's device, so this call does no set-up of its own.
+ *   Event bracketing (atomo_profile_enable) does not cover this call.
+ */
+int atomo_encode_entrywise_noalloc(atomo_ctx* ctx, const float* g, double s, uint64_t seed, uint64_t stream_id,
+                                   const atomo_ew_msg* msg /*host*/, float* p_out, void* stream);
 
 /*
  * l_q quantisation (Section 4, Theorem (lqgrad)): p_i = |g_i| / |g|_q, the variance-optimal entry-wise

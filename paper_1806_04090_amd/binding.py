@@ -18,7 +18,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libatomo.so")
 
-ATOMO_OK, ATOMO_EINVAL, ATOMO_ECAPACITY, ATOMO_ENOCONV, ATOMO_EHIP, ATOMO_ENOMEM = 0, -1, -2, -3, -4, -5
+ATOMO_OK, ATOMO_EINVAL, ATOMO_ECAPACITY, ATOMO_ENOCONV, ATOMO_EHIP, ATOMO_ENOMEM, ATOMO_ETOOLARGE = 0, -1, -2, -3, -4, -5, -6
 ATOMO_KIND_SVD, ATOMO_KIND_ENTRYWISE, ATOMO_KIND_LQ = 0, 1, 2
 
 
@@ -79,6 +79,7 @@ def lib() -> C.CDLL:
                                        C.POINTER(atomo_svd_options), C.POINTER(atomo_svd_msg), vp, vp, vp]
         L.atomo_encode_entrywise.argtypes = [vp, vp, C.c_double, C.c_uint64, C.c_uint64, C.POINTER(atomo_ew_msg),
                                              vp, vp]
+        L.atomo_encode_entrywise_noalloc.argtypes = L.atomo_encode_entrywise.argtypes
         L.atomo_encode_lq.argtypes = [vp, vp, C.c_double, C.c_uint64, C.c_uint64, C.POINTER(atomo_lq_msg), vp, vp]
         L.atomo_decode.argtypes = [vp, C.c_int, vp, C.c_int, C.c_float, vp, C.c_int64, vp]
         L.atomo_decode_svd_batch.argtypes = [vp, C.POINTER(atomo_svd_msg), C.POINTER(C.c_int32), C.c_int, C.c_float,
@@ -91,7 +92,7 @@ def lib() -> C.CDLL:
         L.atomo_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         for name in ("atomo_last_counters", "atomo_svd_sweeps", "atomo_profile_enable", "atomo_profile_read", "atomo_create", "atomo_destroy", "atomo_reserve", "atomo_svd_workspace_bytes",
                      "atomo_entrywise_workspace_bytes", "atomo_status", "atomo_last_hip_error", "atomo_probabilities",
-                     "atomo_encode_svd", "atomo_encode_entrywise", "atomo_encode_lq", "atomo_decode",
+                     "atomo_encode_svd", "atomo_encode_entrywise", "atomo_encode_entrywise_noalloc", "atomo_encode_lq", "atomo_decode",
                      "atomo_decode_svd_batch", "atomo_apply_svd_batch", "atomo_measure_mfma_fp32"):
             getattr(L, name).restype = C.c_int
         _lib = L
@@ -358,6 +359,21 @@ def atomo_encode_entrywise(ctx: Context, g: torch.Tensor, s: float, seed: int, s
                                         int(stream_id) & (2 ** 64 - 1), C.byref(cm),
                                         None if p_out is None else p_out.data_ptr(), _stream_handle(stream)),
            "atomo_encode_entrywise")
+    return msg
+
+
+def atomo_encode_entrywise_noalloc(ctx: Context, g: torch.Tensor, s: float, seed: int, stream_id: int,
+                                   msg: EntrywiseMessage, p_out: Optional[torch.Tensor] = None, stream=None) -> EntrywiseMessage:
+    """atomo_encode_entrywise through the entry point that allocates nothing: the caller brings the message
+    buffers, the library's scratch is its fixed per-GPU array (at most 2^24 elements)."""
+    g = _f32_cuda(g, "g")
+    if not g.is_contiguous():
+        raise ValueError("g must be contiguous")
+    cm = msg.c_struct()
+    _check(lib().atomo_encode_entrywise_noalloc(ctx._h, g.data_ptr(), float(s), int(seed) & (2 ** 64 - 1),
+                                                int(stream_id) & (2 ** 64 - 1), C.byref(cm),
+                                                None if p_out is None else p_out.data_ptr(), _stream_handle(stream)),
+           "atomo_encode_entrywise_noalloc")
     return msg
 
 

@@ -159,6 +159,7 @@ int svd_sweeps(atomo_ctx* ctx, hipStream_t stream, int32_t* sweeps, int32_t* ref
 size_t entrywise_workspace_bytes(int64_t n);
 int encode_entrywise(atomo_ctx* ctx, const float* g, double s, uint64_t seed, uint64_t stream_id,
                      const atomo_ew_msg* msg, float* p_out, hipStream_t stream);
+int entrywise_noalloc_setup(atomo_ctx* ctx);   // device address of the static scratch array, once per device
 int encode_lq(atomo_ctx* ctx, const float* g, double q, uint64_t seed, uint64_t stream_id, const atomo_lq_msg* msg,
               float* p_out, hipStream_t stream);
 int probabilities(atomo_ctx* ctx, const float* lambda, const int64_t* offsets, int n_seg, double s, float* p,

@@ -108,6 +108,13 @@ int atomo_create(atomo_ctx** out, int device)
         delete ctx;
         return ATOMO_EHIP;
     }
+    // set-up for atomo_encode_entrywise_noalloc: the address of its static scratch array on this device
+    if (entrywise_noalloc_setup(ctx) != ATOMO_OK) {
+        (void)hipFree(ctx->d_flags);
+        (void)hipHostFree(ctx->h_flags);
+        delete ctx;
+        return ATOMO_EHIP;
+    }
     *out = ctx;
     return ATOMO_OK;
 }
@@ -281,6 +288,7 @@ const char* atomo_strerror(int status)
         case ATOMO_ENOCONV: return "Jacobi SVD reached the sweep limit";
         case ATOMO_EHIP: return "HIP runtime error";
         case ATOMO_ENOMEM: return "out of device memory";
+        case ATOMO_ETOOLARGE: return "input longer than the fixed scratch of the allocation-free entry point holds";
         default: return "unknown status";
     }
 }

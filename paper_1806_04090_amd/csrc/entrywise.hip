@@ -551,15 +551,14 @@ void enqueue_water_level(atomo_ctx* ctx, const float* x, int64_t n, double s, Ew
 
 size_t entrywise_workspace_bytes(int64_t n) { return ew_layout(nullptr, n).bytes; }
 
-int encode_entrywise(atomo_ctx* ctx, const float* g, double s, uint64_t seed, uint64_t stream_id,
-                     const atomo_ew_msg* msg, float* p_out, hipStream_t stream)
+namespace {
+
+// The encoder proper: every buffer it needs beyond the caller's lies in `l`.
+int enqueue_encode_entrywise(atomo_ctx* ctx, const float* g, double s, uint64_t seed, uint64_t stream_id,
+                             const atomo_ew_msg* msg, float* p_out, const EwLayout& l, hipStream_t stream)
 {
     const int64_t n = msg->n;
-    int rc = ensure_workspace(ctx, entrywise_workspace_bytes(n));
-    if (rc != ATOMO_OK) return rc;
-    const EwLayout l = ew_layout(ctx->ws, n);
     const long long n_chunks = (n + CHUNK - 1) / CHUNK;
-
     enqueue_water_level(ctx, g, n, s, l.st, stream);
     {
         ProfScope ps(ctx, ATOMO_K_EW_SAMPLE, stream);
@@ -572,6 +571,17 @@ int encode_entrywise(atomo_ctx* ctx, const float* g, double s, uint64_t seed, ui
     }
     ATOMO_HIP(ctx, hipGetLastError());
     return ATOMO_OK;
+}
+
+}  // namespace
+
+int encode_entrywise(atomo_ctx* ctx, const float* g, double s, uint64_t seed, uint64_t stream_id,
+                     const atomo_ew_msg* msg, float* p_out, hipStream_t stream)
+{
+    const int64_t n = msg->n;
+    int rc = ensure_workspace(ctx, entrywise_workspace_bytes(n));
+    if (rc != ATOMO_OK) return rc;
+    return enqueue_encode_entrywise(ctx, g, s, seed, stream_id, msg, p_out, ew_layout(ctx->ws, n), stream);
 }
 
 int encode_lq(atomo_ctx* ctx, const float* g, double q, uint64_t seed, uint64_t stream_id, const atomo_lq_msg* msg,
@@ -637,3 +647,65 @@ int probabilities(atomo_ctx* ctx, const float* lambda, const int64_t* offsets, i
 }
 
 }  // namespace atomo
+
+// ---------------------------------------------------------------------------------------------------------
+// atomo_encode_entrywise_noalloc: the entry-wise encoder for callers that cannot allocate (see include/atomo.h).
+// Its scratch memory (the state of the water-level search, per-chunk counts, offsets and keep bits) is the
+// file-scope device array below instead of the context's growable workspace.  Every GPU the library runs on
+// holds its own copy of the array, at its own address, until the process ends; the address on a device is
+// looked up once, with that device current (atomo_create does it, so that no call made later has to).
+// ---------------------------------------------------------------------------------------------------------
+namespace {
+
+constexpr long long NOALLOC_MAX_N = 1ll << 24;                   // 16,777,216 elements (64 MiB of gradient)
+constexpr size_t NOALLOC_SCRATCH_BYTES = (size_t)3 << 20;        // 3 MiB per GPU
+constexpr int NOALLOC_MAX_DEVICES = 64;
+
+static __device__ __align__(256) unsigned char scratch[NOALLOC_SCRATCH_BYTES];
+
+// Device address of `scratch` per HIP device (the array's name is only a host-side handle for the symbol).
+void* scratch_ptr[NOALLOC_MAX_DEVICES];
+
+}  // namespace
+
+namespace atomo {
+
+// Called with ctx->device current.  Looks the address up on the first call for a device.
+int entrywise_noalloc_setup(atomo_ctx* ctx)
+{
+    const int dev = ctx->device;
+    if (dev < 0 || dev >= NOALLOC_MAX_DEVICES) return ATOMO_EINVAL;
+    if (__atomic_load_n(&scratch_ptr[dev], __ATOMIC_ACQUIRE)) return ATOMO_OK;
+    if (ew_layout(nullptr, NOALLOC_MAX_N).bytes > NOALLOC_SCRATCH_BYTES) return ATOMO_EINVAL;   // (a build-time fact)
+    void* ptr = nullptr;
+    ATOMO_HIP(ctx, hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return ATOMO_EHIP;
+    __atomic_store_n(&scratch_ptr[dev], ptr, __ATOMIC_RELEASE);   // (two threads racing here store the same address)
+    return ATOMO_OK;
+}
+
+}  // namespace atomo
+
+extern "C" int atomo_encode_entrywise_noalloc(atomo_ctx* ctx, const float* g, double s, uint64_t seed, uint64_t stream_id,
+                                              const atomo_ew_msg* msg, float* p_out, void* stream)
+{
+    using namespace atomo;
+    if (!ctx || !g || !msg || !(s > 0.0) || std::isinf(s)) return ATOMO_EINVAL;
+    if (msg->n <= 0 || msg->capacity < 1 || !msg->count || !msg->idx || !msg->val) return ATOMO_EINVAL;
+    if (msg->n > NOALLOC_MAX_N) return ATOMO_ETOOLARGE;
+    int prev = -1;
+    if (hipGetDevice(&prev) != hipSuccess) prev = -1;
+    if (prev != ctx->device) ATOMO_HIP(ctx, hipSetDevice(ctx->device));
+    int rc = entrywise_noalloc_setup(ctx);                        // a table look-up after atomo_create
+    if (rc == ATOMO_OK) {
+        // event bracketing of launches creates events on demand: not on this path
+        const bool profiling = ctx->profiling;
+        ctx->profiling = false;
+        void* base = __atomic_load_n(&scratch_ptr[ctx->device], __ATOMIC_ACQUIRE);
+        rc = enqueue_encode_entrywise(ctx, g, s, seed, stream_id, msg, p_out, ew_layout(base, msg->n), (hipStream_t)stream);
+        ctx->profiling = profiling;
+    }
+    if (prev >= 0 && prev != ctx->device) (void)hipSetDevice(prev);
+    return rc;
+}
+
