@@ -144,6 +144,17 @@ typedef struct atomo_svd_options {
     const uint64_t* stream_ids;      /* HOST array of n_mats Philox stream ids, or NULL for stream_base + j: lets */
                                      /* one call encode the gradients of several workers (stream = worker, layer) */
                                      /* and produce the messages that separate calls would                        */
+    int32_t adaptive;                /* 0 (default): the launches of all max_sweeps sweeps are enqueued.  k > 0:  */
+                                     /* for a training loop that encodes the same layer set step after step. The  */
+                                     /* context remembers how many sweeps the matrices of earlier calls with the  */
+                                     /* same shapes took (read without waiting: the most recent call that has     */
+                                     /* finished) and enqueues that many + k, at most max_sweeps, separately for  */
+                                     /* the matrices that iterate on their Gram matrix and for the others; a call */
+                                     /* that used up such a reduced limit is followed by one with the full limit. */
+                                     /* A matrix that needs more sweeps than were enqueued is reported through    */
+                                     /* ATOMO_ENOCONV exactly as at max_sweeps (its message is still an exact,    */
+                                     /* unbiased decomposition); gradients change slowly from step to step, so    */
+                                     /* k = 1 or 2 rarely meets that                                              */
 } atomo_svd_options;
 
 /* -------- context ------------------------------------------------------------------------------ */

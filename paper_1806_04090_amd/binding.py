@@ -50,7 +50,7 @@ class atomo_lq_msg(C.Structure):
 class atomo_svd_options(C.Structure):
     _fields_ = [("max_sweeps", C.c_int32), ("stop_cosine", C.c_float), ("max_inner_sweeps", C.c_int32),
                 ("inner_reduction", C.c_float), ("full_period", C.c_int32), ("block_order", C.c_int32),
-                ("stream_ids", C.POINTER(C.c_uint64))]
+                ("stream_ids", C.POINTER(C.c_uint64)), ("adaptive", C.c_int32)]
 
 
 _lib = None
@@ -311,10 +311,11 @@ def atomo_encode_svd(ctx: Context, mats: Sequence[torch.Tensor], s: float, seed:
                      p_out: Optional[torch.Tensor] = None, max_sweeps: Optional[int] = None,
                      stop_cosine: Optional[float] = None, max_inner_sweeps: int = 0, inner_reduction: float = 0.0,
                      full_period: int = 0, block_order: int = 0, stream_ids: Optional[Sequence[int]] = None,
-                     stream=None) -> List[SvdMessage]:
+                     adaptive: int = 0, stream=None) -> List[SvdMessage]:
     """Spectral-ATOMO encode of a list of 2-D float32 CUDA tensors (row stride = tensor stride).
     stream_ids: one Philox stream id per matrix instead of stream_base + index.
-    block_order: 0 = block pairs by weight (default), 1 = the fixed tournament, for the matrices that iterate in Gram space."""
+    block_order: 0 = block pairs by weight (default), 1 = the fixed tournament, for the matrices that iterate in Gram space.
+    adaptive: k > 0 enqueues only the sweeps that earlier calls with the same shapes needed, plus k (see atomo.h)."""
     n = len(mats)
     c_mats = (atomo_mat * n)()
     for j, g in enumerate(mats):
@@ -327,7 +328,7 @@ def atomo_encode_svd(ctx: Context, mats: Sequence[torch.Tensor], s: float, seed:
     c_msgs = (atomo_svd_msg * n)(*[m.c_struct() for m in msgs])
     opt = None
     if (max_sweeps is not None or stop_cosine is not None or max_inner_sweeps or inner_reduction or full_period
-            or block_order or stream_ids is not None):
+            or block_order or stream_ids is not None or adaptive):
         ids = None
         if stream_ids is not None:
             if len(stream_ids) != n:
@@ -335,7 +336,8 @@ def atomo_encode_svd(ctx: Context, mats: Sequence[torch.Tensor], s: float, seed:
             ids = (C.c_uint64 * n)(*[int(x) & (2 ** 64 - 1) for x in stream_ids])
         opt = C.byref(atomo_svd_options(0 if max_sweeps is None else max_sweeps,
                                         0.0 if stop_cosine is None else stop_cosine,
-                                        max_inner_sweeps, inner_reduction, int(full_period), int(block_order), ids))
+                                        max_inner_sweeps, inner_reduction, int(full_period), int(block_order), ids,
+                                        int(adaptive)))
     _check(lib().atomo_encode_svd(ctx._h, c_mats, n, float(s), int(seed) & (2 ** 64 - 1),
                                   int(stream_base) & (2 ** 64 - 1), opt, c_msgs,
                                   None if sigma_out is None else sigma_out.data_ptr(),

@@ -19,6 +19,18 @@ namespace atomo {
 // Device-side latched flags (int32 each).
 enum { FLAG_CAPACITY = 0, FLAG_NOCONV = 1, FLAG_MAX_SWEEPS = 2, FLAG_EIG_VISITS = 3, FLAG_EIG_INNER = 4, FLAG_COUNT = 8 };
 
+// What an SVD encode learnt about its own sweep counts, for the calls after it (atomo_svd_options.adaptive).
+struct SweepHint {
+    int32_t* host = nullptr;     // pinned, device-visible: [0] most sweeps of a Gram-space matrix, [1] of a data-space one,
+                                 // [2] 1 once written
+    int32_t* dev = nullptr;      // the same memory as the device addresses it
+    hipEvent_t done = nullptr;   // recorded after the kernel that writes `host`
+    bool pending = false;        // the event has not been seen complete yet
+    uint64_t sig = 0;            // shapes of the call
+    uint64_t seq = 0;            // order of the calls (0 = unused)
+    int limit_gs = 0, limit_ds = 0;   // the sweep limits that call ran with
+};
+
 struct StageSlot {
     void* host = nullptr;        // pinned
     size_t bytes = 0;
@@ -43,6 +55,9 @@ struct atomo_ctx {
     size_t report_cap = 0;               // pairs allocated
     size_t report_n = 0;                 // matrices of the last SVD encode
     // streams and events of the SVD encoder's internal fork/join (created on first use, default priority)
+    atomo::SweepHint hints[4];
+    int hint_next = 0;
+    uint64_t hint_seq = 0;
     hipStream_t side = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     // optional event bracketing of kernel launches (atomo_profile_*)

@@ -1,4 +1,5 @@
 // C ABI of libatomo: context management, argument validation, dispatch.  See include/atomo.h.
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -50,7 +51,10 @@ int upload(atomo_ctx* ctx, void* dst, const void* src, size_t bytes, hipStream_t
         if (slot.host) ATOMO_HIP(ctx, hipHostFree(slot.host));
         slot.host = nullptr;
         slot.bytes = 0;
+        // (allocating pinned memory waits for the device: every slot grows to the largest upload seen so far, so that
+        // the ring settles within one round of eight uploads)
         size_t want = align_up(bytes * 2, 4096);
+        for (const StageSlot& other : ctx->ring) want = std::max(want, other.bytes);
         ATOMO_HIP(ctx, hipHostMalloc(&slot.host, want, hipHostMallocDefault));
         slot.bytes = want;
     }
@@ -127,6 +131,10 @@ int atomo_destroy(atomo_ctx* ctx)
     for (auto& slot : ctx->ring) {
         if (slot.ev) (void)hipEventDestroy(slot.ev);
         if (slot.host) (void)hipHostFree(slot.host);
+    }
+    for (auto& h : ctx->hints) {
+        if (h.done) (void)hipEventDestroy(h.done);
+        if (h.host) (void)hipHostFree(h.host);
     }
     for (hipEvent_t e : ctx->ev_pool) (void)hipEventDestroy(e);
     for (hipEvent_t e : {ctx->ev_fork, ctx->ev_join})
@@ -325,7 +333,7 @@ int atomo_encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s
         if (!m.count || !m.idx || !m.U || !m.V) return ATOMO_EINVAL;         // w may be null: folded form
     }
     if (opt && (opt->max_sweeps < 0 || !(opt->stop_cosine >= 0.0f) || opt->max_inner_sweeps < 0 ||
-                !(opt->inner_reduction >= 0.0f) || opt->full_period < 0))
+                !(opt->inner_reduction >= 0.0f) || opt->full_period < 0 || opt->adaptive < 0))
         return ATOMO_EINVAL;
     DeviceGuard guard(ctx);
     if (!guard.ok) return ATOMO_EHIP;

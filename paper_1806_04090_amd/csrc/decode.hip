@@ -8,6 +8,7 @@
 // params += alpha * average gradient), and takes messages in the folded form (weight inside U).
 // Entry-wise messages: zero fill, then one scatter launch per message in call order (bit-identical from run to run).
 #include <algorithm>
+#include <cstring>
 #include <vector>
 
 #include "atomo_internal.h"
@@ -26,102 +27,50 @@ struct DecMsg {
 };
 
 struct DecOut {
-    int rows, cols;
-    int first, last;           // messages [first, last)
-    long long atom_base;       // where this output's atom list starts
-};
-
-// One kept atom as the contraction reads it: its two vectors and scale * weight.
-struct DecAtom {
-    const float* u;
-    const float* v;
-    float w;
-    int pad;
-};
-
-// One tile of one output; everything the tile kernel needs sits in the record it reads first.
-struct DecWork {
     float* out;
     long long ld;
-    const DecAtom* atoms;      // the output's atom list
-    const int* natoms;         // its length (device scalar written by decode_svd_list)
     int rows, cols;
-    int tile_r, tile_c;
+    int first, last;           // messages [first, last)
 };
+
+struct DecWork { int out, tile_r, tile_c, pad; };
 
 constexpr int TR = 64, TC = 256;
 constexpr int TALL_ROWS = 256;     // rows per workgroup for outputs of at most 32 columns
-constexpr int ATOMS_MAX = 256;     // atoms staged in LDS at a time; longer lists are contracted in pieces
+constexpr int ATOMS_MAX = 512;     // atoms listed in LDS at a time
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-// Lists the kept atoms of every message summed into one output (one workgroup per output): the tile kernel then starts
-// from one contiguous list instead of chasing descriptor -> count -> weight -> vectors in every tile.  Messages are
-// taken 256 at a time; wave w lists messages w, w + 4, ... of the group, lane l atoms l, l + 64, ... of a message.
-__global__ __launch_bounds__(256) void decode_svd_list(const DecOut* outs, const DecMsg* msgs, float scale, DecAtom* atoms,
-                                                       int* natoms)
-{
-    __shared__ int kept_sh[256];
-    __shared__ int offs_sh[256];
-    const DecOut o = outs[blockIdx.x];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    DecAtom* list = atoms + o.atom_base;
-    int base = 0;                                                // atoms listed so far (uniform)
-    for (int m0 = o.first; m0 < o.last; m0 += 256) {
-        const int q = m0 + tid;
-        const int kept = q < o.last ? max(0, min(*msgs[q].count, msgs[q].capacity)) : 0;
-        kept_sh[tid] = kept;
-        offs_sh[tid] = kept;
-        __syncthreads();
-        for (int off = 1; off < 256; off <<= 1) {                // inclusive scan
-            const int v = tid >= off ? offs_sh[tid - off] : 0;
-            __syncthreads();
-            offs_sh[tid] += v;
-            __syncthreads();
-        }
-        const int group = min(256, o.last - m0);
-        for (int mm = wave; mm < group; mm += 4) {
-            const DecMsg m = msgs[m0 + mm];
-            const int k_tot = kept_sh[mm];
-            const int at = base + offs_sh[mm] - k_tot;
-            for (int k = lane; k < k_tot; k += 64) {
-                DecAtom a;
-                a.u = m.U + (size_t)k * o.rows;
-                a.v = m.V + (size_t)k * o.cols;
-                a.w = m.w ? scale * m.w[k] : scale;              // folded messages carry the weight in U
-                a.pad = 0;
-                list[at + k] = a;
-            }
-        }
-        base += offs_sh[255];
-        __syncthreads();                                         // the scan arrays are reused by the next group
-    }
-    if (tid == 0) natoms[blockIdx.x] = base;
-}
-
-// out tile (64 x 256) = sum over the listed atoms of (scale w_k u_k) v_k^T as a rank-K update on the matrix cores:
-// A operand (row i, atom k) = scale w_k U[k][i], B operand (atom k, column j) = V[k][j], v_mfma_f32_32x32x2f32, two
-// atoms per instruction.  Wave w owns columns 64 w .. 64 w + 63 of the tile as 2 x 2 blocks of 32 x 32.  The list is
-// staged in LDS ATOMS_MAX atoms at a time; operands come straight from global memory (every atom's u and v are
-// contiguous rows of its message), eight atoms per trip, the loads of the next trip issued before the products of the
-// current one.  An odd atom count pads with a zero weight.
+// out tile (64 x 256) = sum over messages and kept atoms of (scale w_k u_k) v_k^T as a rank-K update on the
+// matrix cores: A operand (row i, atom k) = scale w_k U[k][i], B operand (atom k, column j) = V[k][j],
+// v_mfma_f32_32x32x2f32, two atoms per instruction.  Wave w owns columns 64 w .. 64 w + 63 of the tile as
+// 2 x 2 blocks of 32 x 32.  The kept atoms of a batch of messages (`batch` x largest capacity <= ATOMS_MAX,
+// chosen by the host) are first listed in LDS, one round trip for all counts and weights, so that the
+// contraction loop only chases pointers it already holds; operands come straight from global memory
+// (every atom's u and v are contiguous rows of its message).  An odd atom count pads with a zero weight.
+// A message with a capacity above ATOMS_MAX is a batch of its own and is listed and contracted in pieces of
+// ATOMS_MAX atoms.
 // TALL: outputs of at most 32 columns (the [x*y/2, 2*k*k] reshape of Section 6).  The workgroup owns 256 rows,
 // wave w rows 64 w .. 64 w + 63, one 32-column block.
 template <bool TALL, bool ACCUMULATE>
-__global__ __launch_bounds__(256) void decode_svd_tiles(const DecWork* work)
+__global__ __launch_bounds__(256) void decode_svd_tiles(const DecOut* outs, const DecMsg* msgs, const DecWork* work,
+                                                        float scale, int batch)
 {
     constexpr int NCB = TALL ? 1 : 2;
     __shared__ const float* up[ATOMS_MAX];
     __shared__ const float* vp[ATOMS_MAX];
     __shared__ float wv[ATOMS_MAX];
+    __shared__ int kept_of[ATOMS_MAX];
+    __shared__ int total_sh;
     const DecWork wk = work[blockIdx.x];
+    const DecOut o = outs[wk.out];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int h = lane >> 5, l32 = lane & 31;
     const int r0 = TALL ? wk.tile_r * TALL_ROWS + wave * 64 : wk.tile_r * TR;
     const int c0 = TALL ? 0 : wk.tile_c * TC + wave * 64;
     const int row_a = r0 + l32, row_b = r0 + 32 + l32;          // rows this lane feeds as A operands
     const int col_a = c0 + l32, col_b = c0 + 32 + l32;          // columns this lane feeds as B operands
-    const bool ra = row_a < wk.rows, rb_ok = row_b < wk.rows, ca = col_a < wk.cols, cb_ok = !TALL && col_b < wk.cols;
+    const bool ra = row_a < o.rows, rb_ok = row_b < o.rows, ca = col_a < o.cols, cb_ok = !TALL && col_b < o.cols;
     floatx16 acc[2][NCB];
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb)
@@ -130,19 +79,33 @@ __global__ __launch_bounds__(256) void decode_svd_tiles(const DecWork* work)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[rb][cb][v] = 0.0f;
 
-    const int n_atoms = *wk.natoms;
-    for (int piece = 0; piece < n_atoms; piece += ATOMS_MAX) {
-        const int total = min(ATOMS_MAX, n_atoms - piece);
+    for (int first = o.first; first < o.last; first += batch) {
+        const int nm = min(batch, o.last - first);
+        __syncthreads();                                         // the previous list is spent
+        for (int q = tid; q < nm; q += 256) kept_of[q] = min(*msgs[first + q].count, msgs[first + q].capacity);
+        __syncthreads();
+        // several messages: everything fits the list by the host's choice of `batch` (one piece); a message of its
+        // own: pieces of ATOMS_MAX atoms, `piece` = first atom of the piece
+        const int span = nm == 1 ? kept_of[0] : 1;
+      for (int piece = 0; piece < span; piece += ATOMS_MAX) {
         if (piece > 0) __syncthreads();                          // the previous piece is spent
-        for (int k = tid; k < total; k += 256) {
-            const DecAtom a = wk.atoms[piece + k];
-            up[k] = a.u;
-            vp[k] = a.v;
-            wv[k] = a.w;
+        for (int q = tid; q < nm; q += 256) {
+            int at = 0;
+            for (int e = 0; e < q; ++e) at += kept_of[e];
+            const DecMsg m = msgs[first + q];
+            const int kept = max(0, min(kept_of[q] - piece, ATOMS_MAX - at));
+            for (int k = 0; k < kept; ++k) {
+                up[at + k] = m.U + (size_t)(piece + k) * o.rows;
+                vp[at + k] = m.V + (size_t)(piece + k) * o.cols;
+                wv[at + k] = m.w ? scale * m.w[piece + k] : scale; // folded messages carry the weight in U
+            }
+            if (q == nm - 1) total_sh = at + kept;
         }
         __syncthreads();
-        float a0[2][4], a1[2][4], b0[2][4], b1[2][4];
-        auto fetch = [&](int buf, int k0) {
+        const int total = total_sh;
+        // four atom pairs per trip: all sixteen operand loads are issued before the first MFMA
+        for (int k0 = 0; k0 < total; k0 += 8) {
+            float a0[4], a1[4], b0[4], b1[4];
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 const int kk = k0 + 2 * t + h;
@@ -150,33 +113,24 @@ __global__ __launch_bounds__(256) void decode_svd_tiles(const DecWork* work)
                 const float wgt = live ? wv[kk] : 0.0f;
                 const float* u = up[live ? kk : 0];
                 const float* v = vp[live ? kk : 0];
-                a0[buf][t] = live && ra ? wgt * u[row_a] : 0.0f;
-                a1[buf][t] = live && rb_ok ? wgt * u[row_b] : 0.0f;
-                b0[buf][t] = live && ca ? v[col_a] : 0.0f;
-                b1[buf][t] = live && cb_ok ? v[col_b] : 0.0f;
+                a0[t] = live && ra ? wgt * u[row_a] : 0.0f;
+                a1[t] = live && rb_ok ? wgt * u[row_b] : 0.0f;
+                b0[t] = live && ca ? v[col_a] : 0.0f;
+                b1[t] = live && cb_ok ? v[col_b] : 0.0f;
             }
-        };
-        auto contract = [&](int buf, int k0) {
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 if (k0 + 2 * t < total) {                        // uniform: skip pairs past the end
-                    acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[buf][t], b0[buf][t], acc[0][0], 0, 0, 0);
-                    acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[buf][t], b0[buf][t], acc[1][0], 0, 0, 0);
+                    acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[t], b0[t], acc[0][0], 0, 0, 0);
+                    acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[t], b0[t], acc[1][0], 0, 0, 0);
                     if (!TALL) {
-                        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[buf][t], b1[buf][t], acc[0][1], 0, 0, 0);
-                        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[buf][t], b1[buf][t], acc[1][1], 0, 0, 0);
+                        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[t], b1[t], acc[0][1], 0, 0, 0);
+                        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[t], b1[t], acc[1][1], 0, 0, 0);
                     }
                 }
             }
-        };
-        // two trips per round so that the operand buffers are indexed by constants
-        fetch(0, 0);
-        for (int k0 = 0; k0 < total; k0 += 16) {
-            if (k0 + 8 < total) fetch(1, k0 + 8);
-            contract(0, k0);
-            if (k0 + 16 < total) fetch(0, k0 + 16);
-            if (k0 + 8 < total) contract(1, k0 + 8);
         }
+      }
     }
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb)
@@ -186,8 +140,8 @@ __global__ __launch_bounds__(256) void decode_svd_tiles(const DecWork* work)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int row = r0 + rb * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
-                if (row < wk.rows && col < wk.cols) {
-                    float* dst = wk.out + (size_t)row * wk.ld + col;
+                if (row < o.rows && col < o.cols) {
+                    float* dst = o.out + (size_t)row * o.ld + col;
                     *dst = ACCUMULATE ? *dst + acc[rb][cb][v] : acc[rb][cb][v];
                 }
             }
@@ -258,69 +212,53 @@ int decode_svd_batch(atomo_ctx* ctx, const atomo_svd_msg* msgs, const int32_t* f
                      float* const* outs, const int64_t* lds, bool accumulate, hipStream_t stream)
 {
     const int n_msgs = first[n_out];
-    // workspace: [messages | outputs | tiles] (one upload), then the atom lists and their lengths (device-made)
-    size_t n_wide = 0, n_tall = 0, n_atoms_cap = 0;
+    std::vector<DecMsg> hm(n_msgs);
+    std::vector<DecOut> ho(n_out);
+    std::vector<DecWork> hw, hw_tall;
+    for (int k = 0; k < n_msgs; ++k)
+        hm[k] = DecMsg{msgs[k].count, msgs[k].w, msgs[k].U, msgs[k].V, msgs[k].capacity, 0};
     for (int o = 0; o < n_out; ++o) {
         const atomo_svd_msg& m0 = msgs[first[o]];
-        if (m0.cols <= 32 && m0.rows > TR) n_tall += (size_t)(m0.rows + TALL_ROWS - 1) / TALL_ROWS;
-        else n_wide += (size_t)((m0.rows + TR - 1) / TR) * (size_t)((m0.cols + TC - 1) / TC);
-        for (int k = first[o]; k < first[o + 1]; ++k) n_atoms_cap += (size_t)msgs[k].capacity;
+        ho[o] = DecOut{outs[o], (long long)lds[o], m0.rows, m0.cols, first[o], first[o + 1]};
+        if (m0.cols <= 32 && m0.rows > TR) {
+            for (int a = 0; a < (m0.rows + TALL_ROWS - 1) / TALL_ROWS; ++a) hw_tall.push_back(DecWork{o, a, 0, 0});
+            continue;
+        }
+        const int tr = (m0.rows + TR - 1) / TR, tc = (m0.cols + TC - 1) / TC;
+        for (int a = 0; a < tr; ++a)
+            for (int b = 0; b < tc; ++b) hw.push_back(DecWork{o, a, b, 0});
     }
+    const size_t n_wide = hw.size();
+    hw.insert(hw.end(), hw_tall.begin(), hw_tall.end());
+    // the three tables travel in one copy
     Carver size_only(nullptr);
-    size_only.take<DecMsg>(n_msgs);
-    size_only.take<DecOut>(n_out);
-    size_only.take<DecWork>(n_wide + n_tall);
-    const size_t upload_bytes = size_only.off;
-    size_only.take<DecAtom>(n_atoms_cap);
-    size_only.take<int>(n_out);
+    size_only.take<DecMsg>(hm.size());
+    size_only.take<DecOut>(ho.size());
+    size_only.take<DecWork>(hw.size());
     int rc = ensure_workspace(ctx, size_only.off);
     if (rc != ATOMO_OK) return rc;
     Carver carve(ctx->ws);
-    DecMsg* d_msgs = carve.take<DecMsg>(n_msgs);
-    DecOut* d_outs = carve.take<DecOut>(n_out);
-    DecWork* d_work = carve.take<DecWork>(n_wide + n_tall);
-    DecAtom* d_atoms = carve.take<DecAtom>(n_atoms_cap);
-    int* d_natoms = carve.take<int>(n_out);
-
-    std::vector<char> host(upload_bytes, 0);
-    DecMsg* hm = (DecMsg*)(host.data() + ((char*)d_msgs - (char*)ctx->ws));
-    DecOut* ho = (DecOut*)(host.data() + ((char*)d_outs - (char*)ctx->ws));
-    DecWork* hw = (DecWork*)(host.data() + ((char*)d_work - (char*)ctx->ws));
-    for (int k = 0; k < n_msgs; ++k)
-        hm[k] = DecMsg{msgs[k].count, msgs[k].w, msgs[k].U, msgs[k].V, msgs[k].capacity, 0};
-    size_t at_wide = 0, at_tall = n_wide;
-    long long atom_base = 0;
-    for (int o = 0; o < n_out; ++o) {
-        const atomo_svd_msg& m0 = msgs[first[o]];
-        ho[o] = DecOut{m0.rows, m0.cols, first[o], first[o + 1], atom_base};
-        DecWork w{outs[o], (long long)lds[o], d_atoms + atom_base, d_natoms + o, m0.rows, m0.cols, 0, 0};
-        if (m0.cols <= 32 && m0.rows > TR) {
-            for (int a = 0; a < (m0.rows + TALL_ROWS - 1) / TALL_ROWS; ++a) {
-                w.tile_r = a;
-                hw[at_tall++] = w;
-            }
-        } else {
-            const int tr = (m0.rows + TR - 1) / TR, tc = (m0.cols + TC - 1) / TC;
-            for (int a = 0; a < tr; ++a)
-                for (int b = 0; b < tc; ++b) {
-                    w.tile_r = a;
-                    w.tile_c = b;
-                    hw[at_wide++] = w;
-                }
-        }
-        for (int k = first[o]; k < first[o + 1]; ++k) atom_base += msgs[k].capacity;
-    }
-    if ((rc = upload(ctx, ctx->ws, host.data(), upload_bytes, stream)) != ATOMO_OK) return rc;
+    DecMsg* d_msgs = carve.take<DecMsg>(hm.size());
+    DecOut* d_outs = carve.take<DecOut>(ho.size());
+    DecWork* d_work = carve.take<DecWork>(hw.size());
+    std::vector<char> staged(size_only.off, 0);
+    memcpy(staged.data() + ((char*)d_msgs - (char*)ctx->ws), hm.data(), hm.size() * sizeof(DecMsg));
+    memcpy(staged.data() + ((char*)d_outs - (char*)ctx->ws), ho.data(), ho.size() * sizeof(DecOut));
+    memcpy(staged.data() + ((char*)d_work - (char*)ctx->ws), hw.data(), hw.size() * sizeof(DecWork));
+    if ((rc = upload(ctx, ctx->ws, staged.data(), staged.size(), stream)) != ATOMO_OK) return rc;
     {
         ProfScope ps(ctx, ATOMO_K_DECODE_SVD, stream);
-        decode_svd_list<<<(unsigned)n_out, 256, 0, stream>>>(d_outs, d_msgs, scale, d_atoms, d_natoms);
+        int max_cap = 1;
+        for (int k = 0; k < n_msgs; ++k) max_cap = std::max(max_cap, (int)msgs[k].capacity);
+        const int batch = std::max(1, ATOMS_MAX / max_cap);      // messages whose atoms fit the LDS list together
+        const unsigned n_tall = (unsigned)hw_tall.size();
         if (n_wide > 0) {
-            if (accumulate) decode_svd_tiles<false, true><<<(unsigned)n_wide, 256, 0, stream>>>(d_work);
-            else decode_svd_tiles<false, false><<<(unsigned)n_wide, 256, 0, stream>>>(d_work);
+            if (accumulate) decode_svd_tiles<false, true><<<(unsigned)n_wide, 256, 0, stream>>>(d_outs, d_msgs, d_work, scale, batch);
+            else decode_svd_tiles<false, false><<<(unsigned)n_wide, 256, 0, stream>>>(d_outs, d_msgs, d_work, scale, batch);
         }
         if (n_tall > 0) {
-            if (accumulate) decode_svd_tiles<true, true><<<(unsigned)n_tall, 256, 0, stream>>>(d_work + n_wide);
-            else decode_svd_tiles<true, false><<<(unsigned)n_tall, 256, 0, stream>>>(d_work + n_wide);
+            if (accumulate) decode_svd_tiles<true, true><<<n_tall, 256, 0, stream>>>(d_outs, d_msgs, d_work + n_wide, scale, batch);
+            else decode_svd_tiles<true, false><<<n_tall, 256, 0, stream>>>(d_outs, d_msgs, d_work + n_wide, scale, batch);
         }
     }
     ATOMO_HIP(ctx, hipGetLastError());

@@ -579,6 +579,35 @@ __global__ __launch_bounds__(256) void svd_pack(const SvdMat* mats, const Work* 
     for (int c = threadIdx.x; c < m.r; c += 256) short_out[c] = a[m.Mp + c] * fold;
 }
 
+// Most sweeps any Gram-space matrix and any data-space matrix of the call took, into pinned host memory that the
+// next calls read without waiting (atomo_svd_options.adaptive).  One workgroup.
+__global__ __launch_bounds__(256) void svd_hint(const SvdMat* mats, int n_mats, int* out)
+{
+    __shared__ int red[2][256];
+    int gs = 0, ds = 0;
+    for (int j = threadIdx.x; j < n_mats; j += 256) {
+        const SvdMat& m = mats[j];
+        if (m.thin) continue;
+        const int sw = m.report[0];
+        if (m.gs) gs = max(gs, sw); else ds = max(ds, sw);
+    }
+    red[0][threadIdx.x] = gs;
+    red[1][threadIdx.x] = ds;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) {
+            red[0][threadIdx.x] = max(red[0][threadIdx.x], red[0][threadIdx.x + off]);
+            red[1][threadIdx.x] = max(red[1][threadIdx.x], red[1][threadIdx.x + off]);
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        out[0] = red[0][0];
+        out[1] = red[1][0];
+        out[2] = 1;
+    }
+}
+
 struct Plan {
     std::vector<SvdMat> mats;
     std::vector<Work> prep, gram, fullgram, tiles, apply, eig_gs, eig_ds, rowop1, twosided, norms, pack;
@@ -744,6 +773,50 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     const float fresh_stop = stop_cosine;
     const int full_period = opt && opt->full_period > 0 ? opt->full_period : 8;
     const int cyclic = opt && opt->block_order == 1 ? 1 : 0;
+    const int adaptive = opt ? opt->adaptive : 0;
+
+    // Sweep limits of this call.  With `adaptive`, what the most recent finished call with the same shapes needed plus
+    // the margin; a call that used up a reduced limit tells nothing about what was needed and is followed by a full one.
+    int limit_gs = max_sweeps, limit_ds = max_sweeps;
+    SweepHint* hint = nullptr;
+    if (adaptive > 0) {
+        uint64_t sig = 1469598103934665603ull ^ (uint64_t)n_mats;
+        for (int j = 0; j < n_mats; ++j) {
+            sig = (sig ^ (uint64_t)(uint32_t)mats[j].rows) * 1099511628211ull;
+            sig = (sig ^ (uint64_t)(uint32_t)mats[j].cols) * 1099511628211ull;
+        }
+        const SweepHint* best = nullptr;
+        for (SweepHint& h : ctx->hints) {
+            if (h.seq == 0) continue;
+            if (h.pending) {
+                const hipError_t q = hipEventQuery(h.done);
+                if (q == hipSuccess) h.pending = false;
+                else (void)hipGetLastError();                    // "not ready" is an answer, not an error to keep
+            }
+            if (!h.pending && h.sig == sig && h.host[2] == 1 && (!best || h.seq > best->seq)) best = &h;
+        }
+        if (best) {
+            const int g = best->host[0], d = best->host[1];
+            if (!(g >= best->limit_gs && best->limit_gs < max_sweeps)) limit_gs = std::min(max_sweeps, std::max(1, g + adaptive));
+            if (!(d >= best->limit_ds && best->limit_ds < max_sweeps)) limit_ds = std::min(max_sweeps, std::max(1, d + adaptive));
+        }
+        hint = &ctx->hints[ctx->hint_next];
+        ctx->hint_next = (ctx->hint_next + 1) % (int)(sizeof(ctx->hints) / sizeof(ctx->hints[0]));
+        if (hint->pending) {                                     // four calls in flight: wait for the oldest
+            ATOMO_HIP(ctx, hipEventSynchronize(hint->done));
+            hint->pending = false;
+        }
+        if (!hint->host) {
+            ATOMO_HIP(ctx, hipHostMalloc((void**)&hint->host, 4 * sizeof(int32_t), hipHostMallocDefault));
+            ATOMO_HIP(ctx, hipHostGetDevicePointer((void**)&hint->dev, hint->host, 0));
+            ATOMO_HIP(ctx, hipEventCreateWithFlags(&hint->done, hipEventDisableTiming));
+        }
+        hint->host[0] = hint->host[1] = hint->host[2] = 0;
+        hint->sig = sig;
+        hint->seq = ++ctx->hint_seq;
+        hint->limit_gs = limit_gs;
+        hint->limit_ds = limit_ds;
+    }
 
     if ((size_t)n_mats > ctx->report_cap) {                      // (hipFree waits for the device)
         if (ctx->d_report) ATOMO_HIP(ctx, hipFree(ctx->d_report));
@@ -836,50 +909,50 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     }
     if (have_ds) {
         hipStream_t s_ds = ctx->side;
-        const int ds_ticks = max_sweeps * plan.max_R_ds;
+        const int ds_ticks = limit_ds * plan.max_R_ds;
         for (int tick = 0; tick < ds_ticks; ++tick) {
             {
                 ProfScope ps(ctx, ATOMO_K_SVD_GRAM, s_ds);
-                svd_gram<false><<<grid(plan.gram), 256, 0, s_ds>>>(d_mats, w_gram, tick, max_sweeps);
+                svd_gram<false><<<grid(plan.gram), 256, 0, s_ds>>>(d_mats, w_gram, tick, limit_ds);
             }
             {
                 ProfScope ps(ctx, ATOMO_K_SVD_EIG, s_ds);
-                launch_svd_eig(d_mats, w_eig_ds, (int)plan.eig_ds.size(), nullptr, 0, nullptr, 0, 0, tick, max_sweeps,
+                launch_svd_eig(d_mats, w_eig_ds, (int)plan.eig_ds.size(), nullptr, 0, nullptr, 0, 0, tick, limit_ds,
                                stop_cosine, max_inner, inner_reduction, full_period, 0, ctx->d_flags, s_ds);
             }
             {
                 ProfScope ps(ctx, ATOMO_K_SVD_UPDATE, s_ds);
-                svd_rowop<<<grid(plan.rowop1), 256, 0, s_ds>>>(d_mats, w_rowop1, tick, max_sweeps);
+                svd_rowop<<<grid(plan.rowop1), 256, 0, s_ds>>>(d_mats, w_rowop1, tick, limit_ds);
             }
         }
     }
     if (use_side) ATOMO_HIP(ctx, hipEventRecord(ctx->ev_join, ctx->side));
     if (have_gs) {
-        const int n_ticks = max_sweeps * plan.max_R + 1;
+        const int n_ticks = limit_gs * plan.max_R + 1;
         for (int tick = 0; tick < n_ticks; ++tick) {
             // the matrices that sweep on, and the previous tick's update for every matrix
             if (tick > 0) {
                 ProfScope ps(ctx, ATOMO_K_SVD_EIG, stream);
                 launch_svd_eig(d_mats, w_eig_gs, (int)plan.eig_gs.size(), w_twosided, n_two, w_gs_list,
-                               (int)plan.gs_list.size(), cyclic, tick, max_sweeps, stop_cosine, max_inner,
+                               (int)plan.gs_list.size(), cyclic, tick, limit_gs, stop_cosine, max_inner,
                                inner_reduction, full_period, 0, ctx->d_flags, stream);
             }
             bool boundary = false;
-            for (int period : plan.gs_periods) boundary = boundary || (tick % period == 0 && tick <= max_sweeps * period);
+            for (int period : plan.gs_periods) boundary = boundary || (tick % period == 0 && tick <= limit_gs * period);
             if (!boundary) continue;
             // a sweep boundary of some matrix: those that asked for it get a fresh Gram matrix (their Tgs is
             // complete now), and their pair problems of this tick run in a launch of their own
             {
                 ProfScope ps(ctx, ATOMO_K_SVD_REFRESH, stream);
                 svd_apply<<<grid(plan.apply), 256, 0, stream>>>(d_mats, w_apply);
-                svd_gram<true><<<grid(plan.fullgram), 256, 0, stream>>>(d_mats, w_fullgram, tick, max_sweeps);
+                svd_gram<true><<<grid(plan.fullgram), 256, 0, stream>>>(d_mats, w_fullgram, tick, limit_gs);
                 svd_fullgram_reduce<<<grid(plan.tiles), 256, 0, stream>>>(d_mats, w_tiles, tick);
-                svd_fresh_check<<<grid(plan.tiles), 256, 0, stream>>>(d_mats, w_tiles, tick, max_sweeps, stop_cosine,
+                svd_fresh_check<<<grid(plan.tiles), 256, 0, stream>>>(d_mats, w_tiles, tick, limit_gs, stop_cosine,
                                                                       fresh_stop, ctx->d_flags);
             }
             {
                 ProfScope ps(ctx, ATOMO_K_SVD_EIG, stream);
-                launch_svd_eig(d_mats, w_eig_gs, (int)plan.eig_gs.size(), nullptr, 0, nullptr, 0, 0, tick, max_sweeps,
+                launch_svd_eig(d_mats, w_eig_gs, (int)plan.eig_gs.size(), nullptr, 0, nullptr, 0, 0, tick, limit_gs,
                                stop_cosine, max_inner, inner_reduction, full_period, 1, ctx->d_flags, stream);
             }
         }
@@ -895,6 +968,11 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
         svd_select<<<(unsigned)n_mats, 256, 0, stream>>>(d_mats, s, (unsigned long long)seed, ctx->d_flags);
         if (!plan.pack.empty()) svd_pack<<<grid(plan.pack), 256, 0, stream>>>(d_mats, w_pack);
         if (have_thin) launch_thin_pack(d_mats, w_thin_chunks, (int)plan.thin_chunks.size(), stream);
+        if (hint) svd_hint<<<1, 256, 0, stream>>>(d_mats, n_mats, hint->dev);
+    }
+    if (hint) {
+        ATOMO_HIP(ctx, hipEventRecord(hint->done, stream));
+        hint->pending = true;
     }
     ATOMO_HIP(ctx, hipGetLastError());
     return ATOMO_OK;

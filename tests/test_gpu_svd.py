@@ -286,3 +286,35 @@ def test_largest_supported_rank_and_the_first_rejected_one():
     check_svd_message_against_matrix(G.astype(np.float64), h, *per[0])
     with pytest.raises(binding.AtomoError):
         binding.atomo_encode_svd(ctx(), [torch.zeros(2049, 2049, device="cuda")], 3.0, 1, 0)
+
+
+def test_adaptive_sweep_budget_gives_the_same_messages_and_reports_when_it_falls_short():
+    # a training loop: the same shapes step after step, launches for the sweeps the previous steps needed plus one
+    shapes = [(64, 576), (256, 1152), (512, 600)]
+    easy = inputs.resnet18_layer_set(21, shapes=shapes)
+    want, per_want, status, _ = encode(easy, 3.0, 9)
+    assert status == 0
+    want_h = [m.to_host() for m in want]
+    used = ctx().svd_sweeps(len(shapes))
+    for step in range(3):                                       # the first call has no history and enqueues everything
+        got, per_got, status, sweeps = encode(easy, 3.0, 9, adaptive=1)
+        assert status == 0 and sweeps == max(used)
+        assert ctx().svd_sweeps(len(shapes)) == used
+        for a, m, (s1, p1), (s2, p2) in zip(want_h, got, per_want, per_got):
+            b = m.to_host()
+            assert a["count"] == b["count"] and np.array_equal(a["idx"], b["idx"])
+            assert all(np.array_equal(a[k], b[k]) for k in ("w", "U", "V"))
+            assert np.array_equal(s1, s2) and np.array_equal(p1, p2)
+    # a gradient of the same shapes that needs more sweeps than its predecessors: reported, not hidden; the call after
+    # it gets the full limit again
+    rng = np.random.default_rng(3)
+    low = (rng.standard_normal((512, 40)) @ rng.standard_normal((40, 600))).astype(np.float32)
+    hard = [easy[0], easy[1], low]
+    _, _, status_full, _ = encode(hard, 3.0, 9)
+    needs = ctx().svd_sweeps(len(shapes))
+    assert status_full == 0 and needs[2] > used[2] + 1
+    encode(easy, 3.0, 9, adaptive=1)                            # history: the easy set
+    _, _, status_short, _ = encode(hard, 3.0, 9, adaptive=1)
+    assert status_short == binding.ATOMO_ENOCONV
+    _, _, status_again, _ = encode(hard, 3.0, 9, adaptive=1)
+    assert status_again == 0 and ctx().svd_sweeps(len(shapes)) == needs
