@@ -57,7 +57,9 @@ typedef enum atomo_status_code {
     ATOMO_ENOCONV = -3,    /* (atomo_status only) the Jacobi SVD stopped at the sweep limit         */
     ATOMO_EHIP = -4,       /* a HIP runtime call failed; atomo_last_hip_error gives its code        */
     ATOMO_ENOMEM = -5,     /* the workspace could not be allocated                                  */
-    ATOMO_ETOOLARGE = -6   /* atomo_encode_entrywise_noalloc: n exceeds what its fixed scratch holds */
+    ATOMO_ETOOLARGE = -6,  /* atomo_encode_entrywise_noalloc: n exceeds what its fixed scratch holds */
+    ATOMO_ETIMEOUT = -7    /* (atomo_status only) a kernel whose workgroups wait for each other gave up    */
+                           /* waiting: the results of the calls since the last status read are invalid      */
 } atomo_status_code;
 
 enum { ATOMO_KIND_SVD = 0, ATOMO_KIND_ENTRYWISE = 1, ATOMO_KIND_LQ = 2 };
@@ -232,7 +234,7 @@ int atomo_encode_entrywise(atomo_ctx* ctx, const float* g, double s, uint64_t se
  * atomo_encode_entrywise for callers that cannot allocate device memory: code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc.  Same arguments, same message, bit for bit; the scratch
  * memory of the kernels (water-level search state, per-chunk counts, offsets and keep bits) is a fixed array
- * of 3 MiB that the library holds on every GPU it runs on until the process ends, instead of the context's
+ * of 5 MiB that the library holds on every GPU it runs on until the process ends, instead of the context's
  * growable workspace.  The call allocates nothing (no hipMalloc, hipFree, event or stream creation), on any
  * path.
  *   n = msg->n is limited to 2^24 = 16,777,216 elements; a longer gradient returns ATOMO_ETOOLARGE and
