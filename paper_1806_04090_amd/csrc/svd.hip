@@ -888,6 +888,7 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     const bool have_ds = !plan.gram.empty(), have_gs = !plan.twosided.empty(), have_thin = !plan.thin_list.empty();
     const bool use_side = have_ds || (have_thin && have_gs);
     const int n_two = (int)plan.twosided.size();
+    const int split_two_sided = 4096;                            // tiles per tick (a 512-row matrix has 192)
     if (use_side) {
         rc = ensure_side_streams(ctx);
         if (rc != ATOMO_OK) return rc;
@@ -929,31 +930,45 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     if (use_side) ATOMO_HIP(ctx, hipEventRecord(ctx->ev_join, ctx->side));
     if (have_gs) {
         const int n_ticks = limit_gs * plan.max_R + 1;
+        // Few matrices: the two-sided update of the previous tick rides in the launch of the pair problems (one launch
+        // per tick on the chain of dependent ticks).  Many matrices: the update is the bulk of a tick, and as extra
+        // 1024-thread workgroups of svd_eig (128 registers per lane, one workgroup per compute unit) it runs at a
+        // fraction of the rate of its own kernel of 256-thread workgroups, launched behind the pair problems.  (On a
+        // stream of its own beside the pair problems of the next tick, which do not depend on it, it slowed those
+        // down by more than it gained: 30.6 ms against 27.6 ms for 64 matrices of 512 x 4608.)
+        const bool own_launch = n_two > split_two_sided;
         for (int tick = 0; tick < n_ticks; ++tick) {
             // the matrices that sweep on, and the previous tick's update for every matrix
             if (tick > 0) {
-                ProfScope ps(ctx, ATOMO_K_SVD_EIG, stream);
-                launch_svd_eig(d_mats, w_eig_gs, (int)plan.eig_gs.size(), w_twosided, n_two, w_gs_list,
-                               (int)plan.gs_list.size(), cyclic, tick, limit_gs, stop_cosine, max_inner,
-                               inner_reduction, full_period, 0, ctx->d_flags, stream);
+                {
+                    ProfScope ps(ctx, ATOMO_K_SVD_EIG, stream);
+                    launch_svd_eig(d_mats, w_eig_gs, (int)plan.eig_gs.size(), w_twosided, own_launch ? 0 : n_two, w_gs_list,
+                                   (int)plan.gs_list.size(), cyclic, tick, limit_gs, stop_cosine, max_inner,
+                                   inner_reduction, full_period, 0, ctx->d_flags, stream);
+                }
+                if (own_launch) {
+                    ProfScope ps(ctx, ATOMO_K_SVD_UPDATE, stream);
+                    svd_twosided<<<(unsigned)n_two, 256, 0, stream>>>(d_mats, w_twosided, n_two, tick - 1);
+                }
             }
             bool boundary = false;
             for (int period : plan.gs_periods) boundary = boundary || (tick % period == 0 && tick <= limit_gs * period);
-            if (!boundary) continue;
-            // a sweep boundary of some matrix: those that asked for it get a fresh Gram matrix (their Tgs is
-            // complete now), and their pair problems of this tick run in a launch of their own
-            {
-                ProfScope ps(ctx, ATOMO_K_SVD_REFRESH, stream);
-                svd_apply<<<grid(plan.apply), 256, 0, stream>>>(d_mats, w_apply);
-                svd_gram<true><<<grid(plan.fullgram), 256, 0, stream>>>(d_mats, w_fullgram, tick, limit_gs);
-                svd_fullgram_reduce<<<grid(plan.tiles), 256, 0, stream>>>(d_mats, w_tiles, tick);
-                svd_fresh_check<<<grid(plan.tiles), 256, 0, stream>>>(d_mats, w_tiles, tick, limit_gs, stop_cosine,
-                                                                      fresh_stop, ctx->d_flags);
-            }
-            {
-                ProfScope ps(ctx, ATOMO_K_SVD_EIG, stream);
-                launch_svd_eig(d_mats, w_eig_gs, (int)plan.eig_gs.size(), nullptr, 0, nullptr, 0, 0, tick, limit_gs,
-                               stop_cosine, max_inner, inner_reduction, full_period, 1, ctx->d_flags, stream);
+            if (boundary) {
+                // a sweep boundary of some matrix: those that asked for it get a fresh Gram matrix (their Tgs is
+                // complete now), and their pair problems of this tick run in a launch of their own
+                {
+                    ProfScope ps(ctx, ATOMO_K_SVD_REFRESH, stream);
+                    svd_apply<<<grid(plan.apply), 256, 0, stream>>>(d_mats, w_apply);
+                    svd_gram<true><<<grid(plan.fullgram), 256, 0, stream>>>(d_mats, w_fullgram, tick, limit_gs);
+                    svd_fullgram_reduce<<<grid(plan.tiles), 256, 0, stream>>>(d_mats, w_tiles, tick);
+                    svd_fresh_check<<<grid(plan.tiles), 256, 0, stream>>>(d_mats, w_tiles, tick, limit_gs, stop_cosine,
+                                                                          fresh_stop, ctx->d_flags);
+                }
+                {
+                    ProfScope ps(ctx, ATOMO_K_SVD_EIG, stream);
+                    launch_svd_eig(d_mats, w_eig_gs, (int)plan.eig_gs.size(), nullptr, 0, nullptr, 0, 0, tick, limit_gs,
+                                   stop_cosine, max_inner, inner_reduction, full_period, 1, ctx->d_flags, stream);
+                }
             }
         }
         {
