@@ -10,10 +10,14 @@ Prints ONE JSON line.  `value` = gradient elements encoded+decoded per second.
 `roofline` prices the encode as a whole: contraction flops the algorithm executes on real data (no
 padding, measured sweep counts) over the GPU time of one encode, taken inside the timed region from two HIP
 events per step (one before the encode, one after it, on the stream the library launches on), against the
-fp32 matrix-core peak.  `roofline.by_kernel` breaks the step down by kernel class from a second pass over
-the same K steps with events around every launch (slower than the timed pass: the events cost a few
+fp32 matrix-core peak.  `roofline.by_kernel_event_pass` breaks the step down by kernel class from a second pass
+over the same K steps with events around every launch (slower than the timed pass: the events cost a few
 microseconds per launch and the two streams of the encoder overlap; for detail, not for `achieved`).
 `cpu_baseline` is the fp64 oracle, as it stands, timed on this machine's host cores.
+
+`--leg NAME` runs one part alone, for profiling: `headline` (the timed steps and nothing else; prints the same
+JSON line with the other legs null), or one of `entrywise`, `aggregate`, `section6`, `single`, `batch64` (prints
+that leg's object only).
 """
 from __future__ import annotations
 
@@ -129,6 +133,9 @@ def main():
     ap.add_argument("--no-entrywise", action="store_true", help="skip the entry-wise and 16-worker decode legs")
     ap.add_argument("--no-adaptive", action="store_true",
                     help="enqueue the launches of all max_sweeps sweeps in every step (atomo_svd_options.adaptive = 0)")
+    ap.add_argument("--leg", choices=["headline", "entrywise", "aggregate", "section6", "single", "batch64"], default=None,
+                    help="run this part alone (for a profiler): `headline` prints the usual line without the other "
+                         "legs, the others print their own object only")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run five plain device copies of 1 GiB, the known-size reference that scales the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
@@ -149,6 +156,22 @@ def main():
     ctx = binding.Context(0)
     S, SEED = 3.0, 0
     shapes = list(inputs.RESNET18_SHAPES)
+    if args.leg and args.leg != "headline":
+        if args.leg == "entrywise":
+            result = entrywise_leg(ctx, torch, binding, inputs)
+        elif args.leg == "aggregate":
+            result = aggregate_decode_leg(ctx, torch, binding, inputs, shapes, S, SEED)
+        elif args.leg == "section6":
+            result = section6_leg(ctx, torch, binding, inputs, S, SEED)
+        elif args.leg == "single":
+            result = single_layer_leg(ctx, torch, binding, inputs)
+        else:
+            result = batch64_leg(ctx, torch, binding, inputs, not args.no_cpu_baseline)
+        if args.calibration_copy:
+            calibration_copy(torch)
+        print(json.dumps({"leg": args.leg, "result": result}))
+        return
+    headline_only = args.leg == "headline" or args.no_entrywise
     host = inputs.resnet18_layer_set(0)
     mats = [torch.from_numpy(g).cuda() for g in host]
     n_elem = sum(g.size for g in host)
@@ -248,15 +271,15 @@ def main():
             "tflops_over_encode": round(dense_equivalent / (encode_ms * 1e-3) / 1e12, 3),
         },
     }
-    entrywise = None if args.no_entrywise else entrywise_leg(ctx, torch, binding, inputs)
-    aggregate = None if args.no_entrywise else aggregate_decode_leg(ctx, torch, binding, inputs, shapes, S, SEED)
-    section6 = None if args.no_entrywise else section6_leg(ctx, torch, binding, inputs, S, SEED)
-    single = single_layer_leg(ctx, torch, binding, inputs)
-    batch64 = None if args.no_entrywise else batch64_leg(ctx, torch, binding, inputs, not args.no_cpu_baseline)
+    entrywise = None if headline_only else entrywise_leg(ctx, torch, binding, inputs)
+    aggregate = None if headline_only else aggregate_decode_leg(ctx, torch, binding, inputs, shapes, S, SEED)
+    section6 = None if headline_only else section6_leg(ctx, torch, binding, inputs, S, SEED)
+    single = None if args.leg == "headline" else single_layer_leg(ctx, torch, binding, inputs)
+    batch64 = None if headline_only else batch64_leg(ctx, torch, binding, inputs, not args.no_cpu_baseline)
     # What a plain device-to-device copy reaches on this GPU (1 GiB, so nothing is served from a cache): context for
     # the HBM fractions above, which are all taken against the published 8 TB/s.
     copy_gbs = None
-    if not args.no_entrywise:
+    if not headline_only:
         src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
         dst.copy_(src)
@@ -268,11 +291,7 @@ def main():
         copy_gbs = round(5 * 2.0 * src.numel() * 4 / (time.perf_counter() - t0) / 1e9, 1)
         del src, dst
     if args.calibration_copy:
-        src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
-        dst = torch.empty_like(src)
-        for _ in range(5):
-            dst.copy_(src)
-        torch.cuda.synchronize()
+        calibration_copy(torch)
 
     cpu = None
     if not args.no_cpu_baseline and os.environ.get("ATOMO_BENCH_SKIP_CPU") != "1":
@@ -295,9 +314,19 @@ def main():
         "single_conv_layer_64x576": single,
         "batch_of_64_matrices_512x4608": batch64,
         "plain_copy_read_plus_write_gbs": copy_gbs,
-        "fp32_mfma_loop_tflops": round(ctx.measure_mfma_fp32(), 1),
+        "fp32_mfma_loop_tflops": None if args.leg == "headline" else round(ctx.measure_mfma_fp32(), 1),
     }
     print(json.dumps(line))
+
+
+def calibration_copy(torch):
+    """Five plain device-to-device copies of 1 GiB: the transfer of known size against which the FETCH_SIZE and
+    WRITE_SIZE counters of a rocprofv3 --pmc run of this script are scaled."""
+    src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(5):
+        dst.copy_(src)
+    torch.cuda.synchronize()
 
 
 def aggregate_decode_leg(ctx, torch, binding, inputs, shapes, s, seed, workers=16, reps=20):
@@ -458,7 +487,7 @@ def batch64_leg(ctx, torch, binding, inputs, with_oracle, reps=3):
     msgs = [binding.alloc_svd_message(m, n, binding.default_capacity(s, min(m, n)), "cuda") for m, n in shapes]
     outs = [torch.empty(m, n, dtype=torch.float32, device="cuda") for m, n in shapes]
     groups = [[m] for m in msgs]
-    for _ in range(2):
+    for _ in range(4):          # enough for every slot of the library's staging ring to have grown to this batch
         binding.atomo_encode_svd(ctx, mats, s, seed, 0, msgs=msgs, adaptive=1)
         binding.atomo_decode_svd_batch(ctx, groups, 1.0, outs=outs)
         torch.cuda.synchronize()

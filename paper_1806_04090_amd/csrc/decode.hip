@@ -3,7 +3,8 @@
 // SVD messages: out = scale * sum_msgs sum_k w_k u_k v_k^T, a dense rank-(sum k) update written once.
 // Each workgroup owns a 64 x 256 tile of one output and contracts the atoms of every message summed into
 // it on the matrix cores.  Few atoms (one worker, budget 3): bound by the HBM write of the tile.  Many
-// (the average over 16 workers, rank ~ 48): near the ridge between the two.
+// (the average over 16 workers, rank ~ 48): the 2 m n K flops take as long on the fp32 matrix cores as the write,
+// and the workgroups, which all start together, go through listing, products and stores in step.
 // The same kernel adds the update to what `out` holds instead of overwriting it (the parameter server's step,
 // params += alpha * average gradient), and takes messages in the folded form (weight inside U).
 // Entry-wise messages: zero fill, then one scatter launch per message in call order (bit-identical from run to run).
@@ -44,33 +45,43 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 // out tile (64 x 256) = sum over messages and kept atoms of (scale w_k u_k) v_k^T as a rank-K update on the
 // matrix cores: A operand (row i, atom k) = scale w_k U[k][i], B operand (atom k, column j) = V[k][j],
 // v_mfma_f32_32x32x2f32, two atoms per instruction.  Wave w owns columns 64 w .. 64 w + 63 of the tile as
-// 2 x 2 blocks of 32 x 32.  The kept atoms of a batch of messages (`batch` x largest capacity <= ATOMS_MAX,
-// chosen by the host) are first listed in LDS, one round trip for all counts and weights, so that the
-// contraction loop only chases pointers it already holds; operands come straight from global memory
-// (every atom's u and v are contiguous rows of its message).  An odd atom count pads with a zero weight.
-// A message with a capacity above ATOMS_MAX is a batch of its own and is listed and contracted in pieces of
+// 2 x 2 blocks of 32 x 32.
+// The kept atoms of a batch of messages (`batch` x largest capacity <= ATOMS_MAX, chosen by the host) are first
+// listed in LDS (one round trip for all counts).  The operands then come through LDS in pieces of KP atoms: all
+// 256 threads fetch the piece's slices of u (64 rows) and v (256 columns) with 16-byte loads that are all in
+// flight at once - every atom's u and v are contiguous rows of its message -, and the loads of the next piece
+// are issued before the products of the current one.  The weight is applied on the way into LDS.
+// A message with a capacity above ATOMS_MAX is a batch of its own and is listed and contracted in runs of
 // ATOMS_MAX atoms.
 // TALL: outputs of at most 32 columns (the [x*y/2, 2*k*k] reshape of Section 6).  The workgroup owns 256 rows,
 // wave w rows 64 w .. 64 w + 63, one 32-column block.
+constexpr int KP = 16;             // atoms per piece (8 and 24 measure the same; 32 leaves room for two workgroups per
+                                   // compute unit instead of four and is a third slower)
+
 template <bool TALL, bool ACCUMULATE>
 __global__ __launch_bounds__(256) void decode_svd_tiles(const DecOut* outs, const DecMsg* msgs, const DecWork* work,
                                                         float scale, int batch)
 {
     constexpr int NCB = TALL ? 1 : 2;
+    constexpr int UROWS = TALL ? TALL_ROWS : TR;                 // rows of the tile = length of a u slice
+    constexpr int VCOLS = TALL ? 32 : TC;                        // columns of the tile = length of a v slice
+    constexpr int US = UROWS + 32, VS = VCOLS + 32;              // LDS strides: odd and even atoms on different banks
+    constexpr int NU = (KP * UROWS / 4 + 255) / 256;             // 16-byte loads per thread and piece, u and v
+    constexpr int NV = (KP * VCOLS / 4 + 255) / 256;
     __shared__ const float* up[ATOMS_MAX];
     __shared__ const float* vp[ATOMS_MAX];
-    __shared__ float wv[ATOMS_MAX];
+    __shared__ const float* wp[ATOMS_MAX];                       // the atom's weight (nullptr: folded into u)
     __shared__ int kept_of[ATOMS_MAX];
     __shared__ int total_sh;
+    __shared__ __attribute__((aligned(16))) float Us[KP * US];
+    __shared__ __attribute__((aligned(16))) float Vs[KP * VS];
     const DecWork wk = work[blockIdx.x];
     const DecOut o = outs[wk.out];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int h = lane >> 5, l32 = lane & 31;
-    const int r0 = TALL ? wk.tile_r * TALL_ROWS + wave * 64 : wk.tile_r * TR;
-    const int c0 = TALL ? 0 : wk.tile_c * TC + wave * 64;
-    const int row_a = r0 + l32, row_b = r0 + 32 + l32;          // rows this lane feeds as A operands
-    const int col_a = c0 + l32, col_b = c0 + 32 + l32;          // columns this lane feeds as B operands
-    const bool ra = row_a < o.rows, rb_ok = row_b < o.rows, ca = col_a < o.cols, cb_ok = !TALL && col_b < o.cols;
+    const int tile_r0 = TALL ? wk.tile_r * TALL_ROWS : wk.tile_r * TR;
+    const int tile_c0 = TALL ? 0 : wk.tile_c * TC;
+    const int row_off = TALL ? wave * 64 : 0, col_off = TALL ? 0 : wave * 64;    // this wave's corner inside the tile
     floatx16 acc[2][NCB];
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb)
@@ -79,59 +90,101 @@ __global__ __launch_bounds__(256) void decode_svd_tiles(const DecOut* outs, cons
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[rb][cb][v] = 0.0f;
 
+    // four consecutive elements of an atom's row, zero beyond `limit`; one 16-byte load where the address allows
+    auto load4 = [](const float* base, int at, int limit) {
+        float4 x = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        const float* p = base + at;
+        if (at + 3 < limit && (((size_t)p) & 15) == 0) {
+            x = *(const float4*)p;
+        } else {
+            if (at < limit) x.x = p[0];
+            if (at + 1 < limit) x.y = p[1];
+            if (at + 2 < limit) x.z = p[2];
+            if (at + 3 < limit) x.w = p[3];
+        }
+        return x;
+    };
+    float4 ru[NU], rv[NV];
+    // the loads of the piece that starts at list position k0 (positions from `total` on read as zero)
+    auto fetch = [&](int k0, int total) {
+#pragma unroll
+        for (int e = 0; e < NU; ++e) {
+            const int f = tid + 256 * e, atom = f / (UROWS / 4), part = f % (UROWS / 4);
+            ru[e] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            if (atom < KP && k0 + atom < total) {
+                const float* w = wp[k0 + atom];
+                const float wgt = w ? scale * *w : scale;
+                const float4 x = load4(up[k0 + atom], tile_r0 + 4 * part, o.rows);
+                ru[e] = make_float4(wgt * x.x, wgt * x.y, wgt * x.z, wgt * x.w);
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < NV; ++e) {
+            const int f = tid + 256 * e, atom = f / (VCOLS / 4), part = f % (VCOLS / 4);
+            rv[e] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            if (atom < KP && k0 + atom < total) rv[e] = load4(vp[k0 + atom], tile_c0 + 4 * part, o.cols);
+        }
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int e = 0; e < NU; ++e) {
+            const int f = tid + 256 * e, atom = f / (UROWS / 4), part = f % (UROWS / 4);
+            if (atom < KP) *(float4*)&Us[atom * US + 4 * part] = ru[e];
+        }
+#pragma unroll
+        for (int e = 0; e < NV; ++e) {
+            const int f = tid + 256 * e, atom = f / (VCOLS / 4), part = f % (VCOLS / 4);
+            if (atom < KP) *(float4*)&Vs[atom * VS + 4 * part] = rv[e];
+        }
+    };
+
     for (int first = o.first; first < o.last; first += batch) {
         const int nm = min(batch, o.last - first);
         __syncthreads();                                         // the previous list is spent
         for (int q = tid; q < nm; q += 256) kept_of[q] = min(*msgs[first + q].count, msgs[first + q].capacity);
         __syncthreads();
-        // several messages: everything fits the list by the host's choice of `batch` (one piece); a message of its
-        // own: pieces of ATOMS_MAX atoms, `piece` = first atom of the piece
+        // several messages: everything fits the list by the host's choice of `batch` (one run); a message of its
+        // own: runs of ATOMS_MAX atoms, `run` = first atom of the run
         const int span = nm == 1 ? kept_of[0] : 1;
-      for (int piece = 0; piece < span; piece += ATOMS_MAX) {
-        if (piece > 0) __syncthreads();                          // the previous piece is spent
-        for (int q = tid; q < nm; q += 256) {
-            int at = 0;
-            for (int e = 0; e < q; ++e) at += kept_of[e];
-            const DecMsg m = msgs[first + q];
-            const int kept = max(0, min(kept_of[q] - piece, ATOMS_MAX - at));
-            for (int k = 0; k < kept; ++k) {
-                up[at + k] = m.U + (size_t)(piece + k) * o.rows;
-                vp[at + k] = m.V + (size_t)(piece + k) * o.cols;
-                wv[at + k] = m.w ? scale * m.w[piece + k] : scale; // folded messages carry the weight in U
+        for (int run = 0; run < span; run += ATOMS_MAX) {
+            if (run > 0) __syncthreads();                        // the previous run is spent
+            for (int q = tid; q < nm; q += 256) {
+                int at = 0;
+                for (int e = 0; e < q; ++e) at += kept_of[e];
+                const DecMsg m = msgs[first + q];
+                const int kept = max(0, min(kept_of[q] - run, ATOMS_MAX - at));
+                for (int k = 0; k < kept; ++k) {
+                    up[at + k] = m.U + (size_t)(run + k) * o.rows;
+                    vp[at + k] = m.V + (size_t)(run + k) * o.cols;
+                    wp[at + k] = m.w ? m.w + run + k : nullptr;    // folded messages carry the weight in U
+                }
+                if (q == nm - 1) total_sh = at + kept;
             }
-            if (q == nm - 1) total_sh = at + kept;
-        }
-        __syncthreads();
-        const int total = total_sh;
-        // four atom pairs per trip: all sixteen operand loads are issued before the first MFMA
-        for (int k0 = 0; k0 < total; k0 += 8) {
-            float a0[4], a1[4], b0[4], b1[4];
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const int kk = k0 + 2 * t + h;
-                const bool live = kk < total;
-                const float wgt = live ? wv[kk] : 0.0f;
-                const float* u = up[live ? kk : 0];
-                const float* v = vp[live ? kk : 0];
-                a0[t] = live && ra ? wgt * u[row_a] : 0.0f;
-                a1[t] = live && rb_ok ? wgt * u[row_b] : 0.0f;
-                b0[t] = live && ca ? v[col_a] : 0.0f;
-                b1[t] = live && cb_ok ? v[col_b] : 0.0f;
-            }
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                if (k0 + 2 * t < total) {                        // uniform: skip pairs past the end
-                    acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[t], b0[t], acc[0][0], 0, 0, 0);
-                    acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[t], b0[t], acc[1][0], 0, 0, 0);
+            __syncthreads();
+            const int total = total_sh;
+            if (total > 0) fetch(0, total);
+            for (int k0 = 0; k0 < total; k0 += KP) {
+                stage();
+                __syncthreads();
+                if (k0 + KP < total) fetch(k0 + KP, total);
+                const int pairs = (min(KP, total - k0) + 1) / 2;
+                for (int t = 0; t < pairs; ++t) {
+                    const float* ua = &Us[(2 * t + h) * US + row_off + l32];
+                    const float* vb = &Vs[(2 * t + h) * VS + col_off + l32];
+                    const float a0 = ua[0], a1 = ua[32], b0 = vb[0];
+                    acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+                    acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
                     if (!TALL) {
-                        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[t], b1[t], acc[0][1], 0, 0, 0);
-                        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[t], b1[t], acc[1][1], 0, 0, 0);
+                        const float b1 = vb[32];
+                        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+                        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
                     }
                 }
+                __syncthreads();                                 // the piece is spent
             }
         }
-      }
     }
+    const int r0 = tile_r0 + row_off, c0 = tile_c0 + col_off;
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
@@ -228,6 +281,20 @@ int decode_svd_batch(atomo_ctx* ctx, const atomo_svd_msg* msgs, const int32_t* f
         for (int a = 0; a < tr; ++a)
             for (int b = 0; b < tc; ++b) hw.push_back(DecWork{o, a, b, 0});
     }
+    // Workgroups go to the chip's eight dies in turn (workgroup b to die b mod 8), and each die has its own L2.  The
+    // tiles are dealt so that a die gets one contiguous run of the list, i.e. the tiles of a few outputs: the
+    // singular vectors of an output are then fetched into one L2 instead of all eight.
+    auto deal = [](std::vector<DecWork>& list) {
+        constexpr size_t DIES = 8;
+        const size_t n = list.size();
+        std::vector<DecWork> dealt(n);
+        size_t start[DIES + 1] = {0};
+        for (size_t x = 0; x < DIES; ++x) start[x + 1] = start[x] + (n + DIES - 1 - x) / DIES;
+        for (size_t b = 0; b < n; ++b) dealt[b] = list[start[b % DIES] + b / DIES];
+        list.swap(dealt);
+    };
+    deal(hw);
+    deal(hw_tall);
     const size_t n_wide = hw.size();
     hw.insert(hw.end(), hw_tall.begin(), hw_tall.end());
     // the three tables travel in one copy
