@@ -133,6 +133,21 @@ struct Carver {
     }
 };
 
+// Workgroups go to the chip's eight dies in turn (workgroup b to die b mod 8), and each die has its own L2.  Reorders a
+// work list so that every die gets one contiguous run of it: neighbours in the list, which read the same operands,
+// then find them in the same L2 instead of fetching them into all eight.
+template <typename T>
+inline void deal_to_dies(std::vector<T>& list)
+{
+    constexpr size_t DIES = 8;
+    const size_t n = list.size();
+    std::vector<T> dealt(n);
+    size_t start[DIES + 1] = {0};
+    for (size_t x = 0; x < DIES; ++x) start[x + 1] = start[x] + (n + DIES - 1 - x) / DIES;
+    for (size_t b = 0; b < n; ++b) dealt[b] = list[start[b % DIES] + b / DIES];
+    list.swap(dealt);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Philox4x32-10 (Salmon et al., SC'11): device + host inline so every kernel draws the same stream
 // ---------------------------------------------------------------------------------------------

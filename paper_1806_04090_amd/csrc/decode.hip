@@ -281,20 +281,10 @@ int decode_svd_batch(atomo_ctx* ctx, const atomo_svd_msg* msgs, const int32_t* f
         for (int a = 0; a < tr; ++a)
             for (int b = 0; b < tc; ++b) hw.push_back(DecWork{o, a, b, 0});
     }
-    // Workgroups go to the chip's eight dies in turn (workgroup b to die b mod 8), and each die has its own L2.  The
-    // tiles are dealt so that a die gets one contiguous run of the list, i.e. the tiles of a few outputs: the
-    // singular vectors of an output are then fetched into one L2 instead of all eight.
-    auto deal = [](std::vector<DecWork>& list) {
-        constexpr size_t DIES = 8;
-        const size_t n = list.size();
-        std::vector<DecWork> dealt(n);
-        size_t start[DIES + 1] = {0};
-        for (size_t x = 0; x < DIES; ++x) start[x + 1] = start[x] + (n + DIES - 1 - x) / DIES;
-        for (size_t b = 0; b < n; ++b) dealt[b] = list[start[b % DIES] + b / DIES];
-        list.swap(dealt);
-    };
-    deal(hw);
-    deal(hw_tall);
+    // every die gets a contiguous run of the tiles, i.e. the tiles of a few outputs: the singular vectors of an
+    // output are then fetched into one L2 instead of all eight
+    deal_to_dies(hw);
+    deal_to_dies(hw_tall);
     const size_t n_wide = hw.size();
     hw.insert(hw.end(), hw_tall.begin(), hw_tall.end());
     // the three tables travel in one copy
