@@ -57,8 +57,7 @@ typedef enum atomo_status_code {
     ATOMO_ENOCONV = -3,    /* (atomo_status only) the Jacobi SVD stopped at the sweep limit         */
     ATOMO_EHIP = -4,       /* a HIP runtime call failed; atomo_last_hip_error gives its code        */
     ATOMO_ENOMEM = -5,     /* the workspace could not be allocated                                  */
-    ATOMO_ETOOLARGE = -6,  /* atomo_encode_entrywise_noalloc: n exceeds what its fixed scratch holds */
-    ATOMO_ETIMEOUT = -7    /* (atomo_status only) a kernel whose workgroups wait for each other gave up    */
+    ATOMO_ETOOLARGE = -6   /* atomo_encode_entrywise_noalloc: n exceeds what its fixed scratch holds */
                            /* waiting: the results of the calls since the last status read are invalid      */
 } atomo_status_code;
 

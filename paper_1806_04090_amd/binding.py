@@ -18,7 +18,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libatomo.so")
 
-ATOMO_OK, ATOMO_EINVAL, ATOMO_ECAPACITY, ATOMO_ENOCONV, ATOMO_EHIP, ATOMO_ENOMEM, ATOMO_ETOOLARGE, ATOMO_ETIMEOUT = 0, -1, -2, -3, -4, -5, -6, -7
+ATOMO_OK, ATOMO_EINVAL, ATOMO_ECAPACITY, ATOMO_ENOCONV, ATOMO_EHIP, ATOMO_ENOMEM, ATOMO_ETOOLARGE = 0, -1, -2, -3, -4, -5, -6
 ATOMO_KIND_SVD, ATOMO_KIND_ENTRYWISE, ATOMO_KIND_LQ = 0, 1, 2
 
 

@@ -17,7 +17,7 @@ namespace atomo {
 // ---------------------------------------------------------------------------------------------
 
 // Device-side latched flags (int32 each).
-enum { FLAG_CAPACITY = 0, FLAG_NOCONV = 1, FLAG_MAX_SWEEPS = 2, FLAG_EIG_VISITS = 3, FLAG_EIG_INNER = 4, FLAG_TIMEOUT = 5, FLAG_COUNT = 8 };
+enum { FLAG_CAPACITY = 0, FLAG_NOCONV = 1, FLAG_MAX_SWEEPS = 2, FLAG_EIG_VISITS = 3, FLAG_EIG_INNER = 4, FLAG_COUNT = 8 };
 
 // What an SVD encode learnt about its own sweep counts, for the calls after it (atomo_svd_options.adaptive).
 struct SweepHint {
@@ -55,8 +55,6 @@ struct atomo_ctx {
     size_t report_cap = 0;               // pairs allocated
     size_t report_n = 0;                 // matrices of the last SVD encode
     // streams and events of the SVD encoder's internal fork/join (created on first use, default priority)
-    int n_cus = 0;                       // compute units of the device
-    unsigned int ew_epoch = 0;           // calls of the single-launch entry-wise encoder so far (parity of its counters)
     void* ew_state = nullptr;            // entry-wise encoder: search state kept from call to call (histograms zero between calls)
     atomo::SweepHint hints[4];
     int hint_next = 0;

@@ -112,10 +112,6 @@ int atomo_create(atomo_ctx** out, int device)
         delete ctx;
         return ATOMO_EHIP;
     }
-    {
-        hipDeviceProp_t prop;
-        if (hipGetDeviceProperties(&prop, device) == hipSuccess) ctx->n_cus = prop.multiProcessorCount;
-    }
     // set-up for atomo_encode_entrywise_noalloc: the address of its static scratch array on this device
     if (entrywise_noalloc_setup(ctx) != ATOMO_OK) {
         (void)hipFree(ctx->d_flags);
@@ -184,7 +180,6 @@ int atomo_status(atomo_ctx* ctx, void* stream, int32_t* sweeps)
     ATOMO_HIP(ctx, hipMemsetAsync(ctx->d_flags, 0, FLAG_COUNT * sizeof(int32_t), st));
     ATOMO_HIP(ctx, hipStreamSynchronize(st));
     if (sweeps) *sweeps = ctx->h_flags[FLAG_MAX_SWEEPS];
-    if (ctx->h_flags[FLAG_TIMEOUT]) return ATOMO_ETIMEOUT;
     if (ctx->h_flags[FLAG_CAPACITY]) return ATOMO_ECAPACITY;
     if (ctx->h_flags[FLAG_NOCONV]) return ATOMO_ENOCONV;
     return ATOMO_OK;
@@ -302,7 +297,6 @@ const char* atomo_strerror(int status)
         case ATOMO_ENOCONV: return "Jacobi SVD reached the sweep limit";
         case ATOMO_EHIP: return "HIP runtime error";
         case ATOMO_ENOMEM: return "out of device memory";
-        case ATOMO_ETIMEOUT: return "a bounded wait between workgroups ran out (the GPU could not hold the launch at once)";
         case ATOMO_ETOOLARGE: return "input longer than the fixed scratch of the allocation-free entry point holds";
         default: return "unknown status";
     }

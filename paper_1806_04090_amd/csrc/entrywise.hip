@@ -16,8 +16,11 @@
 // skipped on the device.
 //
 // Sampling and packing.  Coordinate i is kept iff u_i < p_i (Philox stream, float32 compare) and is
-// stored as (i, g_i / p_i) in ascending i: a counting pass per 4096-element chunk, a scan of the
-// chunk counts, and a writing pass that repeats the draws.
+// stored as (i, g_i / p_i) in ascending i.  The encoder reads the gradient twice ("the two-read encoder"
+// below): once for the level-0 histogram, once to draw every uniform and settle it against the bracket
+// that level 0 leaves for p_i; the few draws that fall inside the bracket wait for the exact water level.
+// The l_q encoder (Section 4), whose probabilities need only a norm, uses the plain form: a counting pass
+// per 4096-element chunk, a scan of the chunk counts, and a writing pass that reads the keep bits.
 #include <cmath>
 #include <vector>
 
@@ -538,7 +541,7 @@ __global__ __launch_bounds__(256) void ew_write(const float* __restrict__ g, con
 
 constexpr int SUPER = 256;                   // chunks per entry of the coarse count table
 
-// Second pass, one chunk per workgroup; the level-0 result is read from st->lvl[0] (ew_solve<0> ran before).
+// Second pass, one chunk per workgroup; the level-0 result is read from st->lvl[0] (the launch before left it there).
 // Layout of the keep / undecided bits: see ew_count.
 __global__ __launch_bounds__(256) void ew_pass_b(const float* __restrict__ g, long long n, long long n_chunks, EwState* st,
                                                  double s, unsigned long long stream_id, unsigned long long seed,

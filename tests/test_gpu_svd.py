@@ -288,6 +288,45 @@ def test_largest_supported_rank_and_the_first_rejected_one():
         binding.atomo_encode_svd(ctx(), [torch.zeros(2049, 2049, device="cuda")], 3.0, 1, 0)
 
 
+def test_bias_of_the_rounding_floor_on_a_graded_spectrum():
+    # Singular values graded from 1 down to 1e-9, i.e. across the fp32 rounding floor 32 * 2^-24 * sigma_1 = 1.9e-6
+    # below which the encoder reports sigma = 0 (so p = 0 and the atom is never sent).  With the budget at the
+    # number of atoms every atom that is reported has p = 1 (KKT appendix), the message is deterministic and its
+    # decode IS E[g_hat]: what is missing from G is the bias that the floor costs.  It is bounded by the atoms under
+    # the floor (at most sqrt(r) * floor in Frobenius norm) plus the fp32 error of the ones above; the oracle, in
+    # fp64, keeps every atom and has no such bias.
+    rng = np.random.default_rng(21)
+    r, n = 96, 200
+    sig = 10.0 ** (-9.0 * np.arange(r) / (r - 1))
+    U, _ = np.linalg.qr(rng.standard_normal((r, r)))
+    V, _ = np.linalg.qr(rng.standard_normal((n, r)))
+    G = ((U * sig) @ V.T).astype(np.float32)
+    msgs, per, status, _ = encode([G], float(r), 4, capacity=r, max_sweeps=32)
+    assert status == 0
+    sig_gpu, p_gpu = per[0]
+    ref = np.linalg.svd(G.astype(np.float64), compute_uv=False)
+    floor = 32 * 2.0 ** -24 * ref[0]
+    # reported values are either above the floor or exactly zero; zeros only where the true value is within the
+    # fp32 error of the floor or below it (for those the error is the value itself: up to the floor, not 1e-4 of
+    # anything); everything that is reported meets the usual tolerance
+    zero = sig_gpu == 0
+    assert (zero | (sig_gpu >= 0.5 * floor)).all()
+    assert (ref[zero] <= 2 * floor).all()
+    assert sigma_tolerance_ok(sig_gpu[~zero], ref[~zero]).all(), float(np.abs(sig_gpu - ref)[~zero].max())
+    assert (p_gpu[sig_gpu > 0] == 1).all() and (p_gpu[sig_gpu == 0] == 0).all()
+    h = msgs[0].to_host()
+    assert h["count"] == int((sig_gpu > 0).sum())
+    out = binding.atomo_decode(ctx(), msgs).cpu().numpy().astype(np.float64)
+    bias = np.linalg.norm(out - G.astype(np.float64))
+    dropped = np.sqrt((ref[sig_gpu == 0] ** 2).sum())
+    assert dropped <= np.sqrt(r) * 2 * floor
+    assert bias <= dropped + 1e-5 * ref[0], (bias, dropped)
+    # the oracle's estimator on the same matrix with the same budget returns G itself
+    enc = oracle.encode_svd(G, float(r), 4, 0)
+    want = oracle.decode_svd([enc], r, n)
+    assert np.linalg.norm(want - G.astype(np.float64)) <= 1e-12 * ref[0] * r
+
+
 def test_adaptive_sweep_budget_gives_the_same_messages_and_reports_when_it_falls_short():
     # a training loop: the same shapes step after step, launches for the sweeps the previous steps needed plus one
     shapes = [(64, 576), (256, 1152), (512, 600)]
