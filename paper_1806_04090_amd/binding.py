@@ -16,7 +16,8 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libatomo.so")
+# ATOMO_LIB: load this build of the library instead (the host-sanitizer build of build.py, for instance)
+LIB_PATH = os.environ.get("ATOMO_LIB") or os.path.join(_HERE, "libatomo.so")
 
 ATOMO_OK, ATOMO_EINVAL, ATOMO_ECAPACITY, ATOMO_ENOCONV, ATOMO_EHIP, ATOMO_ENOMEM, ATOMO_ETOOLARGE = 0, -1, -2, -3, -4, -5, -6
 ATOMO_KIND_SVD, ATOMO_KIND_ENTRYWISE, ATOMO_KIND_LQ = 0, 1, 2

@@ -83,6 +83,29 @@ def test_resnet18_layer_set_every_layer_against_the_oracle():
         decode_matches(out, oracle.decode_svd([h], *G.shape))
 
 
+def test_resnet18_layer_set_as_bench_times_it():
+    # bench.py's timed loop: the same message buffers reused step after step, `adaptive = 1` (launches for the sweeps
+    # the steps before needed plus one), decode into the same outputs.  Every step must leave the messages and the
+    # decoded gradients of the default call, bit for bit, and a clean status.
+    mats = inputs.resnet18_layer_set(0)
+    want, _, status, _ = encode_set(mats, 3.0, 0, 0)
+    assert status == 0
+    want_h = [m.to_host() for m in want]
+    want_out = [o.cpu().numpy() for o in binding.atomo_decode_svd_batch(ctx(), [[m] for m in want])]
+    d_mats = [dev(g) for g in mats]
+    msgs = [binding.alloc_svd_message(g.shape[0], g.shape[1], binding.default_capacity(3.0, min(g.shape)), "cuda") for g in mats]
+    outs = [torch.empty(g.shape, dtype=torch.float32, device="cuda") for g in mats]
+    for step in range(4):
+        binding.atomo_encode_svd(ctx(), d_mats, 3.0, 0, 0, msgs=msgs, adaptive=1)
+        binding.atomo_decode_svd_batch(ctx(), [[m] for m in msgs], 1.0, outs=outs)
+    assert ctx().status()[0] == 0
+    for a, m, w, o in zip(want_h, msgs, want_out, outs):
+        b = m.to_host()
+        assert a["count"] == b["count"] and np.array_equal(a["idx"], b["idx"])
+        assert all(np.array_equal(a[k], b[k]) for k in ("w", "U", "V"))
+        assert np.array_equal(w, o.cpu().numpy())
+
+
 def test_vgg_batch_of_64_deep_conv_layers():
     mats = inputs.vgg_deep_conv_batch(0)
     assert len(mats) == 64 and mats[0].shape == (512, 4608)
