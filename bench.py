@@ -47,39 +47,49 @@ def layer_geometry(m, n):
     return r, M, nb2 >= 16
 
 
-def executed_work(shapes, sweeps, refreshes, pair_visits, jacobi_steps, n_elem, kept_atoms):
+def block_rows(r):
+    """Real rows in each 32-row block of a layer with r vectors, the zero block of an odd count included."""
+    nb = -(-r // 32)
+    rows = [min(32, r - 32 * b) for b in range(nb)]
+    return rows + [0] * (nb & 1)
+
+
+def executed_work(shapes, sweeps, refreshes, pair_visits, jacobi_steps, row_update_tiles, n_elem, kept_atoms):
     """Arithmetic and bytes the algorithm executes on real data (no padding) per step, by kernel class.
 
     Thin layers (r <= 32) are streaming passes over the data (svd_thin), priced by their bytes.
-    Data-space layers (32 < r <= 480), per sweep: block-pair Gram matrices 4 M r^2 (svd_gram), rotation of [A | T]
-    4 M r^2 + 4 r^3 (svd_update).
+    A sweep visits every pair (i, j) of the layer's 32-row blocks once, n_i + n_j real rows per pair.
+    Data-space layers (32 < r <= 480): pair Gram matrices 2 (n_i + n_j)^2 M per visit (svd_gram); the row update
+    2 x 64 x 64 x 64 per 64 x 64 tile of [A | T] that svd_rowop rotated, counted on the device (pairs found converged
+    are left alone; svd_update).
     Gram-space layers, per refresh (svd_refresh): upper-triangular tiles of A A^T  M r (r + 64), and (every
-    refresh but the first) A <- T A and T <- T T_old, 2 r^2 (M + r); per sweep, inside the svd_eig launches:
-    two-sided rotation of C 8 r^3, accumulation into T 4 r^3, and per pair problem the three 32x32 blocks
-    it brings up to date itself.
+    refresh but the first) A <- T A and T <- T T_old, 2 r^2 (M + r); per tick of a sweep, inside the svd_eig
+    launches: C <- D^T C D  256 r^2 and Tgs <- D^T Tgs  128 r^2 (D block-diagonal in 64 x 64 blocks), and per pair
+    problem the three 32x32 blocks it brings up to date itself.
     64 x 64 eigen-solves: 32 rotations per Jacobi step (63 steps when every index pair is rotated, 32 when only
     the pairs that couple the two blocks are), each 3 x 64 x 6 flops on the vector ALU (rows and columns of the
     block, columns of the accumulator), plus a Newton-Schulz step of two 64^3 products per solve.  The
     svd_eig class is priced as a whole (vector-ALU rotations + the MFMA work its launches carry) against the
     157.3 TFLOP/s that is both the fp32 vector and the fp32 matrix peak.
     """
-    gram = upd = refresh = twosided = catchup = thin_bytes = 0.0
+    gram = refresh = twosided = catchup = thin_bytes = 0.0
     for (m, n), sw, rf in zip(shapes, sweeps, refreshes):
         r, M, gs = layer_geometry(m, n)
         if r <= 32:
             # thin layers: largest-entry pass, first Gram pass, one read + write per rotation, gather of the kept atoms
             thin_bytes += 4.0 * M * r * (3 + 2 * sw)
-        elif gs:
-            nb = -(-r // 32)
-            nb2 = nb + (nb & 1)
+            continue
+        rows = block_rows(r)
+        nb2 = len(rows)
+        if gs:
             visits = sw * (nb2 - 1) * (nb2 // 2)
             refresh += rf * M * r * (r + 64.0) + max(rf - 1, 0) * 2.0 * r * r * (M + r)
-            twosided += sw * 12.0 * r ** 3
+            twosided += sw * (nb2 - 1) * 384.0 * r * r
             # every pair problem but the first after a refresh forms its block from three 32x32 products
             catchup += max(visits - rf * (nb2 // 2), 0) * 3 * 2.0 * (32 * 64 * 64 + 32 * 64 * 32)
         else:
-            gram += sw * 4.0 * M * r * r
-            upd += sw * (4.0 * M * r * r + 4.0 * r ** 3)
+            gram += sw * sum(2.0 * (rows[i] + rows[j]) ** 2 * M for i in range(nb2) for j in range(i + 1, nb2))
+    upd = row_update_tiles * 2.0 * 64 ** 3
     eig = jacobi_steps * 32 * 3 * 64 * 6 + pair_visits * 2 * 2 * 64 ** 3 + twosided + catchup
     decode_bytes = 4.0 * n_elem + sum(4.0 * k * (m + n + 1) for (m, n), k in zip(shapes, kept_atoms))
     return {
@@ -233,11 +243,11 @@ def main():
     ctx.status()
     step()                                      # one step between two status reads: counters of exactly one step
     ctx.status()
-    pair_visits, jacobi_steps = ctx.last_counters()
+    pair_visits, jacobi_steps, row_update_tiles = ctx.last_counters()
 
     per_step_ms = {k: v[0] / args.steps for k, v in prof.items() if v[1]}
     launches = {k: v[1] / args.steps for k, v in prof.items() if v[1]}
-    work = executed_work(shapes, sweeps, refreshes, pair_visits, jacobi_steps, n_elem, kept_atoms)
+    work = executed_work(shapes, sweeps, refreshes, pair_visits, jacobi_steps, row_update_tiles, n_elem, kept_atoms)
     rotations = jacobi_steps * 32 * 3 * 64 * 6
     # contraction flops executed on the matrix cores in one encode (the vector-ALU rotations are reported beside them)
     contraction = sum(work[k][1] for k in ("svd_gram", "svd_update", "svd_refresh")) + work["svd_eig"][1] - rotations
@@ -262,6 +272,7 @@ def main():
         "jacobi_sweeps_per_layer": sweeps,
         "gram_refreshes_per_layer": refreshes,
         "eigen_solves_per_step": pair_visits, "jacobi_steps_per_step": jacobi_steps,
+        "row_update_tiles_per_step": row_update_tiles,
         "by_kernel_event_pass": by_kernel,
         "ms_per_step_event_pass": round(ms_per_step_profiled, 4),
         # what the same sweep counts would cost as textbook blocked one-sided Jacobi on the data,
@@ -511,8 +522,8 @@ def batch64_leg(ctx, torch, binding, inputs, with_oracle, reps=3):
     kept = [int(m.count.item()) for m in msgs]
     binding.atomo_encode_svd(ctx, mats, s, seed, 0, msgs=msgs, adaptive=1)   # counters of exactly one encode
     ctx.status()
-    pair_visits, jacobi_steps = ctx.last_counters()
-    work = executed_work(shapes, sweeps, refreshes, pair_visits, jacobi_steps, n_elem, kept)
+    pair_visits, jacobi_steps, row_update_tiles = ctx.last_counters()
+    work = executed_work(shapes, sweeps, refreshes, pair_visits, jacobi_steps, row_update_tiles, n_elem, kept)
     rotations = jacobi_steps * 32 * 3 * 64 * 6
     contraction = sum(work[k][1] for k in ("svd_gram", "svd_update", "svd_refresh")) + work["svd_eig"][1] - rotations
     dec_bytes = work["decode_svd"][1]

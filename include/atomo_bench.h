@@ -13,9 +13,12 @@ extern "C" {
 #endif
 
 /* Work counters as read by the most recent atomo_status call (host-side only): how many 64x64
- * block-pair eigenproblems the Jacobi SVD solved since the status call before it, and how many
- * Jacobi steps (32 disjoint plane rotations each) those took in total. */
-int atomo_last_counters(const atomo_ctx* ctx, int32_t* pair_visits /*host*/, int32_t* jacobi_steps /*host*/);
+ * block-pair eigenproblems the Jacobi SVD solved since the status call before it, how many
+ * Jacobi steps (32 disjoint plane rotations each) those took in total, and how many 64-row x
+ * 64-column tiles of the data the row updates of the data-space matrices rotated (pairs that
+ * were found converged are left alone and not counted). */
+int atomo_last_counters(const atomo_ctx* ctx, int32_t* pair_visits /*host*/, int32_t* jacobi_steps /*host*/,
+                        int32_t* row_update_tiles /*host*/);
 
 /* Kernel classes whose GPU time can be measured with HIP events (for benchmarks; not part of the
  * method).  While profiling is on, every launch of these kernels is bracketed by two events on the

@@ -87,7 +87,7 @@ def lib() -> C.CDLL:
                                              C.POINTER(vp), C.POINTER(C.c_int64), vp]
         L.atomo_apply_svd_batch.argtypes = L.atomo_decode_svd_batch.argtypes
         L.atomo_svd_sweeps.argtypes = [vp, vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int]
-        L.atomo_last_counters.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+        L.atomo_last_counters.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         L.atomo_measure_mfma_fp32.argtypes = [vp, C.POINTER(C.c_double), vp]
         L.atomo_profile_enable.argtypes = [vp, C.c_int]
         L.atomo_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
@@ -269,10 +269,11 @@ class Context:
         return {name: (ms[i], cnt[i]) for i, name in enumerate(self.KERNEL_CLASSES)}
 
     def last_counters(self):
-        """(block-pair eigenproblems solved, Jacobi steps of 32 rotations taken) as of the last status() call."""
-        a, b = C.c_int32(0), C.c_int32(0)
-        _check(lib().atomo_last_counters(self._h, C.byref(a), C.byref(b)), "atomo_last_counters")
-        return int(a.value), int(b.value)
+        """(block-pair eigenproblems solved, Jacobi steps of 32 rotations taken, 64 x 64 tiles rotated by the row
+        updates of the data-space matrices) as of the last status() call."""
+        a, b, c = C.c_int32(0), C.c_int32(0), C.c_int32(0)
+        _check(lib().atomo_last_counters(self._h, C.byref(a), C.byref(b), C.byref(c)), "atomo_last_counters")
+        return int(a.value), int(b.value), int(c.value)
 
     def svd_sweeps(self, n_mats: int, stream: Optional[torch.cuda.Stream] = None) -> List[int]:
         """Jacobi sweeps each matrix of the last atomo_encode_svd took (waits for the stream)."""

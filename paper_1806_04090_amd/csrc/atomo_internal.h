@@ -17,7 +17,7 @@ namespace atomo {
 // ---------------------------------------------------------------------------------------------
 
 // Device-side latched flags (int32 each).
-enum { FLAG_CAPACITY = 0, FLAG_NOCONV = 1, FLAG_MAX_SWEEPS = 2, FLAG_EIG_VISITS = 3, FLAG_EIG_INNER = 4, FLAG_COUNT = 8 };
+enum { FLAG_CAPACITY = 0, FLAG_NOCONV = 1, FLAG_MAX_SWEEPS = 2, FLAG_EIG_VISITS = 3, FLAG_EIG_INNER = 4, FLAG_DS_UPDATE_UNITS = 5, FLAG_COUNT = 8 };
 
 // What an SVD encode learnt about its own sweep counts, for the calls after it (atomo_svd_options.adaptive).
 struct SweepHint {

@@ -280,11 +280,12 @@ int atomo_measure_mfma_fp32(atomo_ctx* ctx, double* tflops, void* stream)
 
 int atomo_last_hip_error(const atomo_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
 
-int atomo_last_counters(const atomo_ctx* ctx, int32_t* pair_visits, int32_t* jacobi_steps)
+int atomo_last_counters(const atomo_ctx* ctx, int32_t* pair_visits, int32_t* jacobi_steps, int32_t* row_update_tiles)
 {
-    if (!ctx || !pair_visits || !jacobi_steps) return ATOMO_EINVAL;
+    if (!ctx || !pair_visits || !jacobi_steps || !row_update_tiles) return ATOMO_EINVAL;
     *pair_visits = ctx->h_flags[FLAG_EIG_VISITS];
     *jacobi_steps = ctx->h_flags[FLAG_EIG_INNER];
+    *row_update_tiles = ctx->h_flags[FLAG_DS_UPDATE_UNITS];
     return ATOMO_OK;
 }
 

@@ -519,7 +519,11 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
         // a pair that was left alone and whose rows are in order needs no row update
         const bool in_place = leave && (tid >= PR || dest[tid] == tid);
         const int all_in_place = __syncthreads_and(in_place);
-        if (tid == 0) m.idle[wk.a] = all_in_place;
+        if (tid == 0) {
+            m.idle[wk.a] = all_in_place;
+            // work counter: row updates that svd_rowop will execute for this pair, in tiles of 64 rows x 64 columns
+            if (!all_in_place) atomicAdd(&flags[FLAG_DS_UPDATE_UNITS], m.ldw / 64);
+        }
     }
     if (m.gs && tid < PR) {
         const int cj = qcol(tid);
