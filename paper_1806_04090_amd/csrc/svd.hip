@@ -617,6 +617,7 @@ struct Plan {
     std::vector<int> gs_periods;     // distinct R of the Gram-space matrices
     int max_R = 1;
     int max_R_ds = 1;                // largest R among the data-space matrices
+    bool own_update = false;         // the two-sided update runs as launches of its own (see SPLIT_TWO_SIDED)
     size_t bytes = 0;
     SvdMat* d_mats = nullptr;        // device copies of `mats` and of the concatenated work lists
     Work* d_work = nullptr;
@@ -628,6 +629,13 @@ struct Plan {
     }
 };
 
+// With more update tiles per tick than this (a 512-row matrix has 128: 22 or more such matrices) the two-sided update
+// is the bulk of a tick and runs as a kernel of its own, in front of the pair problems of the next tick instead of
+// beside them.  C is then up to date whenever a pair problem reads it, so it is updated in place (one buffer instead
+// of two alternating ones, which a batch of that size no longer finds in the last-level cache) and the pair problems
+// read their block as it is instead of bringing it up to date themselves.
+constexpr size_t SPLIT_TWO_SIDED = 4096;
+
 // Lays the workspace out (base == nullptr: sizes only).
 void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, float* sigma_out, float* p_out,
                 uint64_t stream_base, const uint64_t* stream_ids, void* base, Plan& plan)
@@ -636,6 +644,13 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
     plan.mats.resize(n_mats);
     plan.d_mats = carve.take<SvdMat>(n_mats);
     size_t atom_off = 0;
+    size_t update_tiles = 0;
+    for (int j = 0; j < n_mats; ++j) {
+        const int r = mats[j].rows < mats[j].cols ? mats[j].rows : mats[j].cols;
+        const int nb = (r + BS - 1) / BS, nb2 = nb + (nb & 1);
+        if (r > THIN_R && nb2 >= GS_MIN_BLOCKS) update_tiles += (size_t)(nb2 / 2) * (nb2 / 2 + nb2 * BS / PR);
+    }
+    plan.own_update = update_tiles > SPLIT_TWO_SIDED;
     for (int j = 0; j < n_mats; ++j) {
         SvdMat& m = plan.mats[j];
         const atomo_mat& a = mats[j];
@@ -699,7 +714,8 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
         m.W0 = carve.take<float>((size_t)m.rows_alloc * m.ldw);
         m.W1 = m.gs ? carve.take<float>((size_t)m.rows_alloc * m.ldw) : nullptr;
         m.CT = m.gs ? carve.take<float>((size_t)m.rows_alloc * m.ldc) : nullptr;
-        m.CT2 = m.gs ? carve.take<float>((size_t)m.rows_alloc * m.ldc) : nullptr;
+        // (the same buffer twice: C is updated in place, and svd_eig reads its block of C as it is)
+        m.CT2 = !m.gs ? nullptr : plan.own_update ? m.CT : carve.take<float>((size_t)m.rows_alloc * m.ldc);
         m.gram = carve.take<float>((size_t)(m.gs ? m.ntiles : m.npairs) * m.nchg * QSZ);
         m.Q = carve.take<float>((size_t)(m.gs ? 2 : 1) * m.npairs * QSZ);
         m.idle = m.gs ? nullptr : carve.take<int>(m.npairs);
@@ -888,7 +904,6 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     const bool have_ds = !plan.gram.empty(), have_gs = !plan.twosided.empty(), have_thin = !plan.thin_list.empty();
     const bool use_side = have_ds || (have_thin && have_gs);
     const int n_two = (int)plan.twosided.size();
-    const int split_two_sided = 4096;                            // tiles per tick (a 512-row matrix has 192)
     if (use_side) {
         rc = ensure_side_streams(ctx);
         if (rc != ATOMO_OK) return rc;
@@ -931,24 +946,24 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     if (have_gs) {
         const int n_ticks = limit_gs * plan.max_R + 1;
         // Few matrices: the two-sided update of the previous tick rides in the launch of the pair problems (one launch
-        // per tick on the chain of dependent ticks).  Many matrices: the update is the bulk of a tick, and as extra
-        // 1024-thread workgroups of svd_eig (128 registers per lane, one workgroup per compute unit) it runs at a
-        // fraction of the rate of its own kernel of 256-thread workgroups, launched behind the pair problems.  (On a
-        // stream of its own beside the pair problems of the next tick, which do not depend on it, it slowed those
-        // down by more than it gained: 30.6 ms against 27.6 ms for 64 matrices of 512 x 4608.)
-        const bool own_launch = n_two > split_two_sided;
+        // per tick on the chain of dependent ticks), C alternates between two buffers and is one tick behind.
+        // Many matrices (SPLIT_TWO_SIDED): the update is the bulk of a tick, and as extra 1024-thread workgroups of
+        // svd_eig (128 registers per lane, one or two workgroups per compute unit) it runs at a fraction of the rate of
+        // its own kernel of 256-thread workgroups, which is launched in front of the pair problems.  (On a stream of
+        // its own beside the pair problems of the next tick it slowed those down by more than it gained.)
+        const bool own_launch = plan.own_update;
         for (int tick = 0; tick < n_ticks; ++tick) {
-            // the matrices that sweep on, and the previous tick's update for every matrix
+            // the previous tick's update for every matrix, and the pair problems of the matrices that sweep on
             if (tick > 0) {
+                if (own_launch) {
+                    ProfScope ps(ctx, ATOMO_K_SVD_UPDATE, stream);
+                    svd_twosided<<<(unsigned)n_two, 256, 0, stream>>>(d_mats, w_twosided, n_two, tick - 1);
+                }
                 {
                     ProfScope ps(ctx, ATOMO_K_SVD_EIG, stream);
                     launch_svd_eig(d_mats, w_eig_gs, (int)plan.eig_gs.size(), w_twosided, own_launch ? 0 : n_two, w_gs_list,
                                    (int)plan.gs_list.size(), cyclic, tick, limit_gs, stop_cosine, max_inner,
                                    inner_reduction, full_period, 0, ctx->d_flags, stream);
-                }
-                if (own_launch) {
-                    ProfScope ps(ctx, ATOMO_K_SVD_UPDATE, stream);
-                    svd_twosided<<<(unsigned)n_two, 256, 0, stream>>>(d_mats, w_twosided, n_two, tick - 1);
                 }
             }
             bool boundary = false;

@@ -251,7 +251,9 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
     //    With the pair's blocks a (then in pair k1, half s1) and b (pair k2, half s2) of the previous round,
     //        [aa ab; ba bb] = [Q1s^T C11 Q1s, Q1s^T C12 Q2s; ., Q2s^T C22 Q2s],   Qks = columns 32 s .. of Q_k,
     //    three 32x32 blocks, each two chained MFMA products (32x64x64, then 32x32x64); ba mirrors ab.
-    const bool fresh = m.gs && m.state[ST_FRESH_AT] == step + 1;
+    //    Gram-space matrices of a call whose updates run as launches of their own (one C buffer, m.CT2 == m.CT):
+    //    C is up to date, the pair's block as it is.
+    const bool fresh = m.gs && (m.state[ST_FRESH_AT] == step + 1 || m.CT2 == m.CT);
     if (m.gs && tid == 0) m.state[(step & 1) ? ST_QTICK_ODD : ST_QTICK] = step + 1;
     for (int e = tid; e < QSZ; e += NT) {
         const int i = e >> 6, j = e & 63;
