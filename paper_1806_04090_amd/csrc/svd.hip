@@ -393,6 +393,122 @@ __global__ __launch_bounds__(256) void svd_twosided(const SvdMat* mats, const Wo
     twosided_tile(mats, work, (int)blockIdx.x, n_items, tick, xs, (int)threadIdx.x);
 }
 
+// The two-sided update of a call with many Gram-space matrices (C updated in place, see SPLIT_TWO_SIDED): a
+// workgroup takes up to STRIP consecutive 64x64 tiles of the 64 rows of pair a - tiles (a, b) of C for kind 1,
+// column chunks of Tgs for kind 2 -, so the chain of dependent look-ups (work item, descriptor, pairing) and the
+// operand Qa^T are paid once per strip, and the loads of the next tile are in flight during the products of the
+// current one.  Same arithmetic, tile by tile, as twosided_tile.
+constexpr int STRIP = 4;                // (2 and 8 measure within 3 % of it)
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void svd_twosided_strip(const SvdMat* mats, const Work* work, int tick)
+{
+    __shared__ float xs[PR * TLD];                               // the tile
+    __shared__ float ys[PR * TLD];                               // Qa^T * tile
+    __shared__ float rs[PR];                                     // 1 / |row| of the pair's rows for the block weights
+    const Work wk = work[blockIdx.x];
+    const SvdMat m = mats[wk.mat];
+    if (m.state[(tick & 1) ? ST_QTICK_ODD : ST_QTICK] != tick + 1) return;    // svd_eig did not rotate in this tick
+    const int kind = wk.c, first = wk.b;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int qi = wave >> 1, qj = wave & 1, h = lane >> 5, l32 = lane & 31;
+    const int n_all = kind == 1 ? m.npairs : m.rows_alloc / PR;
+    const int count = min(STRIP, n_all - first);
+    int ai, aj;
+    tick_pair(m, tick, wk.a, ai, aj);
+    __shared__ int cbs[2 * STRIP];                               // kind 1: the two column blocks of every tile
+    if (tid < STRIP) {
+        int b0 = 0, b1 = 0;
+        if (kind == 1 && tid < count) tick_pair(m, tick, first + tid, b0, b1);
+        cbs[2 * tid] = b0;
+        cbs[2 * tid + 1] = b1;
+    }
+    __syncthreads();
+    float* const CT = m.CT;
+    const float* qa = m.Q + ((size_t)(tick & 1) * m.npairs + wk.a) * QSZ;
+    const float* dd = m.dd + (size_t)(tick & 1) * m.rows_alloc;
+    auto row_of = [&](int i) { return i < BS ? ai * BS + i : aj * BS + i - BS; };
+    auto col_of = [&](int t, int j) {
+        return kind == 1 ? (j < BS ? cbs[2 * t] * BS + j : cbs[2 * t + 1] * BS + j - BS) : m.rows_alloc + (first + t) * PR + j;
+    };
+    float qa_regs[PR / 2], qb_regs[PR / 2], tile_regs[QSZ / 256];
+    // thread tid loads element (wave + 4 p, lane) of the tile: rows of block ai for p < 8, of block aj from there on
+    // (32-bit element offsets: a C | Tgs buffer has at most 2048 x 4096 elements)
+    const int ldc = m.ldc;
+    const int load_lo = (ai * BS + wave) * ldc, load_hi = (aj * BS + wave) * ldc;
+    auto fetch_tile = [&](int t) {
+        const int col = col_of(t, lane);
+#pragma unroll
+        for (int p = 0; p < QSZ / 256; ++p)
+            tile_regs[p] = CT[(p < 8 ? load_lo + 4 * p * ldc : load_hi + 4 * (p - 8) * ldc) + col];
+    };
+    auto fetch_qb = [&](int t) {
+        const float* qb = m.Q + ((size_t)(tick & 1) * m.npairs + first + t) * QSZ;
+#pragma unroll
+        for (int s = 0; s < PR / 2; ++s) qb_regs[s] = qb[(2 * s + h) * PR + qj * BS + l32];    // Qb[k][j]
+    };
+    fetch_tile(0);
+#pragma unroll
+    for (int s = 0; s < PR / 2; ++s) qa_regs[s] = qa[(2 * s + h) * PR + qi * BS + l32];       // (Qa^T)[i][k]
+    if (kind == 1) {
+        fetch_qb(0);
+        if (tid < PR) {
+            const float x = dd[row_of(tid)];
+            rs[tid] = x > 0.0f ? __builtin_amdgcn_rsqf(x) : 0.0f;
+        }
+    }
+#pragma unroll 1
+    for (int t = 0; t < count; ++t) {
+#pragma unroll
+        for (int p = 0; p < QSZ / 256; ++p) {
+            const int e = tid + 256 * p;
+            xs[(e >> 6) * TLD + (e & 63)] = tile_regs[p];
+        }
+        __syncthreads();                                         // the tile is staged (and ys of the tile before is spent)
+        if (t + 1 < count) fetch_tile(t + 1);
+        floatx16 acc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+#pragma unroll
+        for (int s = 0; s < PR / 2; ++s)
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(qa_regs[s], xs[(2 * s + h) * TLD + qj * BS + l32], acc, 0, 0, 0);
+        if (kind == 1) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) ys[(qi * BS + 8 * (v >> 2) + 4 * h + (v & 3)) * TLD + qj * BS + l32] = acc[v];
+        }
+        __syncthreads();                                         // xs is spent, ys complete
+        if (kind == 1) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+#pragma unroll
+            for (int s = 0; s < PR / 2; ++s)
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(ys[(qi * BS + l32) * TLD + 2 * s + h], qb_regs[s], acc, 0, 0, 0);
+            if (t + 1 < count) fetch_qb(t + 1);
+        }
+        // result rows 8 (v / 4) + 4 h + (v mod 4) of block (qi ? aj : ai), column qj * 32 + l32 of the tile
+        const int store0 = ((qi ? aj : ai) * BS + 4 * h) * ldc + col_of(t, qj * BS + l32);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) CT[store0 + (8 * (v >> 2) + (v & 3)) * ldc] = acc[v];
+        if (kind == 1) {
+            // the weight of this block of the new C (see twosided_tile)
+            const int brow = qi ? aj : ai, bcol = cbs[2 * t + qj];
+            const float xc = dd[bcol * BS + l32];
+            const float rcol = xc > 0.0f ? __builtin_amdgcn_rsqf(xc) : 0.0f;
+            float sum = 0.0f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int li = 8 * (v >> 2) + 4 * h + (v & 3);
+                const float w = acc[v] * rs[qi * BS + li] * rcol;
+                if (brow != bcol || li != l32) sum = fmaf(w, w, sum);
+            }
+            for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+            if (lane == 0) {
+                m.bw[((size_t)((tick + 1) & 1) * m.nb2 + brow) * m.nb2 + bcol] = sum;
+                if (wk.a == 0 && first + t == 0 && wave == 0) m.state[ST_WSTAMP + ((tick + 1) & 1)] = tick + 2;
+            }
+        }
+    }
+}
+
 // ------------------------------------------------------------------------------------------------
 // apply: W[other] <- Tgs * W[cur] for a Gram-space matrix (64 output rows x 256 columns per workgroup)
 // ------------------------------------------------------------------------------------------------
@@ -610,7 +726,7 @@ __global__ __launch_bounds__(256) void svd_hint(const SvdMat* mats, int n_mats, 
 
 struct Plan {
     std::vector<SvdMat> mats;
-    std::vector<Work> prep, gram, fullgram, tiles, apply, eig_gs, eig_ds, rowop1, twosided, norms, pack;
+    std::vector<Work> prep, gram, fullgram, tiles, apply, eig_gs, eig_ds, rowop1, twosided, strips, norms, pack;
     std::vector<Work> thin_chunks, thin_list;      // thin matrices: (matrix, chunk of positions); (matrix)
     std::vector<Work> thin_direct, thin_copied;    // the chunks again, split by whether G is used in place
     std::vector<Work> gs_list;                     // the Gram-space matrices
@@ -624,12 +740,12 @@ struct Plan {
     size_t n_work() const
     {
         return prep.size() + gram.size() + fullgram.size() + tiles.size() + apply.size() + eig_gs.size() + eig_ds.size() +
-               rowop1.size() + twosided.size() + norms.size() + pack.size() + 2 * thin_chunks.size() + thin_list.size() +
+               rowop1.size() + twosided.size() + strips.size() + norms.size() + pack.size() + 2 * thin_chunks.size() + thin_list.size() +
                gs_list.size();
     }
 };
 
-// With more update tiles per tick than this (a 512-row matrix has 128: 22 or more such matrices) the two-sided update
+// With more update tiles per tick than this (a 512-row matrix has 128: 33 or more such matrices) the two-sided update
 // is the bulk of a tick and runs as a kernel of its own, in front of the pair problems of the next tick instead of
 // beside them.  C is then up to date whenever a pair problem reads it, so it is updated in place (one buffer instead
 // of two alternating ones, which a batch of that size no longer finds in the last-level cache) and the pair problems
@@ -739,6 +855,10 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
             if (m.gs) {
                 for (int k2 = 0; k2 < m.npairs; ++k2) plan.twosided.push_back(Work{j, k, k2, 1});
                 for (int c = 0; c < m.rows_alloc / PR; ++c) plan.twosided.push_back(Work{j, k, c, 2});
+                if (plan.own_update) {
+                    for (int k2 = 0; k2 < m.npairs; k2 += STRIP) plan.strips.push_back(Work{j, k, k2, 1});
+                    for (int c = 0; c < m.rows_alloc / PR; c += STRIP) plan.strips.push_back(Work{j, k, c, 2});
+                }
             } else {
                 for (int c = 0; c < m.nchg; ++c) plan.gram.push_back(Work{j, k, c, 0});
                 for (int c = 0; c < m.nchu; ++c) plan.rowop1.push_back(Work{j, k, c, 0});
@@ -760,6 +880,7 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
         for (int g = 0; g < m.rows_alloc / 4; ++g) plan.norms.push_back(Work{j, g, 0, 0});
         for (int k = 0; k < m.capacity; ++k) plan.pack.push_back(Work{j, k, 0, 0});
     }
+    deal_to_dies(plan.strips);                                   // a matrix's strips, which share its rotations, on one die
     plan.d_work = carve.take<Work>(plan.n_work());
     plan.bytes = carve.off;
 }
@@ -870,6 +991,7 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     const Work* w_eig_ds = place(plan.eig_ds);
     const Work* w_rowop1 = place(plan.rowop1);
     const Work* w_twosided = place(plan.twosided);
+    const Work* w_strips = place(plan.strips);
     const Work* w_norms = place(plan.norms);
     const Work* w_pack = place(plan.pack);
     const Work* w_thin_chunks = place(plan.thin_chunks);
@@ -957,7 +1079,7 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
             if (tick > 0) {
                 if (own_launch) {
                     ProfScope ps(ctx, ATOMO_K_SVD_UPDATE, stream);
-                    svd_twosided<<<(unsigned)n_two, 256, 0, stream>>>(d_mats, w_twosided, n_two, tick - 1);
+                    svd_twosided_strip<<<grid(plan.strips), 256, 0, stream>>>(d_mats, w_strips, tick - 1);
                 }
                 {
                     ProfScope ps(ctx, ATOMO_K_SVD_EIG, stream);
@@ -988,7 +1110,8 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
         }
         {
             ProfScope ps(ctx, ATOMO_K_SVD_UPDATE, stream);
-            svd_twosided<<<(unsigned)n_two, 256, 0, stream>>>(d_mats, w_twosided, n_two, n_ticks - 1);
+            if (own_launch) svd_twosided_strip<<<grid(plan.strips), 256, 0, stream>>>(d_mats, w_strips, n_ticks - 1);
+            else svd_twosided<<<(unsigned)n_two, 256, 0, stream>>>(d_mats, w_twosided, n_two, n_ticks - 1);
         }
     }
     if (use_side) ATOMO_HIP(ctx, hipStreamWaitEvent(stream, ctx->ev_join, 0));
