@@ -36,6 +36,8 @@
 // Which blocks form the pairs of a Gram-space tick is read from a table that a further workgroup of the
 // launch before has written: the heaviest off-diagonal blocks first (GS_WINDOW in svd_common.h), or the
 // rounds of the fixed tournament.
+// A call with many Gram-space matrices (SPLIT_TWO_SIDED) runs the update as a kernel of its own in front of
+// the pair problems instead (svd_twosided_strip): C is then updated in place and is never behind.
 #include <cfloat>
 #include <algorithm>
 #include <cmath>
