@@ -58,7 +58,6 @@ typedef enum atomo_status_code {
     ATOMO_EHIP = -4,       /* a HIP runtime call failed; atomo_last_hip_error gives its code        */
     ATOMO_ENOMEM = -5,     /* the workspace could not be allocated                                  */
     ATOMO_ETOOLARGE = -6   /* atomo_encode_entrywise_noalloc: n exceeds what its fixed scratch holds */
-                           /* waiting: the results of the calls since the last status read are invalid      */
 } atomo_status_code;
 
 enum { ATOMO_KIND_SVD = 0, ATOMO_KIND_ENTRYWISE = 1, ATOMO_KIND_LQ = 2 };
@@ -232,7 +231,7 @@ int atomo_encode_entrywise(atomo_ctx* ctx, const float* g, double s, uint64_t se
 /*
  * atomo_encode_entrywise for callers that cannot allocate device memory: code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc.  Same arguments, same message, bit for bit; the scratch
- * memory of the kernels (water-level search state, per-chunk counts, offsets and keep bits) is a fixed array
+ * memory of the kernels (water-level search state, per-chunk counts, keep and undecided bits) is a fixed array
  * of 5 MiB that the library holds on every GPU it runs on until the process ends, instead of the context's
  * growable workspace.  The call allocates nothing (no hipMalloc, hipFree, event or stream creation), on any
  * path.
@@ -267,6 +266,8 @@ int atomo_encode_lq(atomo_ctx* ctx, const float* g, double q, uint64_t seed, uin
  *                                out is the dense vector of n floats (ld is ignored).
  *   kind = ATOMO_KIND_LQ:        msgs is a HOST array of n_msgs atomo_lq_msg with equal n; out as above.
  * A message whose count exceeds its capacity contributes its first `capacity` atoms.
+ * The sum is formed in a fixed order (entry-wise and l_q messages one after the other, in the order
+ * given), so the same messages decode to the same bits in every run.
  */
 int atomo_decode(atomo_ctx* ctx, int kind, const void* msgs, int n_msgs, float scale,
                  float* out, int64_t ld, void* stream);
