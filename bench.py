@@ -61,7 +61,8 @@ def executed_work(shapes, sweeps, refreshes, pair_visits, jacobi_steps, row_upda
     A sweep visits every pair (i, j) of the layer's 32-row blocks once, n_i + n_j real rows per pair.
     Data-space layers (32 < r <= 480): pair Gram matrices 2 (n_i + n_j)^2 M per visit (svd_gram); the row update
     2 x 64 x 64 x 64 per 64 x 64 tile of [A | T] that svd_rowop rotated, counted on the device (pairs found converged
-    are left alone; svd_update).
+    are left alone; svd_update); layers of 225 rows and more also form all of A A^T  M r (r + 64) at each check
+    of the whole matrix near the end (the refreshes they report; svd_refresh).
     Gram-space layers, per refresh (svd_refresh): upper-triangular tiles of A A^T  M r (r + 64), and (every
     refresh but the first) A <- T A and T <- T T_old, 2 r^2 (M + r); per tick of a sweep, inside the svd_eig
     launches: C <- D^T C D  256 r^2 and Tgs <- D^T Tgs  128 r^2 (D block-diagonal in 64 x 64 blocks), and per pair
@@ -89,6 +90,7 @@ def executed_work(shapes, sweeps, refreshes, pair_visits, jacobi_steps, row_upda
             catchup += max(visits - rf * (nb2 // 2), 0) * 3 * 2.0 * (32 * 64 * 64 + 32 * 64 * 32)
         else:
             gram += sw * sum(2.0 * (rows[i] + rows[j]) ** 2 * M for i in range(nb2) for j in range(i + 1, nb2))
+            refresh += rf * M * r * (r + 64.0)
     upd = row_update_tiles * 2.0 * 64 ** 3
     eig = jacobi_steps * 32 * 3 * 64 * 6 + pair_visits * 2 * 2 * 64 ** 3 + twosided + catchup
     decode_bytes = 4.0 * n_elem + sum(4.0 * k * (m + n + 1) for (m, n), k in zip(shapes, kept_atoms))

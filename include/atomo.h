@@ -181,8 +181,9 @@ int atomo_last_hip_error(const atomo_ctx* ctx);
 
 /* Waits for `stream`, then copies the number of Jacobi sweeps each matrix of the last
  * atomo_encode_svd took into sweeps[0 .. n_mats) (HOST) and, if refreshes is not NULL, how many
- * times the full Gram matrix of the matrix was formed from the data (0 for matrices small enough
- * to iterate directly on the data).  n_mats must match that call; the counts stay readable until the
+ * times the full Gram matrix of the matrix was formed from the data (matrices of 33 .. 480 rows
+ * iterate directly on the data: 0 below 225 rows, from there on the number of whole-matrix
+ * convergence checks near the end).  n_mats must match that call; the counts stay readable until the
  * next atomo_encode_svd on the context. */
 int atomo_svd_sweeps(atomo_ctx* ctx, void* stream, int32_t* sweeps /*host*/, int32_t* refreshes /*host, optional*/,
                      int n_mats);

@@ -56,6 +56,12 @@ __device__ inline bool refreshing(const SvdMat& m)
     return m.gs && m.state[ST_DONE_AT] == 0 && m.state[ST_MODE] == MODE_NEED_REFRESH;
 }
 
+// data-space matrix whose last sweep asked for the check of its whole Gram matrix (DS_VERIFY)
+__device__ inline bool verifying(const SvdMat& m)
+{
+    return !m.gs && m.state[ST_DONE_AT] == 0 && m.state[ST_VERIFY] == 1;
+}
+
 // ------------------------------------------------------------------------------------------------
 // reset / absmax / prepare
 // ------------------------------------------------------------------------------------------------
@@ -138,11 +144,12 @@ __global__ __launch_bounds__(256) void svd_gram(const SvdMat* mats, const Work* 
     int rowA0, rowA1, rowB0, rowB1, chunk, out_index;
     const float* W;
     if (FULL) {
-        if (!refreshing(m)) return;
+        if (!refreshing(m) && !verifying(m)) return;
         const int cur = m.state[ST_CUR] & 1;
         const float* const w0 = m.W0;
         const float* const w1 = m.W1;
-        W = ((m.state[ST_FIRST] ? cur : cur ^ 1) != 0) ? w1 : w0;    // what svd_apply has just written
+        // what svd_apply has just written; a data-space matrix has the one buffer
+        W = (m.gs && (m.state[ST_FIRST] ? cur : cur ^ 1) != 0) ? w1 : w0;
         const int ti = wk.a, tj = wk.b, nt = m.nb2 / 2;
         rowA0 = ti * PR; rowA1 = rowA0 + BS; rowB0 = tj * PR; rowB1 = rowB0 + BS;
         chunk = wk.c;
@@ -330,6 +337,56 @@ __global__ __launch_bounds__(256) void svd_fresh_check(const SvdMat* mats, const
     const float noise = (lo > 0.0f && lo <= hi) ? fminf(GS_NOISE * sqrtf(hi / lo), GS_NOISE_CAP) : 0.0f;
     m.state[ST_NOISE] = __float_as_int(noise);
     m.state[ST_DMIN] = 0x7f800000;
+}
+
+// Data-space matrices (DS_VERIFY): largest |cos| between any two rows from the partial tiles that svd_gram<true> has
+// just formed; the last tile to finish decides whether the matrix is done.  One workgroup per 64x64 tile.
+__global__ __launch_bounds__(256) void svd_ds_verify(const SvdMat* mats, const Work* work, int tick, int max_sweeps,
+                                                     float stop_cosine, int* flags)
+{
+    __shared__ float dI[PR], dJ[PR], red[4];
+    const Work wk = work[blockIdx.x];
+    const SvdMat m = mats[wk.mat];
+    if (!verifying(m)) return;
+    const int ti = wk.a, tj = wk.b, nt = m.nb2 / 2;
+    auto tile_of = [&](int a, int b) { return a * nt - a * (a - 1) / 2 + (b - a); };
+    const float* gt = m.gram + (size_t)tile_of(ti, tj) * m.nchg * QSZ;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid < 2 * PR) {                                          // squared norms of the tile's rows and columns
+        const int k = tid & (PR - 1), t = tid < PR ? ti : tj;
+        const float* gd = m.gram + (size_t)tile_of(t, t) * m.nchg * QSZ + k * PR + k;
+        float sum = 0.0f;
+        for (int c = 0; c < m.nchg; ++c) sum += gd[(size_t)c * QSZ];
+        (tid < PR ? dI : dJ)[k] = sum;
+    }
+    __syncthreads();
+    const float z2 = ZERO_REL * __int_as_float(m.state[ST_SCALE]);
+    float mx = 0.0f;
+    for (int e = tid; e < QSZ; e += 256) {
+        const int i = e >> 6, j = e & 63;
+        if (ti == tj && i >= j) continue;
+        float sum = 0.0f;
+        for (int c = 0; c < m.nchg; ++c) sum += gt[(size_t)c * QSZ + e];
+        const float dii = dI[i], djj = dJ[j];
+        if (dii > 0.0f && djj > 0.0f) mx = fmaxf(mx, fabsf(sum) / fmaxf(sqrtf(dii * djj), z2));
+    }
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_down(mx, o));
+    if (lane == 0) red[wave] = mx;
+    __syncthreads();
+    if (tid != 0) return;
+    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    atomicMax((unsigned int*)&m.state[ST_FRESH], __float_as_uint(mx));
+    __threadfence();
+    const int arrived = atomicAdd(&m.state[ST_ARRIVE2], 1);
+    if (arrived != m.ntiles - 1) return;
+    __threadfence();
+    const float fresh = __uint_as_float(atomicAdd((unsigned int*)&m.state[ST_FRESH], 0u));
+    m.state[ST_REFRESHES] += 1;
+    if (fresh < stop_cosine) m.state[ST_DONE_AT] = tick;         // this tick's launches already skip the matrix
+    else if (m.state[ST_SWEEPS] >= max_sweeps) atomicMax(&flags[FLAG_NOCONV], 1);
+    m.state[ST_VERIFY] = 0;
+    m.state[ST_FRESH] = 0;
+    m.state[ST_ARRIVE2] = 0;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -729,6 +786,8 @@ __global__ __launch_bounds__(256) void svd_hint(const SvdMat* mats, int n_mats, 
 struct Plan {
     std::vector<SvdMat> mats;
     std::vector<Work> prep, gram, fullgram, tiles, apply, eig_gs, eig_ds, rowop1, twosided, strips, norms, pack;
+    std::vector<Work> ds_full, ds_tiles;           // data-space matrices that check their whole Gram matrix (DS_VERIFY)
+    std::vector<int> ds_periods;                   // their distinct R
     std::vector<Work> thin_chunks, thin_list;      // thin matrices: (matrix, chunk of positions); (matrix)
     std::vector<Work> thin_direct, thin_copied;    // the chunks again, split by whether G is used in place
     std::vector<Work> gs_list;                     // the Gram-space matrices
@@ -742,7 +801,7 @@ struct Plan {
     size_t n_work() const
     {
         return prep.size() + gram.size() + fullgram.size() + tiles.size() + apply.size() + eig_gs.size() + eig_ds.size() +
-               rowop1.size() + twosided.size() + strips.size() + norms.size() + pack.size() + 2 * thin_chunks.size() + thin_list.size() +
+               rowop1.size() + twosided.size() + strips.size() + ds_full.size() + ds_tiles.size() + norms.size() + pack.size() + 2 * thin_chunks.size() + thin_list.size() +
                gs_list.size();
     }
 };
@@ -834,7 +893,8 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
         m.CT = m.gs ? carve.take<float>((size_t)m.rows_alloc * m.ldc) : nullptr;
         // (the same buffer twice: C is updated in place, and svd_eig reads its block of C as it is)
         m.CT2 = !m.gs ? nullptr : plan.own_update ? m.CT : carve.take<float>((size_t)m.rows_alloc * m.ldc);
-        m.gram = carve.take<float>((size_t)(m.gs ? m.ntiles : m.npairs) * m.nchg * QSZ);
+        const bool ds_verify = !m.gs && m.R >= DS_VERIFY_MIN_R;
+        m.gram = carve.take<float>((size_t)(m.gs || ds_verify ? m.ntiles : m.npairs) * m.nchg * QSZ);
         m.Q = carve.take<float>((size_t)(m.gs ? 2 : 1) * m.npairs * QSZ);
         m.idle = m.gs ? nullptr : carve.take<int>(m.npairs);
         m.state = carve.take<int>(ST_WORDS);
@@ -878,6 +938,16 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
                 }
             for (int t = 0; t < nt; ++t)
                 for (int c = 0; c < m.nchu; ++c) plan.apply.push_back(Work{j, t, c, 0});
+        }
+        if (ds_verify) {
+            bool seen = false;
+            for (int p : plan.ds_periods) seen = seen || p == m.R;
+            if (!seen) plan.ds_periods.push_back(m.R);
+            for (int ti = 0; ti < nt; ++ti)
+                for (int tj = ti; tj < nt; ++tj) {
+                    plan.ds_tiles.push_back(Work{j, ti, tj, 0});
+                    for (int c = 0; c < m.nchg; ++c) plan.ds_full.push_back(Work{j, ti, tj, c});
+                }
         }
         for (int g = 0; g < m.rows_alloc / 4; ++g) plan.norms.push_back(Work{j, g, 0, 0});
         for (int k = 0; k < m.capacity; ++k) plan.pack.push_back(Work{j, k, 0, 0});
@@ -994,6 +1064,8 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     const Work* w_rowop1 = place(plan.rowop1);
     const Work* w_twosided = place(plan.twosided);
     const Work* w_strips = place(plan.strips);
+    const Work* w_ds_full = place(plan.ds_full);
+    const Work* w_ds_tiles = place(plan.ds_tiles);
     const Work* w_norms = place(plan.norms);
     const Work* w_pack = place(plan.pack);
     const Work* w_thin_chunks = place(plan.thin_chunks);
@@ -1050,7 +1122,18 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     if (have_ds) {
         hipStream_t s_ds = ctx->side;
         const int ds_ticks = limit_ds * plan.max_R_ds;
-        for (int tick = 0; tick < ds_ticks; ++tick) {
+        // at a sweep boundary: the whole-Gram-matrix check of the matrices whose sweep asked for it (DS_VERIFY)
+        auto verify = [&](int tick) {
+            bool boundary = false;
+            for (int period : plan.ds_periods) boundary = boundary || (tick % period == 0 && tick <= limit_ds * period);
+            if (!boundary) return;
+            ProfScope ps(ctx, ATOMO_K_SVD_REFRESH, s_ds);
+            svd_gram<true><<<grid(plan.ds_full), 256, 0, s_ds>>>(d_mats, w_ds_full, tick, limit_ds);
+            svd_ds_verify<<<grid(plan.ds_tiles), 256, 0, s_ds>>>(d_mats, w_ds_tiles, tick, limit_ds, stop_cosine, ctx->d_flags);
+        };
+        for (int tick = 0; tick <= ds_ticks; ++tick) {
+            if (tick > 0) verify(tick);
+            if (tick == ds_ticks) break;
             {
                 ProfScope ps(ctx, ATOMO_K_SVD_GRAM, s_ds);
                 svd_gram<false><<<grid(plan.gram), 256, 0, s_ds>>>(d_mats, w_gram, tick, limit_ds);

@@ -44,6 +44,7 @@ enum {
     ST_NOISE = 19,      // Gram-space matrices: cosines below this are not resolved by the Gram arithmetic (float bits), see GS_NOISE
     ST_WSTAMP = 20,     // Gram-space matrices: word 20 + (t & 1) holds t + 1 once the block weights of the C after t ticks are written
     ST_CYCLIC_FROM = 22, // Gram-space matrices: ticks from this one on are paired by the fixed tournament (0 = not set)
+    ST_VERIFY = 23,     // data-space matrices: 1 = the sweep that just ended was close enough for the whole-Gram-matrix check (DS_VERIFY)
     ST_WORDS = 24
 };
 
@@ -206,6 +207,14 @@ __device__ inline float* c_of_parity(const SvdMat& m, int parity)
 // Data space: a pair whose largest cosine is below this fraction of stop_cosine is left alone (no Jacobi steps, and no
 // row update if its rows are in order already): the sweep that only confirms convergence then costs its Gram matrices.
 constexpr float DS_LEAVE = 0.1f;
+
+// Data space: a sweep whose largest cosine (measured before rotating) is below DS_VERIFY x stop_cosine has, convergence
+// being quadratic, most likely left the matrix converged.  Instead of a whole further sweep that only confirms it (R ticks
+// of three launches in which nothing rotates), the Gram matrix of all rows is then formed once at the sweep boundary
+// (svd_gram<true>) and its largest cosine decides (svd_ds_verify): finished, or the sweeps go on.  Only for matrices of
+// at least DS_VERIFY_MIN_R ticks per sweep: the check costs two launches at every sweep boundary.
+constexpr float DS_VERIFY = 10.0f;
+constexpr int DS_VERIFY_MIN_R = 7;
 
 constexpr int TLD = PR + 1;      // row stride of a 64x64 tile staged in LDS
 

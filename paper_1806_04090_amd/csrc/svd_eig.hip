@@ -82,11 +82,8 @@ __device__ inline float2 max_cosine(const float* A, float z2, float* red)
 // c = sqrt((1 + cos 2t) / 2),  s = sign(d) w / (2 c sqrt(d^2 + w^2)).  Two reciprocal square roots
 // (hardware approximations, 1 ulp) and no division: what a rotation misses the next sweep picks up,
 // and the orthogonality of the product is restored by the Newton-Schulz step.
-__device__ inline float2 pair_rotation(const float* A, int k, float z2)
+__device__ inline float2 rotation_of(float app, float apq, float aqq, float z2)
 {
-    const float app = A[(2 * k) * ELD + k];
-    const float apq = A[(2 * k) * ELD + 32 + k];
-    const float aqq = A[(2 * k + 1) * ELD + 32 + k];
     float c = 1.0f, s = 0.0f;
     // rotate only if |a_pq| > 1e-7 * max(sqrt(a_pp a_qq), floor), compared in squares
     if (apq * apq > 1e-14f * fmaxf(fabsf(app * aqq), z2 * z2)) {
@@ -98,6 +95,20 @@ __device__ inline float2 pair_rotation(const float* A, int k, float z2)
         s = copysignf(0.5f * w * ir * ic, d * w);
     }
     return make_float2(c, s);
+}
+
+__device__ inline float2 pair_rotation(const float* A, int k, float z2)
+{
+    return rotation_of(A[(2 * k) * ELD + k], A[(2 * k) * ELD + 32 + k], A[(2 * k + 1) * ELD + 32 + k], z2);
+}
+
+// (c, s) of a slot pair together with the two diagonal entries the rotation leaves behind:
+// d_p' = c^2 a_pp - 2 c s a_pq + s^2 a_qq,  d_q' = s^2 a_pp + 2 c s a_pq + c^2 a_qq
+__device__ inline float4 rotation_and_diagonal(float app, float apq, float aqq, float z2)
+{
+    const float2 r = rotation_of(app, apq, aqq, z2);
+    const float cc = r.x * r.x, ss = r.y * r.y, cs2 = 2.0f * r.x * r.y * apq;
+    return make_float4(r.x, r.y, fmaf(cc, app, fmaf(ss, aqq, -cs2)), fmaf(ss, app, fmaf(cc, aqq, cs2)));
 }
 
 // Plans the pairing of tick + 1 for one Gram-space matrix (all NT threads of a workgroup call).
@@ -215,6 +226,8 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
     __shared__ float ref0[PR];           //             the same in the scaling of the first refresh (cref0)
     __shared__ int sits_out[PR];         // Gram space: by slot, rows whose diagonal entry is rounding noise
     __shared__ float red[32];
+    __shared__ float2 rotc[2][32];       // cross rounds: (c, s) of the 32 rotations of a step, by step parity
+    __shared__ float2 rotd[2][32];       //               the diagonal entries (d_p', d_q') those rotations leave behind
 
     const int two_wgs = (n_two + TILES_PER_WG - 1) / TILES_PER_WG;
     if ((int)blockIdx.x >= n_eig + two_wgs) {                     // the last workgroups plan the next tick
@@ -459,14 +472,84 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
             }
             __syncthreads();
         };
+        // A cross round keeps the matrix in registers for its 32 steps.  Thread (b, g) holds the 2x2 block of row pair
+        // a = (b + g) mod 32 and column pair b (group g is the g-th circulant diagonal of the 32 x 32 grid of blocks; its
+        // lanes touch 32 different LDS banks) and the entries of its two rows of Q in column pair b.  The even slots
+        // stay and the odd slots move on by one pair per step, so after the rotation the new block (a, b) keeps its
+        // entry (even, even) and takes (even, odd) from block (a, b - 1), (odd, even) from (a - 1, b) and (odd, odd) from
+        // (a - 1, b - 1): the last is a lane of the same group (lane permute), the other two go through LDS; Q's odd
+        // columns come from the lane next door.  The rotations of the next step are computed before the step's
+        // barrier by group 1 alone: its entry (even, odd) is the off-diagonal entry of the next slot pair b + 1, whose
+        // diagonal entries are what this step's rotations of pairs b + 1 and b leave behind (closed form, carried in
+        // rotd).  Per step: 4 LDS reads, 2 writes and 3 lane permutes per thread and one barrier, against 11 reads,
+        // 8 writes and 2 permutes when the matrix goes through LDS in full (the other rounds).
+        auto cross_sweep = [&](float* A0, float* Q0, float* EX) {
+            const int ar = (b + grp) & 31;
+            float x00 = A0[(2 * ar) * ELD + b],     x01 = A0[(2 * ar) * ELD + 32 + b];
+            float x10 = A0[(2 * ar + 1) * ELD + b], x11 = A0[(2 * ar + 1) * ELD + 32 + b];
+            float q[QR_PER][2];
+#pragma unroll
+            for (int e = 0; e < QR_PER; ++e) {
+                q[e][0] = Q0[(grp * QR_PER + e) * ELD + b];
+                q[e][1] = Q0[(grp * QR_PER + e) * ELD + 32 + b];
+            }
+            if (grp == 0) {                                      // (a = b: the diagonal blocks)
+                const float4 r = rotation_and_diagonal(x00, x01, x11, z2);
+                rotc[0][b] = make_float2(r.x, r.y);
+                rotd[0][b] = make_float2(r.z, r.w);
+            }
+            __syncthreads();
+            const int left = ((lane & 32) | ((b + 31) & 31)) << 2;      // the lane of column pair b - 1 in this group
+            const int own = ar * 32 + b, from01 = ar * 32 + ((b + 31) & 31), from10 = ((ar + 31) & 31) * 32 + b;
+            for (int t = 0; t < 32; ++t) {
+                const int p = t & 1;
+                const float2 ra = rotc[p][ar], rb = rotc[p][b];
+                const float y00 = ra.x * x00 - ra.y * x10, y01 = ra.x * x01 - ra.y * x11;
+                const float y10 = ra.y * x00 + ra.x * x10, y11 = ra.y * x01 + ra.x * x11;
+                const float o01 = rb.y * y00 + rb.x * y01, o10 = rb.x * y10 - rb.y * y11, o11 = rb.y * y10 + rb.x * y11;
+                x00 = rb.x * y00 - rb.y * y01;
+                float* ex = EX + p * 2048;
+                ex[own] = o01;
+                ex[1024 + own] = o10;
+                x11 = __int_as_float(__builtin_amdgcn_ds_bpermute(left, __float_as_int(o11)));
+#pragma unroll
+                for (int e = 0; e < QR_PER; ++e) {
+                    const float u = q[e][0], v = q[e][1];
+                    q[e][0] = rb.x * u - rb.y * v;
+                    q[e][1] = __int_as_float(__builtin_amdgcn_ds_bpermute(left, __float_as_int(rb.y * u + rb.x * v)));
+                }
+                if (grp == 1) {                                  // (a = b + 1)
+                    const float4 r = rotation_and_diagonal(rotd[p][ar].x, o01, rotd[p][b].y, z2);
+                    rotc[p ^ 1][ar] = make_float2(r.x, r.y);
+                    rotd[p ^ 1][ar] = make_float2(r.z, r.w);
+                }
+                __syncthreads();
+                x01 = ex[from01];
+                x10 = ex[1024 + from10];
+            }
+            // 32 steps: every index is back in its slot
+            A0[(2 * ar) * ELD + b] = x00;     A0[(2 * ar) * ELD + 32 + b] = x01;
+            A0[(2 * ar + 1) * ELD + b] = x10; A0[(2 * ar + 1) * ELD + 32 + b] = x11;
+#pragma unroll
+            for (int e = 0; e < QR_PER; ++e) {
+                Q0[(grp * QR_PER + e) * ELD + b] = q[e][0];
+                Q0[(grp * QR_PER + e) * ELD + 32 + b] = q[e][1];
+            }
+            __syncthreads();
+        };
+        static_assert(2 * 2 * 1024 <= PR * ELD, "the exchange buffers of a cross round fit the idle copy of the matrix");
         for (int isw = 0; isw < max_inner; ++isw) {
             float* A0 = As[cur];
             float* A1 = As[cur ^ 1];
             float* Q0 = Qs[cur];
             float* Q1 = Qs[cur ^ 1];
-            for (int t = 0; t < (cross ? 32 : 62); t += 2) {
-                jacobi_step(A0, A1, Q0, Q1);
-                jacobi_step(A1, A0, Q1, Q0);
+            if (cross) {
+                cross_sweep(A0, Q0, A1);
+            } else {
+                for (int t = 0; t < 62; t += 2) {
+                    jacobi_step(A0, A1, Q0, Q1);
+                    jacobi_step(A1, A0, Q1, Q0);
+                }
             }
             if (!cross) {                                        // 63 steps: one more, into the other buffer
                 jacobi_step(A0, A1, Q0, Q1);
@@ -606,6 +689,8 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
                 m.state[ST_SAT_OUT] = 0;
             } else if (worst < stop_cosine) {
                 m.state[ST_DONE_AT] = step + 1;
+            } else if (m.R >= DS_VERIFY_MIN_R && worst < DS_VERIFY * stop_cosine) {
+                m.state[ST_VERIFY] = 1;                          // svd_ds_verify decides at the sweep boundary
             } else if (sweeps >= max_sweeps) {
                 atomicMax(&flags[FLAG_NOCONV], 1);
             }
