@@ -59,10 +59,12 @@ def executed_work(shapes, sweeps, refreshes, pair_visits, jacobi_steps, row_upda
 
     Thin layers (r <= 32) are streaming passes over the data (svd_thin), priced by their bytes.
     A sweep visits every pair (i, j) of the layer's 32-row blocks once, n_i + n_j real rows per pair.
-    Data-space layers (32 < r <= 480): pair Gram matrices 2 (n_i + n_j)^2 M per visit (svd_gram); the row update
-    2 x 64 x 64 x 64 per 64 x 64 tile of [A | T] that svd_rowop rotated, counted on the device (pairs found converged
-    are left alone; svd_update); layers of 225 rows and more also form all of A A^T  M r (r + 64) at each check
-    of the whole matrix near the end (the refreshes they report; svd_refresh).
+    Data-space layers (32 < r <= 480), one launch of svd_rowgram per tick (svd_update): the row update, 2 x 64 x 64 x 64
+    per 64 x 64 tile of [A | T] that was rotated, counted on the device (pairs found converged are left alone), and
+    the Gram matrices of the next tick's pairs, three of the four quadrants each: 2 M (n_i^2 + n_i n_j + n_j^2) per
+    visit.  The Gram matrices of the first tick are a launch of their own (svd_gram).  Layers of 225 rows and more
+    also form all of A A^T  M r (r + 64) at each check of the whole matrix near the end (the refreshes they
+    report; svd_refresh).
     Gram-space layers, per refresh (svd_refresh): upper-triangular tiles of A A^T  M r (r + 64), and (every
     refresh but the first) A <- T A and T <- T T_old, 2 r^2 (M + r); per tick of a sweep, inside the svd_eig
     launches: C <- D^T C D  256 r^2 and Tgs <- D^T Tgs  128 r^2 (D block-diagonal in 64 x 64 blocks), and per pair
@@ -73,7 +75,7 @@ def executed_work(shapes, sweeps, refreshes, pair_visits, jacobi_steps, row_upda
     svd_eig class is priced as a whole (vector-ALU rotations + the MFMA work its launches carry) against the
     157.3 TFLOP/s that is both the fp32 vector and the fp32 matrix peak.
     """
-    gram = refresh = twosided = catchup = thin_bytes = 0.0
+    gram = gram_first = refresh = twosided = catchup = thin_bytes = 0.0
     for (m, n), sw, rf in zip(shapes, sweeps, refreshes):
         r, M, gs = layer_geometry(m, n)
         if r <= 32:
@@ -89,13 +91,16 @@ def executed_work(shapes, sweeps, refreshes, pair_visits, jacobi_steps, row_upda
             # every pair problem but the first after a refresh forms its block from three 32x32 products
             catchup += max(visits - rf * (nb2 // 2), 0) * 3 * 2.0 * (32 * 64 * 64 + 32 * 64 * 32)
         else:
-            gram += sw * sum(2.0 * (rows[i] + rows[j]) ** 2 * M for i in range(nb2) for j in range(i + 1, nb2))
+            quadrants = lambda i, j: 2.0 * M * (rows[i] ** 2 + rows[i] * rows[j] + rows[j] ** 2)
+            first = [(nb2 - 1, 0)] + [(k, nb2 - 1 - k) for k in range(1, nb2 // 2)]    # the pairs of round 0
+            gram_first += sum(quadrants(i, j) for i, j in first)
+            gram += sw * sum(quadrants(i, j) for i in range(nb2) for j in range(i + 1, nb2)) - sum(quadrants(i, j) for i, j in first)
             refresh += rf * M * r * (r + 64.0)
-    upd = row_update_tiles * 2.0 * 64 ** 3
+    upd = row_update_tiles * 2.0 * 64 ** 3 + gram
     eig = jacobi_steps * 32 * 3 * 64 * 6 + pair_visits * 2 * 2 * 64 ** 3 + twosided + catchup
     decode_bytes = 4.0 * n_elem + sum(4.0 * k * (m + n + 1) for (m, n), k in zip(shapes, kept_atoms))
     return {
-        "svd_gram": ("mfma", gram, PEAK_FP32_MFMA_TFLOPS, "TFLOP/s"),
+        "svd_gram": ("mfma", gram_first, PEAK_FP32_MFMA_TFLOPS, "TFLOP/s"),
         "svd_update": ("mfma", upd, PEAK_FP32_MFMA_TFLOPS, "TFLOP/s"),
         "svd_refresh": ("mfma", refresh, PEAK_FP32_MFMA_TFLOPS, "TFLOP/s"),
         "svd_eig": ("alu", eig, PEAK_FP32_VALU_TFLOPS, "TFLOP/s"),

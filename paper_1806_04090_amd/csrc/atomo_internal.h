@@ -59,6 +59,7 @@ struct atomo_ctx {
     atomo::SweepHint hints[4];
     int hint_next = 0;
     uint64_t hint_seq = 0;
+    size_t rowgram_lds = 0;        // dynamic LDS that svd_rowgram has been allowed on this context's device
     hipStream_t side = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     // optional event bracketing of kernel launches (atomo_profile_*)

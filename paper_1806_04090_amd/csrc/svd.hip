@@ -15,18 +15,19 @@
 // tournament over its row blocks.  A sweep is R = (#blocks - 1) rounds.
 //
 // Small matrices (fewer than 16 row blocks) iterate in data space, on a forked stream of the context;
-// per tick and block pair (64 rows):
-//     svd_gram<false> : partial 64x64 Gram matrices of the pair over column chunks          (MFMA)
-//     svd_eig         : sums the partials and diagonalises the Gram matrix (see svd_eig.hip)
-//     svd_rowop       : rows <- Q^T rows over all of W                                      (MFMA)
+// per tick, two launches:
+//     svd_eig     : per block pair (64 rows), sums the partial Gram matrices of the pair and diagonalises the
+//                   sum (see svd_eig.hip)
+//     svd_rowgram : per 64-column chunk of W, rows <- Q^T rows for every pair, then the partial Gram matrices
+//                   of the pairs of the next tick from the rows it still holds in LDS              (MFMA)
 // and stop after the first sweep in which no pair of rows had |cos| above the threshold.
 //
 // Large matrices iterate in Gram space: the rotations of a pair depend on the rows only through
-// their Gram matrix, so the r x r matrix C = A A^T is formed once (svd_gram<true>, MFMA), the sweeps
+// their Gram matrix, so the r x r matrix C = A A^T is formed once (svd_fullgram, MFMA), the sweeps
 // rotate C two-sidedly and accumulate the rotations in Tgs, and only when a sweep finds C diagonal to
 // the threshold are the accumulated rotations applied to the data as one contraction W <- Tgs * W
 // (svd_apply, MFMA).  fp32 rounding makes C drift from the true Gram matrix of the rotated rows, so
-// after every application C is formed afresh from the data (svd_gram<true> again); the matrix is
+// after every application C is formed afresh from the data (svd_fullgram again); the matrix is
 // finished when that fresh C is diagonal to the threshold, otherwise the sweeps continue
 // from it.  The O(M r^2) work thus happens in two or three large contractions instead of in every
 // round.  A Gram-space tick is one launch of svd_eig: the pair problems of the tick, and as extra
@@ -131,39 +132,24 @@ __global__ __launch_bounds__(256) void svd_prepare(const SvdMat* mats, const Wor
 }
 
 // ------------------------------------------------------------------------------------------------
-// gram: partial Gram matrix of 64 rows against 64 rows over one column chunk.
-//   FULL = false: the two row blocks of a tournament pair against themselves (data-space matrices)
-//   FULL = true : tile (ti, tj), ti <= tj, of the full r x r Gram matrix (Gram-space matrices, refresh)
+// fullgram: partial sums, over one column chunk, of tile (ti, tj), ti <= tj, of the Gram matrix of all rows
+// (Gram-space matrices at a refresh, data-space matrices at the check of DS_VERIFY)
 // ------------------------------------------------------------------------------------------------
-template <bool FULL>
-__global__ __launch_bounds__(256) void svd_gram(const SvdMat* mats, const Work* work, int tick, int max_sweeps)
+__global__ __launch_bounds__(256) void svd_fullgram(const SvdMat* mats, const Work* work)
 {
-    __shared__ float tile[FULL ? 2 * PR : PR][68];
+    __shared__ float tile[2 * PR][68];
     const Work wk = work[blockIdx.x];
     const SvdMat m = mats[wk.mat];
-    int rowA0, rowA1, rowB0, rowB1, chunk, out_index;
-    const float* W;
-    if (FULL) {
-        if (!refreshing(m) && !verifying(m)) return;
-        const int cur = m.state[ST_CUR] & 1;
-        const float* const w0 = m.W0;
-        const float* const w1 = m.W1;
-        // what svd_apply has just written; a data-space matrix has the one buffer
-        W = (m.gs && (m.state[ST_FIRST] ? cur : cur ^ 1) != 0) ? w1 : w0;
-        const int ti = wk.a, tj = wk.b, nt = m.nb2 / 2;
-        rowA0 = ti * PR; rowA1 = rowA0 + BS; rowB0 = tj * PR; rowB1 = rowB0 + BS;
-        chunk = wk.c;
-        out_index = ti * nt - ti * (ti - 1) / 2 + (tj - ti);
-    } else {
-        if (m.gs || skip_step(m, tick, max_sweeps)) return;
-        W = m.W0;
-        int bi, bj;
-        pair_blocks(m.nb2, tick % m.R, wk.a, bi, bj);
-        rowA0 = rowB0 = bi * BS; rowA1 = rowB1 = bj * BS;
-        chunk = wk.b;
-        out_index = wk.a;
-    }
-    const bool same = !FULL || rowA0 == rowB0;
+    if (!refreshing(m) && !verifying(m)) return;
+    const int cur = m.state[ST_CUR] & 1;
+    const float* const w0 = m.W0;
+    const float* const w1 = m.W1;
+    // what svd_apply has just written; a data-space matrix has the one buffer
+    const float* W = (m.gs && (m.state[ST_FIRST] ? cur : cur ^ 1) != 0) ? w1 : w0;
+    const int ti = wk.a, tj = wk.b, nt = m.nb2 / 2, chunk = wk.c;
+    const int rowA0 = ti * PR, rowB0 = tj * PR;
+    const int out_index = ti * nt - ti * (ti - 1) / 2 + (tj - ti);
+    const bool same = ti == tj;
     const int c_begin = chunk * KCG;
     const int c_end = min(m.Mp, c_begin + KCG);
 
@@ -179,21 +165,15 @@ __global__ __launch_bounds__(256) void svd_gram(const SvdMat* mats, const Work* 
     for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 
     // (native vector type: an array of the float4 class ended up in scratch memory here)
-    floatx4 ld[FULL ? 8 : 4];
+    floatx4 ld[8];
     auto fetch = [&](int c0) {
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const int lr = lrow + 16 * p;                        // 0..63
-            const int grow = (lr < BS ? rowA0 + lr : rowA1 + lr - BS);
-            ld[p] = *(const floatx4*)(W + (size_t)grow * m.ldw + c0 + lc4);
-        }
-        if (FULL && !same) {
+        for (int p = 0; p < 4; ++p)
+            ld[p] = *(const floatx4*)(W + (size_t)(rowA0 + lrow + 16 * p) * m.ldw + c0 + lc4);
+        if (!same) {
 #pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                const int lr = lrow + 16 * p;
-                const int grow = (lr < BS ? rowB0 + lr : rowB1 + lr - BS);
-                ld[4 + p] = *(const floatx4*)(W + (size_t)grow * m.ldw + c0 + lc4);
-            }
+            for (int p = 0; p < 4; ++p)
+                ld[4 + p] = *(const floatx4*)(W + (size_t)(rowB0 + lrow + 16 * p) * m.ldw + c0 + lc4);
         }
     };
     if (c_begin < c_end) fetch(c_begin);
@@ -201,7 +181,7 @@ __global__ __launch_bounds__(256) void svd_gram(const SvdMat* mats, const Work* 
         __syncthreads();                                         // previous tile fully consumed
 #pragma unroll
         for (int p = 0; p < 4; ++p) *(floatx4*)&tile[lrow + 16 * p][lc4] = ld[p];
-        if (FULL && !same) {
+        if (!same) {
 #pragma unroll
             for (int p = 0; p < 4; ++p) *(floatx4*)&tile[PR + lrow + 16 * p][lc4] = ld[4 + p];
         }
@@ -217,7 +197,7 @@ __global__ __launch_bounds__(256) void svd_gram(const SvdMat* mats, const Work* 
             acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b.w, acc, 0, 0, 0);
         }
     }
-    float* out = m.gram + ((size_t)out_index * m.nchg + chunk) * QSZ;
+    float* out = m.gramf + ((size_t)out_index * m.nchg + chunk) * QSZ;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
         const int i = qi * BS + 8 * (v >> 2) + 4 * h + (v & 3);
@@ -234,7 +214,7 @@ __global__ __launch_bounds__(256) void svd_fullgram_reduce(const SvdMat* mats, c
     if (!refreshing(m)) return;
     const int ti = wk.a, tj = wk.b, nt = m.nb2 / 2;
     const int tile_index = ti * nt - ti * (ti - 1) / 2 + (tj - ti);
-    const float* g = m.gram + (size_t)tile_index * m.nchg * QSZ;
+    const float* g = m.gramf + (size_t)tile_index * m.nchg * QSZ;
     const int tid = threadIdx.x;
     // sixteen independent sums per thread, chunk after chunk in a fixed order: sixteen loads in flight
     float sums[QSZ / 256];
@@ -339,7 +319,7 @@ __global__ __launch_bounds__(256) void svd_fresh_check(const SvdMat* mats, const
     m.state[ST_DMIN] = 0x7f800000;
 }
 
-// Data-space matrices (DS_VERIFY): largest |cos| between any two rows from the partial tiles that svd_gram<true> has
+// Data-space matrices (DS_VERIFY): largest |cos| between any two rows from the partial tiles that svd_fullgram has
 // just formed; the last tile to finish decides whether the matrix is done.  One workgroup per 64x64 tile.
 __global__ __launch_bounds__(256) void svd_ds_verify(const SvdMat* mats, const Work* work, int tick, int max_sweeps,
                                                      float stop_cosine, int* flags)
@@ -350,11 +330,11 @@ __global__ __launch_bounds__(256) void svd_ds_verify(const SvdMat* mats, const W
     if (!verifying(m)) return;
     const int ti = wk.a, tj = wk.b, nt = m.nb2 / 2;
     auto tile_of = [&](int a, int b) { return a * nt - a * (a - 1) / 2 + (b - a); };
-    const float* gt = m.gram + (size_t)tile_of(ti, tj) * m.nchg * QSZ;
+    const float* gt = m.gramf + (size_t)tile_of(ti, tj) * m.nchg * QSZ;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (tid < 2 * PR) {                                          // squared norms of the tile's rows and columns
         const int k = tid & (PR - 1), t = tid < PR ? ti : tj;
-        const float* gd = m.gram + (size_t)tile_of(t, t) * m.nchg * QSZ + k * PR + k;
+        const float* gd = m.gramf + (size_t)tile_of(t, t) * m.nchg * QSZ + k * PR + k;
         float sum = 0.0f;
         for (int c = 0; c < m.nchg; ++c) sum += gd[(size_t)c * QSZ];
         (tid < PR ? dI : dJ)[k] = sum;
@@ -390,57 +370,171 @@ __global__ __launch_bounds__(256) void svd_ds_verify(const SvdMat* mats, const W
 }
 
 // ------------------------------------------------------------------------------------------------
-// rowop: data-space matrices, the 64 rows of a pair <- Q^T rows, over one 256-column chunk of W (in place)
+// rowgram: data-space matrices, the row update of a tick and the pair Gram matrices of the next in one pass
+// over W.  A work item owns a run of 64-column chunks of W = [A | T] of one matrix, with all its rows.  Per chunk:
+//   - all rows of the chunk into LDS;
+//   - a wave takes a pair of the tick and replaces its 64 rows by Q^T rows, in LDS (only that wave touches
+//     those rows); pairs that the pair problem left alone keep their rows;
+//   - the rotated rows go back to memory;
+//   - (chunks of A) a wave takes a pair of the next tick and forms the quadrants aa, ab and bb of its 64x64
+//     Gram matrix over the chunk's columns from LDS; ba mirrors ab and is not written.  A work item with
+//     several chunks adds them up in its own partial matrix, in chunk order.
+// tick = -1: no update, the Gram matrices of tick 0.
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void svd_rowop(const SvdMat* mats, const Work* work, int tick, int max_sweeps)
+constexpr int XLD = 68;                 // row stride of the chunk in LDS (16-byte reads down a column of rows: no bank conflicts)
+constexpr int ROWGRAM_MAX_PARTIALS = 48;    // partial Gram matrices per pair that svd_eig adds up, at most
+constexpr size_t ROWGRAM_LDS_MAX = (size_t)GS_MIN_BLOCKS * BS * XLD * sizeof(float);   // data-space matrices have fewer blocks
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void svd_rowgram(const SvdMat* mats, const Work* work, int tick, int max_sweeps)
 {
+    extern __shared__ float xs[];                                // [rows_alloc][XLD]
+    __shared__ int moved[GS_MIN_BLOCKS];                        // per row block: its pair was rotated in this tick
     const Work wk = work[blockIdx.x];
     const SvdMat m = mats[wk.mat];
-    if (m.gs || skip_step(m, tick, max_sweeps) || m.idle[wk.a]) return;
-    int bi, bj;
-    pair_blocks(m.nb2, tick % m.R, wk.a, bi, bj);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const bool rotate = tick >= 0 && !skip_step(m, tick, max_sweeps);
+    const bool gram = wk.c >= 0 && !skip_step(m, tick + 1, max_sweeps);
+    if (!rotate && !gram) return;
+    // (the wave index as a scalar: addresses that depend on it are then scalar too)
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int h = lane >> 5, l32 = lane & 31;
-    const int c0 = wk.b * KCU + wave * 64;
-    if (c0 >= m.ldw) return;
-    const float* q = m.Q + (size_t)wk.a * QSZ;
+    const int lrow = tid >> 4, lc4 = (tid & 15) * 4;             // loader mapping: 16 threads per row, 16 rows per pass
+    const int round = rotate ? tick % m.R : 0, next_round = (tick + 1) % m.R;
+    if (tid < m.nb2) moved[tid] = rotate && !m.idle[pair_of_block(m.nb2, round, tid)];
 
-    floatx16 acc[2][2];                                          // [column parity][row block]
-#pragma unroll
-    for (int e = 0; e < 2; ++e)
-#pragma unroll
-        for (int ib = 0; ib < 2; ++ib)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[e][ib][v] = 0.0f;
+    // (pointers read from the descriptor are generic to the compiler, and every generic load waits for the LDS
+    // traffic in flight; these are known to be global memory)
+    typedef __attribute__((address_space(1))) float gfloat;
+    typedef __attribute__((address_space(1))) floatx4 gfloatx4;
+    const gfloat* const Qg = (const gfloat*)m.Q;
 
-    float* rowI = m.W0 + (size_t)bi * BS * m.ldw + c0 + 2 * l32;
-    float* rowJ = m.W0 + (size_t)bj * BS * m.ldw + c0 + 2 * l32;
-    // every load of the tile is issued before the first product: the kernel is a chain of memory latencies otherwise
-    float xa[32], xb[32], q0[32], q1[32];
+    float q0[32], q1[32];
+    auto load_q = [&](int k) {
+        // scalar base (forced: the compiler otherwise forms a 64-bit lane address for each of the 64 loads), one
+        // 32-bit lane offset
+        const unsigned long long qa = (unsigned long long)(Qg + (size_t)k * QSZ);
+        const gfloat* q = (const gfloat*)(((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(qa >> 32)) << 32) |
+                                          (unsigned)__builtin_amdgcn_readfirstlane((int)qa));
+        const unsigned at = h * PR + l32;
 #pragma unroll
-    for (int s = 0; s < 32; ++s) {
-        const int k = 2 * s + h;                                 // local row of the pair, 0..63
-        const float* p = (k < BS ? rowI + (size_t)k * m.ldw : rowJ + (size_t)(k - BS) * m.ldw);
-        const float2 x = *(const float2*)p;
-        xa[s] = x.x; xb[s] = x.y;
-        q0[s] = q[k * PR + l32];                                 // (Q^T)[i][k], i in block 0
-        q1[s] = q[k * PR + BS + l32];                            //              i in block 1
-    }
-    __builtin_amdgcn_sched_barrier(0);                           // (keeps the loads above the products)
+        for (int s = 0; s < 32; ++s) {
+            q0[s] = (q + 2 * s * PR)[at];                        // (Q^T)[i][k], i in block 0
+            q1[s] = (q + 2 * s * PR + BS)[at];                   //              i in block 1
+        }
+    };
+
+    for (int sc = 0; sc < wk.b; ++sc) {
+        const int c0 = (wk.a + sc) * 64;
+        gfloat* const wcol = (gfloat*)m.W0 + (size_t)lrow * m.ldw + c0 + lc4;
+        float* const xrow = xs + lrow * XLD + lc4;
+        int k = wave;
+        // (a loaded value is a per-lane value to the compiler: as a scalar it makes the branch and the addresses scalar)
+        bool active = rotate && k < m.npairs && !__builtin_amdgcn_readfirstlane(m.idle[k]);
+        if (active) load_q(k);                                   // in flight while the chunk is staged
+        if (sc > 0) __syncthreads();                             // the previous chunk's products have read LDS
+        // all rows of the chunk into LDS, 128 rows (8 passes of 16) at a time; rows_alloc is a multiple of 64
+        int p0 = 0;
+        for (; p0 + 128 <= m.rows_alloc; p0 += 128) {
+            floatx4 ld[8];
 #pragma unroll
-    for (int s = 0; s < 32; ++s) {
-        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(q0[s], xa[s], acc[0][0], 0, 0, 0);
-        acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(q0[s], xb[s], acc[1][0], 0, 0, 0);
-        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(q1[s], xa[s], acc[0][1], 0, 0, 0);
-        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(q1[s], xb[s], acc[1][1], 0, 0, 0);
-    }
+            for (int p = 0; p < 8; ++p) ld[p] = *(const gfloatx4*)(wcol + (size_t)(p0 + 16 * p) * m.ldw);
 #pragma unroll
-    for (int ib = 0; ib < 2; ++ib) {
-        float* base = (ib == 0 ? rowI : rowJ);
+            for (int p = 0; p < 8; ++p) *(floatx4*)(xrow + (p0 + 16 * p) * XLD) = ld[p];
+        }
+        if (p0 < m.rows_alloc) {
+            floatx4 ld[4];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int i = 8 * (v >> 2) + 4 * h + (v & 3);
-            *(float2*)(base + (size_t)i * m.ldw) = make_float2(acc[0][ib][v], acc[1][ib][v]);
+            for (int p = 0; p < 4; ++p) ld[p] = *(const gfloatx4*)(wcol + (size_t)(p0 + 16 * p) * m.ldw);
+#pragma unroll
+            for (int p = 0; p < 4; ++p) *(floatx4*)(xrow + (p0 + 16 * p) * XLD) = ld[p];
+        }
+        __syncthreads();
+
+        if (rotate) {
+            while (true) {
+                if (active) {
+                    int bi, bj;
+                    pair_blocks(m.nb2, round, k, bi, bj);
+                    float* const xi = xs + bi * BS * XLD + l32;
+                    float* const xj = xs + bj * BS * XLD + l32;
+                    floatx16 acc[2][2];                          // [column half][row block]
+#pragma unroll
+                    for (int e = 0; e < 2; ++e)
+#pragma unroll
+                        for (int ib = 0; ib < 2; ++ib)
+#pragma unroll
+                            for (int v = 0; v < 16; ++v) acc[e][ib][v] = 0.0f;
+#pragma unroll
+                    for (int s = 0; s < 32; ++s) {
+                        const float* xr = s < 16 ? xi + (2 * s + h) * XLD : xj + (2 * s + h - BS) * XLD;
+                        const float xa = xr[0], xb = xr[32];
+                        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(q0[s], xa, acc[0][0], 0, 0, 0);
+                        acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(q0[s], xb, acc[1][0], 0, 0, 0);
+                        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(q1[s], xa, acc[0][1], 0, 0, 0);
+                        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(q1[s], xb, acc[1][1], 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int ib = 0; ib < 2; ++ib) {
+                        float* const xo = ib == 0 ? xi : xj;
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            const int i = 8 * (v >> 2) + 4 * h + (v & 3);
+                            xo[i * XLD] = acc[0][ib][v];
+                            xo[i * XLD + 32] = acc[1][ib][v];
+                        }
+                    }
+                }
+                k += 4;
+                if (k >= m.npairs) break;
+                active = !__builtin_amdgcn_readfirstlane(m.idle[k]);
+                if (active) load_q(k);
+            }
+            __syncthreads();
+            for (int row = 0; row < m.rows_alloc; row += 16)
+                if (moved[(row + lrow) >> 5]) *(gfloatx4*)(wcol + (size_t)row * m.ldw) = *(const floatx4*)(xrow + row * XLD);
+        }
+
+        if (gram) {
+            for (int k = wave; k < m.npairs; k += 4) {
+                int bi, bj;
+                pair_blocks(m.nb2, next_round, k, bi, bj);
+                const float* const pi = xs + (bi * BS + l32) * XLD + h * 32;
+                const float* const pj = xs + (bj * BS + l32) * XLD + h * 32;
+                floatx16 aa, ab, bb;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) aa[v] = ab[v] = bb[v] = 0.0f;
+#pragma unroll
+                for (int s = 0; s < 8; ++s) {
+                    const float4 a = *(const float4*)(pi + 4 * s);
+                    const float4 b = *(const float4*)(pj + 4 * s);
+                    aa = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, a.x, aa, 0, 0, 0);
+                    ab = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, ab, 0, 0, 0);
+                    bb = __builtin_amdgcn_mfma_f32_32x32x2f32(b.x, b.x, bb, 0, 0, 0);
+                    aa = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, a.y, aa, 0, 0, 0);
+                    ab = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.y, ab, 0, 0, 0);
+                    bb = __builtin_amdgcn_mfma_f32_32x32x2f32(b.y, b.y, bb, 0, 0, 0);
+                    aa = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, a.z, aa, 0, 0, 0);
+                    ab = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b.z, ab, 0, 0, 0);
+                    bb = __builtin_amdgcn_mfma_f32_32x32x2f32(b.z, b.z, bb, 0, 0, 0);
+                    aa = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, a.w, aa, 0, 0, 0);
+                    ab = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b.w, ab, 0, 0, 0);
+                    bb = __builtin_amdgcn_mfma_f32_32x32x2f32(b.w, b.w, bb, 0, 0, 0);
+                }
+                gfloat* const out = (gfloat*)m.gram + ((size_t)k * m.nchp + wk.c) * QSZ + l32;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int i = 8 * (v >> 2) + 4 * h + (v & 3);
+                    gfloat* const o = out + i * PR;
+                    if (sc == 0) {
+                        o[0] = aa[v];
+                        o[BS] = ab[v];
+                        o[BS * PR + BS] = bb[v];
+                    } else {                                     // (written by this same lane for the chunk before)
+                        o[0] += aa[v];
+                        o[BS] += ab[v];
+                        o[BS * PR + BS] += bb[v];
+                    }
+                }
+            }
         }
     }
 }
@@ -785,7 +879,7 @@ __global__ __launch_bounds__(256) void svd_hint(const SvdMat* mats, int n_mats, 
 
 struct Plan {
     std::vector<SvdMat> mats;
-    std::vector<Work> prep, gram, fullgram, tiles, apply, eig_gs, eig_ds, rowop1, twosided, strips, norms, pack;
+    std::vector<Work> prep, rowgram, fullgram, tiles, apply, eig_gs, eig_ds, twosided, strips, norms, pack;
     std::vector<Work> ds_full, ds_tiles;           // data-space matrices that check their whole Gram matrix (DS_VERIFY)
     std::vector<int> ds_periods;                   // their distinct R
     std::vector<Work> thin_chunks, thin_list;      // thin matrices: (matrix, chunk of positions); (matrix)
@@ -794,14 +888,15 @@ struct Plan {
     std::vector<int> gs_periods;     // distinct R of the Gram-space matrices
     int max_R = 1;
     int max_R_ds = 1;                // largest R among the data-space matrices
+    size_t rowgram_lds = 0;          // LDS bytes of a svd_rowgram workgroup: all rows of the tallest data-space matrix
     bool own_update = false;         // the two-sided update runs as launches of its own (see SPLIT_TWO_SIDED)
     size_t bytes = 0;
     SvdMat* d_mats = nullptr;        // device copies of `mats` and of the concatenated work lists
     Work* d_work = nullptr;
     size_t n_work() const
     {
-        return prep.size() + gram.size() + fullgram.size() + tiles.size() + apply.size() + eig_gs.size() + eig_ds.size() +
-               rowop1.size() + twosided.size() + strips.size() + ds_full.size() + ds_tiles.size() + norms.size() + pack.size() + 2 * thin_chunks.size() + thin_list.size() +
+        return prep.size() + rowgram.size() + fullgram.size() + tiles.size() + apply.size() + eig_gs.size() + eig_ds.size() +
+               twosided.size() + strips.size() + ds_full.size() + ds_tiles.size() + norms.size() + pack.size() + 2 * thin_chunks.size() + thin_list.size() +
                gs_list.size();
     }
 };
@@ -885,6 +980,10 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
         m.nchg = (m.Mp + KCG - 1) / KCG;
         m.nchu = (m.ldw + KCU - 1) / KCU;
         m.gs = m.nb2 >= GS_MIN_BLOCKS;
+        // data space: work items of svd_rowgram over A, of `run` 64-column chunks each, at most ROWGRAM_MAX_PARTIALS
+        const int chunks_a = m.Mp / 64;
+        const int run = (chunks_a + ROWGRAM_MAX_PARTIALS - 1) / ROWGRAM_MAX_PARTIALS;
+        m.nchp = m.gs ? 0 : (chunks_a + run - 1) / run;
         const int nt = m.nb2 / 2;
         m.ntiles = nt * (nt + 1) / 2;
         m.ldc = 2 * m.rows_alloc;
@@ -894,7 +993,8 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
         // (the same buffer twice: C is updated in place, and svd_eig reads its block of C as it is)
         m.CT2 = !m.gs ? nullptr : plan.own_update ? m.CT : carve.take<float>((size_t)m.rows_alloc * m.ldc);
         const bool ds_verify = !m.gs && m.R >= DS_VERIFY_MIN_R;
-        m.gram = carve.take<float>((size_t)(m.gs || ds_verify ? m.ntiles : m.npairs) * m.nchg * QSZ);
+        m.gram = m.gs ? nullptr : carve.take<float>((size_t)m.npairs * m.nchp * QSZ);
+        m.gramf = m.gs || ds_verify ? carve.take<float>((size_t)m.ntiles * m.nchg * QSZ) : nullptr;
         m.Q = carve.take<float>((size_t)(m.gs ? 2 : 1) * m.npairs * QSZ);
         m.idle = m.gs ? nullptr : carve.take<int>(m.npairs);
         m.state = carve.take<int>(ST_WORDS);
@@ -921,10 +1021,12 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
                     for (int k2 = 0; k2 < m.npairs; k2 += STRIP) plan.strips.push_back(Work{j, k, k2, 1});
                     for (int c = 0; c < m.rows_alloc / PR; c += STRIP) plan.strips.push_back(Work{j, k, c, 2});
                 }
-            } else {
-                for (int c = 0; c < m.nchg; ++c) plan.gram.push_back(Work{j, k, c, 0});
-                for (int c = 0; c < m.nchu; ++c) plan.rowop1.push_back(Work{j, k, c, 0});
             }
+        }
+        if (!m.gs) {
+            for (int c = 0; c < m.nchp; ++c) plan.rowgram.push_back(Work{j, c * run, std::min(run, chunks_a - c * run), c});
+            for (int c = chunks_a; c < m.ldw / 64; ++c) plan.rowgram.push_back(Work{j, c, 1, -1});   // the chunks of T
+            plan.rowgram_lds = std::max(plan.rowgram_lds, (size_t)m.rows_alloc * XLD * sizeof(float));
         }
         if (m.gs) {
             plan.gs_list.push_back(Work{j, 0, 0, 0});
@@ -953,6 +1055,10 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
         for (int k = 0; k < m.capacity; ++k) plan.pack.push_back(Work{j, k, 0, 0});
     }
     deal_to_dies(plan.strips);                                   // a matrix's strips, which share its rotations, on one die
+    // the work items of the tallest matrices first: they set the duration of the launch
+    std::stable_sort(plan.rowgram.begin(), plan.rowgram.end(), [&](const Work& a, const Work& b) {
+        return plan.mats[a.mat].rows_alloc * (a.c >= 0 ? 2 : 1) > plan.mats[b.mat].rows_alloc * (b.c >= 0 ? 2 : 1);
+    });
     plan.d_work = carve.take<Work>(plan.n_work());
     plan.bytes = carve.off;
 }
@@ -1055,13 +1161,12 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
         return at;
     };
     const Work* w_prep = place(plan.prep);
-    const Work* w_gram = place(plan.gram);
+    const Work* w_rowgram = place(plan.rowgram);
     const Work* w_fullgram = place(plan.fullgram);
     const Work* w_tiles = place(plan.tiles);
     const Work* w_apply = place(plan.apply);
     const Work* w_eig_gs = place(plan.eig_gs);
     const Work* w_eig_ds = place(plan.eig_ds);
-    const Work* w_rowop1 = place(plan.rowop1);
     const Work* w_twosided = place(plan.twosided);
     const Work* w_strips = place(plan.strips);
     const Work* w_ds_full = place(plan.ds_full);
@@ -1097,7 +1202,7 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     // t forms its own 64x64 block from the C of parity t-1 and the rotations of tick t-1, which are
     // double-buffered by tick parity as well.
     // Thin matrices share that stream when there are Gram-space matrices to overlap with.
-    const bool have_ds = !plan.gram.empty(), have_gs = !plan.twosided.empty(), have_thin = !plan.thin_list.empty();
+    const bool have_ds = !plan.rowgram.empty(), have_gs = !plan.twosided.empty(), have_thin = !plan.thin_list.empty();
     const bool use_side = have_ds || (have_thin && have_gs);
     const int n_two = (int)plan.twosided.size();
     if (use_side) {
@@ -1128,16 +1233,20 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
             for (int period : plan.ds_periods) boundary = boundary || (tick % period == 0 && tick <= limit_ds * period);
             if (!boundary) return;
             ProfScope ps(ctx, ATOMO_K_SVD_REFRESH, s_ds);
-            svd_gram<true><<<grid(plan.ds_full), 256, 0, s_ds>>>(d_mats, w_ds_full, tick, limit_ds);
+            svd_fullgram<<<grid(plan.ds_full), 256, 0, s_ds>>>(d_mats, w_ds_full);
             svd_ds_verify<<<grid(plan.ds_tiles), 256, 0, s_ds>>>(d_mats, w_ds_tiles, tick, limit_ds, stop_cosine, ctx->d_flags);
         };
-        for (int tick = 0; tick <= ds_ticks; ++tick) {
-            if (tick > 0) verify(tick);
-            if (tick == ds_ticks) break;
-            {
-                ProfScope ps(ctx, ATOMO_K_SVD_GRAM, s_ds);
-                svd_gram<false><<<grid(plan.gram), 256, 0, s_ds>>>(d_mats, w_gram, tick, limit_ds);
-            }
+        // more LDS than a launch gets by default: raised once per context
+        if (plan.rowgram_lds > ctx->rowgram_lds) {
+            ATOMO_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(svd_rowgram),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)ROWGRAM_LDS_MAX));
+            ctx->rowgram_lds = ROWGRAM_LDS_MAX;
+        }
+        {
+            ProfScope ps(ctx, ATOMO_K_SVD_GRAM, s_ds);
+            svd_rowgram<<<grid(plan.rowgram), 256, plan.rowgram_lds, s_ds>>>(d_mats, w_rowgram, -1, limit_ds);
+        }
+        for (int tick = 0; tick < ds_ticks; ++tick) {
             {
                 ProfScope ps(ctx, ATOMO_K_SVD_EIG, s_ds);
                 launch_svd_eig(d_mats, w_eig_ds, (int)plan.eig_ds.size(), nullptr, 0, nullptr, 0, 0, tick, limit_ds,
@@ -1145,8 +1254,9 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
             }
             {
                 ProfScope ps(ctx, ATOMO_K_SVD_UPDATE, s_ds);
-                svd_rowop<<<grid(plan.rowop1), 256, 0, s_ds>>>(d_mats, w_rowop1, tick, limit_ds);
+                svd_rowgram<<<grid(plan.rowgram), 256, plan.rowgram_lds, s_ds>>>(d_mats, w_rowgram, tick, limit_ds);
             }
+            verify(tick + 1);
         }
     }
     if (use_side) ATOMO_HIP(ctx, hipEventRecord(ctx->ev_join, ctx->side));
@@ -1181,7 +1291,7 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
                 {
                     ProfScope ps(ctx, ATOMO_K_SVD_REFRESH, stream);
                     svd_apply<<<grid(plan.apply), 256, 0, stream>>>(d_mats, w_apply);
-                    svd_gram<true><<<grid(plan.fullgram), 256, 0, stream>>>(d_mats, w_fullgram, tick, limit_gs);
+                    svd_fullgram<<<grid(plan.fullgram), 256, 0, stream>>>(d_mats, w_fullgram);
                     svd_fullgram_reduce<<<grid(plan.tiles), 256, 0, stream>>>(d_mats, w_tiles, tick);
                     svd_fresh_check<<<grid(plan.tiles), 256, 0, stream>>>(d_mats, w_tiles, tick, limit_gs, stop_cosine,
                                                                           fresh_stop, ctx->d_flags);

@@ -97,8 +97,12 @@ struct SvdMat {
     float* CT2;              // Gram space: second buffer of the same shape; its C half alternates with CT's by tick parity
     int ldw, ldc, r, M, Mp, rows_alloc;
     int nb2, R, npairs, nchg, nchu, gs, ntiles;
+    int nchp;                // data space: partial Gram matrices per pair, one per work item of svd_rowgram over A
     int* idle;               // data space: [npairs] 1 if the pair problem of the running tick left its rows as they are
-    float* gram;             // data space: [npairs][nchg][64*64]; Gram space: [ntiles][nchg][64*64]
+    float* gram;             // data space: [npairs][nchp][64*64], partial Gram matrices of the pairs of the coming tick
+                             //   (the quadrant of rows 32.. x columns ..31 is not written: it mirrors the one across)
+    float* gramf;            // [ntiles][nchg][64*64]: partial tiles of the Gram matrix of all rows (Gram space: the refresh;
+                             //   data space: the check of DS_VERIFY, null for matrices too small for it)
     float* Q;                // [npairs][64*64]; Gram space: [2][npairs][64*64], indexed by tick parity
     int* state;              // [ST_WORDS]
     float* sig_raw;          // [rows_alloc]
@@ -211,7 +215,7 @@ constexpr float DS_LEAVE = 0.1f;
 // Data space: a sweep whose largest cosine (measured before rotating) is below DS_VERIFY x stop_cosine has, convergence
 // being quadratic, most likely left the matrix converged.  Instead of a whole further sweep that only confirms it (R ticks
 // of three launches in which nothing rotates), the Gram matrix of all rows is then formed once at the sweep boundary
-// (svd_gram<true>) and its largest cosine decides (svd_ds_verify): finished, or the sweeps go on.  Only for matrices of
+// (svd_fullgram) and its largest cosine decides (svd_ds_verify): finished, or the sweeps go on.  Only for matrices of
 // at least DS_VERIFY_MIN_R ticks per sweep: the check costs two launches at every sweep boundary.
 constexpr float DS_VERIFY = 10.0f;
 constexpr int DS_VERIFY_MIN_R = 7;

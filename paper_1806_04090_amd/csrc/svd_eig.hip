@@ -258,7 +258,7 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
     const bool cross = round % full_period != 0;
 
     // 1. the Gram matrix of the pair into As[0] (home slots), Q = I into Qs[0].
-    //    Data-space matrices: the partial sums, added in a fixed order.
+    //    Data-space matrices: the partial sums that svd_rowgram left, added in a fixed order.
     //    Gram-space matrices, first tick after a refresh: the pair's block of C as it is.
     //    Gram-space matrices otherwise: C (previous parity) does not contain the previous tick's rotations yet.
     //    With the pair's blocks a (then in pair k1, half s1) and b (pair k2, half s2) of the previous round,
@@ -276,20 +276,31 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
         ref[tid] = m.gs ? m.cref[tid < BS ? bi * BS + tid : bj * BS + tid - BS] : 0.0f;
         ref0[tid] = m.gs ? m.cref0[tid < BS ? bi * BS + tid : bj * BS + tid - BS] : 0.0f;
     }
-    if (!m.gs || fresh) {
-        const float* g = m.gram + (size_t)wk.a * m.nchg * QSZ;
-        const float* C = m.gs ? c_of_parity(m, step) : nullptr;
+    if (!m.gs) {
+        // one 16-byte piece of the matrix per thread; the quadrant of rows 32.. x columns ..31 is not in the partial
+        // matrices: it mirrors the one across
+        static_assert(NT * 4 == QSZ, "one float4 of the pair's Gram matrix per thread");
+        const int i = tid >> 4, j4 = (tid & 15) * 4;
+        if (i < BS || j4 >= BS) {
+            const float* g = m.gram + (size_t)wk.a * m.nchp * QSZ + i * PR + j4;
+            floatx4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll 4
+            for (int c = 0; c < m.nchp; ++c) sum += *(const floatx4*)(g + (size_t)c * QSZ);
+            const int si = home_slot(i, cross);
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                const int sj = home_slot(j4 + x, cross);
+                As[0][si * ELD + mem_col(sj)] = sum[x];
+                if (i < BS && j4 >= BS) As[0][sj * ELD + mem_col(si)] = sum[x];
+            }
+        }
+    } else if (fresh) {
+        const float* C = c_of_parity(m, step);
         for (int e = tid; e < QSZ; e += NT) {
             const int i = e >> 6, j = e & 63;
-            float sum = 0.0f;
-            if (m.gs) {
-                const int gi = i < BS ? bi * BS + i : bj * BS + i - BS;
-                const int gj = j < BS ? bi * BS + j : bj * BS + j - BS;
-                sum = C[(size_t)gi * m.ldc + gj];
-            } else {
-                for (int c = 0; c < m.nchg; ++c) sum += g[(size_t)c * QSZ + e];
-            }
-            As[0][home_slot(i, cross) * ELD + mem_col(home_slot(j, cross))] = sum;
+            const int gi = i < BS ? bi * BS + i : bj * BS + i - BS;
+            const int gj = j < BS ? bi * BS + j : bj * BS + j - BS;
+            As[0][home_slot(i, cross) * ELD + mem_col(home_slot(j, cross))] = C[(size_t)gi * m.ldc + gj];
         }
     } else {
         const int prev = step - 1, pp = (step - 1) & 1;
@@ -606,7 +617,7 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
         const int all_in_place = __syncthreads_and(in_place);
         if (tid == 0) {
             m.idle[wk.a] = all_in_place;
-            // work counter: row updates that svd_rowop will execute for this pair, in tiles of 64 rows x 64 columns
+            // work counter: row updates that svd_rowgram will execute for this pair, in tiles of 64 rows x 64 columns
             if (!all_in_place) atomicAdd(&flags[FLAG_DS_UPDATE_UNITS], m.ldw / 64);
         }
     }

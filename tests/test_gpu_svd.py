@@ -67,7 +67,9 @@ def test_config1_single_conv_layer():
 
 
 @pytest.mark.parametrize("shape", [(1, 1), (1, 40), (40, 1), (3, 5), (32, 32), (33, 70), (70, 33), (64, 27),
-                                   (10, 512), (96, 200), (65, 64), (128, 64), (160, 300)])
+                                   (10, 512), (96, 200), (65, 64), (128, 64), (160, 300),
+                                   # more than four block pairs per tick; more column chunks than partial Gram matrices
+                                   (300, 420), (480, 500), (72, 3300), (3200, 290)])
 def test_ragged_shapes(shape):
     rng = np.random.default_rng(shape[0] * 7919 + shape[1])
     G = inputs.low_rank_plus_noise(rng, shape[0], shape[1], [1.0, 0.5, 0.2], 0.02)
