@@ -512,8 +512,9 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
             __syncthreads();
             const int left = ((lane & 32) | ((b + 31) & 31)) << 2;      // the lane of column pair b - 1 in this group
             const int own = ar * 32 + b, from01 = ar * 32 + ((b + 31) & 31), from10 = ((ar + 31) & 31) * 32 + b;
-            for (int t = 0; t < 32; ++t) {
-                const int p = t & 1;
+            // (two steps per trip: with the parity a constant every LDS address of a step is a loop invariant plus an
+            // immediate offset)
+            auto step_of_parity = [&](const int p) {
                 const float2 ra = rotc[p][ar], rb = rotc[p][b];
                 const float y00 = ra.x * x00 - ra.y * x10, y01 = ra.x * x01 - ra.y * x11;
                 const float y10 = ra.y * x00 + ra.x * x10, y11 = ra.y * x01 + ra.x * x11;
@@ -537,6 +538,10 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
                 __syncthreads();
                 x01 = ex[from01];
                 x10 = ex[1024 + from10];
+            };
+            for (int t = 0; t < 32; t += 2) {
+                step_of_parity(0);
+                step_of_parity(1);
             }
             // 32 steps: every index is back in its slot
             A0[(2 * ar) * ELD + b] = x00;     A0[(2 * ar) * ELD + 32 + b] = x01;
