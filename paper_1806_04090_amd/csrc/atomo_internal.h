@@ -60,8 +60,8 @@ struct atomo_ctx {
     int hint_next = 0;
     uint64_t hint_seq = 0;
     size_t rowgram_lds = 0;        // dynamic LDS that svd_rowgram has been allowed on this context's device
-    hipStream_t side = nullptr;
-    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    hipStream_t side = nullptr, side2 = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr, ev_join2 = nullptr;
     // optional event bracketing of kernel launches (atomo_profile_*)
     bool profiling = false;
     std::vector<hipEvent_t> ev_pool;     // pairs: [2k] start, [2k+1] stop
@@ -83,7 +83,7 @@ namespace atomo {
 // Grows the workspace to at least `bytes` (contents are not preserved).
 int ensure_workspace(atomo_ctx* ctx, size_t bytes);
 
-// Creates ctx->side and the fork/join events if they do not exist yet.
+// Creates ctx->side, ctx->side2 and the fork/join events if they do not exist yet.
 int ensure_side_streams(atomo_ctx* ctx);
 
 // Copies `bytes` of host data to device address `dst` on `stream` through a pinned staging slot,

@@ -31,7 +31,8 @@ int ensure_workspace(atomo_ctx* ctx, size_t bytes)
 int ensure_side_streams(atomo_ctx* ctx)
 {
     if (!ctx->side) ATOMO_HIP(ctx, hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking));
-    hipEvent_t* events[] = {&ctx->ev_fork, &ctx->ev_join};
+    if (!ctx->side2) ATOMO_HIP(ctx, hipStreamCreateWithFlags(&ctx->side2, hipStreamNonBlocking));
+    hipEvent_t* events[] = {&ctx->ev_fork, &ctx->ev_join, &ctx->ev_join2};
     for (hipEvent_t* e : events)
         if (!*e) ATOMO_HIP(ctx, hipEventCreateWithFlags(e, hipEventDisableTiming));
     return ATOMO_OK;
@@ -137,9 +138,10 @@ int atomo_destroy(atomo_ctx* ctx)
         if (h.host) (void)hipHostFree(h.host);
     }
     for (hipEvent_t e : ctx->ev_pool) (void)hipEventDestroy(e);
-    for (hipEvent_t e : {ctx->ev_fork, ctx->ev_join})
+    for (hipEvent_t e : {ctx->ev_fork, ctx->ev_join, ctx->ev_join2})
         if (e) (void)hipEventDestroy(e);
     if (ctx->side) (void)hipStreamDestroy(ctx->side);
+    if (ctx->side2) (void)hipStreamDestroy(ctx->side2);
     if (ctx->ws) (void)hipFree(ctx->ws);
     if (ctx->ew_state) (void)hipFree(ctx->ew_state);
     if (ctx->d_report) (void)hipFree(ctx->d_report);

@@ -879,7 +879,10 @@ __global__ __launch_bounds__(256) void svd_hint(const SvdMat* mats, int n_mats, 
 
 struct Plan {
     std::vector<SvdMat> mats;
-    std::vector<Work> prep, rowgram, fullgram, tiles, apply, eig_gs, eig_ds, twosided, strips, norms, pack;
+    std::vector<Work> prep, fullgram, tiles, apply, eig_gs, twosided, strips, norms, pack;
+    // the data-space matrices in two groups that iterate side by side: [0] those of DS_VERIFY_MIN_R ticks per sweep
+    // and more, [1] the smaller ones (few pairs, many rounds that rotate all index pairs, done after few ticks)
+    std::vector<Work> rowgram[2], eig_ds[2];
     std::vector<Work> ds_full, ds_tiles;           // data-space matrices that check their whole Gram matrix (DS_VERIFY)
     std::vector<int> ds_periods;                   // their distinct R
     std::vector<Work> thin_chunks, thin_list;      // thin matrices: (matrix, chunk of positions); (matrix)
@@ -887,15 +890,16 @@ struct Plan {
     std::vector<Work> gs_list;                     // the Gram-space matrices
     std::vector<int> gs_periods;     // distinct R of the Gram-space matrices
     int max_R = 1;
-    int max_R_ds = 1;                // largest R among the data-space matrices
-    size_t rowgram_lds = 0;          // LDS bytes of a svd_rowgram workgroup: all rows of the tallest data-space matrix
+    int max_R_ds[2] = {1, 1};        // largest R in each group of data-space matrices
+    size_t rowgram_lds[2] = {0, 0};  // LDS bytes of a svd_rowgram workgroup: all rows of the group's tallest matrix
     bool own_update = false;         // the two-sided update runs as launches of its own (see SPLIT_TWO_SIDED)
     size_t bytes = 0;
     SvdMat* d_mats = nullptr;        // device copies of `mats` and of the concatenated work lists
     Work* d_work = nullptr;
     size_t n_work() const
     {
-        return prep.size() + rowgram.size() + fullgram.size() + tiles.size() + apply.size() + eig_gs.size() + eig_ds.size() +
+        return prep.size() + rowgram[0].size() + rowgram[1].size() + fullgram.size() + tiles.size() + apply.size() +
+               eig_gs.size() + eig_ds[0].size() + eig_ds[1].size() +
                twosided.size() + strips.size() + ds_full.size() + ds_tiles.size() + norms.size() + pack.size() + 2 * thin_chunks.size() + thin_list.size() +
                gs_list.size();
     }
@@ -1009,11 +1013,12 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
         m.src_inv = carve.take<float>(m.capacity);
         m.src_fold = carve.take<float>(m.capacity);
         if (m.R > plan.max_R) plan.max_R = m.R;
-        if (!m.gs && m.R > plan.max_R_ds) plan.max_R_ds = m.R;
+        const int grp = m.R >= DS_VERIFY_MIN_R ? 0 : 1;           // (data-space matrices)
+        if (!m.gs && m.R > plan.max_R_ds[grp]) plan.max_R_ds[grp] = m.R;
         for (int b = 0; b < m.nb2; ++b)
             for (int c = 0; c < (m.ldw + 255) / 256; ++c) plan.prep.push_back(Work{j, b, c, 0});
         for (int k = 0; k < m.npairs; ++k) {
-            (m.gs ? plan.eig_gs : plan.eig_ds).push_back(Work{j, k, 0, 0});
+            (m.gs ? plan.eig_gs : plan.eig_ds[grp]).push_back(Work{j, k, 0, 0});
             if (m.gs) {
                 for (int k2 = 0; k2 < m.npairs; ++k2) plan.twosided.push_back(Work{j, k, k2, 1});
                 for (int c = 0; c < m.rows_alloc / PR; ++c) plan.twosided.push_back(Work{j, k, c, 2});
@@ -1024,9 +1029,9 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
             }
         }
         if (!m.gs) {
-            for (int c = 0; c < m.nchp; ++c) plan.rowgram.push_back(Work{j, c * run, std::min(run, chunks_a - c * run), c});
-            for (int c = chunks_a; c < m.ldw / 64; ++c) plan.rowgram.push_back(Work{j, c, 1, -1});   // the chunks of T
-            plan.rowgram_lds = std::max(plan.rowgram_lds, (size_t)m.rows_alloc * XLD * sizeof(float));
+            for (int c = 0; c < m.nchp; ++c) plan.rowgram[grp].push_back(Work{j, c * run, std::min(run, chunks_a - c * run), c});
+            for (int c = chunks_a; c < m.ldw / 64; ++c) plan.rowgram[grp].push_back(Work{j, c, 1, -1});   // the chunks of T
+            plan.rowgram_lds[grp] = std::max(plan.rowgram_lds[grp], (size_t)m.rows_alloc * XLD * sizeof(float));
         }
         if (m.gs) {
             plan.gs_list.push_back(Work{j, 0, 0, 0});
@@ -1056,9 +1061,10 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
     }
     deal_to_dies(plan.strips);                                   // a matrix's strips, which share its rotations, on one die
     // the work items of the tallest matrices first: they set the duration of the launch
-    std::stable_sort(plan.rowgram.begin(), plan.rowgram.end(), [&](const Work& a, const Work& b) {
-        return plan.mats[a.mat].rows_alloc * (a.c >= 0 ? 2 : 1) > plan.mats[b.mat].rows_alloc * (b.c >= 0 ? 2 : 1);
-    });
+    for (auto& list : plan.rowgram)
+        std::stable_sort(list.begin(), list.end(), [&](const Work& a, const Work& b) {
+            return plan.mats[a.mat].rows_alloc * (a.c >= 0 ? 2 : 1) > plan.mats[b.mat].rows_alloc * (b.c >= 0 ? 2 : 1);
+        });
     plan.d_work = carve.take<Work>(plan.n_work());
     plan.bytes = carve.off;
 }
@@ -1161,12 +1167,12 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
         return at;
     };
     const Work* w_prep = place(plan.prep);
-    const Work* w_rowgram = place(plan.rowgram);
+    const Work* w_rowgram[2] = {place(plan.rowgram[0]), place(plan.rowgram[1])};
     const Work* w_fullgram = place(plan.fullgram);
     const Work* w_tiles = place(plan.tiles);
     const Work* w_apply = place(plan.apply);
     const Work* w_eig_gs = place(plan.eig_gs);
-    const Work* w_eig_ds = place(plan.eig_ds);
+    const Work* w_eig_ds[2] = {place(plan.eig_ds[0]), place(plan.eig_ds[1])};
     const Work* w_twosided = place(plan.twosided);
     const Work* w_strips = place(plan.strips);
     const Work* w_ds_full = place(plan.ds_full);
@@ -1195,24 +1201,28 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
             svd_norms<<<grid(plan.norms), 256, 0, stream>>>(d_mats, w_norms, 1);
         }
     }
-    // The data-space matrices iterate on a stream of their own from here to the end (one fork, one join).
+    // The data-space matrices iterate on streams of their own from here to the end, the large ones on one, the small
+    // ones on another (one fork, one join each): a tick lasts as long as its slowest pair problem, and the small
+    // matrices have far more rounds that rotate all index pairs (every third, or every single one) than the large.
     // The Gram-space matrices iterate on the caller's stream, one launch per tick: svd_eig of tick t, which
     // carries the two-sided update of tick t-1 as extra workgroups.  That works because C alternates between
     // two buffers: the update of tick t-1 reads the C of parity t-1 and writes parity t, while svd_eig of tick
     // t forms its own 64x64 block from the C of parity t-1 and the rotations of tick t-1, which are
     // double-buffered by tick parity as well.
-    // Thin matrices share that stream when there are Gram-space matrices to overlap with.
-    const bool have_ds = !plan.rowgram.empty(), have_gs = !plan.twosided.empty(), have_thin = !plan.thin_list.empty();
-    const bool use_side = have_ds || (have_thin && have_gs);
+    // Thin matrices go in front of the small ones when there are Gram-space matrices to overlap with.
+    const bool have_ds[2] = {!plan.rowgram[0].empty(), !plan.rowgram[1].empty()};
+    const bool have_gs = !plan.twosided.empty(), have_thin = !plan.thin_list.empty();
+    const bool use_side[2] = {have_ds[0], have_ds[1] || (have_thin && have_gs)};
     const int n_two = (int)plan.twosided.size();
-    if (use_side) {
+    if (use_side[0] || use_side[1]) {
         rc = ensure_side_streams(ctx);
         if (rc != ATOMO_OK) return rc;
         ATOMO_HIP(ctx, hipEventRecord(ctx->ev_fork, stream));
-        ATOMO_HIP(ctx, hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0));
+        if (use_side[0]) ATOMO_HIP(ctx, hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0));
+        if (use_side[1]) ATOMO_HIP(ctx, hipStreamWaitEvent(ctx->side2, ctx->ev_fork, 0));
     }
     if (have_thin) {
-        hipStream_t s_thin = have_gs ? ctx->side : stream;
+        hipStream_t s_thin = have_gs ? ctx->side2 : stream;
         // a pass over the data does the work of many sweeps of the blocked iteration: one rotating pass per eight
         // sweeps of the limit, and the pass that confirms (no input tried, however graded or rank-deficient, has
         // needed more than two rotating passes)
@@ -1224,42 +1234,44 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
             launch_thin_pass(d_mats, w_thin_chunks, (int)plan.thin_chunks.size(), w_thin_list, (int)plan.thin_list.size(),
                              pass, passes - 1, stop_cosine, ctx->d_flags, s_thin);
     }
-    if (have_ds) {
-        hipStream_t s_ds = ctx->side;
-        const int ds_ticks = limit_ds * plan.max_R_ds;
-        // at a sweep boundary: the whole-Gram-matrix check of the matrices whose sweep asked for it (DS_VERIFY)
+    if (have_ds[0] || have_ds[1]) {
+        hipStream_t s_ds[2] = {ctx->side, ctx->side2};
+        const int ds_ticks[2] = {have_ds[0] ? limit_ds * plan.max_R_ds[0] : 0, have_ds[1] ? limit_ds * plan.max_R_ds[1] : 0};
+        // at a sweep boundary: the whole-Gram-matrix check of the matrices whose sweep asked for it (DS_VERIFY; they
+        // are all in the first group)
         auto verify = [&](int tick) {
             bool boundary = false;
             for (int period : plan.ds_periods) boundary = boundary || (tick % period == 0 && tick <= limit_ds * period);
             if (!boundary) return;
-            ProfScope ps(ctx, ATOMO_K_SVD_REFRESH, s_ds);
-            svd_fullgram<<<grid(plan.ds_full), 256, 0, s_ds>>>(d_mats, w_ds_full);
-            svd_ds_verify<<<grid(plan.ds_tiles), 256, 0, s_ds>>>(d_mats, w_ds_tiles, tick, limit_ds, stop_cosine, ctx->d_flags);
+            ProfScope ps(ctx, ATOMO_K_SVD_REFRESH, s_ds[0]);
+            svd_fullgram<<<grid(plan.ds_full), 256, 0, s_ds[0]>>>(d_mats, w_ds_full);
+            svd_ds_verify<<<grid(plan.ds_tiles), 256, 0, s_ds[0]>>>(d_mats, w_ds_tiles, tick, limit_ds, stop_cosine, ctx->d_flags);
         };
         // more LDS than a launch gets by default: raised once per context
-        if (plan.rowgram_lds > ctx->rowgram_lds) {
+        if (std::max(plan.rowgram_lds[0], plan.rowgram_lds[1]) > ctx->rowgram_lds) {
             ATOMO_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(svd_rowgram),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)ROWGRAM_LDS_MAX));
             ctx->rowgram_lds = ROWGRAM_LDS_MAX;
         }
-        {
-            ProfScope ps(ctx, ATOMO_K_SVD_GRAM, s_ds);
-            svd_rowgram<<<grid(plan.rowgram), 256, plan.rowgram_lds, s_ds>>>(d_mats, w_rowgram, -1, limit_ds);
-        }
-        for (int tick = 0; tick < ds_ticks; ++tick) {
-            {
-                ProfScope ps(ctx, ATOMO_K_SVD_EIG, s_ds);
-                launch_svd_eig(d_mats, w_eig_ds, (int)plan.eig_ds.size(), nullptr, 0, nullptr, 0, 0, tick, limit_ds,
-                               stop_cosine, max_inner, inner_reduction, full_period, 0, ctx->d_flags, s_ds);
+        // (the two groups' launches are enqueued alternately, so that both streams have work from the start)
+        for (int tick = -1; tick < std::max(ds_ticks[0], ds_ticks[1]); ++tick)
+            for (int g = 0; g < 2; ++g) {
+                if (!have_ds[g] || tick >= ds_ticks[g]) continue;
+                if (tick >= 0) {
+                    ProfScope ps(ctx, ATOMO_K_SVD_EIG, s_ds[g]);
+                    launch_svd_eig(d_mats, w_eig_ds[g], (int)plan.eig_ds[g].size(), nullptr, 0, nullptr, 0, 0, tick, limit_ds,
+                                   stop_cosine, max_inner, inner_reduction, full_period, 0, ctx->d_flags, s_ds[g]);
+                }
+                {
+                    // tick -1: the Gram matrices of the first tick's pairs
+                    ProfScope ps(ctx, tick < 0 ? ATOMO_K_SVD_GRAM : ATOMO_K_SVD_UPDATE, s_ds[g]);
+                    svd_rowgram<<<grid(plan.rowgram[g]), 256, plan.rowgram_lds[g], s_ds[g]>>>(d_mats, w_rowgram[g], tick, limit_ds);
+                }
+                if (g == 0 && tick >= 0) verify(tick + 1);
             }
-            {
-                ProfScope ps(ctx, ATOMO_K_SVD_UPDATE, s_ds);
-                svd_rowgram<<<grid(plan.rowgram), 256, plan.rowgram_lds, s_ds>>>(d_mats, w_rowgram, tick, limit_ds);
-            }
-            verify(tick + 1);
-        }
     }
-    if (use_side) ATOMO_HIP(ctx, hipEventRecord(ctx->ev_join, ctx->side));
+    if (use_side[0]) ATOMO_HIP(ctx, hipEventRecord(ctx->ev_join, ctx->side));
+    if (use_side[1]) ATOMO_HIP(ctx, hipEventRecord(ctx->ev_join2, ctx->side2));
     if (have_gs) {
         const int n_ticks = limit_gs * plan.max_R + 1;
         // Few matrices: the two-sided update of the previous tick rides in the launch of the pair problems (one launch
@@ -1309,7 +1321,8 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
             else svd_twosided<<<(unsigned)n_two, 256, 0, stream>>>(d_mats, w_twosided, n_two, n_ticks - 1);
         }
     }
-    if (use_side) ATOMO_HIP(ctx, hipStreamWaitEvent(stream, ctx->ev_join, 0));
+    if (use_side[0]) ATOMO_HIP(ctx, hipStreamWaitEvent(stream, ctx->ev_join, 0));
+    if (use_side[1]) ATOMO_HIP(ctx, hipStreamWaitEvent(stream, ctx->ev_join2, 0));
     {
         ProfScope ps(ctx, ATOMO_K_SVD_FINALIZE, stream);
         if (!plan.norms.empty()) svd_norms<<<grid(plan.norms), 256, 0, stream>>>(d_mats, w_norms, 0);
