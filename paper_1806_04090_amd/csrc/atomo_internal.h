@@ -122,10 +122,12 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 struct Carver {
     char* base;
     size_t off = 0;
+    size_t last = 0;                     // offset of what the last take returned
     explicit Carver(void* b) : base((char*)b) {}
     template <typename T>
     T* take(size_t count) {
         off = align_up(off, 256);
+        last = off;
         T* p = base ? (T*)(base + off) : nullptr;
         off += count * sizeof(T);
         return p;

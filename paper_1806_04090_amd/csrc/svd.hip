@@ -85,6 +85,13 @@ __global__ __launch_bounds__(64) void svd_first_pairs(const SvdMat* mats, const 
         m.sched[(size_t)e * 2 + 1] = bj;
         m.where[(size_t)t * m.nb2 + bi] = 2 * k;
         m.where[(size_t)t * m.nb2 + bj] = 2 * k + 1;
+        // where the two blocks sat in the round before (tick 0 has none: its pair problems read C as it is)
+        const int before = (t + m.R - 1) % m.R;
+        const int ki = pair_of_block(m.nb2, before, bi), kj = pair_of_block(m.nb2, before, bj);
+        int xi0, xi1, xj0, xj1;
+        pair_blocks(m.nb2, before, ki, xi0, xi1);
+        pair_blocks(m.nb2, before, kj, xj0, xj1);
+        write_pair_desc(m, t, k, bi, bj, 2 * ki + (bi == xi1), xi0, xi1, 2 * kj + (bj == xj1), xj0, xj1);
     }
 }
 
@@ -1002,10 +1009,13 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
         m.Q = carve.take<float>((size_t)(m.gs ? 2 : 1) * m.npairs * QSZ);
         m.idle = m.gs ? nullptr : carve.take<int>(m.npairs);
         m.state = carve.take<int>(ST_WORDS);
+        const size_t state_off = carve.last;
         m.sig_raw = carve.take<float>(m.rows_alloc);
         m.cref = m.gs ? carve.take<float>(m.rows_alloc) : nullptr;
         m.cref0 = m.gs ? carve.take<float>(m.rows_alloc) : nullptr;
         m.sched = m.gs ? carve.take<int>((size_t)3 * m.npairs * 2) : nullptr;
+        m.pdesc = m.gs ? carve.take<int>((size_t)m.npairs * 3 * PD_WORDS) : nullptr;
+        const size_t pdesc_off = carve.last;
         m.where = m.gs ? carve.take<int>((size_t)3 * m.nb2) : nullptr;
         m.bw = m.gs ? carve.take<float>((size_t)2 * m.nb2 * m.nb2) : nullptr;
         m.dd = m.gs ? carve.take<float>((size_t)2 * m.rows_alloc) : nullptr;
@@ -1018,7 +1028,12 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
         for (int b = 0; b < m.nb2; ++b)
             for (int c = 0; c < (m.ldw + 255) / 256; ++c) plan.prep.push_back(Work{j, b, c, 0});
         for (int k = 0; k < m.npairs; ++k) {
-            (m.gs ? plan.eig_gs : plan.eig_ds[grp]).push_back(Work{j, k, 0, 0});
+            // (offsets from the matrices' descriptors, which are the first thing in the workspace)
+            if (m.gs)
+                plan.eig_gs.push_back(Work{j, k, (int)(unsigned)(state_off / HOT_UNIT),
+                                           (int)(unsigned)((pdesc_off + (size_t)k * 3 * PD_WORDS * sizeof(int)) / HOT_UNIT)});
+            else
+                plan.eig_ds[grp].push_back(Work{j, k, 0, 0});
             if (m.gs) {
                 for (int k2 = 0; k2 < m.npairs; ++k2) plan.twosided.push_back(Work{j, k, k2, 1});
                 for (int c = 0; c < m.rows_alloc / PR; ++c) plan.twosided.push_back(Work{j, k, c, 2});
@@ -1150,6 +1165,7 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     Plan sizing;
     const uint64_t* stream_ids = opt ? opt->stream_ids : nullptr;
     build_plan(mats, n_mats, msgs, sigma_out, p_out, stream_base, stream_ids, nullptr, sizing);
+    if (sizing.bytes >= (HOT_UNIT << 32)) return ATOMO_EINVAL;   // (the work items address the workspace in 32 bits of 16-byte units)
     int rc = ensure_workspace(ctx, sizing.bytes);
     if (rc != ATOMO_OK) return rc;
 

@@ -133,6 +133,7 @@ struct SvdMat {
     const float* X;          // the data before the first rotation, position-major with row stride r: G itself, or its copy in B
     // Gram-space matrices: the pairing of the ticks, tables indexed by tick mod 3
     int* sched;              // [3][npairs][2]: the two blocks (smaller first) of every pair
+    int* pdesc;              // [npairs][3][PD_WORDS]: what a pair problem needs to know about its pair, see PD_*
     int* where;              // [3][nb2]: 2 x pair + half for every block
     float* bw;               // [2][nb2][nb2]: weight of every off-diagonal block, by parity of the tick count of its C
     float* dd;               // [2][rows_alloc]: the scale of every row for the block weights, by tick parity: cref0
@@ -140,6 +141,16 @@ struct SvdMat {
 };
 
 struct Work { int mat, a, b, c; };
+
+// Gram space, per pair and tick (mod 3), written with the pairing by whoever plans the tick: the pair's blocks, and
+// for each of the two where it sat in the tick before: the pair it was in (PD_K*), which half of that pair (PD_S*)
+// and that pair's two blocks (PD_X*, PD_Y*).  One read instead of three dependent ones at the head of a pair problem.
+enum { PD_BI = 0, PD_BJ, PD_K1, PD_S1, PD_X0, PD_X1, PD_K2, PD_S2, PD_Y0, PD_Y1, PD_WORDS = 12 };
+
+// The work item of a Gram-space pair problem carries where the matrix's state words and the pair's descriptors are,
+// as offsets from the descriptor table of the matrices in units of 16 bytes (b and c; 0 for data-space matrices), so
+// that they are read beside the matrix's descriptor, not after it.
+constexpr size_t HOT_UNIT = 16;
 
 // Index of the pair that holds block x in `round` (inverse of pair_blocks).
 __device__ inline int pair_of_block(int nb2, int round, int x)
@@ -170,6 +181,17 @@ __device__ inline void tick_pair(const SvdMat& m, int tick, int k, int& bi, int&
     } else {
         pair_blocks(m.nb2, tick % m.R, k, bi, bj);
     }
+}
+
+// Writes the descriptor of pair k = (bi, bj) of tick t; (w, x0, x1) for each block: its entry of the `where` table of
+// tick t - 1 and the two blocks of the pair it names.
+__device__ inline void write_pair_desc(const SvdMat& m, int t, int k, int bi, int bj, int wi, int xi0, int xi1, int wj,
+                                       int xj0, int xj1)
+{
+    int* d = m.pdesc + ((size_t)k * 3 + t % 3) * PD_WORDS;
+    d[PD_BI] = bi;      d[PD_BJ] = bj;
+    d[PD_K1] = wi >> 1; d[PD_S1] = wi & 1; d[PD_X0] = xi0; d[PD_X1] = xi1;
+    d[PD_K2] = wj >> 1; d[PD_S2] = wj & 1; d[PD_Y0] = xj0; d[PD_Y1] = xj1;
 }
 
 // exponent e such that absmax * 2^-e lies in [1, 2); 0 for an all-zero matrix

@@ -128,12 +128,21 @@ __device__ inline void plan_next_tick(const SvdMat& m, int tick, int cyclic, flo
     const bool weighted = !cyclic && tick >= 2 && (tick + 1) / m.R < GS_DYNAMIC_SWEEPS &&
                           !(cyclic_from != 0 && tick + 1 >= cyclic_from) &&
                           m.state[ST_WSTAMP + ((tick - 1) & 1)] == tick;
+    // the tables of this tick, for the descriptors of the next tick's pairs
+    const int* sch_now = m.sched + (size_t)(tick % 3) * np * 2;
+    const int* whr_now = m.where + (size_t)(tick % 3) * nb;
+    auto describe = [&](int k, int bi, int bj) {
+        const int wi = whr_now[bi], wj = whr_now[bj];
+        write_pair_desc(m, tick + 1, k, bi, bj, wi, sch_now[2 * (wi >> 1)], sch_now[2 * (wi >> 1) + 1], wj,
+                        sch_now[2 * (wj >> 1)], sch_now[2 * (wj >> 1) + 1]);
+    };
     if (!weighted) {
         for (int k = tid; k < np; k += NT) {
             int bi, bj;
             pair_blocks(nb, (tick + 1) % m.R, k, bi, bj);
             sch[2 * k] = bi; sch[2 * k + 1] = bj;
             whr[bi] = 2 * k; whr[bj] = 2 * k + 1;
+            describe(k, bi, bj);
         }
         return;
     }
@@ -206,6 +215,7 @@ __device__ inline void plan_next_tick(const SvdMat& m, int tick, int cyclic, flo
         const int k = __popcll(leaders & ((1ull << lane) - 1ull));
         sch[2 * k] = lane; sch[2 * k + 1] = mate;
         whr[lane] = 2 * k; whr[mate] = 2 * k + 1;
+        describe(k, lane, mate);
     }
 }
 
@@ -242,18 +252,38 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
         return;
     }
     const Work wk = work[blockIdx.x];
+    // Gram space: the state words and the pair's descriptor are read beside the matrix's descriptor (the work item
+    // says where they are), all before the first of them is looked at: one trip to memory instead of a chain of them.
+    int st_fresh = 0;
+    int pdw[PD_Y1 + 1];
+#pragma unroll
+    for (int i = 0; i <= PD_Y1; ++i) pdw[i] = 0;
+    int st_done = 0, st_mode = 0;
+    if (wk.c) {
+        const int* hot = (const int*)((const char*)mats + (size_t)(unsigned)wk.b * HOT_UNIT);
+        const int* pd = (const int*)((const char*)mats + (size_t)(unsigned)wk.c * HOT_UNIT) + (step % 3) * PD_WORDS;
+        st_done = hot[ST_DONE_AT]; st_mode = hot[ST_MODE]; st_fresh = hot[ST_FRESH_AT];
+#pragma unroll
+        for (int i = 0; i <= PD_Y1; ++i) pdw[i] = pd[i];
+    }
     const SvdMat m = mats[wk.mat];
     if (m.gs) {
-        if (m.state[ST_DONE_AT] != 0 || m.state[ST_MODE] != MODE_SWEEPS) return;
+        // (the same for every lane: as scalars)
+        st_done = __builtin_amdgcn_readfirstlane(st_done);
+        st_mode = __builtin_amdgcn_readfirstlane(st_mode);
+        st_fresh = __builtin_amdgcn_readfirstlane(st_fresh);
+#pragma unroll
+        for (int i = 0; i <= PD_Y1; ++i) pdw[i] = __builtin_amdgcn_readfirstlane(pdw[i]);
+        if (st_done != 0 || st_mode != MODE_SWEEPS) return;
         // a tick with a refresh has two launches: before it, the matrices that sweep on; after it, those
         // whose Gram matrix the refresh has just formed
-        if ((m.state[ST_FRESH_AT] == step + 1) != (fresh_only != 0)) return;
+        if ((st_fresh == step + 1) != (fresh_only != 0)) return;
     } else if (skip_step(m, step, max_sweeps)) {
         return;
     }
     const int round = step % m.R;
-    int bi, bj;
-    tick_pair(m, step, wk.a, bi, bj);
+    int bi = pdw[PD_BI], bj = pdw[PD_BJ];
+    if (!m.gs) pair_blocks(m.nb2, round, wk.a, bi, bj);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const bool cross = round % full_period != 0;
 
@@ -266,7 +296,7 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
     //    three 32x32 blocks, each two chained MFMA products (32x64x64, then 32x32x64); ba mirrors ab.
     //    Gram-space matrices of a call whose updates run as launches of their own (one C buffer, m.CT2 == m.CT):
     //    C is up to date, the pair's block as it is.
-    const bool fresh = m.gs && (m.state[ST_FRESH_AT] == step + 1 || m.CT2 == m.CT);
+    const bool fresh = m.gs && (st_fresh == step + 1 || m.CT2 == m.CT);
     if (m.gs && tid == 0) m.state[(step & 1) ? ST_QTICK_ODD : ST_QTICK] = step + 1;
     for (int e = tid; e < QSZ; e += NT) {
         const int i = e >> 6, j = e & 63;
@@ -303,14 +333,10 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
             As[0][home_slot(i, cross) * ELD + mem_col(home_slot(j, cross))] = C[(size_t)gi * m.ldc + gj];
         }
     } else {
-        const int prev = step - 1, pp = (step - 1) & 1;
+        const int pp = (step - 1) & 1;
         const float* C = c_of_parity(m, pp);
-        const int* was = m.where + (size_t)(prev % 3) * m.nb2;
-        const int k1 = was[bi] >> 1, k2 = was[bj] >> 1;
-        const int s1 = was[bi] & 1, s2 = was[bj] & 1;
-        int x0, x1, y0, y1;
-        tick_pair(m, prev, k1, x0, x1);
-        tick_pair(m, prev, k2, y0, y1);
+        const int k1 = pdw[PD_K1], k2 = pdw[PD_K2], s1 = pdw[PD_S1], s2 = pdw[PD_S2];
+        const int x0 = pdw[PD_X0], x1 = pdw[PD_X1], y0 = pdw[PD_Y0], y1 = pdw[PD_Y1];
         const float* Q1 = m.Q + ((size_t)pp * m.npairs + k1) * QSZ;
         const float* Q2 = m.Q + ((size_t)pp * m.npairs + k2) * QSZ;
         const int h = lane >> 5, l32 = lane & 31;
