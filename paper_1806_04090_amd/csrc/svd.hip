@@ -1007,6 +1007,7 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
         m.gram = m.gs ? nullptr : carve.take<float>((size_t)m.npairs * m.nchp * QSZ);
         m.gramf = m.gs || ds_verify ? carve.take<float>((size_t)m.ntiles * m.nchg * QSZ) : nullptr;
         m.Q = carve.take<float>((size_t)(m.gs ? 2 : 1) * m.npairs * QSZ);
+        m.QT = m.gs ? carve.take<float>((size_t)2 * m.npairs * QSZ) : nullptr;
         m.idle = m.gs ? nullptr : carve.take<int>(m.npairs);
         m.state = carve.take<int>(ST_WORDS);
         const size_t state_off = carve.last;

@@ -104,6 +104,7 @@ struct SvdMat {
     float* gramf;            // [ntiles][nchg][64*64]: partial tiles of the Gram matrix of all rows (Gram space: the refresh;
                              //   data space: the check of DS_VERIFY, null for matrices too small for it)
     float* Q;                // [npairs][64*64]; Gram space: [2][npairs][64*64], indexed by tick parity
+    float* QT;               // Gram space: the same matrices transposed (else null)
     int* state;              // [ST_WORDS]
     float* sig_raw;          // [rows_alloc]
     float* cref;             // Gram space: [rows_alloc] reference squared norm of every row, see GS_RELIABLE

@@ -337,17 +337,22 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
         const float* C = c_of_parity(m, pp);
         const int k1 = pdw[PD_K1], k2 = pdw[PD_K2], s1 = pdw[PD_S1], s2 = pdw[PD_S2];
         const int x0 = pdw[PD_X0], x1 = pdw[PD_X1], y0 = pdw[PD_Y0], y1 = pdw[PD_Y1];
-        const float* Q1 = m.Q + ((size_t)pp * m.npairs + k1) * QSZ;
-        const float* Q2 = m.Q + ((size_t)pp * m.npairs + k2) * QSZ;
+        // Every operand is read along its contraction index, 16 bytes at a time: the rotations from their transposed
+        // copies (m.QT), the tile of C through its mirror image (C is symmetric up to the rounding of its updates, which
+        // step 2 evens out anyway).  Instruction s of a product contracts the indices s (lanes 0..31) and 32 + s
+        // (lanes 32..63).
+        const float* Q1 = m.QT + ((size_t)pp * m.npairs + k1) * QSZ;
+        const float* Q2 = m.QT + ((size_t)pp * m.npairs + k2) * QSZ;
         const int h = lane >> 5, l32 = lane & 31;
         float* P = As[1];                                        // three 32 x 64 intermediates, row stride ELD
         float* P2 = Qs[1];
-        float qb[PR / 2];                                        // operand of the second product, loaded up front
+        floatx4 qb[PR / 8];                                      // operand of the second product, loaded up front
         if (wave < 3) {
             const float* QR = wave == 0 ? Q1 : Q2;
             const int sR = wave == 0 ? s1 : s2;
+            const float* qrp = QR + (sR * BS + l32) * PR + BS * h;
 #pragma unroll
-            for (int s = 0; s < PR / 2; ++s) qb[s] = QR[(2 * s + h) * PR + sR * BS + l32];
+            for (int u = 0; u < PR / 8; ++u) qb[u] = *(const floatx4*)(qrp + 4 * u);
         }
         // product 1: waves 0..5 = (block sb, column half): Qs^T (32 x 64) * C tile (64 x 32 of its 64 columns)
         if (wave < 6) {
@@ -357,24 +362,22 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
             const int r0 = sb == 2 ? y0 : x0, r1 = sb == 2 ? y1 : x1;       // row blocks of the tile
             const int c0 = sb == 0 ? x0 : y0, c1 = sb == 0 ? x1 : y1;       // column blocks of the tile
             const int col = (half == 0 ? c0 : c1) * BS + l32;
-            float qa[PR / 2], cb[PR / 2];
-            // row k = 2 s + h of the tile: block r0 for s < 16, block r1 above; constant strides per half
-            const float* qlp = QL + h * PR + sL * BS + l32;
-            const float* c_lo = C + (size_t)(r0 * BS + h) * m.ldc + col;
-            const float* c_hi = C + (size_t)(r1 * BS + h) * m.ldc + col;
-            const size_t two_rows = 2 * (size_t)m.ldc;
+            floatx4 qa[PR / 8], cb[PR / 8];
+            // rows of the tile: block r0 for the lanes 0..31, block r1 for the lanes above
+            const float* qlp = QL + (sL * BS + l32) * PR + BS * h;
+            const float* clp = C + (size_t)col * m.ldc + (h == 0 ? r0 : r1) * BS;
 #pragma unroll
-            for (int s = 0; s < PR / 4; ++s) {
-                qa[s] = qlp[s * 2 * PR];
-                cb[s] = c_lo[s * two_rows];
-                qa[PR / 4 + s] = qlp[(PR / 4 + s) * 2 * PR];
-                cb[PR / 4 + s] = c_hi[s * two_rows];
+            for (int u = 0; u < PR / 8; ++u) {
+                qa[u] = *(const floatx4*)(qlp + 4 * u);
+                cb[u] = *(const floatx4*)(clp + 4 * u);
             }
             floatx16 acc;
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 #pragma unroll
-            for (int s = 0; s < PR / 2; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(qa[s], cb[s], acc, 0, 0, 0);
+            for (int u = 0; u < PR / 8; ++u)
+#pragma unroll
+                for (int x = 0; x < 4; ++x) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(qa[u][x], cb[u][x], acc, 0, 0, 0);
             float* out = sb == 0 ? P : sb == 1 ? P + BS * ELD : P2;
 #pragma unroll
             for (int v = 0; v < 16; ++v) out[(8 * (v >> 2) + 4 * h + (v & 3)) * ELD + half * BS + l32] = acc[v];
@@ -389,7 +392,7 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
             for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 #pragma unroll
             for (int s = 0; s < PR / 2; ++s)
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(in[l32 * ELD + 2 * s + h], qb[s], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(in[l32 * ELD + BS * h + s], qb[s >> 2][s & 3], acc, 0, 0, 0);
             const int ro = sb == 2 ? BS : 0, co = sb == 0 ? 0 : BS;         // where the block sits in the 64 x 64
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
@@ -701,6 +704,8 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
         const int dj = dest[tj * 16 + lo];
 #pragma unroll
         for (int v = 0; v < 4; ++v) qout[(ti * 16 + 4 * hi + v) * PR + dj] = q4[v];
+        // Gram space: and transposed, for the pair problems of the next tick (step 1)
+        if (m.gs) *(floatx4*)(m.QT + ((size_t)(step & 1) * m.npairs + wk.a) * QSZ + dj * PR + ti * 16 + 4 * hi) = q4;
     }
 
     if (tid == 0) {
