@@ -236,6 +236,8 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
     __shared__ float ref0[PR];           //             the same in the scaling of the first refresh (cref0)
     __shared__ int sits_out[PR];         // Gram space: by slot, rows whose diagonal entry is rounding noise
     __shared__ float red[32];
+    __shared__ float rlen[PR];           // by slot: 1 / length of the row as the pair problem starts
+    __shared__ unsigned int entry_bits[2];   // largest cosine and largest squared norm as the pair problem starts
     __shared__ float2 rotc[2][32];       // cross rounds: (c, s) of the 32 rotations of a step, by step parity
     __shared__ float2 rotd[2][32];       //               the diagonal entries (d_p', d_q') those rotations leave behind
 
@@ -409,40 +411,50 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
     const float z2 = ZERO_REL * __int_as_float(m.state[ST_SCALE]);
     if (tid < PR) {
         const int sl = home_slot(tid, cross);
-        const bool out = m.gs && As[0][sl * ELD + mem_col(sl)] < GS_RELIABLE * ref[tid];
+        const float d = As[0][sl * ELD + mem_col(sl)];
+        const bool out = m.gs && d < GS_RELIABLE * ref[tid];
         sits_out[sl] = out;
+        // 1 / length of the row, 0 for a row without one (nothing is measured against it)
+        rlen[sl] = d > 0.0f ? __builtin_amdgcn_rsqf(d) : 0.0f;
         // (rows at the rounding floor of the data are not waiting for anything: they are finished)
         if (out && ref[tid] > z2) atomicMax(&m.state[ST_SAT_OUT], 1);
     }
+    if (tid == PR) { entry_bits[0] = 0u; entry_bits[1] = 0u; }
     __syncthreads();
     float2 entry;
     {
-        float mx = 0.0f, dmax = 0.0f;
-        for (int e = tid; e < QSZ; e += NT) {
-            const int i = e >> 6, j = e & 63;                    // slot of the row, memory column
-            const int js = j < 32 ? 2 * j : 2 * (j - 32) + 1;    // slot of the column
-            if (i < js) {
+        // The 2016 slot pairs i < j, two per thread: row c of the strict upper triangle (63 - c entries) and row
+        // 63 - c (c entries) together make one line of 63.
+        float mx = 0.0f;
+        const float floor_inv = __builtin_amdgcn_rcpf(z2);
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int e = tid + NT * q;
+            if (e < 63 * 32) {
+                const int c = e / 63, pos = e - 63 * c;
+                const int i = pos < 63 - c ? c : 63 - c;
+                const int js = pos < 63 - c ? c + 1 + pos : pos + 1;     // (63 - c) + 1 + (pos - (63 - c))
+                float* upper = &As[0][i * ELD + mem_col(js)];
+                float* lower = &As[0][js * ELD + mem_col(i)];
                 // a row that sits out is cut loose: no rotation touches it, nothing is measured against it
-                const float v = (sits_out[i] | sits_out[js]) ? 0.0f
-                                                             : 0.5f * (As[0][i * ELD + j] + As[0][js * ELD + mem_col(i)]);
-                As[0][i * ELD + j] = v;
-                As[0][js * ELD + mem_col(i)] = v;
-                const float dii = As[0][i * ELD + mem_col(i)], djj = As[0][js * ELD + j];
-                if (dii > 0.0f && djj > 0.0f)
-                    mx = fmaxf(mx, fabsf(v) * __builtin_amdgcn_rcpf(fmaxf(__builtin_amdgcn_sqrtf(dii * djj), z2)));
-            } else if (i == js) {
-                dmax = fmaxf(dmax, As[0][i * ELD + j]);
+                const float v = (sits_out[i] | sits_out[js]) ? 0.0f : 0.5f * (*upper + *lower);
+                *upper = v;
+                *lower = v;
+                mx = fmaxf(mx, fabsf(v) * fminf(rlen[i] * rlen[js], floor_inv));
             }
         }
+        float dmax = tid < PR ? fmaxf(As[0][tid * ELD + mem_col(tid)], 0.0f) : 0.0f;
         for (int o = 32; o > 0; o >>= 1) {
             mx = fmaxf(mx, __shfl_down(mx, o));
             dmax = fmaxf(dmax, __shfl_down(dmax, o));
         }
-        if (lane == 0) { red[wave] = mx; red[16 + wave] = dmax; }
+        // (non-negative floats compare like their bit patterns)
+        if (lane == 0) {
+            atomicMax(&entry_bits[0], __float_as_uint(mx));
+            if (wave == 0) atomicMax(&entry_bits[1], __float_as_uint(dmax));
+        }
         __syncthreads();
-        mx = 0.0f; dmax = 0.0f;
-        for (int w = 0; w < NT / 64; ++w) { mx = fmaxf(mx, red[w]); dmax = fmaxf(dmax, red[16 + w]); }
-        entry = make_float2(mx, dmax);
+        entry = make_float2(__uint_as_float(entry_bits[0]), __uint_as_float(entry_bits[1]));
     }
     if (tid == 0) {
         // (Gram space: the pairs of the last ticks of the sweep are the heaviest of that moment, see GS_WINDOW)
