@@ -14,8 +14,8 @@
 // One Jacobi "tick" visits, for every matrix of the call at once, one round of a round-robin
 // tournament over its row blocks.  A sweep is R = (#blocks - 1) rounds.
 //
-// Small matrices (fewer than 16 row blocks) iterate in data space, on a forked stream of the context;
-// per tick, two launches:
+// Small matrices (fewer than 16 row blocks) iterate in data space, in two groups (eight blocks and more; fewer) on two
+// forked streams of the context; per tick and group, two launches:
 //     svd_eig     : per block pair (64 rows), sums the partial Gram matrices of the pair and diagonalises the
 //                   sum (see svd_eig.hip)
 //     svd_rowgram : per 64-column chunk of W, rows <- Q^T rows for every pair, then the partial Gram matrices
