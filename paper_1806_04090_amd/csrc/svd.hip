@@ -1122,6 +1122,14 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
             sig = (sig ^ (uint64_t)(uint32_t)mats[j].rows) * 1099511628211ull;
             sig = (sig ^ (uint64_t)(uint32_t)mats[j].cols) * 1099511628211ull;
         }
+        // The slot this call will use: with four calls in flight its last user is the oldest of them; wait for that one
+        // first, so that a host that runs four calls ahead of the device still finds a finished call to learn from.
+        hint = &ctx->hints[ctx->hint_next];
+        ctx->hint_next = (ctx->hint_next + 1) % (int)(sizeof(ctx->hints) / sizeof(ctx->hints[0]));
+        if (hint->pending) {
+            ATOMO_HIP(ctx, hipEventSynchronize(hint->done));
+            hint->pending = false;
+        }
         const SweepHint* best = nullptr;
         for (SweepHint& h : ctx->hints) {
             if (h.seq == 0) continue;
@@ -1136,12 +1144,6 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
             const int g = best->host[0], d = best->host[1];
             if (!(g >= best->limit_gs && best->limit_gs < max_sweeps)) limit_gs = std::min(max_sweeps, std::max(1, g + adaptive));
             if (!(d >= best->limit_ds && best->limit_ds < max_sweeps)) limit_ds = std::min(max_sweeps, std::max(1, d + adaptive));
-        }
-        hint = &ctx->hints[ctx->hint_next];
-        ctx->hint_next = (ctx->hint_next + 1) % (int)(sizeof(ctx->hints) / sizeof(ctx->hints[0]));
-        if (hint->pending) {                                     // four calls in flight: wait for the oldest
-            ATOMO_HIP(ctx, hipEventSynchronize(hint->done));
-            hint->pending = false;
         }
         if (!hint->host) {
             ATOMO_HIP(ctx, hipHostMalloc((void**)&hint->host, 4 * sizeof(int32_t), hipHostMallocDefault));
