@@ -147,8 +147,9 @@ typedef struct atomo_svd_options {
     int32_t adaptive;                /* 0 (default): the launches of all max_sweeps sweeps are enqueued.  k > 0:  */
                                      /* for a training loop that encodes the same layer set step after step. The  */
                                      /* context remembers how many sweeps the matrices of earlier calls with the  */
-                                     /* same shapes took (read without waiting: the most recent call that has     */
-                                     /* finished) and enqueues that many + k, at most max_sweeps, separately for  */
+                                     /* same shapes took (the most recent call that has finished; at most four    */
+                                     /* such calls are in flight: a fifth waits for the oldest before it is       */
+                                     /* enqueued) and enqueues that many + k, at most max_sweeps, separately for  */
                                      /* the matrices that iterate on their Gram matrix and for the others; a call */
                                      /* that used up such a reduced limit is followed by one with the full limit. */
                                      /* A matrix that needs more sweeps than were enqueued is reported through    */
