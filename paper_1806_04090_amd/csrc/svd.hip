@@ -670,11 +670,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void s
 }
 
 // ------------------------------------------------------------------------------------------------
-// apply: W[other] <- Tgs * W[cur] for a Gram-space matrix (64 output rows x 256 columns per workgroup)
+// apply: W[other] <- Tgs * W[cur] for a Gram-space matrix.  128 x 128 output tile per workgroup (a wave: 64 x 64, four
+// 32 x 32 accumulators); both operands go through LDS in steps of 32 of the contraction index, double-buffered: the
+// next step's tiles are on their way from memory while the current ones are multiplied.
 // ------------------------------------------------------------------------------------------------
+constexpr int AP_TILE = 128;            // output rows and columns per workgroup
+constexpr int AP_K = 16;                // contraction indices per step
+constexpr int AP_LDA = AP_TILE + 1;     // Tgs tile, stored [k][row]: odd stride, the 16-k segments of a row land in different banks
+constexpr int AP_LDB = AP_TILE + 4;     // W tile, stored [k][column]: 16-byte stores
+
 __global__ __launch_bounds__(256) void svd_apply(const SvdMat* mats, const Work* work)
 {
-    __shared__ float tt[PR][PR + 1];
+    __shared__ float at[2][AP_K * AP_LDA];
+    __shared__ float bt[2][AP_K * AP_LDB];
     const Work wk = work[blockIdx.x];
     const SvdMat m = mats[wk.mat];
     if (!refreshing(m) || m.state[ST_FIRST]) return;
@@ -685,50 +693,77 @@ __global__ __launch_bounds__(256) void svd_apply(const SvdMat* mats, const Work*
     float* dst = cur ? w0 : w1;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int h = lane >> 5, l32 = lane & 31;
-    const int row0 = wk.a * PR;
-    const int c0 = wk.b * KCU + wave * 64;
-    const bool active = c0 < m.ldw;                              // all waves take part in the staging
     const int Rp = m.rows_alloc;
+    const int row0 = wk.a * AP_TILE, c0 = wk.b * AP_TILE;
     const float* T = m.CT + Rp;                                  // Tgs: columns Rp.. of [C | Tgs]
+    const int wr = (wave >> 1) * 64, wc = (wave & 1) * 64;       // the wave's corner of the tile
 
-    floatx16 acc[2][2];
+    // staging: thread -> (row, AP_K / 2 contraction indices) of the Tgs tile and (contraction index, a run of columns) of
+    // the W tile, AP_Q 16-byte pieces each
+    constexpr int AP_Q = AP_K / 8;
+    const int a_row = tid >> 1, a_k = (tid & 1) * (AP_K / 2);
+    const int b_k = tid / (256 / AP_K), b_c = (tid % (256 / AP_K)) * (4 * AP_Q);
+    const bool a_live = row0 + a_row < Rp, b_live = c0 + b_c < m.ldw;       // (rows come in multiples of 64, columns of 16)
+    const float* a_src = T + (size_t)(row0 + a_row) * m.ldc + a_k;
+    const float* b_src = src + (size_t)b_k * m.ldw + c0 + b_c;
+    floatx4 ra[AP_Q], rb[AP_Q];
+    auto fetch = [&](int k0) {
 #pragma unroll
-    for (int e = 0; e < 2; ++e)
+        for (int q = 0; q < AP_Q; ++q) {
+            ra[q] = a_live ? *(const floatx4*)(a_src + k0 + 4 * q) : floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+            rb[q] = b_live ? *(const floatx4*)(b_src + (size_t)k0 * m.ldw + 4 * q) : floatx4{0.0f, 0.0f, 0.0f, 0.0f};
+        }
+    };
+    auto stage = [&](int buf) {
 #pragma unroll
-        for (int ib = 0; ib < 2; ++ib)
+        for (int q = 0; q < AP_Q; ++q) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[e][ib][v] = 0.0f;
+            for (int x = 0; x < 4; ++x) at[buf][(a_k + 4 * q + x) * AP_LDA + a_row] = ra[q][x];
+            *(floatx4*)&bt[buf][b_k * AP_LDB + b_c + 4 * q] = rb[q];
+        }
+    };
 
-    for (int k0 = 0; k0 < Rp; k0 += PR) {
+    floatx16 acc[2][2];                                          // [row block][column block]
+#pragma unroll
+    for (int ib = 0; ib < 2; ++ib)
+#pragma unroll
+        for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[ib][jb][v] = 0.0f;
+
+    fetch(0);
+    stage(0);
+    __syncthreads();
+    int buf = 0;
+    for (int k0 = 0; k0 < Rp; k0 += AP_K) {
+        const bool more = k0 + AP_K < Rp;
+        if (more) fetch(k0 + AP_K);
+        const float* ap = at[buf] + h * AP_LDA + wr + l32;
+        const float* bp = bt[buf] + h * AP_LDB + wc + l32;
+#pragma unroll
+        for (int s = 0; s < AP_K / 2; ++s) {
+            const float a0 = ap[2 * s * AP_LDA], a1 = ap[2 * s * AP_LDA + BS];
+            const float b0 = bp[2 * s * AP_LDB], b1 = bp[2 * s * AP_LDB + BS];
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+        }
+        if (more) stage(buf ^ 1);
         __syncthreads();
-        for (int e = tid; e < QSZ; e += 256)
-            tt[e >> 6][e & 63] = T[(size_t)(row0 + (e >> 6)) * m.ldc + k0 + (e & 63)];
-        __syncthreads();
-        if (active) {
-            const float* x0 = src + (size_t)k0 * m.ldw + c0 + 2 * l32;
-#pragma unroll 4
-            for (int s = 0; s < 32; ++s) {
-                const int k = 2 * s + h;
-                const float2 x = *(const float2*)(x0 + (size_t)k * m.ldw);
-                const float a0 = tt[l32][k];                     // Tgs[row0 + i][k0 + k], i in block 0
-                const float a1 = tt[BS + l32][k];
-                acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, x.x, acc[0][0], 0, 0, 0);
-                acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, x.y, acc[1][0], 0, 0, 0);
-                acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, x.x, acc[0][1], 0, 0, 0);
-                acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, x.y, acc[1][1], 0, 0, 0);
+        buf ^= 1;
+    }
+#pragma unroll
+    for (int ib = 0; ib < 2; ++ib)
+#pragma unroll
+        for (int jb = 0; jb < 2; ++jb) {
+            const int col = c0 + wc + jb * BS + l32;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = row0 + wr + ib * BS + 8 * (v >> 2) + 4 * h + (v & 3);
+                if (row < Rp && col < m.ldw) dst[(size_t)row * m.ldw + col] = acc[ib][jb][v];
             }
         }
-    }
-    if (!active) return;
-#pragma unroll
-    for (int ib = 0; ib < 2; ++ib) {
-        float* base = dst + (size_t)(row0 + ib * BS) * m.ldw + c0 + 2 * l32;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int i = 8 * (v >> 2) + 4 * h + (v & 3);
-            *(float2*)(base + (size_t)i * m.ldw) = make_float2(acc[0][ib][v], acc[1][ib][v]);
-        }
-    }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1059,8 +1094,8 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
                     plan.tiles.push_back(Work{j, ti, tj, 0});
                     for (int c = 0; c < m.nchg; ++c) plan.fullgram.push_back(Work{j, ti, tj, c});
                 }
-            for (int t = 0; t < nt; ++t)
-                for (int c = 0; c < m.nchu; ++c) plan.apply.push_back(Work{j, t, c, 0});
+            for (int t = 0; t < (m.rows_alloc + AP_TILE - 1) / AP_TILE; ++t)
+                for (int c = 0; c < (m.ldw + AP_TILE - 1) / AP_TILE; ++c) plan.apply.push_back(Work{j, t, c, 0});
         }
         if (ds_verify) {
             bool seen = false;
