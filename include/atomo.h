@@ -130,7 +130,7 @@ typedef struct atomo_svd_options {
     int32_t max_inner_sweeps;        /* default 1 (0 = default): most Jacobi sweeps per 64x64 block-pair problem */
     float   inner_reduction;         /* default 0.01 (0 = default): a block-pair problem stops sweeping once */
                                      /* its largest |cos| is below inner_reduction x the value it started at */
-    int32_t full_period;             /* default 8 (0 = default): a block-pair problem rotates all 2016 index     */
+    int32_t full_period;             /* default 12 (0 = default): a block-pair problem rotates all 2016 index    */
                                      /* pairs in the rounds of an outer sweep whose number is a multiple of this */
                                      /* and only the 1024 pairs that couple its two blocks in the other rounds;  */
                                      /* 1: all 2016 pairs in every round                                         */

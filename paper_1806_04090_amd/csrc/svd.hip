@@ -1143,7 +1143,7 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     const int max_inner = opt && opt->max_inner_sweeps > 0 ? opt->max_inner_sweeps : 1;
     const float inner_reduction = opt && opt->inner_reduction > 0.0f ? opt->inner_reduction : 0.01f;
     const float fresh_stop = stop_cosine;
-    const int full_period = opt && opt->full_period > 0 ? opt->full_period : 8;
+    const int full_period = opt && opt->full_period > 0 ? opt->full_period : 12;
     const int cyclic = opt && opt->block_order == 1 ? 1 : 0;
     const int adaptive = opt ? opt->adaptive : 0;
 

@@ -18,6 +18,7 @@
 // only the 32 x 32 pairs that couple the two blocks: block a sits in the even slots, block b in the odd
 // slots, the even slots stay and the odd slots move on by one pair per step, 32 steps instead of 63.
 #include <cfloat>
+#include <type_traits>
 
 #include "svd_common.h"
 
@@ -95,6 +96,17 @@ __device__ inline float2 rotation_of(float app, float apq, float aqq, float z2)
         s = copysignf(0.5f * w * ir * ic, d * w);
     }
     return make_float2(c, s);
+}
+
+// The same values without a branch; where no rotation is due the discarded operands may be NaN or infinite.
+__device__ inline float2 rotation_of_select(float app, float apq, float aqq, float z2)
+{
+    const bool rot = apq * apq > 1e-14f * fmaxf(fabsf(app * aqq), z2 * z2);
+    const float d = aqq - app, w = 2.0f * apq;
+    const float ir = __builtin_amdgcn_rsqf(fmaf(d, d, w * w));
+    const float hc = fmaf(0.5f * fabsf(d), ir, 0.5f);
+    const float ic = __builtin_amdgcn_rsqf(hc);
+    return make_float2(rot ? hc * ic : 1.0f, rot ? copysignf(0.5f * w * ir * ic, d * w) : 0.0f);
 }
 
 __device__ inline float2 pair_rotation(const float* A, int k, float z2)
@@ -238,7 +250,7 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
     __shared__ float red[32];
     __shared__ float rlen[PR];           // by slot: 1 / length of the row as the pair problem starts
     __shared__ unsigned int entry_bits[2];   // largest cosine and largest squared norm as the pair problem starts
-    __shared__ float2 rotc[2][32];       // cross rounds: (c, s) of the 32 rotations of a step, by step parity
+    __shared__ __align__(16) float2 rotc[2][32];       // cross rounds: (c, s) of the 32 rotations of a step, by step parity
     __shared__ float2 rotd[2][32];       //               the diagonal entries (d_p', d_q') those rotations leave behind
 
     const int two_wgs = (n_two + TILES_PER_WG - 1) / TILES_PER_WG;
@@ -524,76 +536,144 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
             }
             __syncthreads();
         };
-        // A cross round keeps the matrix in registers for its 32 steps.  Thread (b, g) holds the 2x2 block of row pair
-        // a = (b + g) mod 32 and column pair b (group g is the g-th circulant diagonal of the 32 x 32 grid of blocks; its
-        // lanes touch 32 different LDS banks) and the entries of its two rows of Q in column pair b.  The even slots
-        // stay and the odd slots move on by one pair per step, so after the rotation the new block (a, b) keeps its
-        // entry (even, even) and takes (even, odd) from block (a, b - 1), (odd, even) from (a - 1, b) and (odd, odd) from
-        // (a - 1, b - 1): the last is a lane of the same group (lane permute), the other two go through LDS; Q's odd
-        // columns come from the lane next door.  The rotations of the next step are computed before the step's
-        // barrier by group 1 alone: its entry (even, odd) is the off-diagonal entry of the next slot pair b + 1, whose
-        // diagonal entries are what this step's rotations of pairs b + 1 and b leave behind (closed form, carried in
-        // rotd).  Per step: 4 LDS reads, 2 writes and 3 lane permutes per thread and one barrier, against 11 reads,
-        // 8 writes and 2 permutes when the matrix goes through LDS in full (the other rounds).
+        // A cross round keeps the matrix in registers for its 32 steps, and only one triangle of it.  The 32 x 32 grid of
+        // 2x2 blocks (row pair a, column pair b) is cut into its circulant diagonals g = (a - b) mod 32; block (b, a) is
+        // the mirror image of (a, b), so the diagonals 0 .. 16 hold everything.  Waves 0 .. 8 (thread groups 0 .. 17 of
+        // 32 lanes) carry them: thread b of group g holds block ((b + g) mod 32, b) -- its lanes touch 32 different LDS
+        // banks -- and group 17 repeats group 16 value for value (diagonal 16 is its own mirror image and holds every
+        // block twice, once from either side).  Waves 9 .. 15 carry Q: a lane holds, of three (waves 9, 10) or two
+        // rows, the entries in the slot pairs 2j and 2j + 1, j = lane mod 16.
+        // The even slots stay and the odd slots move on by one pair per step.  After the rotation the new block (a, b)
+        // keeps its entry (even, even) and takes (even, odd) from block (a, b - 1), (odd, even) from (a - 1, b) and
+        // (odd, odd) from (a - 1, b - 1): the last is a lane of the same group (lane permute), the other two go through
+        // LDS -- from the diagonals g + 1 and g - 1, where for g = 0 the second is the mirror image of the first and
+        // for g = 16 the first is a mirror image from diagonal 15.  In Q the odd entry of pair 2j moves to pair 2j + 1
+        // of the same lane and that of pair 2j + 1 to the next lane of the row of 16, a data-parallel move inside the
+        // vector unit: no LDS traffic but the rotations.
+        // The rotations of the next step are computed before the step's barrier by group 1 alone: its entry (even, odd)
+        // is the off-diagonal entry of the next slot pair b + 1, whose diagonal entries are what this step's rotations
+        // of pairs b + 1 and b leave behind (closed form, carried in rotd).  Everybody waits for that wave at the
+        // barrier, so it reads the two diagonal entries together with the rotations and computes the new rotation as
+        // soon as its off-diagonal entry is there.
+        // Measured on one workgroup, cycles per step: 760 with every thread holding a block of the full matrix and two
+        // rows of Q (24 multiply-adds and 3 lane permutes through LDS per thread); 700 with the roles; 650 with Q's
+        // moves in the vector unit; 610 with the early reads.  Without the rotation arithmetic it would be 465.
         auto cross_sweep = [&](float* A0, float* Q0, float* EX) {
-            const int ar = (b + grp) & 31;
-            float x00 = A0[(2 * ar) * ELD + b],     x01 = A0[(2 * ar) * ELD + 32 + b];
-            float x10 = A0[(2 * ar + 1) * ELD + b], x11 = A0[(2 * ar + 1) * ELD + 32 + b];
-            float q[QR_PER][2];
-#pragma unroll
-            for (int e = 0; e < QR_PER; ++e) {
-                q[e][0] = Q0[(grp * QR_PER + e) * ELD + b];
-                q[e][1] = Q0[(grp * QR_PER + e) * ELD + 32 + b];
-            }
-            if (grp == 0) {                                      // (a = b: the diagonal blocks)
-                const float4 r = rotation_and_diagonal(x00, x01, x11, z2);
-                rotc[0][b] = make_float2(r.x, r.y);
-                rotd[0][b] = make_float2(r.z, r.w);
-            }
-            __syncthreads();
-            const int left = ((lane & 32) | ((b + 31) & 31)) << 2;      // the lane of column pair b - 1 in this group
-            const int own = ar * 32 + b, from01 = ar * 32 + ((b + 31) & 31), from10 = ((ar + 31) & 31) * 32 + b;
-            // (two steps per trip: with the parity a constant every LDS address of a step is a loop invariant plus an
-            // immediate offset)
-            auto step_of_parity = [&](const int p) {
-                const float2 ra = rotc[p][ar], rb = rotc[p][b];
-                const float y00 = ra.x * x00 - ra.y * x10, y01 = ra.x * x01 - ra.y * x11;
-                const float y10 = ra.y * x00 + ra.x * x10, y11 = ra.y * x01 + ra.x * x11;
-                const float o01 = rb.y * y00 + rb.x * y01, o10 = rb.x * y10 - rb.y * y11, o11 = rb.y * y10 + rb.x * y11;
-                x00 = rb.x * y00 - rb.y * y01;
-                float* ex = EX + p * 2048;
-                ex[own] = o01;
-                ex[1024 + own] = o10;
-                x11 = __int_as_float(__builtin_amdgcn_ds_bpermute(left, __float_as_int(o11)));
-#pragma unroll
-                for (int e = 0; e < QR_PER; ++e) {
-                    const float u = q[e][0], v = q[e][1];
-                    q[e][0] = rb.x * u - rb.y * v;
-                    q[e][1] = __int_as_float(__builtin_amdgcn_ds_bpermute(left, __float_as_int(rb.y * u + rb.x * v)));
-                }
-                if (grp == 1) {                                  // (a = b + 1)
-                    const float4 r = rotation_and_diagonal(rotd[p][ar].x, o01, rotd[p][b].y, z2);
-                    rotc[p ^ 1][ar] = make_float2(r.x, r.y);
-                    rotd[p ^ 1][ar] = make_float2(r.z, r.w);
+            // (scalar branches: every role passes the same 34 barriers, and a wave runs exactly one role)
+            const int role = __builtin_amdgcn_readfirstlane(wave);
+            if (role <= 8) {
+                const int g = min(grp, 16);
+                const int ar = (b + g) & 31;
+                float x00 = A0[(2 * ar) * ELD + b],     x01 = A0[(2 * ar) * ELD + 32 + b];
+                float x10 = A0[(2 * ar + 1) * ELD + b], x11 = A0[(2 * ar + 1) * ELD + 32 + b];
+                if (grp == 0) {                                  // (a = b: the diagonal blocks)
+                    const float4 r = rotation_and_diagonal(x00, x01, x11, z2);
+                    rotc[0][b] = make_float2(r.x, r.y);
+                    rotd[0][b] = make_float2(r.z, r.w);
                 }
                 __syncthreads();
-                x01 = ex[from01];
-                x10 = ex[1024 + from10];
-            };
-            for (int t = 0; t < 32; t += 2) {
-                step_of_parity(0);
-                step_of_parity(1);
-            }
-            // 32 steps: every index is back in its slot
-            A0[(2 * ar) * ELD + b] = x00;     A0[(2 * ar) * ELD + 32 + b] = x01;
-            A0[(2 * ar + 1) * ELD + b] = x10; A0[(2 * ar + 1) * ELD + 32 + b] = x11;
+                // exchange buffer of a step: [0, 1024) the entries (even, odd) that the blocks hand on, [1024, 2048) the
+                // entries (odd, even), both indexed by block
+                const int left = ((lane & 32) | ((b + 31) & 31)) << 2;  // the lane of column pair b - 1 in this group
+                const int bl = (b + 31) & 31, al = (ar + 31) & 31;
+                const int own = ar * 32 + b;
+                const int from01 = g == 16 ? 1024 + bl * 32 + ar : ar * 32 + bl;      // (a, b - 1), or its mirror image (b - 1, a)
+                const int from10 = g == 0 ? ar * 32 + bl : 1024 + al * 32 + b;        // (a - 1, b), or its mirror image (b, a - 1)
+                // (two steps per trip: with the parity a constant every LDS address of a step is a loop invariant plus
+                // an immediate offset)
+                auto step_of_parity = [&](const int p, auto lead_tag) {
+                    constexpr bool lead = decltype(lead_tag)::value;
+                    const float2 ra = rotc[p][ar], rb = rotc[p][b];
+                    float dpa = 0.0f, dqb = 0.0f;
+                    if (lead) {
+                        dpa = rotd[p][ar].x;
+                        dqb = rotd[p][b].y;
+                        asm volatile("" : "+v"(dpa), "+v"(dqb)); // (keeps the two reads up here, beside the rotations')
+                    }
+                    const float y00 = ra.x * x00 - ra.y * x10, y01 = ra.x * x01 - ra.y * x11;
+                    const float y10 = ra.y * x00 + ra.x * x10, y11 = ra.y * x01 + ra.x * x11;
+                    const float o01 = rb.y * y00 + rb.x * y01, o10 = rb.x * y10 - rb.y * y11, o11 = rb.y * y10 + rb.x * y11;
+                    x00 = rb.x * y00 - rb.y * y01;
+                    float* ex = EX + p * 2048;
+                    ex[own] = o01;
+                    ex[1024 + own] = o10;
+                    x11 = __int_as_float(__builtin_amdgcn_ds_bpermute(left, __float_as_int(o11)));
+                    if (lead && grp == 1) {                      // (a = b + 1)
+                        const float2 r = rotation_of_select(dpa, o01, dqb, z2);
+                        const float cc = r.x * r.x, ss = r.y * r.y, cs2 = 2.0f * r.x * r.y * o01;
+                        rotc[p ^ 1][ar] = r;
+                        rotd[p ^ 1][ar] = make_float2(fmaf(cc, dpa, fmaf(ss, dqb, -cs2)), fmaf(ss, dpa, fmaf(cc, dqb, cs2)));
+                    }
+                    __syncthreads();
+                    x01 = ex[from01];
+                    x10 = ex[from10];
+                };
+                if (role == 0) {
+                    for (int t = 0; t < 32; t += 2) {
+                        step_of_parity(0, std::true_type{});
+                        step_of_parity(1, std::true_type{});
+                    }
+                } else {
+                    for (int t = 0; t < 32; t += 2) {
+                        step_of_parity(0, std::false_type{});
+                        step_of_parity(1, std::false_type{});
+                    }
+                }
+                // 32 steps: every index is back in its slot.  Both triangles go back to LDS.
+                A0[(2 * ar) * ELD + b] = x00;     A0[(2 * ar) * ELD + 32 + b] = x01;
+                A0[(2 * ar + 1) * ELD + b] = x10; A0[(2 * ar + 1) * ELD + 32 + b] = x11;
+                if (g >= 1 && g <= 15) {
+                    A0[(2 * b) * ELD + ar] = x00;     A0[(2 * b) * ELD + 32 + ar] = x10;
+                    A0[(2 * b + 1) * ELD + ar] = x01; A0[(2 * b + 1) * ELD + 32 + ar] = x11;
+                }
+                __syncthreads();
+            } else {
+                auto rows_of_q = [&](auto n_tag) {
+                    constexpr int NR = decltype(n_tag)::value;
+                    const int j = lane & 15, rsub = lane >> 4;
+                    const int row0 = NR == 3 ? (role - 9) * 12 + rsub * 3 : 24 + (role - 11) * 8 + rsub * 2;
+                    float e0[NR], o0[NR], e1[NR], o1[NR];
 #pragma unroll
-            for (int e = 0; e < QR_PER; ++e) {
-                Q0[(grp * QR_PER + e) * ELD + b] = q[e][0];
-                Q0[(grp * QR_PER + e) * ELD + 32 + b] = q[e][1];
+                    for (int e = 0; e < NR; ++e) {
+                        const float* q = Q0 + (row0 + e) * ELD;
+                        e0[e] = q[2 * j];
+                        e1[e] = q[2 * j + 1];
+                        o0[e] = q[32 + 2 * j];
+                        o1[e] = q[32 + 2 * j + 1];
+                    }
+                    __syncthreads();
+                    auto step_of_parity = [&](const int p) {
+                        const float4 r = *(const float4*)&rotc[p][2 * j];       // (c, s) of the pairs 2j and 2j + 1
+#pragma unroll
+                        for (int e = 0; e < NR; ++e) {
+                            const float t0 = r.y * e0[e] + r.x * o0[e], t1 = r.w * e1[e] + r.z * o1[e];
+                            e0[e] = r.x * e0[e] - r.y * o0[e];
+                            e1[e] = r.z * e1[e] - r.w * o1[e];
+                            o1[e] = t0;
+                            // row_ror:1 -- every lane takes the value of the lane before it in its row of 16, lane 0 that of lane 15
+                            o0[e] = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(t1), 0x121, 0xf, 0xf, false));
+                        }
+                        __syncthreads();
+                    };
+                    for (int t = 0; t < 32; t += 2) {
+                        step_of_parity(0);
+                        step_of_parity(1);
+                    }
+#pragma unroll
+                    for (int e = 0; e < NR; ++e) {
+                        float* q = Q0 + (row0 + e) * ELD;
+                        q[2 * j] = e0[e];
+                        q[2 * j + 1] = e1[e];
+                        q[32 + 2 * j] = o0[e];
+                        q[32 + 2 * j + 1] = o1[e];
+                    }
+                    __syncthreads();
+                };
+                if (role <= 10) rows_of_q(std::integral_constant<int, 3>{});
+                else rows_of_q(std::integral_constant<int, 2>{});
             }
-            __syncthreads();
         };
+        static_assert(NT == 1024 && PR == 64, "the roles of a cross round: 18 groups for one triangle of A, 2 x 12 + 5 x 8 rows of Q");
         static_assert(2 * 2 * 1024 <= PR * ELD, "the exchange buffers of a cross round fit the idle copy of the matrix");
         for (int isw = 0; isw < max_inner; ++isw) {
             float* A0 = As[cur];
