@@ -1,22 +1,22 @@
 // svd_eig: eigen-decomposition of the 64x64 Gram matrix of one block pair (the inner problem of the
 // blocked one-sided Jacobi SVD), one workgroup per pair.
 //
-// Two-sided Jacobi with the round-robin ("chess tournament") parallel ordering: 63 steps per sweep,
-// each applying 32 disjoint rotations.  The matrix A and the accumulated rotations Q live in LDS in
-// "slot" order: at every step the 32 rotations act on the slot pairs (0,1), (2,3), ..., (62,63), so
-// no index tables are needed, and the tournament is realised by writing every result to the slot its
-// index occupies in the next step (slot 0 stays; even slots move up by two, 62 -> 63; odd slots move
-// down by two, 1 -> 2).  After 63 steps every index is back in its own slot.  Within a row the even
-// slots are stored in columns 0..31 and the odd slots in columns 32..63, so that the 32 lanes that
-// own the 32 slot pairs read and write consecutive LDS words (no bank conflicts).  A and Q are
-// double-buffered, so a step is: read buffer X, rotate, write buffer Y permuted, barrier.  Every
-// lane computes the rotation of its own column pair from the diagonal 2x2 block (redundantly in
-// every wave, so no second barrier) and fetches the rotations of its row pairs with lane reads.
+// Two-sided Jacobi with parallel orderings, 32 disjoint rotations per step.  The matrix A and the accumulated
+// rotations Q live in LDS in "slot" order: block i of the pair sits in the even slots, block j in the odd slots, and
+// within a row the even slots are stored in columns 0..31 and the odd slots in columns 32..63.
 //
-// Cross schedule.  The two diagonal 32x32 blocks of the pair only need to be diagonalised once per outer
-// sweep (cyclic Jacobi rotates every index pair once per sweep); in the other rounds the kernel rotates
-// only the 32 x 32 pairs that couple the two blocks: block a sits in the even slots, block b in the odd
-// slots, the even slots stay and the odd slots move on by one pair per step, 32 steps instead of 63.
+// Cross round (most rounds).  The two diagonal 32x32 blocks of the pair only need to be diagonalised now and then
+// (cyclic Jacobi rotates every index pair once per sweep); a cross round rotates only the 32 x 32 index pairs that
+// couple the two blocks: at every step the rotations act on the slot pairs (0,1), (2,3), ..., (62,63), the even slots
+// stay and the odd slots move on by one pair per step, 32 steps.  Matrix and rotations stay in registers for the
+// whole round (see cross_sweep).
+//
+// Full round (every full_period-th round of an outer sweep): first the 2 x 496 index pairs inside the two blocks,
+// as two round-robin ("chess tournament") schedules of 32 players side by side, 31 steps; then a cross round: all 2016
+// pairs in 63 steps.  The 31 steps go through LDS: A and Q are double-buffered, a step is: read buffer X, rotate,
+// write buffer Y permuted (every result goes to the place its index occupies in the next step), barrier.  Every lane
+// computes the rotation of its own column pair from the diagonal 2x2 block (redundantly in every wave, so no second
+// barrier) and fetches the rotation of its row pair with a lane read.
 #include <cfloat>
 #include <type_traits>
 
@@ -31,24 +31,35 @@ constexpr int NT = 1024;                // threads per workgroup
 constexpr int TILES_PER_WG = NT / 256;  // two-sided tiles a workgroup without a pair problem applies
 constexpr int ELD = 65;                 // LDS row stride
 constexpr int GROUPS = NT / 32;         // thread groups of 32 (one slot pair of columns per thread)
-constexpr int RP_PER = 32 / GROUPS;     // row pairs of A per thread
 constexpr int QR_PER = 64 / GROUPS;     // rows of Q per thread
 
-__device__ inline int next_slot(int s)
+// A round inside the two blocks (the first 31 steps of a full round) numbers the 64 indices of the pair by positions:
+// positions 0 .. 31 hold the indices of block i, 32 .. 63 those of block j, the rotations pair the positions
+// (2k, 2k + 1), and between two steps the positions of either half move like a round-robin tournament of 32 players:
+// position 0 stays, the odd ones move down by two (1 -> 2), the even ones up by two (30 -> 31); after 31 steps everybody
+// is back.  The matrix itself stays in the layout of the cross rounds (below); within_col / within_row say where a
+// position lives in it.  The columns are chosen so that the 32 lanes of a step, one per pair, read 32 different LDS
+// banks: pair k of block i = the indices k and k + 16 (columns k, 16 + k), pair k of block j = the indices 16 + k and k
+// (columns 48 + k, 32 + k).
+__device__ inline int next_within(int v)
 {
-    if (s == 0) return 0;
-    if (s & 1) return s == 1 ? 2 : s - 2;
-    return s == 62 ? 63 : s + 2;
+    const int s = v & 31;
+    const int n = s == 0 ? 0 : (s & 1) ? (s == 1 ? 2 : s - 2) : (s == 30 ? 31 : s + 2);
+    return (v & 32) | n;
 }
-
-// the cross schedule: even slots stay, odd slot 2k+1 moves to 2(k+1 mod 32)+1
-__device__ inline int next_slot_cross(int s) { return (s & 1) ? ((((s >> 1) + 1) & 31) << 1) | 1 : s; }
+__device__ inline int within_col(int v)
+{
+    const int k = (v & 31) >> 1, side = v & 1;
+    return v < 32 ? 16 * side + k : 32 + (side ? k : 16 + k);
+}
+// (column c of the cross layout holds slot 2c, or 2(c - 32) + 1; row = slot)
+__device__ inline int within_row(int v) { const int c = within_col(v); return c < 32 ? 2 * c : 2 * (c - 32) + 1; }
 
 // column of slot s inside a row: even slots first, then odd slots
 __device__ inline int mem_col(int s) { return (s >> 1) + 32 * (s & 1); }
 
 // slot in which index i of the pair starts (and ends) a sweep
-__device__ inline int home_slot(int i, bool cross) { return cross ? (i < 32 ? 2 * i : 2 * (i - 32) + 1) : i; }
+__device__ inline int home_slot(int i) { return i < 32 ? 2 * i : 2 * (i - 32) + 1; }
 
 // Largest |A_ij| / max(sqrt(A_ii A_jj), z2) over i < j, and largest diagonal entry.  All threads call.
 __device__ inline float2 max_cosine(const float* A, float z2, float* red)
@@ -107,11 +118,6 @@ __device__ inline float2 rotation_of_select(float app, float apq, float aqq, flo
     const float hc = fmaf(0.5f * fabsf(d), ir, 0.5f);
     const float ic = __builtin_amdgcn_rsqf(hc);
     return make_float2(rot ? hc * ic : 1.0f, rot ? copysignf(0.5f * w * ir * ic, d * w) : 0.0f);
-}
-
-__device__ inline float2 pair_rotation(const float* A, int k, float z2)
-{
-    return rotation_of(A[(2 * k) * ELD + k], A[(2 * k) * ELD + 32 + k], A[(2 * k + 1) * ELD + 32 + k], z2);
 }
 
 // (c, s) of a slot pair together with the two diagonal entries the rotation leaves behind:
@@ -314,7 +320,7 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
     if (m.gs && tid == 0) m.state[(step & 1) ? ST_QTICK_ODD : ST_QTICK] = step + 1;
     for (int e = tid; e < QSZ; e += NT) {
         const int i = e >> 6, j = e & 63;
-        Qs[0][i * ELD + mem_col(home_slot(j, cross))] = (i == j) ? 1.0f : 0.0f;
+        Qs[0][i * ELD + mem_col(home_slot(j))] = (i == j) ? 1.0f : 0.0f;
     }
     if (tid < PR) {
         ref[tid] = m.gs ? m.cref[tid < BS ? bi * BS + tid : bj * BS + tid - BS] : 0.0f;
@@ -330,10 +336,10 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
             floatx4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll 4
             for (int c = 0; c < m.nchp; ++c) sum += *(const floatx4*)(g + (size_t)c * QSZ);
-            const int si = home_slot(i, cross);
+            const int si = home_slot(i);
 #pragma unroll
             for (int x = 0; x < 4; ++x) {
-                const int sj = home_slot(j4 + x, cross);
+                const int sj = home_slot(j4 + x);
                 As[0][si * ELD + mem_col(sj)] = sum[x];
                 if (i < BS && j4 >= BS) As[0][sj * ELD + mem_col(si)] = sum[x];
             }
@@ -344,7 +350,7 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
             const int i = e >> 6, j = e & 63;
             const int gi = i < BS ? bi * BS + i : bj * BS + i - BS;
             const int gj = j < BS ? bi * BS + j : bj * BS + j - BS;
-            As[0][home_slot(i, cross) * ELD + mem_col(home_slot(j, cross))] = C[(size_t)gi * m.ldc + gj];
+            As[0][home_slot(i) * ELD + mem_col(home_slot(j))] = C[(size_t)gi * m.ldc + gj];
         }
     } else {
         const int pp = (step - 1) & 1;
@@ -410,7 +416,7 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
             const int ro = sb == 2 ? BS : 0, co = sb == 0 ? 0 : BS;         // where the block sits in the 64 x 64
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int si = home_slot(ro + 8 * (v >> 2) + 4 * h + (v & 3), cross), sj = home_slot(co + l32, cross);
+                const int si = home_slot(ro + 8 * (v >> 2) + 4 * h + (v & 3)), sj = home_slot(co + l32);
                 As[0][si * ELD + mem_col(sj)] = acc[v];
                 if (sb == 1) As[0][sj * ELD + mem_col(si)] = acc[v];
             }
@@ -422,7 +428,7 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
     //    measured against the floor instead of their own length) and the largest squared norm
     const float z2 = ZERO_REL * __int_as_float(m.state[ST_SCALE]);
     if (tid < PR) {
-        const int sl = home_slot(tid, cross);
+        const int sl = home_slot(tid);
         const float d = As[0][sl * ELD + mem_col(sl)];
         const bool out = m.gs && d < GS_RELIABLE * ref[tid];
         sits_out[sl] = out;
@@ -474,59 +480,46 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
         atomicMax((unsigned int*)&m.state[ST_SCALE_NEXT], __float_as_uint(entry.y));
     }
 
-    // 3. Jacobi sweeps.  Thread (b, g): slot pair b of the columns, row pairs g*RP_PER.. of A, rows
-    //    g*QR_PER.. of Q.  Its two outputs per row go to the columns of slots next(2b), next(2b+1).
+    // 3. Jacobi sweeps.
     const int b = tid & 31, grp = tid >> 5;
-    auto advance = [&](int s) { return cross ? next_slot_cross(s) : next_slot(s); };
-    const int wc0 = mem_col(advance(2 * b)), wc1 = mem_col(advance(2 * b + 1));
-    int wr0[RP_PER], wr1[RP_PER];
-#pragma unroll
-    for (int e = 0; e < RP_PER; ++e) {
-        wr0[e] = advance(2 * (grp * RP_PER + e)) * ELD;
-        wr1[e] = advance(2 * (grp * RP_PER + e) + 1) * ELD;
-    }
     int cur = 0;
     int inner_done = 0;
     const bool leave = !m.gs && entry.x <= DS_LEAVE * stop_cosine;
     if (entry.x > 0.0f && !leave) {
         // inner target: a fixed factor below what came in is enough for the outer iteration
         const float inner_stop = fmaxf(2e-7f, inner_reduction * entry.x);
-        // One step: read buffer X, rotate, write buffer Y with the slots advanced.  Written as a lambda
-        // and called with the buffers swapped so that every LDS address is loop-invariant.
-        auto jacobi_step = [&](const float* X, float* Y, const float* XQ, float* YQ) {
+        // One step of a round inside the blocks: read buffer X, rotate, write buffer Y with the positions advanced.
+        // Thread (b, g): pair b of the columns, pair g of the rows of A, rows 2g and 2g + 1 of Q; its two outputs per
+        // row go to the columns of the positions next(2b), next(2b + 1).  Written as a lambda and called with the
+        // buffers swapped so that every LDS address is loop-invariant.
+        const int rc0 = within_col(2 * b), rc1 = within_col(2 * b + 1);
+        const int wc0 = within_col(next_within(2 * b)), wc1 = within_col(next_within(2 * b + 1));
+        const int rr0 = within_row(2 * grp) * ELD, rr1 = within_row(2 * grp + 1) * ELD;
+        const int wr0 = within_row(next_within(2 * grp)) * ELD, wr1 = within_row(next_within(2 * grp + 1)) * ELD;
+        const int dr0 = within_row(2 * b) * ELD, dr1 = within_row(2 * b + 1) * ELD;
+        auto within_step = [&](const float* X, float* Y, const float* XQ, float* YQ) {
             // issue every LDS read of the step first; the rotation arithmetic overlaps their latency
-            float xa[RP_PER][4], xq[QR_PER][2];
-#pragma unroll
-            for (int e = 0; e < RP_PER; ++e) {
-                const int a = grp * RP_PER + e;
-                xa[e][0] = X[(2 * a) * ELD + b];     xa[e][1] = X[(2 * a) * ELD + 32 + b];
-                xa[e][2] = X[(2 * a + 1) * ELD + b]; xa[e][3] = X[(2 * a + 1) * ELD + 32 + b];
-            }
+            const float x00 = X[rr0 + rc0], x01 = X[rr0 + rc1], x10 = X[rr1 + rc0], x11 = X[rr1 + rc1];
+            float xq[QR_PER][2];
 #pragma unroll
             for (int e = 0; e < QR_PER; ++e) {
                 const int i = grp * QR_PER + e;
-                xq[e][0] = XQ[i * ELD + b];
-                xq[e][1] = XQ[i * ELD + 32 + b];
+                xq[e][0] = XQ[i * ELD + rc0];
+                xq[e][1] = XQ[i * ELD + rc1];
             }
             // every lane computes the rotation of its own column pair b (both halves of the wave
-            // redundantly); the rotation of a row pair is fetched from the lane of this half-wave
+            // redundantly); the rotation of the row pair is fetched from the lane of this half-wave
             // that owns it
-            const float2 pb = pair_rotation(X, b, z2);
-#pragma unroll
-            for (int e = 0; e < RP_PER; ++e) {
-                const int a = grp * RP_PER + e;
-                const int from = ((lane & 32) | a) << 2;
-                const float2 pa = make_float2(__int_as_float(__builtin_amdgcn_ds_bpermute(from, __float_as_int(pb.x))),
-                                              __int_as_float(__builtin_amdgcn_ds_bpermute(from, __float_as_int(pb.y))));
-                const float x00 = xa[e][0], x01 = xa[e][1], x10 = xa[e][2], x11 = xa[e][3];
-                const float y00 = pa.x * x00 - pa.y * x10, y01 = pa.x * x01 - pa.y * x11;
-                const float y10 = pa.y * x00 + pa.x * x10, y11 = pa.y * x01 + pa.x * x11;
-                const int r0 = wr0[e], r1 = wr1[e];
-                Y[r0 + wc0] = pb.x * y00 - pb.y * y01;
-                Y[r0 + wc1] = pb.y * y00 + pb.x * y01;
-                Y[r1 + wc0] = pb.x * y10 - pb.y * y11;
-                Y[r1 + wc1] = pb.y * y10 + pb.x * y11;
-            }
+            const float2 pb = rotation_of(X[dr0 + rc0], X[dr0 + rc1], X[dr1 + rc1], z2);
+            const int from = ((lane & 32) | grp) << 2;
+            const float2 pa = make_float2(__int_as_float(__builtin_amdgcn_ds_bpermute(from, __float_as_int(pb.x))),
+                                          __int_as_float(__builtin_amdgcn_ds_bpermute(from, __float_as_int(pb.y))));
+            const float y00 = pa.x * x00 - pa.y * x10, y01 = pa.x * x01 - pa.y * x11;
+            const float y10 = pa.y * x00 + pa.x * x10, y11 = pa.y * x01 + pa.x * x11;
+            Y[wr0 + wc0] = pb.x * y00 - pb.y * y01;
+            Y[wr0 + wc1] = pb.y * y00 + pb.x * y01;
+            Y[wr1 + wc0] = pb.x * y10 - pb.y * y11;
+            Y[wr1 + wc1] = pb.y * y10 + pb.x * y11;
 #pragma unroll
             for (int e = 0; e < QR_PER; ++e) {
                 const int i = grp * QR_PER + e;
@@ -676,22 +669,22 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
         static_assert(NT == 1024 && PR == 64, "the roles of a cross round: 18 groups for one triangle of A, 2 x 12 + 5 x 8 rows of Q");
         static_assert(2 * 2 * 1024 <= PR * ELD, "the exchange buffers of a cross round fit the idle copy of the matrix");
         for (int isw = 0; isw < max_inner; ++isw) {
-            float* A0 = As[cur];
-            float* A1 = As[cur ^ 1];
-            float* Q0 = Qs[cur];
-            float* Q1 = Qs[cur ^ 1];
-            if (cross) {
-                cross_sweep(A0, Q0, A1);
-            } else {
-                for (int t = 0; t < 62; t += 2) {
-                    jacobi_step(A0, A1, Q0, Q1);
-                    jacobi_step(A1, A0, Q1, Q0);
+            if (!cross) {
+                // a full round rotates the 2 x 496 index pairs inside the two blocks first: 31 steps through LDS, the last
+                // one into the other buffer
+                float* A0 = As[cur];
+                float* A1 = As[cur ^ 1];
+                float* Q0 = Qs[cur];
+                float* Q1 = Qs[cur ^ 1];
+                for (int t = 0; t < 30; t += 2) {
+                    within_step(A0, A1, Q0, Q1);
+                    within_step(A1, A0, Q1, Q0);
                 }
-            }
-            if (!cross) {                                        // 63 steps: one more, into the other buffer
-                jacobi_step(A0, A1, Q0, Q1);
+                within_step(A0, A1, Q0, Q1);
                 cur ^= 1;
             }
+            // the 1024 pairs that couple the blocks
+            cross_sweep(As[cur], Qs[cur], As[cur ^ 1]);
             ++inner_done;
             if (isw + 1 < max_inner) {
                 const float2 now = max_cosine(As[cur], z2, red);
@@ -703,14 +696,14 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
     const float* Qc = Qs[cur];                                   // Q, columns in slot order
     float* F0 = As[cur ^ 1];                                     // scratch for the Newton-Schulz factor
     // memory column of natural column j of Q
-    auto qcol = [&](int j) { return mem_col(home_slot(j, cross)); };
+    auto qcol = [&](int j) { return mem_col(home_slot(j)); };
 
     // 4. eigenvalues, and where each eigenvector goes: decreasing eigenvalue over the live rows of
     //    the pair, padding rows stay padding rows
     const int nI = max(0, min(BS, m.r - bi * BS)), nJ = max(0, min(BS, m.r - bj * BS));
     if (tid < PR) {
         const bool live = tid < BS ? tid < nI : tid - BS < nJ;
-        const int sl = home_slot(tid, cross);
+        const int sl = home_slot(tid);
         ev[tid] = live ? Acur[sl * ELD + mem_col(sl)] : -FLT_MAX;
     }
     __syncthreads();
@@ -761,7 +754,7 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
         m.cref[grow] = r;
         // the scale of the row for the block weights that the two-sided update forms (rows that are not rotated: 0)
         m.cref0[grow] = r0;
-        m.dd[(size_t)(step & 1) * m.rows_alloc + grow] = (ev[tid] > z2 && !sits_out[home_slot(tid, cross)]) ? r0 : 0.0f;
+        m.dd[(size_t)(step & 1) * m.rows_alloc + grow] = (ev[tid] > z2 && !sits_out[home_slot(tid)]) ? r0 : 0.0f;
     }
 
     // 5. one Newton-Schulz step  Q <- Q (1.5 I - 0.5 Q^T Q): removes the drift that thousands of
