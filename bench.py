@@ -54,6 +54,9 @@ def block_rows(r):
     return rows + [0] * (nb & 1)
 
 
+ROTATION_UNITS = 1.0 + 2.0 * 17.0 / 32.0   # vectors of 64 that one rotation of a Jacobi step updates, see executed_work
+
+
 def executed_work(shapes, sweeps, refreshes, pair_visits, jacobi_steps, row_update_tiles, n_elem, kept_atoms):
     """Arithmetic and bytes the algorithm executes on real data (no padding) per step, by kernel class.
 
@@ -70,8 +73,11 @@ def executed_work(shapes, sweeps, refreshes, pair_visits, jacobi_steps, row_upda
     launches: C <- D^T C D  256 r^2 and Tgs <- D^T Tgs  128 r^2 (D block-diagonal in 64 x 64 blocks), and per pair
     problem the three 32x32 blocks it brings up to date itself.
     64 x 64 eigen-solves: 32 rotations per Jacobi step (63 steps when every index pair is rotated, 32 when only
-    the pairs that couple the two blocks are), each 3 x 64 x 6 flops on the vector ALU (rows and columns of the
-    block, columns of the accumulator), plus a Newton-Schulz step of two 64^3 products per solve.  The
+    the pairs that couple the two blocks are), each ROTATION_UNITS x 64 x 6 flops on the vector ALU: 64 x 6 for the
+    columns of the accumulator, and for the rows and the columns of the symmetric block 2 x 64 x 6 x 17/32, because the
+    register-resident steps update 17 of its 32 block diagonals (one triangle) and mirror the rest.  (The 31 steps of a
+    full round that go through LDS update the whole block, 3 x 64 x 6: they are priced like the others, an under-count.)
+    Plus a Newton-Schulz step of two 64^3 products per solve.  The
     svd_eig class is priced as a whole (vector-ALU rotations + the MFMA work its launches carry) against the
     157.3 TFLOP/s that is both the fp32 vector and the fp32 matrix peak.
     """
@@ -97,7 +103,7 @@ def executed_work(shapes, sweeps, refreshes, pair_visits, jacobi_steps, row_upda
             gram += sw * sum(quadrants(i, j) for i in range(nb2) for j in range(i + 1, nb2)) - sum(quadrants(i, j) for i, j in first)
             refresh += rf * M * r * (r + 64.0)
     upd = row_update_tiles * 2.0 * 64 ** 3 + gram
-    eig = jacobi_steps * 32 * 3 * 64 * 6 + pair_visits * 2 * 2 * 64 ** 3 + twosided + catchup
+    eig = jacobi_steps * 32 * ROTATION_UNITS * 64 * 6 + pair_visits * 2 * 2 * 64 ** 3 + twosided + catchup
     decode_bytes = 4.0 * n_elem + sum(4.0 * k * (m + n + 1) for (m, n), k in zip(shapes, kept_atoms))
     return {
         "svd_gram": ("mfma", gram_first, PEAK_FP32_MFMA_TFLOPS, "TFLOP/s"),
@@ -255,7 +261,7 @@ def main():
     per_step_ms = {k: v[0] / args.steps for k, v in prof.items() if v[1]}
     launches = {k: v[1] / args.steps for k, v in prof.items() if v[1]}
     work = executed_work(shapes, sweeps, refreshes, pair_visits, jacobi_steps, row_update_tiles, n_elem, kept_atoms)
-    rotations = jacobi_steps * 32 * 3 * 64 * 6
+    rotations = jacobi_steps * 32 * ROTATION_UNITS * 64 * 6
     # contraction flops executed on the matrix cores in one encode (the vector-ALU rotations are reported beside them)
     contraction = sum(work[k][1] for k in ("svd_gram", "svd_update", "svd_refresh")) + work["svd_eig"][1] - rotations
     by_kernel = {}
@@ -531,7 +537,7 @@ def batch64_leg(ctx, torch, binding, inputs, with_oracle, reps=3):
     ctx.status()
     pair_visits, jacobi_steps, row_update_tiles = ctx.last_counters()
     work = executed_work(shapes, sweeps, refreshes, pair_visits, jacobi_steps, row_update_tiles, n_elem, kept)
-    rotations = jacobi_steps * 32 * 3 * 64 * 6
+    rotations = jacobi_steps * 32 * ROTATION_UNITS * 64 * 6
     contraction = sum(work[k][1] for k in ("svd_gram", "svd_update", "svd_refresh")) + work["svd_eig"][1] - rotations
     dec_bytes = work["decode_svd"][1]
     out = {"workload": "64 matrices 512 x 4608, rank-16 signal sigma ~ U(0.1, 1) + N(0, 0.01^2), s = 4, one encode call + "
