@@ -127,9 +127,13 @@ typedef struct atomo_svd_options {
                                      /* |<a_i,a_j>| / (|a_i||a_j|), measured before rotating, is below; matrices   */
                                      /* that iterate on their Gram matrix stop once the Gram matrix formed afresh  */
                                      /* from the rotated data has no cosine above it                               */
-    int32_t max_inner_sweeps;        /* default 1 (0 = default): most Jacobi sweeps per 64x64 block-pair problem */
-    float   inner_reduction;         /* default 0.01 (0 = default): a block-pair problem stops sweeping once */
-                                     /* its largest |cos| is below inner_reduction x the value it started at */
+    int32_t max_inner_sweeps;        /* most Jacobi sweeps per 64x64 block-pair problem; 0 = default: 1 for the   */
+                                     /* matrices that iterate on their Gram matrix (481 or more vectors on the    */
+                                     /* shorter side), 2 for the others                                            */
+    float   inner_reduction;         /* a block-pair problem stops sweeping once its largest |cos| is below        */
+                                     /* inner_reduction x the value it started at; 0 = default: 0.1 (0.01 for the  */
+                                     /* matrices that iterate on their Gram matrix, which matters only with        */
+                                     /* max_inner_sweeps above 1)                                                  */
     int32_t full_period;             /* default 12 (0 = default): a block-pair problem rotates all 2016 index    */
                                      /* pairs in the rounds of an outer sweep whose number is a multiple of this */
                                      /* and only the 1024 pairs that couple its two blocks in the other rounds;  */

@@ -1043,6 +1043,7 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
         m.gramf = m.gs || ds_verify ? carve.take<float>((size_t)m.ntiles * m.nchg * QSZ) : nullptr;
         m.Q = carve.take<float>((size_t)(m.gs ? 2 : 1) * m.npairs * QSZ);
         m.QT = m.gs ? carve.take<float>((size_t)2 * m.npairs * QSZ) : nullptr;
+        m.DB = m.gs && !plan.own_update ? carve.take<float>((size_t)m.npairs * QSZ) : nullptr;
         m.idle = m.gs ? nullptr : carve.take<int>(m.npairs);
         m.state = carve.take<int>(ST_WORDS);
         const size_t state_off = carve.last;
@@ -1140,8 +1141,13 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
 {
     const int max_sweeps = opt && opt->max_sweeps > 0 ? opt->max_sweeps : 16;
     const float stop_cosine = opt && opt->stop_cosine > 0.0f ? opt->stop_cosine : 1e-4f;
+    // (defaults: one round per pair problem in Gram space, where a tick is one launch and the chain of ticks sets the
+    // time of a call; on the data a second round where the first left more than a tenth of the largest cosine: those
+    // matrices then need 5 - 6 sweeps instead of 8 - 10, at a third more per tick)
     const int max_inner = opt && opt->max_inner_sweeps > 0 ? opt->max_inner_sweeps : 1;
     const float inner_reduction = opt && opt->inner_reduction > 0.0f ? opt->inner_reduction : 0.01f;
+    const int max_inner_ds = opt && opt->max_inner_sweeps > 0 ? opt->max_inner_sweeps : 2;
+    const float inner_reduction_ds = opt && opt->inner_reduction > 0.0f ? opt->inner_reduction : 0.1f;
     const float fresh_stop = stop_cosine;
     const int full_period = opt && opt->full_period > 0 ? opt->full_period : 12;
     const int cyclic = opt && opt->block_order == 1 ? 1 : 0;
@@ -1314,7 +1320,7 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
                 if (tick >= 0) {
                     ProfScope ps(ctx, ATOMO_K_SVD_EIG, s_ds[g]);
                     launch_svd_eig(d_mats, w_eig_ds[g], (int)plan.eig_ds[g].size(), nullptr, 0, nullptr, 0, 0, tick, limit_ds,
-                                   stop_cosine, max_inner, inner_reduction, full_period, 0, ctx->d_flags, s_ds[g]);
+                                   stop_cosine, max_inner_ds, inner_reduction_ds, full_period, 0, ctx->d_flags, s_ds[g]);
                 }
                 {
                     // tick -1: the Gram matrices of the first tick's pairs

@@ -105,6 +105,8 @@ struct SvdMat {
                              //   data space: the check of DS_VERIFY, null for matrices too small for it)
     float* Q;                // [npairs][64*64]; Gram space: [2][npairs][64*64], indexed by tick parity
     float* QT;               // Gram space: the same matrices transposed (else null)
+    float* DB;               // Gram space with C one tick behind: [2][npairs][2][32*32], by tick parity the two diagonal blocks
+                             // of every pair problem's rotated matrix (else null)
     int* state;              // [ST_WORDS]
     float* sig_raw;          // [rows_alloc]
     float* cref;             // Gram space: [rows_alloc] reference squared norm of every row, see GS_RELIABLE

@@ -357,35 +357,36 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
         const float* C = c_of_parity(m, pp);
         const int k1 = pdw[PD_K1], k2 = pdw[PD_K2], s1 = pdw[PD_S1], s2 = pdw[PD_S2];
         const int x0 = pdw[PD_X0], x1 = pdw[PD_X1], y0 = pdw[PD_Y0], y1 = pdw[PD_Y1];
-        // Every operand is read along its contraction index, 16 bytes at a time: the rotations from their transposed
+        // aa and bb: the pair problems of the previous tick left the two diagonal 32 x 32 blocks of their rotated
+        // matrices behind (m.DB, step 4): two entries per thread, requested before the operands of ab
+        float dv[2 * BS * BS / NT];
+#pragma unroll
+        for (int q = 0; q < 2 * BS * BS / NT; ++q) {
+            const int e = tid + NT * q, blk = e >> 10;
+            dv[q] = m.DB[(((size_t)pp * m.npairs + (blk ? k2 : k1)) * 2 + (blk ? s2 : s1)) * (BS * BS) + (e & (BS * BS - 1))];
+        }
+        // ab: every operand is read along its contraction index, 16 bytes at a time: the rotations from their transposed
         // copies (m.QT), the tile of C through its mirror image (C is symmetric up to the rounding of its updates, which
         // step 2 evens out anyway).  Instruction s of a product contracts the indices s (lanes 0..31) and 32 + s
         // (lanes 32..63).
         const float* Q1 = m.QT + ((size_t)pp * m.npairs + k1) * QSZ;
         const float* Q2 = m.QT + ((size_t)pp * m.npairs + k2) * QSZ;
         const int h = lane >> 5, l32 = lane & 31;
-        float* P = As[1];                                        // three 32 x 64 intermediates, row stride ELD
-        float* P2 = Qs[1];
+        float* P = As[1];                                        // the 32 x 64 intermediate, row stride ELD
         floatx4 qb[PR / 8];                                      // operand of the second product, loaded up front
-        if (wave < 3) {
-            const float* QR = wave == 0 ? Q1 : Q2;
-            const int sR = wave == 0 ? s1 : s2;
-            const float* qrp = QR + (sR * BS + l32) * PR + BS * h;
+        if (wave == 0) {
+            const float* qrp = Q2 + (s2 * BS + l32) * PR + BS * h;
 #pragma unroll
             for (int u = 0; u < PR / 8; ++u) qb[u] = *(const floatx4*)(qrp + 4 * u);
         }
-        // product 1: waves 0..5 = (block sb, column half): Qs^T (32 x 64) * C tile (64 x 32 of its 64 columns)
-        if (wave < 6) {
-            const int sb = wave >> 1, half = wave & 1;           // sb 0: aa, 1: ab, 2: bb
-            const float* QL = sb == 2 ? Q2 : Q1;
-            const int sL = sb == 2 ? s2 : s1;
-            const int r0 = sb == 2 ? y0 : x0, r1 = sb == 2 ? y1 : x1;       // row blocks of the tile
-            const int c0 = sb == 0 ? x0 : y0, c1 = sb == 0 ? x1 : y1;       // column blocks of the tile
-            const int col = (half == 0 ? c0 : c1) * BS + l32;
+        // product 1: waves 0 and 1 = the two column halves: Q1s^T (32 x 64) * C tile (64 x 32 of its 64 columns)
+        if (wave < 2) {
+            const int half = wave;
+            const int col = (half == 0 ? y0 : y1) * BS + l32;
             floatx4 qa[PR / 8], cb[PR / 8];
-            // rows of the tile: block r0 for the lanes 0..31, block r1 for the lanes above
-            const float* qlp = QL + (sL * BS + l32) * PR + BS * h;
-            const float* clp = C + (size_t)col * m.ldc + (h == 0 ? r0 : r1) * BS;
+            // rows of the tile: block x0 for the lanes 0..31, block x1 for the lanes above
+            const float* qlp = Q1 + (s1 * BS + l32) * PR + BS * h;
+            const float* clp = C + (size_t)col * m.ldc + (h == 0 ? x0 : x1) * BS;
 #pragma unroll
             for (int u = 0; u < PR / 8; ++u) {
                 qa[u] = *(const floatx4*)(qlp + 4 * u);
@@ -398,27 +399,28 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
             for (int u = 0; u < PR / 8; ++u)
 #pragma unroll
                 for (int x = 0; x < 4; ++x) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(qa[u][x], cb[u][x], acc, 0, 0, 0);
-            float* out = sb == 0 ? P : sb == 1 ? P + BS * ELD : P2;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) out[(8 * (v >> 2) + 4 * h + (v & 3)) * ELD + half * BS + l32] = acc[v];
+            for (int v = 0; v < 16; ++v) P[(8 * (v >> 2) + 4 * h + (v & 3)) * ELD + half * BS + l32] = acc[v];
+        }
+#pragma unroll
+        for (int q = 0; q < 2 * BS * BS / NT; ++q) {
+            const int e = tid + NT * q, blk = e >> 10, i = (e >> 5) & (BS - 1), j = e & (BS - 1);
+            As[0][home_slot(blk * BS + i) * ELD + mem_col(home_slot(blk * BS + j))] = dv[q];
         }
         __syncthreads();
-        // product 2: waves 0..2 = block sb: intermediate (32 x 64) * Qs (64 x 32)
-        if (wave < 3) {
-            const int sb = wave;
-            const float* in = sb == 0 ? P : sb == 1 ? P + BS * ELD : P2;
+        // product 2: wave 0: intermediate (32 x 64) * Q2s (64 x 32)
+        if (wave == 0) {
             floatx16 acc;
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 #pragma unroll
             for (int s = 0; s < PR / 2; ++s)
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(in[l32 * ELD + BS * h + s], qb[s >> 2][s & 3], acc, 0, 0, 0);
-            const int ro = sb == 2 ? BS : 0, co = sb == 0 ? 0 : BS;         // where the block sits in the 64 x 64
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(P[l32 * ELD + BS * h + s], qb[s >> 2][s & 3], acc, 0, 0, 0);
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int si = home_slot(ro + 8 * (v >> 2) + 4 * h + (v & 3)), sj = home_slot(co + l32);
+                const int si = home_slot(8 * (v >> 2) + 4 * h + (v & 3)), sj = home_slot(BS + l32);
                 As[0][si * ELD + mem_col(sj)] = acc[v];
-                if (sb == 1) As[0][sj * ELD + mem_col(si)] = acc[v];
+                As[0][sj * ELD + mem_col(si)] = acc[v];
             }
         }
     }
@@ -730,6 +732,18 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
 
     // Gram space: the reference values follow the rows, ref'_j = sum_i Q_ij^2 ref_i
     __syncthreads();                                             // dest[] is complete
+    // Gram space: the two diagonal 32 x 32 blocks of the rotated matrix, rows and columns in their new order, for the
+    // pair problems of the next tick (they would otherwise have to form them from C, which is one tick behind)
+    if (m.gs && m.DB) {
+        float* db = m.DB + ((size_t)(step & 1) * m.npairs + wk.a) * (2 * BS * BS);
+#pragma unroll
+        for (int q = 0; q < QSZ / NT; ++q) {
+            const int e = tid + NT * q, ti = e >> 6, tj = e & 63;
+            const int di = dest[ti], dj = dest[tj];
+            if ((di ^ dj) < BS)                                  // both in the same block
+                db[(di >> 5) * (BS * BS) + (di & (BS - 1)) * BS + (dj & (BS - 1))] = Acur[home_slot(ti) * ELD + mem_col(home_slot(tj))];
+        }
+    }
     if (!m.gs) {
         // a pair that was left alone and whose rows are in order needs no row update
         const bool in_place = leave && (tid >= PR || dest[tid] == tid);
