@@ -366,7 +366,8 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
             dv[q] = m.DB[(((size_t)pp * m.npairs + (blk ? k2 : k1)) * 2 + (blk ? s2 : s1)) * (BS * BS) + (e & (BS * BS - 1))];
         }
         // ab: every operand is read along its contraction index, 16 bytes at a time: the rotations from their transposed
-        // copies (m.QT), the tile of C through its mirror image (C is symmetric up to the rounding of its updates, which
+        // copies (m.QT: entry (row, k) at ((k / 4) * 64 + row) * 4 + k % 4, so that the 32 lanes of an instruction, one
+        // per row, read 512 consecutive bytes), the tile of C through its mirror image (C is symmetric up to the rounding of its updates, which
         // step 2 evens out anyway).  Instruction s of a product contracts the indices s (lanes 0..31) and 32 + s
         // (lanes 32..63).
         const float* Q1 = m.QT + ((size_t)pp * m.npairs + k1) * QSZ;
@@ -375,9 +376,9 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
         float* P = As[1];                                        // the 32 x 64 intermediate, row stride ELD
         floatx4 qb[PR / 8];                                      // operand of the second product, loaded up front
         if (wave == 0) {
-            const float* qrp = Q2 + (s2 * BS + l32) * PR + BS * h;
+            const float* qrp = Q2 + ((8 * h) * PR + s2 * BS + l32) * 4;
 #pragma unroll
-            for (int u = 0; u < PR / 8; ++u) qb[u] = *(const floatx4*)(qrp + 4 * u);
+            for (int u = 0; u < PR / 8; ++u) qb[u] = *(const floatx4*)(qrp + 4 * PR * u);
         }
         // product 1: waves 0 and 1 = the two column halves: Q1s^T (32 x 64) * C tile (64 x 32 of its 64 columns)
         if (wave < 2) {
@@ -385,11 +386,11 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
             const int col = (half == 0 ? y0 : y1) * BS + l32;
             floatx4 qa[PR / 8], cb[PR / 8];
             // rows of the tile: block x0 for the lanes 0..31, block x1 for the lanes above
-            const float* qlp = Q1 + (s1 * BS + l32) * PR + BS * h;
+            const float* qlp = Q1 + ((8 * h) * PR + s1 * BS + l32) * 4;
             const float* clp = C + (size_t)col * m.ldc + (h == 0 ? x0 : x1) * BS;
 #pragma unroll
             for (int u = 0; u < PR / 8; ++u) {
-                qa[u] = *(const floatx4*)(qlp + 4 * u);
+                qa[u] = *(const floatx4*)(qlp + 4 * PR * u);
                 cb[u] = *(const floatx4*)(clp + 4 * u);
             }
             floatx16 acc;
@@ -804,7 +805,7 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
 #pragma unroll
         for (int v = 0; v < 4; ++v) qout[(ti * 16 + 4 * hi + v) * PR + dj] = q4[v];
         // Gram space: and transposed, for the pair problems of the next tick (step 1)
-        if (m.gs) *(floatx4*)(m.QT + ((size_t)(step & 1) * m.npairs + wk.a) * QSZ + dj * PR + ti * 16 + 4 * hi) = q4;
+        if (m.gs) *(floatx4*)(m.QT + ((size_t)(step & 1) * m.npairs + wk.a) * QSZ + ((ti * 4 + hi) * PR + dj) * 4) = q4;
     }
 
     if (tid == 0) {
