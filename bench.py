@@ -71,7 +71,8 @@ def executed_work(shapes, sweeps, refreshes, pair_visits, jacobi_steps, row_upda
     Gram-space layers, per refresh (svd_refresh): upper-triangular tiles of A A^T  M r (r + 64), and (every
     refresh but the first) A <- T A and T <- T T_old, 2 r^2 (M + r); per tick of a sweep, inside the svd_eig
     launches: C <- D^T C D  256 r^2 and Tgs <- D^T Tgs  128 r^2 (D block-diagonal in 64 x 64 blocks), and per pair
-    problem the three 32x32 blocks it brings up to date itself.
+    problem the 32x32 block between its two row blocks, which it brings up to date itself (two chained products; the
+    two diagonal blocks come from the pair problems of the tick before).
     64 x 64 eigen-solves: 32 rotations per Jacobi step (63 steps when every index pair is rotated, 32 when only
     the pairs that couple the two blocks are), each ROTATION_UNITS x 64 x 6 flops on the vector ALU: 64 x 6 for the
     columns of the accumulator, and for the rows and the columns of the symmetric block 2 x 64 x 6 x 17/32, because the
@@ -95,7 +96,7 @@ def executed_work(shapes, sweeps, refreshes, pair_visits, jacobi_steps, row_upda
             refresh += rf * M * r * (r + 64.0) + max(rf - 1, 0) * 2.0 * r * r * (M + r)
             twosided += sw * (nb2 - 1) * 384.0 * r * r
             # every pair problem but the first after a refresh forms its block from three 32x32 products
-            catchup += max(visits - rf * (nb2 // 2), 0) * 3 * 2.0 * (32 * 64 * 64 + 32 * 64 * 32)
+            catchup += max(visits - rf * (nb2 // 2), 0) * 2.0 * (32 * 64 * 64 + 32 * 64 * 32)
         else:
             quadrants = lambda i, j: 2.0 * M * (rows[i] ** 2 + rows[i] * rows[j] + rows[j] ** 2)
             first = [(nb2 - 1, 0)] + [(k, nb2 - 1 - k) for k in range(1, nb2 // 2)]    # the pairs of round 0
