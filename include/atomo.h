@@ -159,7 +159,11 @@ typedef struct atomo_svd_options {
                                      /* A matrix that needs more sweeps than were enqueued is reported through    */
                                      /* ATOMO_ENOCONV exactly as at max_sweeps (its message is still an exact,    */
                                      /* unbiased decomposition); gradients change slowly from step to step, so    */
-                                     /* k = 1 or 2 rarely meets that                                              */
+                                     /* k = 1 or 2 rarely meets that.  The matrices that iterate on their Gram     */
+                                     /* matrix confirm convergence on a Gram matrix formed afresh from the rotated */
+                                     /* data, at a sweep boundary; the context also remembers after how many sweeps */
+                                     /* the first of them asked for that, and a call enqueues those launches only  */
+                                     /* from k sweeps before: a matrix that is ready sooner sweeps on until then   */
 } atomo_svd_options;
 
 /* -------- context ------------------------------------------------------------------------------ */

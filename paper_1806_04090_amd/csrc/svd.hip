@@ -890,31 +890,37 @@ __global__ __launch_bounds__(256) void svd_pack(const SvdMat* mats, const Work* 
     for (int c = threadIdx.x; c < m.r; c += 256) short_out[c] = a[m.Mp + c] * fold;
 }
 
-// Most sweeps any Gram-space matrix and any data-space matrix of the call took, into pinned host memory that the
-// next calls read without waiting (atomo_svd_options.adaptive).  One workgroup.
+// Most sweeps any Gram-space matrix and any data-space matrix of the call took, and the fewest sweeps after which a
+// Gram-space matrix asked for a refresh (0: none did), into pinned host memory that the next calls read without
+// waiting (atomo_svd_options.adaptive).  One workgroup.
 __global__ __launch_bounds__(256) void svd_hint(const SvdMat* mats, int n_mats, int* out)
 {
-    __shared__ int red[2][256];
-    int gs = 0, ds = 0;
+    __shared__ int red[3][256];
+    const int never = 1 << 30;
+    int gs = 0, ds = 0, ask = never;
     for (int j = threadIdx.x; j < n_mats; j += 256) {
         const SvdMat& m = mats[j];
         if (m.thin) continue;
         const int sw = m.report[0];
         if (m.gs) gs = max(gs, sw); else ds = max(ds, sw);
+        if (m.gs) ask = min(ask, m.state[ST_FIRST_ASK] > 0 ? m.state[ST_FIRST_ASK] : never);
     }
     red[0][threadIdx.x] = gs;
     red[1][threadIdx.x] = ds;
+    red[2][threadIdx.x] = ask;
     __syncthreads();
     for (int off = 128; off > 0; off >>= 1) {
         if ((int)threadIdx.x < off) {
             red[0][threadIdx.x] = max(red[0][threadIdx.x], red[0][threadIdx.x + off]);
             red[1][threadIdx.x] = max(red[1][threadIdx.x], red[1][threadIdx.x + off]);
+            red[2][threadIdx.x] = min(red[2][threadIdx.x], red[2][threadIdx.x + off]);
         }
         __syncthreads();
     }
     if (threadIdx.x == 0) {
         out[0] = red[0][0];
         out[1] = red[1][0];
+        out[3] = red[2][0] == never ? 0 : red[2][0];
         out[2] = 1;
     }
 }
@@ -1156,6 +1162,10 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     // Sweep limits of this call.  With `adaptive`, what the most recent finished call with the same shapes needed plus
     // the margin; a call that used up a reduced limit tells nothing about what was needed and is followed by a full one.
     int limit_gs = max_sweeps, limit_ds = max_sweeps;
+    // ... and the first sweep boundary at which the Gram-space matrices can get a refresh: the margin before the first
+    // one that a matrix of that call asked for (0: every boundary).  The refresh launches of an idle boundary cost what
+    // five empty launches cost, on the chain of launches that sets the time of the call.
+    int ask_from = 0;
     SweepHint* hint = nullptr;
     if (adaptive > 0) {
         uint64_t sig = 1469598103934665603ull ^ (uint64_t)n_mats;
@@ -1183,7 +1193,10 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
         }
         if (best) {
             const int g = best->host[0], d = best->host[1];
-            if (!(g >= best->limit_gs && best->limit_gs < max_sweeps)) limit_gs = std::min(max_sweeps, std::max(1, g + adaptive));
+            if (!(g >= best->limit_gs && best->limit_gs < max_sweeps)) {
+                limit_gs = std::min(max_sweeps, std::max(1, g + adaptive));
+                ask_from = std::max(0, best->host[3] - adaptive);
+            }
             if (!(d >= best->limit_ds && best->limit_ds < max_sweeps)) limit_ds = std::min(max_sweeps, std::max(1, d + adaptive));
         }
         if (!hint->host) {
@@ -1191,7 +1204,7 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
             ATOMO_HIP(ctx, hipHostGetDevicePointer((void**)&hint->dev, hint->host, 0));
             ATOMO_HIP(ctx, hipEventCreateWithFlags(&hint->done, hipEventDisableTiming));
         }
-        hint->host[0] = hint->host[1] = hint->host[2] = 0;
+        hint->host[0] = hint->host[1] = hint->host[2] = hint->host[3] = 0;
         hint->sig = sig;
         hint->seq = ++ctx->hint_seq;
         hint->limit_gs = limit_gs;
@@ -1319,7 +1332,7 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
                 if (!have_ds[g] || tick >= ds_ticks[g]) continue;
                 if (tick >= 0) {
                     ProfScope ps(ctx, ATOMO_K_SVD_EIG, s_ds[g]);
-                    launch_svd_eig(d_mats, w_eig_ds[g], (int)plan.eig_ds[g].size(), nullptr, 0, nullptr, 0, 0, tick, limit_ds,
+                    launch_svd_eig(d_mats, w_eig_ds[g], (int)plan.eig_ds[g].size(), nullptr, 0, nullptr, 0, 0, tick, limit_ds, 0,
                                    stop_cosine, max_inner_ds, inner_reduction_ds, full_period, 0, ctx->d_flags, s_ds[g]);
                 }
                 {
@@ -1351,12 +1364,13 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
                 {
                     ProfScope ps(ctx, ATOMO_K_SVD_EIG, stream);
                     launch_svd_eig(d_mats, w_eig_gs, (int)plan.eig_gs.size(), w_twosided, own_launch ? 0 : n_two, w_gs_list,
-                                   (int)plan.gs_list.size(), cyclic, tick, limit_gs, stop_cosine, max_inner,
+                                   (int)plan.gs_list.size(), cyclic, tick, limit_gs, ask_from, stop_cosine, max_inner,
                                    inner_reduction, full_period, 0, ctx->d_flags, stream);
                 }
             }
             bool boundary = false;
-            for (int period : plan.gs_periods) boundary = boundary || (tick % period == 0 && tick <= limit_gs * period);
+            for (int period : plan.gs_periods)
+                boundary = boundary || (tick % period == 0 && tick <= limit_gs * period && (tick == 0 || tick >= ask_from * period));
             if (boundary) {
                 // a sweep boundary of some matrix: those that asked for it get a fresh Gram matrix (their Tgs is
                 // complete now), and their pair problems of this tick run in a launch of their own
@@ -1371,7 +1385,7 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
                 {
                     ProfScope ps(ctx, ATOMO_K_SVD_EIG, stream);
                     launch_svd_eig(d_mats, w_eig_gs, (int)plan.eig_gs.size(), nullptr, 0, nullptr, 0, 0, tick, limit_gs,
-                                   stop_cosine, max_inner, inner_reduction, full_period, 1, ctx->d_flags, stream);
+                                   ask_from, stop_cosine, max_inner, inner_reduction, full_period, 1, ctx->d_flags, stream);
                 }
             }
         }

@@ -45,7 +45,8 @@ enum {
     ST_WSTAMP = 20,     // Gram-space matrices: word 20 + (t & 1) holds t + 1 once the block weights of the C after t ticks are written
     ST_CYCLIC_FROM = 22, // Gram-space matrices: ticks from this one on are paired by the fixed tournament (0 = not set)
     ST_VERIFY = 23,     // data-space matrices: 1 = the sweep that just ended was close enough for the whole-Gram-matrix check (DS_VERIFY)
-    ST_WORDS = 24
+    ST_FIRST_ASK = 24,  // Gram-space matrices: the sweep count at which the matrix first asked for a refresh (0 = not yet)
+    ST_WORDS = 28
 };
 
 enum { MODE_NEED_REFRESH = 0, MODE_SWEEPS = 1, MODE_DONE = 2 };
@@ -361,10 +362,12 @@ __device__ inline void twosided_tile(const SvdMat* mats, const Work* work, int i
 // matrices, those whose Gram matrix was formed in this very tick (1) or all the others (0).
 // With n_plan > 0 the launch also plans the pairing of tick + 1 for the Gram-space matrices of d_plan_work (one
 // workgroup each): by block weight, or, with cyclic != 0, the fixed tournament.
+// ask_from: a Gram-space matrix does not ask for a refresh before it has completed that many sweeps (the host enqueues
+// no refresh launches at the sweep boundaries before; the sweep limit overrides it).
 void launch_svd_eig(const SvdMat* d_mats, const Work* d_work, int n_items, const Work* d_two_work, int n_two,
-                    const Work* d_plan_work, int n_plan, int cyclic, int tick, int max_sweeps, float stop_cosine,
-                    int max_inner, float inner_reduction, int full_period, int fresh_only, int* d_flags,
-                    hipStream_t stream);
+                    const Work* d_plan_work, int n_plan, int cyclic, int tick, int max_sweeps, int ask_from,
+                    float stop_cosine, int max_inner, float inner_reduction, int full_period, int fresh_only,
+                    int* d_flags, hipStream_t stream);
 
 // Thin matrices (defined in svd_thin.hip).  d_chunks lists (matrix, chunk of positions), d_list the thin matrices.
 // d_direct: chunks of the matrices used in place (largest |entry| only); d_copied: chunks of those copied into B first.

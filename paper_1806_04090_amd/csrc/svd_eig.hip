@@ -242,7 +242,7 @@ __device__ inline void plan_next_tick(const SvdMat& m, int tick, int cyclic, flo
 // would use).  The update writes the C of this tick's parity; the pair problems read the C of the previous
 // parity and bring their own 64x64 block up to date themselves (step 1 below), so the two do not meet.
 __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* work, int n_eig, const Work* two_work,
-                                              int n_two, const Work* plan_work, int cyclic, int step, int max_sweeps,
+                                              int n_two, const Work* plan_work, int cyclic, int step, int max_sweeps, int ask_from,
                                               float stop_cosine, int max_inner, float inner_reduction, int full_period,
                                               int fresh_only, int* flags)
 {
@@ -830,8 +830,12 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
                 // convergence is quadratic: a sweep that started below ten times the threshold has ended well below
                 // it, which the fresh Gram matrix then confirms (or the sweeps go on)
                 const float resolved = fmaxf(10.0f * stop_cosine, __int_as_float(m.state[ST_NOISE]));
-                if (worst < resolved || sweeps >= max_sweeps || waiting)
+                // (a call that goes by the history of the calls before it has no refresh launches at the first sweep
+                // boundaries: the matrix sweeps on until there are)
+                if (((worst < resolved || waiting) && sweeps >= ask_from) || sweeps >= max_sweeps) {
                     m.state[ST_MODE] = MODE_NEED_REFRESH;
+                    if (m.state[ST_FIRST_ASK] == 0) m.state[ST_FIRST_ASK] = sweeps;
+                }
                 if (waiting && m.state[ST_CYCLIC_FROM] == 0) m.state[ST_CYCLIC_FROM] = step + 2;
                 m.state[ST_SAT_OUT] = 0;
             } else if (worst < stop_cosine) {
@@ -853,9 +857,9 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
 
 
 void launch_svd_eig(const SvdMat* d_mats, const Work* d_work, int n_items, const Work* d_two_work, int n_two,
-                    const Work* d_plan_work, int n_plan, int cyclic, int step, int max_sweeps, float stop_cosine,
-                    int max_inner, float inner_reduction, int full_period, int fresh_only, int* d_flags,
-                    hipStream_t stream)
+                    const Work* d_plan_work, int n_plan, int cyclic, int step, int max_sweeps, int ask_from,
+                    float stop_cosine, int max_inner, float inner_reduction, int full_period, int fresh_only,
+                    int* d_flags, hipStream_t stream)
 {
     static_assert(PR * ELD == PR * TLD, "the two-sided tiles are staged in the LDS arrays of the pair problem");
     static_assert((MAX_R / BS) * (MAX_R / BS) <= PR * ELD, "the block weights are staged in an LDS array of the pair problem");
@@ -867,7 +871,7 @@ void launch_svd_eig(const SvdMat* d_mats, const Work* d_work, int n_items, const
     // when it shares its SIMDs.
     const size_t pad = n_items <= 200 ? 20 * 1024 : 0;
     svd_eig<<<grid, NT, pad, stream>>>(d_mats, d_work, n_items, d_two_work, n_two, d_plan_work, cyclic, step, max_sweeps,
-                                     stop_cosine, max_inner, inner_reduction, full_period, fresh_only, d_flags);
+                                     ask_from, stop_cosine, max_inner, inner_reduction, full_period, fresh_only, d_flags);
 }
 
 }  // namespace svd

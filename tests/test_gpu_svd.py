@@ -358,3 +358,31 @@ def test_adaptive_sweep_budget_gives_the_same_messages_and_reports_when_it_falls
     assert status_short == binding.ATOMO_ENOCONV
     _, _, status_again, _ = encode(hard, 3.0, 9, adaptive=1)
     assert status_again == 0 and ctx().svd_sweeps(len(shapes)) == needs
+
+
+def test_adaptive_budget_after_a_slower_gradient_still_gives_a_full_decomposition():
+    # The adaptive budget also skips the refresh launches of the sweep boundaries before the first one that the call
+    # before used.  A gradient that would have asked sooner than its predecessor sweeps on until a boundary has them:
+    # more sweeps than with the full budget, the same decomposition to the tolerance.
+    shape = (512, 600)
+    slow = (np.random.default_rng(3).standard_normal((512, 300)) @ np.random.default_rng(4).standard_normal((300, 600))).astype(np.float32)
+    quick = inputs.resnet18_layer_set(22, shapes=[shape])[0]
+    _, _, status, _ = encode([quick], 3.0, 5)
+    assert status == 0
+    alone = ctx().svd_sweeps(1)[0]
+    _, _, status, _ = encode([slow], 3.0, 5, adaptive=1)        # no history for this shape yet: full budget
+    assert status == 0
+    needed = ctx().svd_sweeps(1)[0]
+    assert needed > alone + 2
+    _, _, status, _ = encode([slow], 3.0, 5, adaptive=1)        # history: the slow gradient
+    assert status == 0 and ctx().svd_sweeps(1)[0] == needed
+    msgs, per, status, _ = encode([quick], 3.0, 5, adaptive=1)  # the quick one cannot ask before the slow one did
+    assert status == 0
+    took = ctx().svd_sweeps(1)[0]
+    assert alone <= took <= needed
+    full_parity(quick, 3.0, 5, 0, msgs[0], *per[0])
+    for _ in range(needed):                                      # the history follows the gradients down again
+        msgs, per, status, _ = encode([quick], 3.0, 5, adaptive=1)
+        assert status == 0
+    assert ctx().svd_sweeps(1)[0] == alone
+    full_parity(quick, 3.0, 5, 0, msgs[0], *per[0])
