@@ -365,43 +365,43 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
             const int e = tid + NT * q, blk = e >> 10;
             dv[q] = m.DB[(((size_t)pp * m.npairs + (blk ? k2 : k1)) * 2 + (blk ? s2 : s1)) * (BS * BS) + (e & (BS * BS - 1))];
         }
-        // ab: every operand is read along its contraction index, 16 bytes at a time: the rotations from their transposed
-        // copies (m.QT: entry (row, k) at ((k / 4) * 64 + row) * 4 + k % 4, so that the 32 lanes of an instruction, one
-        // per row, read 512 consecutive bytes), the tile of C through its mirror image (C is symmetric up to the rounding of its updates, which
-        // step 2 evens out anyway).  Instruction s of a product contracts the indices s (lanes 0..31) and 32 + s
-        // (lanes 32..63).
+        // ab = Q1s^T C12 Q2s, two chained products in 16 x 16 tiles (v_mfma_f32_16x16x4f32: lane l holds A[l & 15][g]
+        // and B[g][l & 15], g = l >> 4, and four results D[4 g + v][l & 15]), eight waves for the first, four for the
+        // second, 16 instructions each.  Every operand is read along its contraction index k, 16 bytes at a time: lane
+        // (., g) takes k = 16 u + 4 g + x, u, x = 0 .. 3, and instruction (u, x) contracts its four values of g.  The
+        // rotations come from their transposed copies (m.QT: entry (row, k) at ((k / 4) * 64 + row) * 4 + k % 4, so that
+        // lanes of consecutive rows read consecutive 16-byte pieces), the tile of C through its mirror image (C is
+        // symmetric up to the rounding of its updates, which step 2 evens out anyway).
         const float* Q1 = m.QT + ((size_t)pp * m.npairs + k1) * QSZ;
         const float* Q2 = m.QT + ((size_t)pp * m.npairs + k2) * QSZ;
-        const int h = lane >> 5, l32 = lane & 31;
+        const int g = lane >> 4, l16 = lane & 15;
+        const int ti = (wave >> 2) & 1, tj = wave & 3;           // tile of the first product (waves 0 .. 7)
         float* P = As[1];                                        // the 32 x 64 intermediate, row stride ELD
-        floatx4 qb[PR / 8];                                      // operand of the second product, loaded up front
-        if (wave == 0) {
-            const float* qrp = Q2 + ((8 * h) * PR + s2 * BS + l32) * 4;
+        floatx4 qa[4], cb[4], qb[4];
+        if (wave < 8) {
+            const float* qlp = Q1 + (g * PR + s1 * BS + ti * 16 + l16) * 4;
+            // column tj * 16 + l16 of the tile: in block y0 or y1; its rows 16 u + 4 g ..: in block x0 (u < 2) or x1
+            const int j = tj * 16 + l16;
+            const float* clp = C + (size_t)((j < BS ? y0 : y1) * BS + (j & (BS - 1))) * m.ldc + 4 * g;
 #pragma unroll
-            for (int u = 0; u < PR / 8; ++u) qb[u] = *(const floatx4*)(qrp + 4 * PR * u);
-        }
-        // product 1: waves 0 and 1 = the two column halves: Q1s^T (32 x 64) * C tile (64 x 32 of its 64 columns)
-        if (wave < 2) {
-            const int half = wave;
-            const int col = (half == 0 ? y0 : y1) * BS + l32;
-            floatx4 qa[PR / 8], cb[PR / 8];
-            // rows of the tile: block x0 for the lanes 0..31, block x1 for the lanes above
-            const float* qlp = Q1 + ((8 * h) * PR + s1 * BS + l32) * 4;
-            const float* clp = C + (size_t)col * m.ldc + (h == 0 ? x0 : x1) * BS;
-#pragma unroll
-            for (int u = 0; u < PR / 8; ++u) {
-                qa[u] = *(const floatx4*)(qlp + 4 * PR * u);
-                cb[u] = *(const floatx4*)(clp + 4 * u);
+            for (int u = 0; u < 4; ++u) {
+                qa[u] = *(const floatx4*)(qlp + 16 * PR * u);
+                cb[u] = *(const floatx4*)(clp + (u < 2 ? x0 : x1) * BS + 16 * (u & 1));
             }
-            floatx16 acc;
+        }
+        if (wave < 4) {                                          // tile (wave >> 1, wave & 1) of the second product
+            const float* qrp = Q2 + (g * PR + s2 * BS + (wave & 1) * 16 + l16) * 4;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+            for (int u = 0; u < 4; ++u) qb[u] = *(const floatx4*)(qrp + 16 * PR * u);
+        }
+        if (wave < 8) {
+            floatx4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-            for (int u = 0; u < PR / 8; ++u)
+            for (int u = 0; u < 4; ++u)
 #pragma unroll
-                for (int x = 0; x < 4; ++x) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(qa[u][x], cb[u][x], acc, 0, 0, 0);
+                for (int x = 0; x < 4; ++x) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(qa[u][x], cb[u][x], acc, 0, 0, 0);
 #pragma unroll
-            for (int v = 0; v < 16; ++v) P[(8 * (v >> 2) + 4 * h + (v & 3)) * ELD + half * BS + l32] = acc[v];
+            for (int v = 0; v < 4; ++v) P[(ti * 16 + 4 * g + v) * ELD + tj * 16 + l16] = acc[v];
         }
 #pragma unroll
         for (int q = 0; q < 2 * BS * BS / NT; ++q) {
@@ -409,17 +409,17 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
             As[0][home_slot(blk * BS + i) * ELD + mem_col(home_slot(blk * BS + j))] = dv[q];
         }
         __syncthreads();
-        // product 2: wave 0: intermediate (32 x 64) * Q2s (64 x 32)
-        if (wave == 0) {
-            floatx16 acc;
+        if (wave < 4) {
+            const int t2i = wave >> 1, t2j = wave & 1;
+            floatx4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+            const float* pr = P + (t2i * 16 + l16) * ELD + 4 * g;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+            for (int u = 0; u < 4; ++u)
 #pragma unroll
-            for (int s = 0; s < PR / 2; ++s)
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(P[l32 * ELD + BS * h + s], qb[s >> 2][s & 3], acc, 0, 0, 0);
+                for (int x = 0; x < 4; ++x) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(pr[16 * u + x], qb[u][x], acc, 0, 0, 0);
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int si = home_slot(8 * (v >> 2) + 4 * h + (v & 3)), sj = home_slot(BS + l32);
+            for (int v = 0; v < 4; ++v) {
+                const int si = home_slot(t2i * 16 + 4 * g + v), sj = home_slot(BS + t2j * 16 + l16);
                 As[0][si * ELD + mem_col(sj)] = acc[v];
                 As[0][sj * ELD + mem_col(si)] = acc[v];
             }
