@@ -271,8 +271,9 @@ __device__ inline void twosided_tile(const SvdMat* mats, const Work* work, int i
         tick_pair(m, tick, wk.a, ai, aj);
         if (kind == 1) tick_pair(m, tick, wk.b, bi, bj);
     }
-    const float* qa = m.Q + ((size_t)(tick & 1) * m.npairs + wk.a) * QSZ;
-    const float* qb = m.Q + ((size_t)(tick & 1) * m.npairs + wk.b) * QSZ;
+    // (the rotations from their transposed copies: 16 bytes of a row per load, consecutive lanes consecutive rows)
+    const float* qa = m.QT + ((size_t)(tick & 1) * m.npairs + wk.a) * QSZ;
+    const float* qb = m.QT + ((size_t)(tick & 1) * m.npairs + wk.b) * QSZ;
     const float* src = kind == 1 ? c_of_parity(m, tick) : m.CT;
     float* dst = kind == 1 ? c_of_parity(m, tick + 1) : m.CT;
     // column of local index j: inside C the columns of pair b, inside Tgs a plain 64-column chunk
@@ -280,7 +281,8 @@ __device__ inline void twosided_tile(const SvdMat* mats, const Work* work, int i
     auto row_of = [&](int i) { return i < BS ? ai * BS + i : aj * BS + i - BS; };
 
     // every global load is issued before the first use: the tile, and the MFMA operands from Qa and Qb
-    float tile_regs[QSZ / 256], qa_regs[PR / 2], qb_regs[PR / 2];
+    // (instruction (u, x) of a product contracts the indices 8 u + x, lanes 0..31, and 8 u + 4 + x, lanes 32..63)
+    floatx4 tile_regs[QSZ / 1024], qa_regs[PR / 8], qb_regs[PR / 8];
     // for the weight of the wave's 32x32 block of the new C: 1 / |row| of its rows and of its column (0: skip the row)
     float rrow[16], rcol = 0.0f;
     const int brow = qi ? aj : ai, bcol = qj ? bj : bi;
@@ -296,19 +298,20 @@ __device__ inline void twosided_tile(const SvdMat* mats, const Work* work, int i
     }
     if (active) {
 #pragma unroll
-        for (int p = 0; p < QSZ / 256; ++p) {
-            const int e = tid + 256 * p, i = e >> 6, j = e & 63;
-            tile_regs[p] = src[(size_t)row_of(i) * m.ldc + col_of(j)];
+        for (int p = 0; p < QSZ / 1024; ++p) {
+            const int e = tid + 256 * p, i = e >> 4, j = (e & 15) * 4;
+            tile_regs[p] = *(const floatx4*)(src + (size_t)row_of(i) * m.ldc + col_of(j));
         }
 #pragma unroll
-        for (int s = 0; s < PR / 2; ++s) {
-            qa_regs[s] = qa[(2 * s + h) * PR + qi * BS + l32];       // (Qa^T)[i][k]
-            qb_regs[s] = kind == 1 ? qb[(2 * s + h) * PR + qj * BS + l32] : 0.0f;    // Qb[k][j]
+        for (int u = 0; u < PR / 8; ++u) {
+            qa_regs[u] = *(const floatx4*)(qa + ((2 * u + h) * PR + qi * BS + l32) * 4);      // (Qa^T)[i][8 u + 4 h ..]
+            if (kind == 1) qb_regs[u] = *(const floatx4*)(qb + ((2 * u + h) * PR + qj * BS + l32) * 4);    // Qb[8 u + 4 h ..][j]
         }
 #pragma unroll
-        for (int p = 0; p < QSZ / 256; ++p) {
-            const int e = tid + 256 * p;
-            xs[(e >> 6) * TLD + (e & 63)] = tile_regs[p];
+        for (int p = 0; p < QSZ / 1024; ++p) {
+            const int e = tid + 256 * p, i = e >> 4, j = (e & 15) * 4;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) xs[i * TLD + j + x] = tile_regs[p][x];
         }
     }
     __syncthreads();
@@ -317,8 +320,10 @@ __device__ inline void twosided_tile(const SvdMat* mats, const Work* work, int i
     for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
     if (active) {
 #pragma unroll
-        for (int s = 0; s < PR / 2; ++s)
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(qa_regs[s], xs[(2 * s + h) * TLD + qj * BS + l32], acc, 0, 0, 0);
+        for (int u = 0; u < PR / 8; ++u)
+#pragma unroll
+            for (int x = 0; x < 4; ++x)
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(qa_regs[u][x], xs[(8 * u + 4 * h + x) * TLD + qj * BS + l32], acc, 0, 0, 0);
     }
     __syncthreads();                                             // the tile is consumed; xs now takes Qa^T * tile
     if (active && kind == 1) {
@@ -331,8 +336,10 @@ __device__ inline void twosided_tile(const SvdMat* mats, const Work* work, int i
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 #pragma unroll
-        for (int s = 0; s < PR / 2; ++s)
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(xs[(qi * BS + l32) * TLD + 2 * s + h], qb_regs[s], acc, 0, 0, 0);
+        for (int u = 0; u < PR / 8; ++u)
+#pragma unroll
+            for (int x = 0; x < 4; ++x)
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(xs[(qi * BS + l32) * TLD + 8 * u + 4 * h + x], qb_regs[u][x], acc, 0, 0, 0);
     }
     const int c = col_of(qj * BS + l32);
 #pragma unroll
