@@ -975,6 +975,7 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
         if (r > THIN_R && nb2 >= GS_MIN_BLOCKS) update_tiles += (size_t)(nb2 / 2) * (nb2 / 2 + nb2 * BS / PR);
     }
     plan.own_update = update_tiles > SPLIT_TWO_SIDED;
+    const bool gs_chain = update_tiles > 0 && !plan.own_update;    // Gram-space matrices, one launch per tick
     for (int j = 0; j < n_mats; ++j) {
         SvdMat& m = plan.mats[j];
         const atomo_mat& a = mats[j];
@@ -1034,7 +1035,12 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
         m.gs = m.nb2 >= GS_MIN_BLOCKS;
         // data space: work items of svd_rowgram over A, of `run` 64-column chunks each, at most ROWGRAM_MAX_PARTIALS
         const int chunks_a = m.Mp / 64;
-        const int run = (chunks_a + ROWGRAM_MAX_PARTIALS - 1) / ROWGRAM_MAX_PARTIALS;
+        int run = (chunks_a + ROWGRAM_MAX_PARTIALS - 1) / ROWGRAM_MAX_PARTIALS;
+        // Beside Gram-space matrices, whose chain of launches sets the time of the call and whose every launch wants 160
+        // free compute units at once, the small data-space matrices (done in a third of that time) take four chunks per
+        // work item: a quarter of the workgroups, each four times as long (3.03 -> 2.97 ms for the ResNet-18 set; six
+        // chunks 2.96, nine 3.25: their chain is then the longest).
+        if (gs_chain && m.nb2 - 1 < DS_VERIFY_MIN_R) run = std::max(run, 4);
         m.nchp = m.gs ? 0 : (chunks_a + run - 1) / run;
         const int nt = m.nb2 / 2;
         m.ntiles = nt * (nt + 1) / 2;
