@@ -1084,8 +1084,13 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
             else
                 plan.eig_ds[grp].push_back(Work{j, k, 0, 0});
             if (m.gs) {
-                for (int k2 = 0; k2 < m.npairs; ++k2) plan.twosided.push_back(Work{j, k, k2, 1});
-                for (int c = 0; c < m.rows_alloc / PR; ++c) plan.twosided.push_back(Work{j, k, c, 2});
+                // (tiles of C, two products each, and tiles of Tgs, one product, two and two: svd_eig's update
+                // workgroups take four consecutive tiles each, and the slowest of them sets when the launch ends)
+                static_assert(PR == 2 * BS, "a pair's strip of C has as many tiles as its strip of Tgs");
+                for (int q = 0; q < m.npairs; q += 2) {
+                    for (int e = q; e < std::min(q + 2, m.npairs); ++e) plan.twosided.push_back(Work{j, k, e, 1});
+                    for (int e = q; e < std::min(q + 2, m.rows_alloc / PR); ++e) plan.twosided.push_back(Work{j, k, e, 2});
+                }
                 if (plan.own_update) {
                     for (int k2 = 0; k2 < m.npairs; k2 += STRIP) plan.strips.push_back(Work{j, k, k2, 1});
                     for (int c = 0; c < m.rows_alloc / PR; c += STRIP) plan.strips.push_back(Work{j, k, c, 2});
