@@ -799,13 +799,17 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
             const float bq = F0[(k + hi) * ELD + tj * 16 + lo];        // F[k][j]
             q4 = __builtin_amdgcn_mfma_f32_16x16x4f32(a, bq, q4, 0, 0, 0);
         }
-        // 6. write Q with its columns permuted to their destination rows
-        float* qout = m.Q + ((size_t)(m.gs ? (step & 1) * m.npairs : 0) + wk.a) * QSZ;
+        // 6. write Q with its columns permuted to their destination rows.  Gram-space matrices whose update rides in
+        //    the tick launches (m.DB set): only the transposed copy, which the update tiles and the pair problems of
+        //    the next tick (step 1) read; the others: Q itself, for svd_rowgram or svd_twosided_strip.
         const int dj = dest[tj * 16 + lo];
+        if (m.gs && m.DB) {
+            *(floatx4*)(m.QT + ((size_t)(step & 1) * m.npairs + wk.a) * QSZ + ((ti * 4 + hi) * PR + dj) * 4) = q4;
+        } else {
+            float* qout = m.Q + ((size_t)(m.gs ? (step & 1) * m.npairs : 0) + wk.a) * QSZ;
 #pragma unroll
-        for (int v = 0; v < 4; ++v) qout[(ti * 16 + 4 * hi + v) * PR + dj] = q4[v];
-        // Gram space: and transposed, for the pair problems of the next tick (step 1)
-        if (m.gs) *(floatx4*)(m.QT + ((size_t)(step & 1) * m.npairs + wk.a) * QSZ + ((ti * 4 + hi) * PR + dj) * 4) = q4;
+            for (int v = 0; v < 4; ++v) qout[(ti * 16 + 4 * hi + v) * PR + dj] = q4[v];
+        }
     }
 
     if (tid == 0) {
