@@ -584,31 +584,34 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void s
     }
     __syncthreads();
     float* const CT = m.CT;
-    const float* qa = m.Q + ((size_t)(tick & 1) * m.npairs + wk.a) * QSZ;
+    // (the rotations from their transposed copies, 16 bytes of a row per load, consecutive lanes consecutive rows;
+    // instruction (u, x) of a product contracts the indices 8 u + x, lanes 0..31, and 8 u + 4 + x, lanes 32..63)
+    const float* qa = m.QT + ((size_t)(tick & 1) * m.npairs + wk.a) * QSZ;
     const float* dd = m.dd + (size_t)(tick & 1) * m.rows_alloc;
     auto row_of = [&](int i) { return i < BS ? ai * BS + i : aj * BS + i - BS; };
     auto col_of = [&](int t, int j) {
         return kind == 1 ? (j < BS ? cbs[2 * t] * BS + j : cbs[2 * t + 1] * BS + j - BS) : m.rows_alloc + (first + t) * PR + j;
     };
-    float qa_regs[PR / 2], qb_regs[PR / 2], tile_regs[QSZ / 256];
-    // thread tid loads element (wave + 4 p, lane) of the tile: rows of block ai for p < 8, of block aj from there on
-    // (32-bit element offsets: a C | Tgs buffer has at most 2048 x 4096 elements)
+    floatx4 qa_regs[PR / 8], qb_regs[PR / 8], tile_regs[QSZ / 1024];
+    // thread tid loads four entries of row tid / 16 + 16 p of the tile: rows of block ai for p < 2, of block aj from
+    // there on (32-bit element offsets: a C | Tgs buffer has at most 2048 x 4096 elements)
     const int ldc = m.ldc;
-    const int load_lo = (ai * BS + wave) * ldc, load_hi = (aj * BS + wave) * ldc;
+    const int lrow = tid >> 4, lc4 = (tid & 15) * 4;
+    const int load_lo = (ai * BS + lrow) * ldc, load_hi = (aj * BS + lrow) * ldc;
     auto fetch_tile = [&](int t) {
-        const int col = col_of(t, lane);
+        const int col = col_of(t, lc4);
 #pragma unroll
-        for (int p = 0; p < QSZ / 256; ++p)
-            tile_regs[p] = CT[(p < 8 ? load_lo + 4 * p * ldc : load_hi + 4 * (p - 8) * ldc) + col];
+        for (int p = 0; p < QSZ / 1024; ++p)
+            tile_regs[p] = *(const floatx4*)(CT + (p < 2 ? load_lo + 16 * p * ldc : load_hi + 16 * (p - 2) * ldc) + col);
     };
     auto fetch_qb = [&](int t) {
-        const float* qb = m.Q + ((size_t)(tick & 1) * m.npairs + first + t) * QSZ;
+        const float* qb = m.QT + ((size_t)(tick & 1) * m.npairs + first + t) * QSZ;
 #pragma unroll
-        for (int s = 0; s < PR / 2; ++s) qb_regs[s] = qb[(2 * s + h) * PR + qj * BS + l32];    // Qb[k][j]
+        for (int u = 0; u < PR / 8; ++u) qb_regs[u] = *(const floatx4*)(qb + ((2 * u + h) * PR + qj * BS + l32) * 4);    // Qb[8 u + 4 h ..][j]
     };
     fetch_tile(0);
 #pragma unroll
-    for (int s = 0; s < PR / 2; ++s) qa_regs[s] = qa[(2 * s + h) * PR + qi * BS + l32];       // (Qa^T)[i][k]
+    for (int u = 0; u < PR / 8; ++u) qa_regs[u] = *(const floatx4*)(qa + ((2 * u + h) * PR + qi * BS + l32) * 4);       // (Qa^T)[i][8 u + 4 h ..]
     if (kind == 1) {
         fetch_qb(0);
         if (tid < PR) {
@@ -619,18 +622,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void s
 #pragma unroll 1
     for (int t = 0; t < count; ++t) {
 #pragma unroll
-        for (int p = 0; p < QSZ / 256; ++p) {
-            const int e = tid + 256 * p;
-            xs[(e >> 6) * TLD + (e & 63)] = tile_regs[p];
-        }
+        for (int p = 0; p < QSZ / 1024; ++p)
+#pragma unroll
+            for (int x = 0; x < 4; ++x) xs[(lrow + 16 * p) * TLD + lc4 + x] = tile_regs[p][x];
         __syncthreads();                                         // the tile is staged (and ys of the tile before is spent)
         if (t + 1 < count) fetch_tile(t + 1);
         floatx16 acc;
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 #pragma unroll
-        for (int s = 0; s < PR / 2; ++s)
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(qa_regs[s], xs[(2 * s + h) * TLD + qj * BS + l32], acc, 0, 0, 0);
+        for (int u = 0; u < PR / 8; ++u)
+#pragma unroll
+            for (int x = 0; x < 4; ++x)
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(qa_regs[u][x], xs[(8 * u + 4 * h + x) * TLD + qj * BS + l32], acc, 0, 0, 0);
         if (kind == 1) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) ys[(qi * BS + 8 * (v >> 2) + 4 * h + (v & 3)) * TLD + qj * BS + l32] = acc[v];
@@ -640,8 +644,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void s
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 #pragma unroll
-            for (int s = 0; s < PR / 2; ++s)
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(ys[(qi * BS + l32) * TLD + 2 * s + h], qb_regs[s], acc, 0, 0, 0);
+            for (int u = 0; u < PR / 8; ++u)
+#pragma unroll
+                for (int x = 0; x < 4; ++x)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(ys[(qi * BS + l32) * TLD + 8 * u + 4 * h + x], qb_regs[u][x], acc, 0, 0, 0);
             if (t + 1 < count) fetch_qb(t + 1);
         }
         // result rows 8 (v / 4) + 4 h + (v mod 4) of block (qi ? aj : ai), column qj * 32 + l32 of the tile
@@ -1053,7 +1059,7 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
         const bool ds_verify = !m.gs && m.R >= DS_VERIFY_MIN_R;
         m.gram = m.gs ? nullptr : carve.take<float>((size_t)m.npairs * m.nchp * QSZ);
         m.gramf = m.gs || ds_verify ? carve.take<float>((size_t)m.ntiles * m.nchg * QSZ) : nullptr;
-        m.Q = carve.take<float>((size_t)(m.gs ? 2 : 1) * m.npairs * QSZ);
+        m.Q = m.gs ? nullptr : carve.take<float>((size_t)m.npairs * QSZ);
         m.QT = m.gs ? carve.take<float>((size_t)2 * m.npairs * QSZ) : nullptr;
         m.DB = m.gs && !plan.own_update ? carve.take<float>((size_t)m.npairs * QSZ) : nullptr;
         m.idle = m.gs ? nullptr : carve.take<int>(m.npairs);

@@ -104,9 +104,9 @@ struct SvdMat {
                              //   (the quadrant of rows 32.. x columns ..31 is not written: it mirrors the one across)
     float* gramf;            // [ntiles][nchg][64*64]: partial tiles of the Gram matrix of all rows (Gram space: the refresh;
                              //   data space: the check of DS_VERIFY, null for matrices too small for it)
-    float* Q;                // [npairs][64*64]; Gram space: [2][npairs][64*64], indexed by tick parity
-    float* QT;               // Gram space: the same matrices transposed, four entries of a row at a time: (Q^T)[row][k] at
-                             // ((k / 4) * 64 + row) * 4 + k % 4 (else null)
+    float* Q;                // data space: [npairs][64*64], the rotations of the running tick (Gram space: null)
+    float* QT;               // Gram space: [2][npairs][64*64], by tick parity the rotations transposed, four entries of a row at a
+                             // time: (Q^T)[row][k] at ((k / 4) * 64 + row) * 4 + k % 4 (else null)
     float* DB;               // Gram space with C one tick behind: [2][npairs][2][32*32], by tick parity the two diagonal blocks
                              // of every pair problem's rotated matrix (else null)
     int* state;              // [ST_WORDS]

@@ -799,14 +799,14 @@ __global__ __launch_bounds__(NT) void svd_eig(const SvdMat* mats, const Work* wo
             const float bq = F0[(k + hi) * ELD + tj * 16 + lo];        // F[k][j]
             q4 = __builtin_amdgcn_mfma_f32_16x16x4f32(a, bq, q4, 0, 0, 0);
         }
-        // 6. write Q with its columns permuted to their destination rows.  Gram-space matrices whose update rides in
-        //    the tick launches (m.DB set): only the transposed copy, which the update tiles and the pair problems of
-        //    the next tick (step 1) read; the others: Q itself, for svd_rowgram or svd_twosided_strip.
+        // 6. write Q with its columns permuted to their destination rows.  Gram-space matrices: only the transposed
+        //    copy, which the two-sided update and the pair problems of the next tick (step 1) read; data-space
+        //    matrices: Q itself, for svd_rowgram.
         const int dj = dest[tj * 16 + lo];
-        if (m.gs && m.DB) {
+        if (m.gs) {
             *(floatx4*)(m.QT + ((size_t)(step & 1) * m.npairs + wk.a) * QSZ + ((ti * 4 + hi) * PR + dj) * 4) = q4;
         } else {
-            float* qout = m.Q + ((size_t)(m.gs ? (step & 1) * m.npairs : 0) + wk.a) * QSZ;
+            float* qout = m.Q + (size_t)wk.a * QSZ;
 #pragma unroll
             for (int v = 0; v < 4; ++v) qout[(ti * 16 + 4 * hi + v) * PR + dj] = q4[v];
         }
