@@ -114,7 +114,9 @@ def test_rank_deficient_and_zero_matrices():
     np.testing.assert_allclose(out, e11, atol=1e-6)
 
 
-@pytest.mark.parametrize("shape", [(512, 600), (600, 512), (500, 700), (481, 481)])
+@pytest.mark.parametrize("shape", [(512, 600), (600, 512), (500, 700), (481, 481),
+                                   # an odd number of blocks (one of the pairs has a padding block), an odd number of pairs
+                                   (544, 600), (700, 720)])
 def test_gram_space_shapes(shape):
     # 16 row blocks or more: the sweeps run on the Gram matrix, the data is only touched by the refreshes
     rng = np.random.default_rng(shape[0] * 31 + shape[1])
