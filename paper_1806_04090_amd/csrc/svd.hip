@@ -66,18 +66,10 @@ __device__ inline bool verifying(const SvdMat& m)
 // ------------------------------------------------------------------------------------------------
 // reset / absmax / prepare
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void svd_reset(const SvdMat* mats, int n_mats)
-{
-    const int t = blockIdx.x * 256 + threadIdx.x;
-    const int j = t / ST_WORDS, w = t % ST_WORDS;
-    if (j < n_mats) mats[j].state[w] = (w == ST_FIRST) ? 1 : (w == ST_DMIN) ? 0x7f800000 : 0;
-}
-
 // Gram-space matrices: the pairing of the first ticks is that of the fixed tournament (no block weights exist yet).
-__global__ __launch_bounds__(64) void svd_first_pairs(const SvdMat* mats, const Work* list)
+__device__ inline void first_pairs(const SvdMat& m)
 {
-    const SvdMat m = mats[list[blockIdx.x].mat];
-    for (int e = threadIdx.x; e < 3 * m.npairs; e += 64) {
+    for (int e = threadIdx.x; e < 3 * m.npairs; e += 256) {
         const int t = e / m.npairs, k = e - t * m.npairs;
         int bi, bj;
         pair_blocks(m.nb2, t % m.R, k, bi, bj);
@@ -95,6 +87,19 @@ __global__ __launch_bounds__(64) void svd_first_pairs(const SvdMat* mats, const 
     }
 }
 
+// The state words of every matrix (workgroups below `reset_wgs`) and, in the same launch, the first pairings of the
+// Gram-space matrices (one workgroup each behind them; they touch no state word).
+__global__ __launch_bounds__(256) void svd_reset(const SvdMat* mats, int n_mats, int reset_wgs, const Work* gs_list)
+{
+    if ((int)blockIdx.x >= reset_wgs) {
+        first_pairs(mats[gs_list[blockIdx.x - reset_wgs].mat]);
+        return;
+    }
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    const int j = t / ST_WORDS, w = t % ST_WORDS;
+    if (j < n_mats) mats[j].state[w] = (w == ST_FIRST) ? 1 : (w == ST_DMIN) ? 0x7f800000 : 0;
+}
+
 __global__ __launch_bounds__(256) void svd_absmax(const SvdMat* mats, const Work* work)
 {
     __shared__ float red[4];
@@ -104,10 +109,14 @@ __global__ __launch_bounds__(256) void svd_absmax(const SvdMat* mats, const Work
     const int c = wk.b * 256 + threadIdx.x;
     float mx = 0.0f;
     if (c < m.M) {
-        for (int i = row0; i < min(m.r, row0 + BS); ++i) {
-            const float v = m.transposed ? m.G[(long long)c * m.ldg + i] : m.G[(long long)i * m.ldg + c];
-            mx = fmaxf(mx, fabsf(v));
-        }
+        // all loads of the column piece in flight at once: one at a time, the pass is a chain of memory latencies
+        float v[BS];
+        const long long by_row = m.transposed ? 1 : m.ldg, by_col = m.transposed ? m.ldg : 1;
+        const float* g = m.G + c * by_col;
+#pragma unroll
+        for (int k = 0; k < BS; ++k) v[k] = g[min(row0 + k, m.r - 1) * by_row];    // (a row read twice changes no maximum)
+#pragma unroll
+        for (int k = 0; k < BS; ++k) mx = fmaxf(mx, fabsf(v[k]));
     }
     for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_down(mx, o));
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
@@ -784,9 +793,17 @@ __global__ __launch_bounds__(256) void svd_norms(const SvdMat* mats, const Work*
     if (row >= m.rows_alloc) return;
     const float* a = current_w(m) + (size_t)row * m.ldw;
     float sum = 0.0f;
-    for (int c = lane * 4; c < m.Mp; c += 256) {
-        const float4 x = *(const float4*)(a + c);
-        sum += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
+    // eight loads in flight per lane, added in the order of the columns
+    for (int c0 = lane * 4; c0 < m.Mp; c0 += 8 * 256) {
+        float4 x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int c = c0 + 256 * u;
+            x[u] = c < m.Mp ? *(const float4*)(a + c) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (c0 + 256 * u < m.Mp) sum += x[u].x * x[u].x + x[u].y * x[u].y + x[u].z * x[u].z + x[u].w * x[u].w;
     }
     for (int o = 32; o > 0; o >>= 1) sum += __shfl_down(sum, o);
     if (lane == 0) {
@@ -878,28 +895,10 @@ __global__ __launch_bounds__(256) void svd_select(const SvdMat* mats, double s, 
     }
 }
 
-// Copies the kept singular vectors into the message: grid = (matrix, slot).
-__global__ __launch_bounds__(256) void svd_pack(const SvdMat* mats, const Work* work)
-{
-    const Work wk = work[blockIdx.x];
-    const SvdMat m = mats[wk.mat];
-    const int slot = wk.a;
-    const int kept = min(*m.count, m.capacity);
-    if (slot >= kept) return;
-    const int row = m.src_row[slot];
-    const float inv = m.src_inv[slot];
-    const float* a = current_w(m) + (size_t)row * m.ldw;
-    float* long_out = m.transposed ? m.U + (size_t)slot * m.rows : m.V + (size_t)slot * m.cols;
-    float* short_out = m.transposed ? m.V + (size_t)slot * m.cols : m.U + (size_t)slot * m.rows;
-    for (int c = threadIdx.x; c < m.M; c += 256) long_out[c] = a[c] * inv;
-    const float fold = m.src_fold[slot];
-    for (int c = threadIdx.x; c < m.r; c += 256) short_out[c] = a[m.Mp + c] * fold;
-}
-
 // Most sweeps any Gram-space matrix and any data-space matrix of the call took, and the fewest sweeps after which a
 // Gram-space matrix asked for a refresh (0: none did), into pinned host memory that the next calls read without
 // waiting (atomo_svd_options.adaptive).  One workgroup.
-__global__ __launch_bounds__(256) void svd_hint(const SvdMat* mats, int n_mats, int* out)
+__device__ inline void sweep_hint(const SvdMat* mats, int n_mats, int* out)
 {
     __shared__ int red[3][256];
     const int never = 1 << 30;
@@ -929,6 +928,36 @@ __global__ __launch_bounds__(256) void svd_hint(const SvdMat* mats, int n_mats, 
         out[3] = red[2][0] == never ? 0 : red[2][0];
         out[2] = 1;
     }
+}
+
+// Copies the kept singular vectors into the message: one workgroup per (matrix, slot); with `hint_out`, one more
+// behind them that writes the sweep counts for the next calls.
+__global__ __launch_bounds__(256) void svd_pack(const SvdMat* mats, const Work* work, int n_pack, int n_mats, int* hint_out)
+{
+    if ((int)blockIdx.x >= n_pack) {
+        sweep_hint(mats, n_mats, hint_out);
+        return;
+    }
+    const Work wk = work[blockIdx.x];
+    const SvdMat m = mats[wk.mat];
+    const int slot = wk.a;
+    const int kept = min(*m.count, m.capacity);
+    if (slot >= kept) return;
+    const int row = m.src_row[slot];
+    const float inv = m.src_inv[slot];
+    const float* a = current_w(m) + (size_t)row * m.ldw;
+    float* long_out = m.transposed ? m.U + (size_t)slot * m.rows : m.V + (size_t)slot * m.cols;
+    float* short_out = m.transposed ? m.V + (size_t)slot * m.cols : m.U + (size_t)slot * m.rows;
+    for (int c0 = threadIdx.x; c0 < m.M; c0 += 8 * 256) {         // eight loads in flight per thread
+        float x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) x[u] = c0 + 256 * u < m.M ? a[c0 + 256 * u] : 0.0f;
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (c0 + 256 * u < m.M) long_out[c0 + 256 * u] = x[u] * inv;
+    }
+    const float fold = m.src_fold[slot];
+    for (int c = threadIdx.x; c < m.r; c += 256) short_out[c] = a[m.Mp + c] * fold;
 }
 
 struct Plan {
@@ -1283,8 +1312,8 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     auto grid = [](const std::vector<Work>& list) { return (unsigned)list.size(); };
     {
         ProfScope ps(ctx, ATOMO_K_SVD_PREPARE, stream);
-        svd_reset<<<(unsigned)((n_mats * ST_WORDS + 255) / 256), 256, 0, stream>>>(d_mats, n_mats);
-        if (!plan.gs_list.empty()) svd_first_pairs<<<grid(plan.gs_list), 64, 0, stream>>>(d_mats, w_gs_list);
+        const int reset_wgs = (n_mats * ST_WORDS + 255) / 256;
+        svd_reset<<<(unsigned)reset_wgs + grid(plan.gs_list), 256, 0, stream>>>(d_mats, n_mats, reset_wgs, w_gs_list);
         if (!plan.prep.empty()) {
             svd_absmax<<<grid(plan.prep), 256, 0, stream>>>(d_mats, w_prep);
             svd_prepare<<<grid(plan.prep), 256, 0, stream>>>(d_mats, w_prep);
@@ -1418,9 +1447,10 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
         ProfScope ps(ctx, ATOMO_K_SVD_FINALIZE, stream);
         if (!plan.norms.empty()) svd_norms<<<grid(plan.norms), 256, 0, stream>>>(d_mats, w_norms, 0);
         svd_select<<<(unsigned)n_mats, 256, 0, stream>>>(d_mats, s, (unsigned long long)seed, ctx->d_flags);
-        if (!plan.pack.empty()) svd_pack<<<grid(plan.pack), 256, 0, stream>>>(d_mats, w_pack);
+        const unsigned pack_wgs = grid(plan.pack) + (hint ? 1u : 0u);     // the hint rides behind the pack items
+        if (pack_wgs > 0)
+            svd_pack<<<pack_wgs, 256, 0, stream>>>(d_mats, w_pack, (int)plan.pack.size(), n_mats, hint ? hint->dev : nullptr);
         if (have_thin) launch_thin_pack(d_mats, w_thin_chunks, (int)plan.thin_chunks.size(), stream);
-        if (hint) svd_hint<<<1, 256, 0, stream>>>(d_mats, n_mats, hint->dev);
     }
     if (hint) {
         ATOMO_HIP(ctx, hipEventRecord(hint->done, stream));
