@@ -221,34 +221,47 @@ __global__ __launch_bounds__(256) void svd_fullgram(const SvdMat* mats, const Wo
     }
 }
 
-// Sums the partial tiles of the full Gram matrix into C (both triangles) and resets Tgs to I.
-__global__ __launch_bounds__(256) void svd_fullgram_reduce(const SvdMat* mats, const Work* work, int tick)
+// Sums the partial tiles of the full Gram matrix into C (both triangles), resets Tgs to I, and takes the largest
+// |cos| between two rows of the tile from the sums it has just formed (the diagonal entries that the cosines need
+// belong to the two diagonal tiles: every workgroup sums those 2 x 64 entries itself, in the order in which their
+// own workgroups do).  The last tile of a matrix to finish decides whether the matrix is done or sweeps on.
+__global__ __launch_bounds__(256) void svd_fullgram_reduce(const SvdMat* mats, const Work* work, int tick, int max_sweeps,
+                                                           float stop_cosine, float fresh_stop, int* flags)
 {
     __shared__ float t[PR][PR + 1];
+    __shared__ float diag[2][PR];
+    __shared__ float red[12];
     const Work wk = work[blockIdx.x];
     const SvdMat m = mats[wk.mat];
     if (!refreshing(m)) return;
     const int ti = wk.a, tj = wk.b, nt = m.nb2 / 2;
-    const int tile_index = ti * nt - ti * (ti - 1) / 2 + (tj - ti);
-    const float* g = m.gramf + (size_t)tile_index * m.nchg * QSZ;
-    const int tid = threadIdx.x;
+    auto tile_of = [&](int a, int b) { return a * nt - a * (a - 1) / 2 + (b - a); };
+    const float* g = m.gramf + (size_t)tile_of(ti, tj) * m.nchg * QSZ;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     // sixteen independent sums per thread, chunk after chunk in a fixed order: sixteen loads in flight
     float sums[QSZ / 256];
 #pragma unroll
     for (int p = 0; p < QSZ / 256; ++p) sums[p] = 0.0f;
+    float dsum = 0.0f;
+    const int dt = tid < PR ? ti : tj, de = (tid & (PR - 1)) * (PR + 1);
+    const float* gd = m.gramf + (size_t)tile_of(dt, dt) * m.nchg * QSZ + de;
     for (int c = 0; c < m.nchg; ++c) {
 #pragma unroll
         for (int p = 0; p < QSZ / 256; ++p) sums[p] += g[(size_t)c * QSZ + tid + 256 * p];
+        if (tid < 2 * PR) dsum += gd[(size_t)c * QSZ];
     }
 #pragma unroll
     for (int p = 0; p < QSZ / 256; ++p) {
         const int e = tid + 256 * p;
         t[e >> 6][e & 63] = sums[p];
     }
+    if (tid < 2 * PR) diag[tid >> 6][tid & (PR - 1)] = dsum;
     __syncthreads();
     const int Rp = m.rows_alloc;
     float* C = c_of_parity(m, tick);                             // the C that this tick's svd_eig reads
     const bool first = m.state[ST_FIRST] != 0;
+    const float z2 = ZERO_REL * __int_as_float(m.state[ST_SCALE]);
+    float mx = 0.0f, dmax = 0.0f, dmin = __int_as_float(0x7f800000);
     for (int e = tid; e < QSZ; e += 256) {
         const int i = e >> 6, j = e & 63;
         const float v = ti == tj ? 0.5f * (t[i][j] + t[j][i]) : t[i][j];
@@ -262,33 +275,14 @@ __global__ __launch_bounds__(256) void svd_fullgram_reduce(const SvdMat* mats, c
             C[(size_t)(tj * PR + i) * m.ldc + ti * PR + j] = t[j][i];
             m.CT[(size_t)(tj * PR + i) * m.ldc + Rp + ti * PR + j] = 0.0f;
         }
-    }
-}
-
-// Largest |cos| between two rows according to the fresh Gram matrix; the last tile to finish decides
-// whether the matrix is done or sweeps on.
-__global__ __launch_bounds__(256) void svd_fresh_check(const SvdMat* mats, const Work* work, int tick, int max_sweeps,
-                                                       float stop_cosine, float fresh_stop, int* flags)
-{
-    __shared__ float red[12];
-    const Work wk = work[blockIdx.x];
-    const SvdMat m = mats[wk.mat];
-    if (!refreshing(m)) return;
-    const int ti = wk.a, tj = wk.b;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const float z2 = ZERO_REL * __int_as_float(m.state[ST_SCALE]);
-    const float* C = c_of_parity(m, tick);
-    float mx = 0.0f, dmax = 0.0f, dmin = __int_as_float(0x7f800000);
-    for (int e = tid; e < QSZ; e += 256) {
-        const int gi = ti * PR + (e >> 6), gj = tj * PR + (e & 63);
+        // the check, on the upper triangle of the whole matrix
+        const int gi = ti * PR + i, gj = tj * PR + j;
         if (gi < gj) {
-            const float dii = C[(size_t)gi * m.ldc + gi], djj = C[(size_t)gj * m.ldc + gj];
-            if (dii > 0.0f && djj > 0.0f)
-                mx = fmaxf(mx, fabsf(C[(size_t)gi * m.ldc + gj]) / fmaxf(sqrtf(dii * djj), z2));
+            const float dii = diag[0][i], djj = diag[1][j];
+            if (dii > 0.0f && djj > 0.0f) mx = fmaxf(mx, fabsf(v) / fmaxf(sqrtf(dii * djj), z2));
         } else if (gi == gj) {
-            const float d = C[(size_t)gi * m.ldc + gi];
-            dmax = fmaxf(dmax, d);
-            if (d > z2) dmin = fminf(dmin, d);
+            dmax = fmaxf(dmax, v);
+            if (v > z2) dmin = fminf(dmin, v);
         }
     }
     for (int o = 32; o > 0; o >>= 1) {
@@ -1424,9 +1418,8 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
                     ProfScope ps(ctx, ATOMO_K_SVD_REFRESH, stream);
                     svd_apply<<<grid(plan.apply), 256, 0, stream>>>(d_mats, w_apply);
                     svd_fullgram<<<grid(plan.fullgram), 256, 0, stream>>>(d_mats, w_fullgram);
-                    svd_fullgram_reduce<<<grid(plan.tiles), 256, 0, stream>>>(d_mats, w_tiles, tick);
-                    svd_fresh_check<<<grid(plan.tiles), 256, 0, stream>>>(d_mats, w_tiles, tick, limit_gs, stop_cosine,
-                                                                          fresh_stop, ctx->d_flags);
+                    svd_fullgram_reduce<<<grid(plan.tiles), 256, 0, stream>>>(d_mats, w_tiles, tick, limit_gs, stop_cosine,
+                                                                              fresh_stop, ctx->d_flags);
                 }
                 {
                     ProfScope ps(ctx, ATOMO_K_SVD_EIG, stream);

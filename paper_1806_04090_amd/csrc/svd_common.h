@@ -32,7 +32,7 @@ enum {
     ST_CUR = 7,         // Gram-space matrices: which of the two W buffers holds A
     ST_FIRST = 8,       // Gram-space matrices: 1 until the first refresh has run (nothing to apply yet)
     ST_FRESH = 9,       // largest |cos| of the freshly computed Gram matrix (float bits)
-    ST_ARRIVE2 = 10,    // workgroups of svd_fresh_check that finished
+    ST_ARRIVE2 = 10,    // workgroups of svd_fullgram_reduce that finished
     ST_EXP = 11,        // input was multiplied by 2^-ST_EXP before the iteration
     ST_ABSMAX = 12,     // largest |entry| of the input (float bits)
     ST_REFRESHES = 14,  // Gram-space matrices: fresh Gram matrices formed so far
