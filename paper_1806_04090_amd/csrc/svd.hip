@@ -1416,7 +1416,7 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
                 // complete now), and their pair problems of this tick run in a launch of their own
                 {
                     ProfScope ps(ctx, ATOMO_K_SVD_REFRESH, stream);
-                    svd_apply<<<grid(plan.apply), 256, 0, stream>>>(d_mats, w_apply);
+                    if (tick > 0) svd_apply<<<grid(plan.apply), 256, 0, stream>>>(d_mats, w_apply);   // (tick 0: nothing to apply yet)
                     svd_fullgram<<<grid(plan.fullgram), 256, 0, stream>>>(d_mats, w_fullgram);
                     svd_fullgram_reduce<<<grid(plan.tiles), 256, 0, stream>>>(d_mats, w_tiles, tick, limit_gs, stop_cosine,
                                                                               fresh_stop, ctx->d_flags);
