@@ -785,6 +785,9 @@ __global__ __launch_bounds__(256) void svd_norms(const SvdMat* mats, const Work*
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int row = wk.a * 4 + wave;
     if (row >= m.rows_alloc) return;
+    // a Gram-space matrix ends on a refresh, whose Gram matrix has the squared norms of the final rows on its
+    // diagonal (cref): svd_select takes its singular values from there
+    if (!init && m.gs) return;
     const float* a = current_w(m) + (size_t)row * m.ldw;
     float sum = 0.0f;
     // eight loads in flight per lane, added in the order of the columns
@@ -825,7 +828,7 @@ __global__ __launch_bounds__(256) void svd_select(const SvdMat* mats, double s, 
     int P = 1;
     while (P < r) P <<= 1;
     for (int i = tid; i < P; i += 256) {
-        key[i] = i < r ? m.sig_raw[i] : -1.0f;
+        key[i] = i < r ? (m.gs ? ldexpf(sqrtf(m.cref[i]), m.state[ST_EXP]) : m.sig_raw[i]) : -1.0f;
         src[i] = i;
     }
     __syncthreads();
