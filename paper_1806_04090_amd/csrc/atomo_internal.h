@@ -60,6 +60,16 @@ struct atomo_ctx {
     int hint_next = 0;
     uint64_t hint_seq = 0;
     size_t rowgram_lds = 0;        // dynamic LDS that svd_rowgram has been allowed on this context's device
+    // Descriptor tables of the last SVD encode (at the start of the workspace) and of the last SVD decode (in a block
+    // of their own): a training loop passes the same layer set and buffers step after step, so a call whose tables
+    // come out byte for byte the same, on the same stream, with the device copy untouched since, uploads nothing.
+    std::vector<char> svd_tables;        // host copy of what the workspace holds
+    bool svd_tables_intact = false;      // nothing has asked for the workspace since they were uploaded
+    hipStream_t svd_tables_stream = nullptr;
+    void* dec_tables_dev = nullptr;
+    size_t dec_tables_cap = 0;
+    std::vector<char> dec_tables;        // host copy of what dec_tables_dev holds
+    hipStream_t dec_tables_stream = nullptr;
     hipStream_t side = nullptr, side2 = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr, ev_join2 = nullptr;
     // optional event bracketing of kernel launches (atomo_profile_*)
@@ -80,7 +90,8 @@ namespace atomo {
         }                                                      \
     } while (0)
 
-// Grows the workspace to at least `bytes` (contents are not preserved).
+// Grows the workspace to at least `bytes` (contents are not preserved).  Every user of the workspace asks for it here
+// first, so this is also where the SVD encoder's tables stop counting as intact.
 int ensure_workspace(atomo_ctx* ctx, size_t bytes);
 
 // Creates ctx->side, ctx->side2 and the fork/join events if they do not exist yet.

@@ -10,6 +10,7 @@ namespace atomo {
 
 int ensure_workspace(atomo_ctx* ctx, size_t bytes)
 {
+    ctx->svd_tables_intact = false;
     if (bytes <= ctx->ws_bytes) return ATOMO_OK;
     // Growing frees the old block; hipFree waits for the device, so no kernel still uses it.
     if (ctx->ws) {
@@ -143,6 +144,7 @@ int atomo_destroy(atomo_ctx* ctx)
     if (ctx->side) (void)hipStreamDestroy(ctx->side);
     if (ctx->side2) (void)hipStreamDestroy(ctx->side2);
     if (ctx->ws) (void)hipFree(ctx->ws);
+    if (ctx->dec_tables_dev) (void)hipFree(ctx->dec_tables_dev);
     if (ctx->ew_state) (void)hipFree(ctx->ew_state);
     if (ctx->d_report) (void)hipFree(ctx->d_report);
     if (ctx->d_flags) (void)hipFree(ctx->d_flags);

@@ -287,22 +287,37 @@ int decode_svd_batch(atomo_ctx* ctx, const atomo_svd_msg* msgs, const int32_t* f
     deal_to_dies(hw_tall);
     const size_t n_wide = hw.size();
     hw.insert(hw.end(), hw_tall.begin(), hw_tall.end());
-    // the three tables travel in one copy
+    // the three tables travel in one copy, into a block of their own: a loop that decodes the same messages into the
+    // same outputs call after call finds them there and uploads nothing (see atomo_ctx::dec_tables)
     Carver size_only(nullptr);
     size_only.take<DecMsg>(hm.size());
     size_only.take<DecOut>(ho.size());
     size_only.take<DecWork>(hw.size());
-    int rc = ensure_workspace(ctx, size_only.off);
-    if (rc != ATOMO_OK) return rc;
-    Carver carve(ctx->ws);
+    int rc = ATOMO_OK;
+    if (size_only.off > ctx->dec_tables_cap) {
+        // (hipFree waits for the device, so no kernel still reads the old block)
+        if (ctx->dec_tables_dev) ATOMO_HIP(ctx, hipFree(ctx->dec_tables_dev));
+        ctx->dec_tables_dev = nullptr;
+        ctx->dec_tables_cap = 0;
+        ctx->dec_tables.clear();
+        const size_t want = align_up(size_only.off * 2, (size_t)1 << 16);
+        if (hipMalloc(&ctx->dec_tables_dev, want) != hipSuccess) return ATOMO_ENOMEM;
+        ctx->dec_tables_cap = want;
+    }
+    Carver carve(ctx->dec_tables_dev);
     DecMsg* d_msgs = carve.take<DecMsg>(hm.size());
     DecOut* d_outs = carve.take<DecOut>(ho.size());
     DecWork* d_work = carve.take<DecWork>(hw.size());
     std::vector<char> staged(size_only.off, 0);
-    memcpy(staged.data() + ((char*)d_msgs - (char*)ctx->ws), hm.data(), hm.size() * sizeof(DecMsg));
-    memcpy(staged.data() + ((char*)d_outs - (char*)ctx->ws), ho.data(), ho.size() * sizeof(DecOut));
-    memcpy(staged.data() + ((char*)d_work - (char*)ctx->ws), hw.data(), hw.size() * sizeof(DecWork));
-    if ((rc = upload(ctx, ctx->ws, staged.data(), staged.size(), stream)) != ATOMO_OK) return rc;
+    memcpy(staged.data() + ((char*)d_msgs - (char*)ctx->dec_tables_dev), hm.data(), hm.size() * sizeof(DecMsg));
+    memcpy(staged.data() + ((char*)d_outs - (char*)ctx->dec_tables_dev), ho.data(), ho.size() * sizeof(DecOut));
+    memcpy(staged.data() + ((char*)d_work - (char*)ctx->dec_tables_dev), hw.data(), hw.size() * sizeof(DecWork));
+    if (ctx->dec_tables_stream != stream || staged != ctx->dec_tables) {
+        ctx->dec_tables.clear();                                 // (an upload that fails leaves nothing to match)
+        if ((rc = upload(ctx, ctx->dec_tables_dev, staged.data(), staged.size(), stream)) != ATOMO_OK) return rc;
+        ctx->dec_tables = staged;
+        ctx->dec_tables_stream = stream;
+    }
     {
         ProfScope ps(ctx, ATOMO_K_DECODE_SVD, stream);
         int max_cap = 1;

@@ -42,6 +42,7 @@
 #include <cfloat>
 #include <algorithm>
 #include <cmath>
+#include <cstring>
 #include <vector>
 
 #include "svd_common.h"
@@ -1266,6 +1267,8 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     const uint64_t* stream_ids = opt ? opt->stream_ids : nullptr;
     build_plan(mats, n_mats, msgs, sigma_out, p_out, stream_base, stream_ids, nullptr, sizing);
     if (sizing.bytes >= (HOT_UNIT << 32)) return ATOMO_EINVAL;   // (the work items address the workspace in 32 bits of 16-byte units)
+    const bool tables_intact = ctx->svd_tables_intact;
+    const void* const ws_before = ctx->ws;
     int rc = ensure_workspace(ctx, sizing.bytes);
     if (rc != ATOMO_OK) return rc;
 
@@ -1301,10 +1304,24 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     const Work* w_thin_copied = place(plan.thin_copied);
     const Work* w_gs_list = place(plan.gs_list);
 
-    rc = upload(ctx, d_mats, plan.mats.data(), plan.mats.size() * sizeof(SvdMat), stream);
-    if (rc != ATOMO_OK) return rc;
-    rc = upload(ctx, plan.d_work, all.data(), all.size() * sizeof(Work), stream);
-    if (rc != ATOMO_OK) return rc;
+    // the tables go up unless the workspace still holds these very bytes (see atomo_ctx::svd_tables)
+    {
+        const size_t mats_bytes = plan.mats.size() * sizeof(SvdMat), work_bytes = all.size() * sizeof(Work);
+        const bool same = tables_intact && ws_before == ctx->ws && ctx->svd_tables_stream == stream &&
+                          ctx->svd_tables.size() == mats_bytes + work_bytes &&
+                          memcmp(ctx->svd_tables.data(), plan.mats.data(), mats_bytes) == 0 &&
+                          memcmp(ctx->svd_tables.data() + mats_bytes, all.data(), work_bytes) == 0;
+        if (!same) {
+            rc = upload(ctx, d_mats, plan.mats.data(), mats_bytes, stream);
+            if (rc != ATOMO_OK) return rc;
+            rc = upload(ctx, plan.d_work, all.data(), work_bytes, stream);
+            if (rc != ATOMO_OK) return rc;
+            ctx->svd_tables.resize(mats_bytes + work_bytes);
+            memcpy(ctx->svd_tables.data(), plan.mats.data(), mats_bytes);
+            memcpy(ctx->svd_tables.data() + mats_bytes, all.data(), work_bytes);
+            ctx->svd_tables_stream = stream;
+        }
+    }
 
     auto grid = [](const std::vector<Work>& list) { return (unsigned)list.size(); };
     {
@@ -1453,6 +1470,7 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
         hint->pending = true;
     }
     ATOMO_HIP(ctx, hipGetLastError());
+    ctx->svd_tables_intact = true;                               // until anything asks for the workspace again
     return ATOMO_OK;
 }
 
