@@ -388,3 +388,51 @@ def test_adaptive_budget_after_a_slower_gradient_still_gives_a_full_decompositio
         assert status == 0
     assert ctx().svd_sweeps(1)[0] == alone
     full_parity(quick, 3.0, 5, 0, msgs[0], *per[0])
+
+
+def test_descriptor_tables_are_uploaded_again_whenever_they_or_the_workspace_changed():
+    # A call whose descriptor tables match what the device still holds from the call before uploads nothing.  The
+    # tables must go up again when another operation used the workspace in between, when the buffers differ, and
+    # the decoder's likewise; every result is compared bit for bit with the one of a call that did upload.
+    c = binding.Context(0)
+    shapes = [(64, 576), (128, 1152), (512, 600), (40, 30), (96, 18)]
+    host_a = inputs.resnet18_layer_set(3, shapes=shapes)
+    host_b = inputs.resnet18_layer_set(4, shapes=shapes)
+    d_a, d_b = [dev(g) for g in host_a], [dev(g) for g in host_b]
+    msgs = [binding.alloc_svd_message(m, n, 8, "cuda") for m, n in shapes]
+
+    def run(ctx_, mats, into):
+        binding.atomo_encode_svd(ctx_, mats, 3.0, 11, 0, msgs=into)
+        assert ctx_.status()[0] == 0
+        return [m.to_host() for m in into]
+
+    def same(x, y):
+        return all(a["count"] == b["count"] and np.array_equal(a["idx"], b["idx"]) and np.array_equal(a["w"], b["w"])
+                   and np.array_equal(a["U"], b["U"]) and np.array_equal(a["V"], b["V"]) for a, b in zip(x, y))
+
+    first = run(c, d_a, msgs)
+    assert same(run(c, d_a, msgs), first)                        # tables reused
+    g = dev(np.random.default_rng(8).standard_normal(1 << 20).astype(np.float32))
+    ew = binding.atomo_encode_entrywise(c, g, (1 << 20) / 100.0, 3)   # overwrites the head of the workspace
+    assert same(run(c, d_a, msgs), first)
+    other = run(c, d_b, msgs)                                    # same shapes, other buffers
+    msgs2 = [binding.alloc_svd_message(m, n, 8, "cuda") for m, n in shapes]
+    assert same(other, run(binding.Context(0), d_b, msgs2))
+    assert not same(other, first)
+    assert same(run(c, d_a, msgs), first)
+
+    groups = [[m] for m in msgs]
+    outs = [torch.empty(m, n, dtype=torch.float32, device="cuda") for m, n in shapes]
+    binding.atomo_decode_svd_batch(c, groups, 1.0, outs=outs)
+    want = [o.clone() for o in outs]
+    for o in outs:
+        o.fill_(7.0)
+    binding.atomo_decode_svd_batch(c, groups, 1.0, outs=outs)    # tables reused
+    assert all(torch.equal(a, b) for a, b in zip(outs, want))
+    binding.atomo_decode(c, [ew])                                # a decode of another kind in between
+    outs2 = [torch.full((m, n), 7.0, dtype=torch.float32, device="cuda") for m, n in shapes]
+    binding.atomo_decode_svd_batch(c, groups, 1.0, outs=outs2)   # other outputs
+    assert all(torch.equal(a, b) for a, b in zip(outs2, want))
+    binding.atomo_decode_svd_batch(c, groups, 0.5, outs=outs)    # same tables, other scale
+    assert all(torch.equal(a, 0.5 * b) for a, b in zip(outs, want))
+    c.close()
