@@ -25,7 +25,10 @@
  *    Descriptor tables travel to the device through a ring of eight pinned
  *    staging buffers owned by the context: a call that needs a buffer whose
  *    previous copy (eight uploads ago) has not been executed yet waits for
- *    that copy, and for nothing else.
+ *    that copy, and for nothing else.  The SVD encoder and the SVD decoder
+ *    skip the upload when a call, on the same stream, describes exactly the
+ *    buffers of the call before it (a training loop): the tables hold
+ *    addresses and sizes, never data, and the device still has them.
  *  - The caller owns every input, output and message buffer.  Inputs are never
  *    modified.  The context owns a device workspace that grows on demand
  *    (growing it allocates, which synchronises the device; atomo_reserve
