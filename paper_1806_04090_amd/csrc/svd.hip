@@ -130,21 +130,58 @@ __global__ __launch_bounds__(256) void svd_absmax(const SvdMat* mats, const Work
 
 __global__ __launch_bounds__(256) void svd_prepare(const SvdMat* mats, const Work* work)
 {
+    __shared__ float part[4][BS];
     const Work wk = work[blockIdx.x];
     const SvdMat m = mats[wk.mat];
     const int row0 = wk.a * BS;
     const int c = wk.b * 256 + threadIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int e = scale_exponent(m);
     if (wk.a == 0 && wk.b == 0 && threadIdx.x == 0) m.state[ST_EXP] = e;
-    if (c >= m.ldw) return;
     const float factor = ldexpf(1.0f, -e);
+    // the scaled copy, and on the way the squared norm of every row's piece of 256 columns (summed over the lanes in
+    // a fixed order): svd_scale adds the pieces up, so the copy is not read again for the scale of the matrix
     for (int i = row0; i < row0 + BS; ++i) {
-        float v = 0.0f;
-        if (i < m.r) {
-            if (c < m.M) v = factor * (m.transposed ? m.G[(long long)c * m.ldg + i] : m.G[(long long)i * m.ldg + c]);
-            else if (c - m.Mp == i) v = 1.0f;
+        float v = 0.0f, sq = 0.0f;
+        if (i < m.r && c < m.ldw) {
+            if (c < m.M) {
+                v = factor * (m.transposed ? m.G[(long long)c * m.ldg + i] : m.G[(long long)i * m.ldg + c]);
+                sq = v * v;
+            } else if (c - m.Mp == i) {
+                v = 1.0f;
+            }
         }
-        m.W0[(size_t)i * m.ldw + c] = v;
+        if (c < m.ldw) m.W0[(size_t)i * m.ldw + c] = v;
+        for (int o = 32; o > 0; o >>= 1) sq += __shfl_down(sq, o);
+        if (lane == 0) part[wave][i - row0] = sq;
+    }
+    __syncthreads();
+    if (threadIdx.x < BS)
+        m.rowsq[(size_t)(row0 + threadIdx.x) * ((m.ldw + 255) / 256) + wk.b] =
+            ((part[0][threadIdx.x] + part[1][threadIdx.x]) + part[2][threadIdx.x]) + part[3][threadIdx.x];
+}
+
+// The scale of every matrix before the first sweep: its largest squared row norm, from the pieces that svd_prepare
+// left.  One workgroup per matrix.
+__global__ __launch_bounds__(256) void svd_scale(const SvdMat* mats)
+{
+    __shared__ float red[4];
+    const SvdMat m = mats[blockIdx.x];
+    if (m.thin) return;
+    const int pieces = (m.ldw + 255) / 256;
+    float mx = 0.0f;
+    for (int row = threadIdx.x; row < m.rows_alloc; row += 256) {
+        float sum = 0.0f;
+        for (int p = 0; p < pieces; ++p) sum += m.rowsq[(size_t)row * pieces + p];
+        mx = fmaxf(mx, sum);
+    }
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_down(mx, o));
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        m.state[ST_SCALE] = __float_as_int(mx);
+        m.state[ST_SCALE_NEXT] = __float_as_int(mx);
     }
 }
 
@@ -779,7 +816,7 @@ __global__ __launch_bounds__(256) void svd_apply(const SvdMat* mats, const Work*
 // ------------------------------------------------------------------------------------------------
 // finalise: singular values, Algorithm 1, Bernoulli draws, message
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void svd_norms(const SvdMat* mats, const Work* work, int init)
+__global__ __launch_bounds__(256) void svd_norms(const SvdMat* mats, const Work* work)
 {
     const Work wk = work[blockIdx.x];
     const SvdMat m = mats[wk.mat];
@@ -788,7 +825,7 @@ __global__ __launch_bounds__(256) void svd_norms(const SvdMat* mats, const Work*
     if (row >= m.rows_alloc) return;
     // a Gram-space matrix ends on a refresh, whose Gram matrix has the squared norms of the final rows on its
     // diagonal (cref): svd_select takes its singular values from there
-    if (!init && m.gs) return;
+    if (m.gs) return;
     const float* a = current_w(m) + (size_t)row * m.ldw;
     float sum = 0.0f;
     // eight loads in flight per lane, added in the order of the columns
@@ -804,14 +841,8 @@ __global__ __launch_bounds__(256) void svd_norms(const SvdMat* mats, const Work*
             if (c0 + 256 * u < m.Mp) sum += x[u].x * x[u].x + x[u].y * x[u].y + x[u].z * x[u].z + x[u].w * x[u].w;
     }
     for (int o = 32; o > 0; o >>= 1) sum += __shfl_down(sum, o);
-    if (lane == 0) {
-        if (init) {                                              // before the first sweep: scale of the matrix
-            atomicMax((unsigned int*)&m.state[ST_SCALE], __float_as_uint(sum));
-            atomicMax((unsigned int*)&m.state[ST_SCALE_NEXT], __float_as_uint(sum));
-        } else {                                                 // singular values, input scaling undone
-            m.sig_raw[row] = row < m.r ? ldexpf(sqrtf(sum), m.state[ST_EXP]) : 0.0f;
-        }
-    }
+    // singular values, input scaling undone
+    if (lane == 0) m.sig_raw[row] = row < m.r ? ldexpf(sqrtf(sum), m.state[ST_EXP]) : 0.0f;
 }
 
 // One workgroup per matrix.  Sorts sigma (descending), runs Algorithm 1 on it, draws the Bernoulli
@@ -1036,7 +1067,7 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
             m.nchg = (m.M + m.tchunk - 1) / m.tchunk;
             m.Mp = m.M; m.ldw = 0; m.nb2 = 0; m.rows_alloc = THIN_R; m.R = 1; m.npairs = 0; m.nchu = 0; m.gs = 0;
             m.ntiles = 0; m.ldc = 0;
-            m.W0 = nullptr; m.W1 = nullptr; m.CT = nullptr; m.CT2 = nullptr; m.cref = nullptr; m.cref0 = nullptr;
+            m.W0 = nullptr; m.W1 = nullptr; m.CT = nullptr; m.CT2 = nullptr; m.cref = nullptr; m.cref0 = nullptr; m.rowsq = nullptr;
             m.sched = nullptr; m.where = nullptr; m.bw = nullptr; m.dd = nullptr; m.idle = nullptr;
             m.gram = carve.take<float>((size_t)m.nchg * THIN_R * THIN_R);
             m.Q = carve.take<float>(2 * THIN_R * THIN_R);
@@ -1093,6 +1124,7 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
         m.state = carve.take<int>(ST_WORDS);
         const size_t state_off = carve.last;
         m.sig_raw = carve.take<float>(m.rows_alloc);
+        m.rowsq = carve.take<float>((size_t)m.rows_alloc * ((m.ldw + 255) / 256));
         m.cref = m.gs ? carve.take<float>(m.rows_alloc) : nullptr;
         m.cref0 = m.gs ? carve.take<float>(m.rows_alloc) : nullptr;
         m.sched = m.gs ? carve.take<int>((size_t)3 * m.npairs * 2) : nullptr;
@@ -1331,7 +1363,7 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
         if (!plan.prep.empty()) {
             svd_absmax<<<grid(plan.prep), 256, 0, stream>>>(d_mats, w_prep);
             svd_prepare<<<grid(plan.prep), 256, 0, stream>>>(d_mats, w_prep);
-            svd_norms<<<grid(plan.norms), 256, 0, stream>>>(d_mats, w_norms, 1);
+            svd_scale<<<(unsigned)n_mats, 256, 0, stream>>>(d_mats);
         }
     }
     // The data-space matrices iterate on streams of their own from here to the end, the large ones on one, the small
@@ -1458,7 +1490,7 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     if (use_side[1]) ATOMO_HIP(ctx, hipStreamWaitEvent(stream, ctx->ev_join2, 0));
     {
         ProfScope ps(ctx, ATOMO_K_SVD_FINALIZE, stream);
-        if (!plan.norms.empty()) svd_norms<<<grid(plan.norms), 256, 0, stream>>>(d_mats, w_norms, 0);
+        if (!plan.norms.empty()) svd_norms<<<grid(plan.norms), 256, 0, stream>>>(d_mats, w_norms);
         svd_select<<<(unsigned)n_mats, 256, 0, stream>>>(d_mats, s, (unsigned long long)seed, ctx->d_flags);
         const unsigned pack_wgs = grid(plan.pack) + (hint ? 1u : 0u);     // the hint rides behind the pack items
         if (pack_wgs > 0)

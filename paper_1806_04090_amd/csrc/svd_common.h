@@ -111,6 +111,7 @@ struct SvdMat {
                              // of every pair problem's rotated matrix (else null)
     int* state;              // [ST_WORDS]
     float* sig_raw;          // [rows_alloc]
+    float* rowsq;            // [rows_alloc][ceil(ldw / 256)] squared norm of every row's piece of 256 columns (svd_prepare)
     float* cref;             // Gram space: [rows_alloc] reference squared norm of every row, see GS_RELIABLE
     float* cref0;            // Gram space: [rows_alloc] the same, but never measured again after the first refresh: the
                              //   scale of the row for the block weights
