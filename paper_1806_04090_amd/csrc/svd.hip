@@ -1190,7 +1190,8 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
                     for (int c = 0; c < m.nchg; ++c) plan.ds_full.push_back(Work{j, ti, tj, c});
                 }
         }
-        for (int g = 0; g < m.rows_alloc / 4; ++g) plan.norms.push_back(Work{j, g, 0, 0});
+        if (!m.gs)                                               // (Gram-space matrices: svd_select reads cref)
+            for (int g = 0; g < m.rows_alloc / 4; ++g) plan.norms.push_back(Work{j, g, 0, 0});
         for (int k = 0; k < m.capacity; ++k) plan.pack.push_back(Work{j, k, 0, 0});
     }
     deal_to_dies(plan.strips);                                   // a matrix's strips, which share its rotations, on one die
