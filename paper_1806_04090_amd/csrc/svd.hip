@@ -991,10 +991,11 @@ __global__ __launch_bounds__(256) void svd_pack(const SvdMat* mats, const Work* 
 
 struct Plan {
     std::vector<SvdMat> mats;
-    std::vector<Work> prep, fullgram, tiles, apply, eig_gs, twosided, strips, norms, pack;
+    std::vector<Work> prep, fullgram, tiles, apply, eig_gs, twosided, strips, pack;
     // the data-space matrices in two groups that iterate side by side: [0] those of DS_VERIFY_MIN_R ticks per sweep
     // and more, [1] the smaller ones (few pairs, many rounds that rotate all index pairs, done after few ticks)
     std::vector<Work> rowgram[2], eig_ds[2];
+    std::vector<Work> norms[2];                    // four rows of a data-space matrix per item: the final row norms
     std::vector<Work> ds_full, ds_tiles;           // data-space matrices that check their whole Gram matrix (DS_VERIFY)
     std::vector<int> ds_periods;                   // their distinct R
     std::vector<Work> thin_chunks, thin_list;      // thin matrices: (matrix, chunk of positions); (matrix)
@@ -1012,7 +1013,7 @@ struct Plan {
     {
         return prep.size() + rowgram[0].size() + rowgram[1].size() + fullgram.size() + tiles.size() + apply.size() +
                eig_gs.size() + eig_ds[0].size() + eig_ds[1].size() +
-               twosided.size() + strips.size() + ds_full.size() + ds_tiles.size() + norms.size() + pack.size() + 2 * thin_chunks.size() + thin_list.size() +
+               twosided.size() + strips.size() + ds_full.size() + ds_tiles.size() + norms[0].size() + norms[1].size() + pack.size() + 2 * thin_chunks.size() + thin_list.size() +
                gs_list.size();
     }
 };
@@ -1191,7 +1192,7 @@ void build_plan(const atomo_mat* mats, int n_mats, const atomo_svd_msg* msgs, fl
                 }
         }
         if (!m.gs)                                               // (Gram-space matrices: svd_select reads cref)
-            for (int g = 0; g < m.rows_alloc / 4; ++g) plan.norms.push_back(Work{j, g, 0, 0});
+            for (int g = 0; g < m.rows_alloc / 4; ++g) plan.norms[grp].push_back(Work{j, g, 0, 0});
         for (int k = 0; k < m.capacity; ++k) plan.pack.push_back(Work{j, k, 0, 0});
     }
     deal_to_dies(plan.strips);                                   // a matrix's strips, which share its rotations, on one die
@@ -1329,7 +1330,7 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     const Work* w_strips = place(plan.strips);
     const Work* w_ds_full = place(plan.ds_full);
     const Work* w_ds_tiles = place(plan.ds_tiles);
-    const Work* w_norms = place(plan.norms);
+    const Work* w_norms[2] = {place(plan.norms[0]), place(plan.norms[1])};
     const Work* w_pack = place(plan.pack);
     const Work* w_thin_chunks = place(plan.thin_chunks);
     const Work* w_thin_list = place(plan.thin_list);
@@ -1436,6 +1437,13 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
                 if (g == 0 && tick >= 0) verify(tick + 1);
             }
     }
+    // the singular values of the data-space matrices, at the end of their own chains
+    for (int g = 0; g < 2; ++g)
+        if (!plan.norms[g].empty()) {
+            hipStream_t s_g = g == 0 ? ctx->side : ctx->side2;
+            ProfScope ps(ctx, ATOMO_K_SVD_FINALIZE, s_g);
+            svd_norms<<<grid(plan.norms[g]), 256, 0, s_g>>>(d_mats, w_norms[g]);
+        }
     if (use_side[0]) ATOMO_HIP(ctx, hipEventRecord(ctx->ev_join, ctx->side));
     if (use_side[1]) ATOMO_HIP(ctx, hipEventRecord(ctx->ev_join2, ctx->side2));
     if (have_gs) {
@@ -1491,7 +1499,6 @@ int encode_svd(atomo_ctx* ctx, const atomo_mat* mats, int n_mats, double s, uint
     if (use_side[1]) ATOMO_HIP(ctx, hipStreamWaitEvent(stream, ctx->ev_join2, 0));
     {
         ProfScope ps(ctx, ATOMO_K_SVD_FINALIZE, stream);
-        if (!plan.norms.empty()) svd_norms<<<grid(plan.norms), 256, 0, stream>>>(d_mats, w_norms);
         svd_select<<<(unsigned)n_mats, 256, 0, stream>>>(d_mats, s, (unsigned long long)seed, ctx->d_flags);
         const unsigned pack_wgs = grid(plan.pack) + (hint ? 1u : 0u);     // the hint rides behind the pack items
         if (pack_wgs > 0)
